@@ -1,0 +1,132 @@
+#!/usr/bin/env python3
+"""Benchmark of the LC-RWMD hot path on one MI355X.
+
+One step = one call of lcrwmd_rwmd over the whole workload (both directions of the bound: first phase,
+second phase, swapped pass, transposed maximum), with E, the database and the queries already resident
+in HBM.  Prints ONE JSON line: whole-job throughput in query x database pairs per second, the roofline
+figures of the dominant kernel (first-phase fp32 MFMA contraction, timed with HIP events on its own
+stream inside the library) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_F32_MFMA_TFLOPS = 157.3     # MI355X, dense fp32 matrix
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X, dense bf16 matrix
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "long"])
+    ap.add_argument("--compute", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-queries", type=int, default=24, help="queries in the CPU oracle's timed sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1711_07227_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.workload]
+    t_gen = time.perf_counter()
+    prob = synth.make(cfg)
+    t_gen = time.perf_counter() - t_gen
+    v, m, n, q = prob["v"], cfg.m, prob["n"], prob["q"]
+
+    torch.cuda.set_device(0)
+    E = torch.from_numpy(prob["E"]).cuda()
+    db = binding.Csr.from_numpy(prob["db"], v)
+    qs = binding.Csr.from_numpy(prob["queries"], v)
+    ctx = binding.Context(0)
+    compute = binding.BF16 if args.compute == "bf16" else binding.F32
+    ctx.set_options(compute=compute)
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, binding.F32))
+    D = torch.empty((n, q), dtype=torch.float32, device="cuda")
+
+    for _ in range(args.warmup):
+        ctx.rwmd(qs, db, E, D, ws)
+    torch.cuda.synchronize()
+    ctx.profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.rwmd(qs, db, E, D, ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.profile_end()
+    sec = t1 - t0
+    ms_per_step = 1e3 * sec / args.steps
+    pairs_per_s = n * q * args.steps / sec
+
+    p1_ms = prof["phase1_ms"] / max(prof["phase1_launches"], 1)
+    p1_flops = prof["phase1_flops"] / max(prof["phase1_launches"], 1)
+    achieved_tflops = p1_flops / (p1_ms * 1e-3) / 1e12 if p1_ms > 0 else 0.0
+    peak = PEAK_BF16_MFMA_TFLOPS if args.compute == "bf16" else PEAK_F32_MFMA_TFLOPS
+    p2_ms = prof["phase2_ms"] / max(prof["phase2_launches"], 1)
+    p2_gbs = prof["phase2_bytes"] / max(prof["phase2_ms"], 1e-9) / 1e6
+    p2_gather_gbs = prof["phase2_gather_bytes"] / max(prof["phase2_ms"], 1e-9) / 1e6
+
+    # sampled check of the timed result against the oracle's per-pair brute force
+    cpu = None
+    check = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rng = np.random.default_rng(1)
+        pi = rng.integers(0, n, 512)
+        pj = rng.integers(0, q, 512)
+        ref = oracle.rwmd_pairs(prob["E"], prob["db"], prob["queries"], pi, pj)
+        got = D[torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()].cpu().numpy().astype(np.float64)
+        check = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-6)))
+        qn = max(1, min(args.cpu_queries, q))
+        sub = synth.csr_rows(*prob["queries"], np.arange(qn))
+        tc = time.perf_counter()
+        oracle.rwmd_table(prob["E"], prob["db"], sub)
+        tc = time.perf_counter() - tc
+        cpu = {"value": n * qn / tc, "unit": "pairs/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"per-query table oracle (fp64), all {n} database docs x first {qn} queries, {tc:.1f} s"}
+
+    out = {
+        "metric": "query x database RWMD pairs/s on 1 MI355X (both directions + max)",
+        "value": pairs_per_s,
+        "unit": "pairs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": args.compute,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: v={v} m={m} n={n} q={q} h={cfg.h_lo}-{cfg.h_hi} zipf={cfg.zipf_s}",
+                   "nnz_db": db.nnz, "nnz_q": qs.nnz, "data_gen_s": round(t_gen, 1)},
+        "roofline": {"bound": "mfma", "kernel": f"phase1_{args.compute}", "achieved": achieved_tflops, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved_tflops / peak, "traffic": None,
+                     "launches_per_step": prof["phase1_launches"] / args.steps, "avg_launch_ms": p1_ms,
+                     "flops_per_launch": p1_flops,
+                     "share_of_step": prof["phase1_ms"] / (1e3 * sec)},
+        "phase2": {"bound": "hbm", "achieved": p2_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": p2_gbs / PEAK_HBM_GBS,
+                   "gather_GBps": p2_gather_gbs, "launches_per_step": prof["phase2_launches"] / args.steps,
+                   "avg_launch_ms": p2_ms, "share_of_step": prof["phase2_ms"] / (1e3 * sec)},
+        "cpu_baseline": cpu,
+        "max_rel_err_vs_oracle_512_pairs": check,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,195 @@
+/*
+ * lcrwmd - Linear-Complexity Relaxed Word Mover's Distance on one AMD MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of arXiv:1711.07227.  Notation is the paper's
+ * (Tables I and II): v vocabulary size, m embedding dimension, E the v x m embedding
+ * matrix, X1 the resident ("database") histograms, X2 the transient ("query")
+ * histograms, Z the per-word minimum distances, D the distance matrix, R the top-k
+ * result.  n = rows of X1, q = rows of X2.
+ *
+ * Conventions that hold for every call
+ *   - Pointers named in lcrwmd_csr / lcrwmd_emb and every Z, D, R, workspace pointer
+ *     are DEVICE pointers on the context's device, unless a comment says "host".
+ *   - The caller owns every buffer.  The library allocates no device memory and frees
+ *     nothing it is given; temporary storage comes from the caller's workspace
+ *     (size from lcrwmd_workspace_bytes).  The workspace must be 256-byte aligned.
+ *   - Work is enqueued on the hipStream_t passed as `hip_stream` (NULL = the default
+ *     stream) and is asynchronous with respect to the host, except where a call's
+ *     comment lists a synchronisation.
+ *   - Every function returns an lcrwmd_status.  Argument errors are detected before
+ *     anything is launched.  The library never aborts, throws or prints; the text
+ *     for the last failure of a context is available from lcrwmd_last_error.
+ *   - A context is not thread safe; use one per host thread.  Calls on the same
+ *     stream may share a workspace; calls on different streams must not.
+ *   - Histograms: CSR with int64 row_ptr (row_ptr[0] == 0), int32 col_idx strictly
+ *     increasing inside a row and < cols, fp32 val > 0 summing to 1 per row
+ *     (Sec. II: L1-normalised histograms; Sec. III: rows of X store the weights of the
+ *     unique words).  Every row must hold at least one word: the minimum over an empty
+ *     word set is undefined.  The library does not renormalise weights.
+ */
+#ifndef LCRWMD_H
+#define LCRWMD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lcrwmd_ctx lcrwmd_ctx;   /* opaque */
+
+typedef enum {
+    LCRWMD_OK = 0,
+    LCRWMD_EINVAL = 1,        /* null pointer, negative size, bad leading dimension, bad option      */
+    LCRWMD_EBADCSR = 2,       /* validation on: row_ptr not monotone, column out of range/unsorted   */
+    LCRWMD_EEMPTYDOC = 3,     /* a histogram without words                                           */
+    LCRWMD_EWORKSPACE = 4,    /* workspace missing, misaligned or too small                          */
+    LCRWMD_EUNSUPPORTED = 5,  /* e.g. k larger than the supported maximum                            */
+    LCRWMD_EHIP = 6           /* a HIP runtime call failed; see lcrwmd_last_error                    */
+} lcrwmd_status;
+
+/* Storage type of embedding values.  Accumulation is always fp32. */
+typedef enum { LCRWMD_F32 = 0, LCRWMD_BF16 = 1 } lcrwmd_dtype;
+
+/* A set of histograms X (Sec. III, Fig. 2): one sparse row per document. */
+typedef struct {
+    int64_t rows, cols, nnz;        /* cols == v                                                     */
+    const int64_t* row_ptr;         /* device, [rows + 1]                                            */
+    const int32_t* col_idx;         /* device, [nnz]                                                 */
+    const float* val;               /* device, [nnz]                                                 */
+    const int64_t* row_ptr_host;    /* HOST copy of row_ptr, or NULL.  When NULL, calls that plan
+                                       batches from the row lengths (lcrwmd_rwmd, lcrwmd_rwmd_topk)
+                                       copy row_ptr back themselves, which synchronises the stream. */
+} lcrwmd_csr;
+
+/* The embedding matrix E (Sec. III): row w holds the m-vector of word w, row-major. */
+typedef struct {
+    const void* data;               /* device, v rows of m values, consecutive rows `ld` values apart */
+    int64_t v, m, ld;               /* ld >= m                                                       */
+    lcrwmd_dtype dtype;             /* LCRWMD_F32: float; LCRWMD_BF16: 16-bit bfloat16               */
+} lcrwmd_emb;
+
+typedef struct {
+    int validate;                   /* 1: check every CSR on the device before use (one extra stream
+                                       synchronisation per call); 0 (default): trust the caller       */
+    int compute;                    /* lcrwmd_dtype the first-phase contraction multiplies in.
+                                       LCRWMD_F32 (default for fp32 E): fp32 MFMA.  LCRWMD_BF16: E is
+                                       rounded to bf16 (round-to-nearest-even) unless already bf16,
+                                       products accumulate in fp32.  bf16 E always computes in bf16.  */
+    int64_t max_query_batch;        /* upper limit on histograms of X2 per pass (Sec. IV, many-to-many:
+                                       X2 is divided into batches); 0 = chosen from the workspace     */
+    int64_t max_db_batch;           /* same for the database rows handled per pass of the swapped
+                                       direction; 0 = chosen from the workspace                      */
+} lcrwmd_options;
+
+/* Create a context bound to HIP device `device`.  No device memory is allocated. */
+lcrwmd_status lcrwmd_create(lcrwmd_ctx** out, int device);
+void lcrwmd_destroy(lcrwmd_ctx* ctx);
+
+/* Text for the last non-OK status returned on this context (owned by the context; "" if none). */
+const char* lcrwmd_last_error(const lcrwmd_ctx* ctx);
+
+/* Copy the options in / out.  Defaults: validate 0, compute LCRWMD_F32, batches 0. */
+lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt);
+lcrwmd_status lcrwmd_get_options(const lcrwmd_ctx* ctx, lcrwmd_options* opt);
+
+/*
+ * Workspace, in bytes, that lets every entry point below run the given problem with its
+ * preferred batch sizes.  lcrwmd_rwmd and lcrwmd_rwmd_topk also run with less, in smaller
+ * batches, down to a floor below which they return LCRWMD_EWORKSPACE.
+ * nnz_db / nnz_q are the stored entries of X1 / X2; k = 0 when no top-k is wanted.
+ */
+lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db,
+                                     int64_t q, int64_t nnz_q, lcrwmd_dtype emb_dtype, int k,
+                                     size_t* out_bytes);
+
+/*
+ * First phase of LC-RWMD in its many-to-many form (Sec. IV, Fig. 6, and the paragraph
+ * "Many-to-many LC-RWMD"): for every vocabulary word w and every histogram j of `queries`
+ *
+ *     Z[w * ldz + j] = min over the words a of queries[j] of || E[w] - E[a] ||_2
+ *
+ * i.e. the row-wise minima of E o T2 taken separately for each j.  Z is v x queries->rows
+ * fp32, row-major, ldz >= queries->rows.  queries->val is not read.  The distance is
+ * evaluated as sqrt(max(|x|^2 + |y|^2 - 2 x.y, 0)) with the x.y contraction on the matrix
+ * cores, and is exactly 0 where w itself occurs in queries[j].
+ * No host synchronisation (unless validation is on).
+ */
+lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const lcrwmd_csr* queries,
+                                    float* Z, int64_t ldz, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Second phase (Sec. IV, Fig. 7): the sparse histogram matrix times the dense minima,
+ *
+ *     S[i][j] = sum over stored p of X[i] of  X.val[p] * Z[X.col_idx[p] * ldz + j],   j < ncols
+ *
+ * combine == 0:  D[i * ldd + j]  = S[i][j]                       (D is X->rows x ncols)
+ * combine == 1:  D[i * ldd + j]  = max(D[i * ldd + j], S[i][j])
+ * combine == 2:  D[j * ldd + i]  = max(D[j * ldd + i], S[i][j])  (D is ncols x X->rows: the
+ *                transposed maximum D = max(D1, D2^T) of Sec. IV, used after swapping the sets)
+ * Z is X->cols x ncols fp32 row-major.  Needs no workspace.  No host synchronisation.
+ */
+lcrwmd_status lcrwmd_phase2_spmm(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const float* Z, int64_t ldz,
+                                 int64_t ncols, float* D, int64_t ldd, int combine, void* hip_stream);
+
+/*
+ * The full bound (Sec. III "Solving the RWMD problem", Sec. IV): for database doc i and query j
+ *
+ *     D[i * ldd + j] = max( sum_p X1[i][p] * min_{a in X2[j]} ||E[p]-E[a]|| ,
+ *                           sum_a X2[j][a] * min_{p in X1[i]} ||E[p]-E[a]|| )
+ *
+ * D is n x q fp32 row-major (n = database->rows, q = queries->rows, ldd >= q).  Both directions
+ * run the two phases, the second one with the sets swapped; words that do not occur in the
+ * set that plays X1 are dropped from the vocabulary of that pass (Sec. IV, vocabulary
+ * reduction), queries are processed in batches and so are the database rows of the swapped
+ * pass.  Results do not depend on the batch sizes.
+ * Synchronises the stream to read back the two vocabulary sizes, which decide grids and batch
+ * sizes (and before that once more when it has to fetch the row pointers because no host
+ * copies were given); everything else is asynchronous.
+ */
+lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                          const lcrwmd_emb* E, float* D, int64_t ldd, void* ws, size_t ws_bytes,
+                          void* hip_stream);
+
+/*
+ * Top-k on the same bound (Sec. III: the k smallest distances of a query and the positions of
+ * the respective database histograms, stored in an n2 x k matrix R): for each query j,
+ * R_idx[j * k + r] / R_dist[j * k + r], r < k, are the database rows with the r-th smallest
+ * D[.][j] and those distances, ordered by (distance, row index) ascending.  D is formed one
+ * query batch at a time inside the workspace and never returned.  1 <= k <= min(n, 64).
+ * Same synchronisation as lcrwmd_rwmd, once per query batch.
+ */
+lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                               const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist,
+                               void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Top-k of an existing distance matrix: D is n x q fp32 row-major (ldd >= q); outputs as in
+ * lcrwmd_rwmd_topk.  The workspace is optional (ws may be NULL): with it the rows of D are
+ * split over more workgroups and the partial lists merged.  No host synchronisation.
+ */
+lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q, int64_t ldd, int k,
+                          int32_t* R_idx, float* R_dist, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks (not part of the method).  Between lcrwmd_profile_begin and
+ * lcrwmd_profile_end every launch of the first-phase contraction kernel and of the second-phase
+ * SpMM kernel made through this context is bracketed by HIP events on the stream it is launched
+ * on.  lcrwmd_profile_end synchronises the device, sums the event times and stops recording.
+ * Work figures are algorithmic: first-phase flops = 2 * vocabulary rows * stored tokens * m per
+ * launch (padding, norms and the epilogue earn nothing); second-phase bytes = the CSR arrays,
+ * the rows of Z and the output, each counted once per launch; gather bytes = 4 * stored
+ * entries * columns (what the lanes actually load from Z through the caches).
+ */
+typedef struct {
+    double phase1_ms;  int64_t phase1_launches;  double phase1_flops;
+    double phase2_ms;  int64_t phase2_launches;  double phase2_bytes;  double phase2_gather_bytes;
+} lcrwmd_profile;
+lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
+lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCRWMD_H */

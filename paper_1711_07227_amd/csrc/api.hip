@@ -1,0 +1,593 @@
+// C ABI of the LC-RWMD library: argument checks, workspace carving, batching and launch order.
+// All arithmetic is in the kernels of the other translation units.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "lcrwmd_internal.h"
+
+using namespace lcrwmd;
+
+namespace {
+
+lcrwmd_status fail(lcrwmd_ctx* ctx, lcrwmd_status st, const char* fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess)                                                                           \
+            return fail(ctx, LCRWMD_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));               \
+    } while (0)
+
+#define ST_TRY(expr)                          \
+    do {                                      \
+        lcrwmd_status s_ = (expr);            \
+        if (s_ != LCRWMD_OK) return s_;       \
+    } while (0)
+
+// Event bracket around one kernel launch while profiling is on.
+struct ProfScope {
+    lcrwmd_ctx* ctx;
+    hipStream_t s;
+    lcrwmd_prof_rec rec;
+    bool on;
+    ProfScope(lcrwmd_ctx* c, hipStream_t st, int kind, double work, double work2 = 0.0) : ctx(c), s(st), on(false)
+    {
+        if (!c->profiling) return;
+        rec.kind = kind;
+        rec.work = work;
+        rec.work2 = work2;
+        if (hipEventCreate(&rec.start) != hipSuccess) return;
+        if (hipEventCreate(&rec.stop) != hipSuccess) { (void)hipEventDestroy(rec.start); return; }
+        on = hipEventRecord(rec.start, s) == hipSuccess;
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, s);
+        ctx->prof.push_back(rec);
+    }
+};
+
+constexpr int64_t kMaxTokens = (int64_t)1 << 30;   // padded tokens per launch (int32 offsets)
+
+lcrwmd_status check_csr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, bool need_val)
+{
+    if (!X) return fail(ctx, LCRWMD_EINVAL, "%s is NULL", name);
+    if (X->rows < 0 || X->cols < 0 || X->nnz < 0) return fail(ctx, LCRWMD_EINVAL, "%s has a negative size", name);
+    if (!X->row_ptr) return fail(ctx, LCRWMD_EINVAL, "%s.row_ptr is NULL", name);
+    if (X->nnz > 0 && !X->col_idx) return fail(ctx, LCRWMD_EINVAL, "%s.col_idx is NULL", name);
+    if (need_val && X->nnz > 0 && !X->val) return fail(ctx, LCRWMD_EINVAL, "%s.val is NULL", name);
+    if (X->cols > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "%s.cols exceeds int32", name);
+    if (X->rows > 0 && X->nnz < X->rows)
+        return fail(ctx, LCRWMD_EEMPTYDOC, "%s stores fewer entries than rows: some histogram is empty", name);
+    return LCRWMD_OK;
+}
+
+lcrwmd_status check_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E)
+{
+    if (!E) return fail(ctx, LCRWMD_EINVAL, "E is NULL");
+    if (E->v <= 0 || E->m <= 0) return fail(ctx, LCRWMD_EINVAL, "E must have v > 0 and m > 0");
+    if (!E->data) return fail(ctx, LCRWMD_EINVAL, "E.data is NULL");
+    if (E->ld < E->m) return fail(ctx, LCRWMD_EINVAL, "E.ld < E.m");
+    if (E->dtype != LCRWMD_F32 && E->dtype != LCRWMD_BF16) return fail(ctx, LCRWMD_EINVAL, "unknown E.dtype");
+    if (E->v > 0x7fffffffLL || E->m > 65536) return fail(ctx, LCRWMD_EUNSUPPORTED, "E is too large (v < 2^31, m <= 65536)");
+    return LCRWMD_OK;
+}
+
+lcrwmd_status check_ws(lcrwmd_ctx* ctx, const void* ws, size_t ws_bytes)
+{
+    if (!ws || ws_bytes == 0) return fail(ctx, LCRWMD_EWORKSPACE, "a workspace is required");
+    if (((uintptr_t)ws & 255) != 0) return fail(ctx, LCRWMD_EWORKSPACE, "the workspace must be 256-byte aligned");
+    return LCRWMD_OK;
+}
+
+bool use_bf16(const lcrwmd_ctx* ctx, const lcrwmd_emb* E) { return E->dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16; }
+
+lcrwmd_status validate_on_device(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, int32_t* dev_status,
+                                 hipStream_t s)
+{
+    HIP_TRY(launch_fill_i32(dev_status, 1, 0, s));
+    HIP_TRY(launch_validate_csr(*X, dev_status, s));
+    int32_t h = 0;
+    HIP_TRY(hipMemcpyAsync(&h, dev_status, sizeof(h), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (h == LCRWMD_EEMPTYDOC) return fail(ctx, LCRWMD_EEMPTYDOC, "%s contains an empty histogram", name);
+    if (h != 0) return fail(ctx, LCRWMD_EBADCSR, "%s is not a valid CSR matrix (row_ptr, column order/range or weights)", name);
+    return LCRWMD_OK;
+}
+
+// Embedding operand prepared for the first phase: squared norms, and for bf16 the packed copy.
+struct EmbPrep {
+    const void* data;
+    int64_t ld;
+    float* normE;
+    bool bf16;
+};
+
+size_t emb_prep_bytes(int64_t v, int32_t m, bool bf16)
+{
+    return (size_t)v * 4 + 256 + (bf16 ? pack_bf16_bytes(v, m) + 256 : 0);
+}
+
+lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep& ep, hipStream_t s)
+{
+    ep.bf16 = use_bf16(ctx, E);
+    ep.normE = b.take_n<float>((size_t)E->v);
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the word norms");
+    if (ep.bf16) {
+        void* packed = b.take(pack_bf16_bytes(E->v, (int32_t)E->m));
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the bf16 copy of E");
+        HIP_TRY(launch_pack_bf16(E->data, E->dtype, E->v, (int32_t)E->m, E->ld, packed, ep.normE, s));
+        ep.data = packed;
+        ep.ld = bf16_pitch((int32_t)E->m);
+    } else {
+        HIP_TRY(launch_row_norms_f32((const float*)E->data, E->v, (int32_t)E->m, E->ld, ep.normE, s));
+        ep.data = E->data;
+        ep.ld = E->ld;
+    }
+    return LCRWMD_OK;
+}
+
+// One first-phase pass over histograms [r0, r0 + nseg) of a CSR whose row_ptr is `rp` (device).
+lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const int32_t* voc_rows, int64_t nvoc,
+                         int z_by_position, const int32_t* zero_map, const int64_t* rp_batch,
+                         const int32_t* col_idx, int64_t tokens, const TokenPlan& tp, float* Z, int64_t ldz,
+                         hipStream_t s)
+{
+    HIP_TRY(launch_token_plan(tp, rp_batch, col_idx, ep.normE, s));
+    Phase1Args a;
+    a.E = ep.data;
+    a.ld = ep.ld;
+    a.m = m;
+    a.normE = ep.normE;
+    a.voc_rows = voc_rows;
+    a.nvoc = nvoc;
+    a.z_by_position = z_by_position;
+    a.Z = Z;
+    a.ldz = ldz;
+    {
+        ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m);
+        if (ep.bf16) HIP_TRY(launch_phase1_bf16(a, tp, s));
+        else HIP_TRY(launch_phase1_f32(a, tp, s));
+    }
+    // a word that occurs in the histogram is at distance exactly 0 from it; the norm expansion
+    // only gets there up to cancellation error
+    HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
+    return LCRWMD_OK;
+}
+
+// Second-phase launch with its algorithmic traffic: CSR arrays, `zrows` rows of Z, and the output once
+// (twice when it is read back for a maximum).
+lcrwmd_status run_spmm(lcrwmd_ctx* ctx, const int64_t* rp, const int32_t* ci, const float* xv, int64_t rows,
+                       int64_t nnz, int64_t zrows, const float* Z, int64_t ldz, int64_t ncols, float* D, int64_t ldd,
+                       int combine, hipStream_t s)
+{
+    const double bytes = 8.0 * (double)nnz + 8.0 * (double)(rows + 1) + 4.0 * (double)ncols * (double)zrows +
+                         (combine ? 8.0 : 4.0) * (double)ncols * (double)rows;
+    ProfScope ps(ctx, s, 2, bytes, 4.0 * (double)nnz * (double)ncols);
+    HIP_TRY(launch_spmm(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, combine, s));
+    return LCRWMD_OK;
+}
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
+size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, bool bf16)
+{
+    size_t b = emb_prep_bytes(v, m, bf16);
+    b += 3 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position map of the queries
+    b += (size_t)(v < nnz_q ? v : nnz_q) * 4 + 256;   // word list of the queries
+    b += (size_t)nnz_q * 4 + 256;             // query columns renumbered to positions
+    b += 1024;                                // counters
+    return b;
+}
+
+size_t fwd_batch_bytes(int64_t v, int64_t qb, int64_t tokens)
+{
+    return token_plan_bytes(qb, tokens) + (size_t)v * (size_t)round_up(qb, 4) * 4 + 256;
+}
+
+size_t rev_batch_bytes(int64_t vq, int64_t nb, int64_t tokens)
+{
+    return token_plan_bytes(nb, tokens) + (size_t)vq * (size_t)round_up(nb, 4) * 4 + 256;
+}
+
+struct HostPtr {   // host copy of a row_ptr array, borrowed or owned
+    const int64_t* p = nullptr;
+    std::vector<int64_t> own;
+};
+
+lcrwmd_status host_row_ptr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, HostPtr& out, hipStream_t s)
+{
+    if (X->row_ptr_host) { out.p = X->row_ptr_host; return LCRWMD_OK; }
+    try {
+        out.own.resize((size_t)X->rows + 1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, LCRWMD_EINVAL, "out of host memory for a row_ptr copy");
+    }
+    HIP_TRY(hipMemcpyAsync(out.own.data(), X->row_ptr, sizeof(int64_t) * ((size_t)X->rows + 1),
+                           hipMemcpyDeviceToHost, s));
+    out.p = out.own.data();
+    return LCRWMD_OK;
+}
+
+int64_t max_tokens_per_batch(const int64_t* rp, int64_t rows, int64_t batch)
+{
+    int64_t mx = 0;
+    for (int64_t a = 0; a < rows; a += batch) {
+        int64_t b = a + batch < rows ? a + batch : rows;
+        if (rp[b] - rp[a] > mx) mx = rp[b] - rp[a];
+    }
+    return mx;
+}
+
+// The whole bound for the query rows [jq0, jq1) of Q against the database, into D (n x (jq1 - jq0), ldd).
+// rq / rdb are host copies of the two row_ptr arrays.
+lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq, int64_t jq0, int64_t jq1,
+                        const lcrwmd_csr* DB, const int64_t* rdb, const lcrwmd_emb* E, float* D, int64_t ldd,
+                        void* ws, size_t ws_bytes, hipStream_t s)
+{
+    const int64_t v = E->v, n = DB->rows, q = jq1 - jq0;
+    const int64_t qoff = rq[jq0], nnz_q = rq[jq1] - rq[jq0];
+    const int32_t m = (int32_t)E->m;
+    Bump b(ws, ws_bytes);
+
+    int32_t* counters = b.take_n<int32_t>(64);
+    EmbPrep ep;
+    ST_TRY(prepare_emb(ctx, E, b, ep, s));
+
+    // Vocabulary reduction (Sec. IV): the forward pass needs only the words of the database, the
+    // swapped pass only the words of the queries.
+    int32_t* flags = b.take_n<int32_t>((size_t)v);
+    int32_t* list_db = b.take_n<int32_t>((size_t)v);
+    int32_t* map_q = b.take_n<int32_t>((size_t)v);
+    int32_t* list_q = b.take_n<int32_t>((size_t)(v < nnz_q ? v : nnz_q));
+    int32_t* qcol_pos = b.take_n<int32_t>((size_t)nnz_q);
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the vocabulary maps");
+
+    HIP_TRY(launch_fill_i32(flags, v, 0, s));
+    HIP_TRY(launch_mark_words(DB->col_idx, DB->nnz, flags, s));
+    HIP_TRY(launch_compact_words(flags, v, list_db, nullptr, counters + 0, s));
+    HIP_TRY(launch_fill_i32(flags, v, 0, s));
+    HIP_TRY(launch_mark_words(Q->col_idx + qoff, nnz_q, flags, s));
+    HIP_TRY(launch_compact_words(flags, v, list_q, map_q, counters + 1, s));
+    HIP_TRY(launch_remap_cols(Q->col_idx + qoff, nnz_q, map_q, qcol_pos, s));
+
+    int32_t hc[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(hc, counters, sizeof(hc), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));          // the vocabulary sizes decide grids and batch sizes
+    const int64_t ve = hc[0], vq = hc[1];
+
+    const size_t region_off = (b.used + 255) & ~(size_t)255;
+    if (region_off >= b.size) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+    const size_t region = b.size - region_off;
+
+    // ---- forward: cost of moving database docs onto the queries, D1 = X1 * Z ----
+    int64_t qb = q;
+    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+    for (;;) {
+        int64_t tok = max_tokens_per_batch(rq + jq0, q, qb);
+        if (tok + 7 * qb < kMaxTokens && fwd_batch_bytes(v, qb, tok) <= region) break;
+        if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one query (forward pass)");
+        qb = (qb + 1) / 2;
+    }
+    const int64_t nvt_f = (ve + kTileVocab - 1) / kTileVocab;
+    for (int64_t j0 = jq0; j0 < jq1; j0 += qb) {
+        const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
+        Bump bb(b.base + region_off, region);
+        TokenPlan tp;
+        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], nvt_f);
+        const int64_t ldz = round_up(j1 - j0, 4);
+        float* Z = bb.take_n<float>((size_t)v * ldz);
+        if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
+        ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/0, /*zero_map=*/nullptr, Q->row_ptr + j0,
+                          Q->col_idx, rq[j1] - rq[j0], tp, Z, ldz, s));
+        ST_TRY(run_spmm(ctx, DB->row_ptr, DB->col_idx, DB->val, n, DB->nnz, ve, Z, ldz, j1 - j0, D + (j0 - jq0), ldd, 0, s));
+    }
+
+    // ---- swapped: cost of moving the queries onto database docs, D = max(D1, (X2 * Z')^T) ----
+    int64_t nb = n < 16384 ? n : 16384;
+    if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
+    for (;;) {
+        int64_t tok = max_tokens_per_batch(rdb, n, nb);
+        if (tok + 7 * nb < kMaxTokens && rev_batch_bytes(vq, nb, tok) <= region) break;
+        if (nb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one database row (swapped pass)");
+        nb = (nb + 1) / 2;
+    }
+    const int64_t nvt_r = (vq + kTileVocab - 1) / kTileVocab;
+    for (int64_t i0 = 0; i0 < n; i0 += nb) {
+        const int64_t i1 = i0 + nb < n ? i0 + nb : n;
+        Bump bb(b.base + region_off, region);
+        TokenPlan tp;
+        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], nvt_r);
+        const int64_t ldz = round_up(i1 - i0, 4);
+        float* Z = bb.take_n<float>((size_t)vq * ldz);
+        if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");
+        ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
+                          DB->col_idx, rdb[i1] - rdb[i0], tp, Z, ldz, s));
+        // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
+        ST_TRY(run_spmm(ctx, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, nnz_q, vq, Z, ldz, i1 - i0, D + i0 * ldd, ldd, 2, s));
+    }
+    return LCRWMD_OK;
+}
+
+// Host row pointers of both sets (one synchronisation when a copy has to be fetched) and optional validation.
+lcrwmd_status fetch_rows_and_validate(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_csr* DB, HostPtr& rq,
+                                      HostPtr& rdb, void* ws, size_t ws_bytes, hipStream_t s)
+{
+    if (ctx->opt.validate) {
+        Bump b(ws, ws_bytes);
+        int32_t* st = b.take_n<int32_t>(64);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+        ST_TRY(validate_on_device(ctx, Q, "queries", st, s));
+        ST_TRY(validate_on_device(ctx, DB, "database", st, s));
+    }
+    ST_TRY(host_row_ptr(ctx, Q, rq, s));
+    ST_TRY(host_row_ptr(ctx, DB, rdb, s));
+    if (!Q->row_ptr_host || !DB->row_ptr_host) HIP_TRY(hipStreamSynchronize(s));
+    if (rq.p[0] != 0 || rq.p[Q->rows] != Q->nnz || rdb.p[0] != 0 || rdb.p[DB->rows] != DB->nnz)
+        return fail(ctx, LCRWMD_EBADCSR, "row_ptr does not span [0, nnz]");
+    for (int64_t r = 0; r < Q->rows; ++r)
+        if (rq.p[r + 1] <= rq.p[r]) return fail(ctx, LCRWMD_EEMPTYDOC, "queries row %lld is empty or row_ptr decreases", (long long)r);
+    for (int64_t r = 0; r < DB->rows; ++r)
+        if (rdb.p[r + 1] <= rdb.p[r]) return fail(ctx, LCRWMD_EEMPTYDOC, "database row %lld is empty or row_ptr decreases", (long long)r);
+    return LCRWMD_OK;
+}
+
+lcrwmd_status check_rwmd_args(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_csr* DB, const lcrwmd_emb* E)
+{
+    ST_TRY(check_emb(ctx, E));
+    ST_TRY(check_csr(ctx, Q, "queries", true));
+    ST_TRY(check_csr(ctx, DB, "database", true));
+    if (Q->cols != E->v || DB->cols != E->v) return fail(ctx, LCRWMD_EINVAL, "histogram columns must equal E.v");
+    return LCRWMD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+lcrwmd_status lcrwmd_create(lcrwmd_ctx** out, int device)
+{
+    if (!out) return LCRWMD_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return LCRWMD_EHIP;
+    lcrwmd_ctx* c = new (std::nothrow) lcrwmd_ctx();
+    if (!c) return LCRWMD_EINVAL;
+    c->err[0] = 0;
+    c->profiling = false;
+    c->opt = lcrwmd_options{0, LCRWMD_F32, 0, 0};
+    c->device = device;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
+    c->num_cu = prop.multiProcessorCount;
+    c->opt.validate = 0;
+    c->opt.compute = LCRWMD_F32;
+    *out = c;
+    return LCRWMD_OK;
+}
+
+void lcrwmd_destroy(lcrwmd_ctx* ctx)
+{
+    if (!ctx) return;
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    delete ctx;
+}
+
+lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    ctx->prof.clear();
+    ctx->profiling = true;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!out) return fail(ctx, LCRWMD_EINVAL, "out is NULL");
+    ctx->profiling = false;
+    memset(out, 0, sizeof(*out));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HIP_TRY(hipDeviceSynchronize());
+    for (auto& r : ctx->prof) {
+        float ms = 0.f;
+        hipError_t e = hipEventElapsedTime(&ms, r.start, r.stop);
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+        if (e != hipSuccess) continue;
+        if (r.kind == 1) { out->phase1_ms += ms; out->phase1_launches += 1; out->phase1_flops += r.work; }
+        else { out->phase2_ms += ms; out->phase2_launches += 1; out->phase2_bytes += r.work; out->phase2_gather_bytes += r.work2; }
+    }
+    ctx->prof.clear();
+    return LCRWMD_OK;
+}
+
+const char* lcrwmd_last_error(const lcrwmd_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!opt) return fail(ctx, LCRWMD_EINVAL, "options are NULL");
+    if ((opt->validate != 0 && opt->validate != 1) || (opt->compute != LCRWMD_F32 && opt->compute != LCRWMD_BF16) ||
+        opt->max_query_batch < 0 || opt->max_db_batch < 0)
+        return fail(ctx, LCRWMD_EINVAL, "option out of range");
+    ctx->opt = *opt;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_get_options(const lcrwmd_ctx* ctx, lcrwmd_options* opt)
+{
+    if (!ctx || !opt) return LCRWMD_EINVAL;
+    *opt = ctx->opt;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db, int64_t q,
+                                     int64_t nnz_q, lcrwmd_dtype emb_dtype, int k, size_t* out_bytes)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
+    if (v <= 0 || m <= 0 || n < 0 || nnz_db < 0 || q < 0 || nnz_q < 0 || k < 0)
+        return fail(ctx, LCRWMD_EINVAL, "negative size");
+    const bool bf16 = emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16;
+    int64_t qb = q;
+    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+    if (k > 0 && qb > 2048) qb = 2048;
+    int64_t nb = n < 16384 ? n : 16384;
+    if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
+    const int64_t vq = v < nnz_q ? v : nnz_q;
+    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, bf16);
+    size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
+    size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
+    size_t total = fixed + (f > r ? f : r) + 4096;
+    if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
+    // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
+    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
+    *out_bytes = total > p1 ? total : p1;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const lcrwmd_csr* queries, float* Z,
+                                    int64_t ldz, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_emb(ctx, E));
+    ST_TRY(check_csr(ctx, queries, "queries", false));
+    if (queries->cols != E->v) return fail(ctx, LCRWMD_EINVAL, "queries.cols must equal E.v");
+    if (!Z) return fail(ctx, LCRWMD_EINVAL, "Z is NULL");
+    if (ldz < queries->rows) return fail(ctx, LCRWMD_EINVAL, "ldz < queries.rows");
+    if (queries->rows == 0) return LCRWMD_OK;
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    if (queries->nnz + 7 * queries->rows >= kMaxTokens)
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "too many tokens for one pass; split the queries");
+    HIP_TRY(hipSetDevice(ctx->device));
+    Bump b(ws, ws_bytes);
+    if (ctx->opt.validate) {
+        int32_t* st = b.take_n<int32_t>(64);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+        lcrwmd_csr tmp = *queries;
+        tmp.val = nullptr;
+        ST_TRY(validate_on_device(ctx, &tmp, "queries", st, s));
+    }
+    EmbPrep ep;
+    ST_TRY(prepare_emb(ctx, E, b, ep, s));
+    TokenPlan tp;
+    carve_token_plan(b, tp, queries->rows, queries->nnz, (E->v + kTileVocab - 1) / kTileVocab);
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
+                           emb_prep_bytes(E->v, (int32_t)E->m, ep.bf16) + token_plan_bytes(queries->rows, queries->nnz));
+    return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,
+                      queries->nnz, tp, Z, ldz, s);
+}
+
+lcrwmd_status lcrwmd_phase2_spmm(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const float* Z, int64_t ldz, int64_t ncols,
+                                 float* D, int64_t ldd, int combine, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_csr(ctx, X, "X", true));
+    if (ncols < 0) return fail(ctx, LCRWMD_EINVAL, "ncols < 0");
+    if (combine < 0 || combine > 2) return fail(ctx, LCRWMD_EINVAL, "combine must be 0, 1 or 2");
+    if (X->rows == 0 || ncols == 0) return LCRWMD_OK;
+    if (!Z || !D) return fail(ctx, LCRWMD_EINVAL, "Z or D is NULL");
+    if (ldz < ncols) return fail(ctx, LCRWMD_EINVAL, "ldz < ncols");
+    if (ldd < (combine == 2 ? X->rows : ncols)) return fail(ctx, LCRWMD_EINVAL, "ldd smaller than a row of D");
+    HIP_TRY(hipSetDevice(ctx->device));
+    return run_spmm(ctx, X->row_ptr, X->col_idx, X->val, X->rows, X->nnz, X->cols, Z, ldz, ncols, D, ldd, combine, s);
+}
+
+lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                          const lcrwmd_emb* E, float* D, int64_t ldd, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    if (queries->rows == 0 || database->rows == 0) return LCRWMD_OK;
+    if (!D) return fail(ctx, LCRWMD_EINVAL, "D is NULL");
+    if (ldd < queries->rows) return fail(ctx, LCRWMD_EINVAL, "ldd < queries.rows");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HostPtr rq, rdb;
+    ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    return rwmd_core(ctx, queries, rq.p, 0, queries->rows, database, rdb.p, E, D, ldd, ws, ws_bytes, s);
+}
+
+lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx,
+                          float* R_dist, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n < 0 || q < 0) return fail(ctx, LCRWMD_EINVAL, "negative size");
+    if (q == 0) return LCRWMD_OK;
+    if (!D || !R_idx || !R_dist) return fail(ctx, LCRWMD_EINVAL, "D, R_idx or R_dist is NULL");
+    if (ldd < q) return fail(ctx, LCRWMD_EINVAL, "ldd < q");
+    if (k < 1 || k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    if (n > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "n exceeds int32 row indices");
+    if (ws && ((uintptr_t)ws & 255) != 0) return fail(ctx, LCRWMD_EWORKSPACE, "the workspace must be 256-byte aligned");
+    HIP_TRY(hipSetDevice(ctx->device));
+    HIP_TRY(launch_topk(D, n, q, ldd, k, R_idx, R_dist, ws, ws ? ws_bytes : 0, s));
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                               const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist, void* ws, size_t ws_bytes,
+                               void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    const int64_t n = database->rows, q = queries->rows;
+    if (q == 0) return LCRWMD_OK;
+    if (!R_idx || !R_dist) return fail(ctx, LCRWMD_EINVAL, "R_idx or R_dist is NULL");
+    if (k < 1 || k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+
+    // Query batches: the n x qb tile of D lives at the front of the workspace, the rest serves the bound.
+    HostPtr rq, rdb;
+    ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    int64_t qb = q < 2048 ? q : 2048;
+    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+    const bool bf16 = use_bf16(ctx, E);
+    for (;;) {
+        size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
+        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, bf16) +
+                      fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
+        if (need <= ws_bytes) break;
+        if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query tile of D");
+        qb = (qb + 1) / 2;
+    }
+    for (int64_t j0 = 0; j0 < q; j0 += qb) {
+        const int64_t j1 = j0 + qb < q ? j0 + qb : q;
+        Bump b(ws, ws_bytes);
+        const int64_t ldt = round_up(j1 - j0, 4);
+        float* tile = b.take_n<float>((size_t)n * ldt);
+        const size_t tkb = topk_bytes(n, j1 - j0, k) + 512;
+        void* tk = b.take(tkb);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: top-k tile does not fit");
+        const size_t off = (b.used + 255) & ~(size_t)255;
+        ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, (char*)ws + off, ws_bytes - off, s));
+        HIP_TRY(launch_topk(tile, n, j1 - j0, ldt, k, R_idx + j0 * k, R_dist + j0 * k, tk, tkb, s));
+    }
+    return LCRWMD_OK;
+}
+
+}  // extern "C"

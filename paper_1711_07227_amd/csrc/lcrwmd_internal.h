@@ -1,0 +1,125 @@
+// Internal declarations shared by the translation units of the LC-RWMD library.
+// Host-side launch wrappers live next to their kernels; api.hip only orchestrates.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/lcrwmd.h"
+
+struct lcrwmd_prof_rec {
+    hipEvent_t start, stop;
+    int kind;              // 1: first-phase kernel, 2: second-phase kernel
+    double work, work2;
+};
+
+struct lcrwmd_ctx {
+    int device;
+    int num_cu;
+    lcrwmd_options opt;
+    char err[512];
+    bool profiling;
+    std::vector<lcrwmd_prof_rec> prof;
+};
+
+namespace lcrwmd {
+
+// ---------------------------------------------------------------------------------------------
+// Padded token list of a batch of histograms (the stacked T matrix of Sec. IV, many-to-many
+// form, kept as word ids instead of gathered vectors).  Every histogram ("segment") is padded to
+// a multiple of 8 tokens by repeating its last word, which leaves every minimum unchanged and
+// makes each group of 8 consecutive tokens belong to exactly one segment.
+// ---------------------------------------------------------------------------------------------
+constexpr int kGroup = 8;          // tokens per group; the 32x32 MFMA accumulator holds 8-row groups
+constexpr int kTileTokens = 128;   // token rows per tile of the first-phase kernel
+constexpr int kTileVocab = 128;    // vocabulary columns per workgroup of the first-phase kernel
+
+struct TokenPlan {
+    // sizes known on the host
+    int64_t nseg;          // histograms in the batch
+    int64_t tok_bound;     // upper bound on padded tokens: stored entries + 7 per histogram
+    int64_t tok_alloc;     // allocated padded tokens (bound rounded up to a tile, plus one tile)
+    int32_t chunk_tokens;  // target padded tokens per chunk (multiple of kTileTokens)
+    int32_t nchunks;       // upper bound on chunks
+    // device arrays (carved from the workspace)
+    int32_t* pofs;         // [nseg + 1] padded token offset of each segment
+    int32_t* tok_ids;      // [tok_alloc] word id per padded token (0 beyond the end)
+    float* tok_hn;         // [tok_alloc] -0.5 * |E[word]|^2 per padded token
+    int32_t* grp_seg;      // [tok_alloc / 8] segment of each group, -1 beyond the end
+    int32_t* chunk_seg;    // [nchunks + 1] first segment of each chunk
+};
+
+size_t token_plan_bytes(int64_t nseg, int64_t nnz_batch);
+
+struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
+    char* base;
+    size_t size, used;
+    bool ok;
+    Bump(void* p, size_t n) : base((char*)p), size(n), used(0), ok(true) {}
+    void* take(size_t bytes)
+    {
+        size_t a = (used + 255) & ~(size_t)255;
+        if (!ok || a + bytes > size) { ok = false; return nullptr; }
+        used = a + bytes;
+        return base + a;
+    }
+    template <class T> T* take_n(size_t count) { return (T*)take(count * sizeof(T)); }
+};
+
+bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles);
+
+// Operand description of one first-phase launch.
+struct Phase1Args {
+    const void* E;            // fp32: caller's E.  bf16: packed copy made by pack_bf16
+    int64_t ld;               // row pitch of E in elements
+    int32_t m;                // embedding dimension
+    const float* normE;       // [v] squared norms by word id
+    const int32_t* voc_rows;  // word ids that form the vocabulary of this pass, or nullptr = 0..nvoc-1
+    int64_t nvoc;
+    int z_by_position;        // 1: Z row = position in voc_rows; 0: Z row = word id
+    float* Z;
+    int64_t ldz;
+};
+
+// prep.hip
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s);
+hipError_t launch_row_norms_f32(const float* E, int64_t v, int32_t m, int64_t ld, float* normE, hipStream_t s);
+hipError_t launch_mark_words(const int32_t* col_idx, int64_t nnz, int32_t* flags, hipStream_t s);
+// list[pos] = w and map[w] = pos for flagged words (map[w] = -1 otherwise); *count = number flagged
+hipError_t launch_compact_words(const int32_t* flags, int64_t v, int32_t* list, int32_t* map, int32_t* count,
+                                hipStream_t s);
+hipError_t launch_remap_cols(const int32_t* col_idx, int64_t nnz, const int32_t* map, int32_t* out, hipStream_t s);
+hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, const int32_t* col_idx,
+                             const float* normE, hipStream_t s);
+// Z[row(word) * ldz + seg] = 0 for every stored (seg, word) of the batch; row() through map when given
+hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg,
+                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s);
+// status[0] = 0 ok, 2 bad csr, 3 empty doc (values of lcrwmd_status)
+hipError_t launch_validate_csr(const lcrwmd_csr& X, int32_t* status, hipStream_t s);
+
+// phase1_f32.hip
+hipError_t launch_phase1_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+
+// phase1_bf16.hip
+constexpr int kBf16Pitch = 320;   // elements per packed bf16 row: 300 values padded for 16-wide K steps
+size_t pack_bf16_bytes(int64_t v, int32_t m);
+int32_t bf16_pitch(int32_t m);
+hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_t m, int64_t ld, void* packed,
+                            float* normE, hipStream_t s);
+hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+
+// phase2.hip
+hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,
+                       const float* Z, int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine,
+                       hipStream_t s);
+
+// topk.hip
+constexpr int kMaxTopK = 64;
+size_t topk_bytes(int64_t n, int64_t q, int k);
+hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
+                       void* ws, size_t ws_bytes, hipStream_t s);
+
+}  // namespace lcrwmd

@@ -1,0 +1,164 @@
+// Second phase of LC-RWMD (Sec. IV, Fig. 7): S = X * Z with X the CSR histogram matrix and Z the dense
+// matrix of per-word minima, one column per histogram of the other set (many-to-many form).
+// Every stored entry (i, p) gathers row p of Z and scales it by the weight, so the work is one fused
+// multiply-add per 4-byte load: bandwidth bound.  Lanes run along the columns of Z, so every gather is a
+// contiguous row segment; the column and weight of an entry are wave-uniform.
+//
+// Three write-backs: plain store (D1 of Sec. IV), maximum with what is already in D, and the transposed
+// maximum D = max(D1, D2^T) used after the two sets have been swapped.
+#include "lcrwmd_internal.h"
+
+namespace lcrwmd {
+
+namespace {
+
+// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers.
+template <int W, int COMBINE>
+__global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                                                   const float* __restrict__ xv, int64_t rows,
+                                                   const float* __restrict__ Z, int64_t ldz, int64_t ncols,
+                                                   float* __restrict__ D, int64_t ldd, int64_t strips)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    // strips vary fastest: neighbouring wavefronts read the same CSR row and adjacent pieces of Z rows
+    const int64_t i = unit / strips;
+    const int64_t strip = unit - i * strips;
+    if (i >= rows) return;
+    const int64_t j = strip * (64 * W) + (int64_t)lane * W;
+    const int64_t a = rp[i], b = rp[i + 1];
+    float acc[W];
+#pragma unroll
+    for (int t = 0; t < W; ++t) acc[t] = 0.f;
+
+    if (W == 4) {
+        const bool full = j + 3 < ncols;
+        int64_t p = a;
+        for (; p + 1 < b; p += 2) {     // two gathers in flight per lane
+            const int32_t c0 = ci[p], c1 = ci[p + 1];
+            const float x0 = xv[p], x1 = xv[p + 1];
+            if (full) {
+                const float4 z0 = *reinterpret_cast<const float4*>(Z + (int64_t)c0 * ldz + j);
+                const float4 z1 = *reinterpret_cast<const float4*>(Z + (int64_t)c1 * ldz + j);
+                acc[0] = fmaf(x0, z0.x, acc[0]); acc[1] = fmaf(x0, z0.y, acc[1]);
+                acc[2] = fmaf(x0, z0.z, acc[2]); acc[3] = fmaf(x0, z0.w, acc[3]);
+                acc[0] = fmaf(x1, z1.x, acc[0]); acc[1] = fmaf(x1, z1.y, acc[1]);
+                acc[2] = fmaf(x1, z1.z, acc[2]); acc[3] = fmaf(x1, z1.w, acc[3]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (j + t < ncols) {
+                        acc[t] = fmaf(x0, Z[(int64_t)c0 * ldz + j + t], acc[t]);
+                        acc[t] = fmaf(x1, Z[(int64_t)c1 * ldz + j + t], acc[t]);
+                    }
+            }
+        }
+        if (p < b) {
+            const int32_t c0 = ci[p];
+            const float x0 = xv[p];
+            if (full) {
+                const float4 z0 = *reinterpret_cast<const float4*>(Z + (int64_t)c0 * ldz + j);
+                acc[0] = fmaf(x0, z0.x, acc[0]); acc[1] = fmaf(x0, z0.y, acc[1]);
+                acc[2] = fmaf(x0, z0.z, acc[2]); acc[3] = fmaf(x0, z0.w, acc[3]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (j + t < ncols) acc[t] = fmaf(x0, Z[(int64_t)c0 * ldz + j + t], acc[t]);
+            }
+        }
+    } else {
+        if (j < ncols)
+            for (int64_t p = a; p < b; ++p) acc[0] = fmaf(xv[p], Z[(int64_t)ci[p] * ldz + j], acc[0]);
+    }
+
+#pragma unroll
+    for (int t = 0; t < W; ++t) {
+        if (j + t < ncols) {
+            float* d = D + i * ldd + j + t;
+            if (COMBINE == 0) *d = acc[t];
+            else *d = fmaxf(*d, acc[t]);
+        }
+    }
+}
+
+// Transposed maximum: X has `rows` histograms (the queries after the swap), Z has ncols columns (the
+// database rows of the current batch); D[c * ldd + r] = max(D[c * ldd + r], S[r][c]).
+// A workgroup computes a 32 (rows of X) x 64 (columns) tile of S with lanes along the columns, then
+// turns it through LDS so that the read-modify-write of D is along D's rows.
+constexpr int TR = 32, TC = 64;
+
+__global__ __launch_bounds__(256) void k_spmm_tmax(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                                                   const float* __restrict__ xv, int64_t rows,
+                                                   const float* __restrict__ Z, int64_t ldz, int64_t ncols,
+                                                   float* __restrict__ D, int64_t ldd, int64_t row_tiles)
+{
+    __shared__ float tile[TR][TC + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // row tiles vary fastest: the workgroups that share a strip of Z columns run together
+    const int64_t ct = blockIdx.x / row_tiles;
+    const int64_t rt = blockIdx.x - ct * row_tiles;
+    const int64_t r0 = rt * TR, c0 = ct * TC;
+    const int64_t c = c0 + lane;
+    const bool c_ok = c < ncols;
+    const int64_t cc = c_ok ? c : ncols - 1;
+
+    for (int k = 0; k < TR / 4; ++k) {
+        const int rr = wave * (TR / 4) + k;
+        const int64_t r = r0 + rr;
+        float acc = 0.f;
+        if (r < rows) {
+            const int64_t a = rp[r], b = rp[r + 1];
+            int64_t p = a;
+            for (; p + 3 < b; p += 4) {
+                const float z0 = Z[(int64_t)ci[p] * ldz + cc], z1 = Z[(int64_t)ci[p + 1] * ldz + cc];
+                const float z2 = Z[(int64_t)ci[p + 2] * ldz + cc], z3 = Z[(int64_t)ci[p + 3] * ldz + cc];
+                acc = fmaf(xv[p], z0, acc);
+                acc = fmaf(xv[p + 1], z1, acc);
+                acc = fmaf(xv[p + 2], z2, acc);
+                acc = fmaf(xv[p + 3], z3, acc);
+            }
+            for (; p < b; ++p) acc = fmaf(xv[p], Z[(int64_t)ci[p] * ldz + cc], acc);
+        }
+        tile[rr][lane] = acc;
+    }
+    __syncthreads();
+    // thread -> (column of the tile = row of D, 32 consecutive entries of that row)
+    const int tr = threadIdx.x & (TR - 1);
+    for (int tc = threadIdx.x / TR; tc < TC; tc += 256 / TR) {
+        const int64_t dr = c0 + tc, dc = r0 + tr;
+        if (dr < ncols && dc < rows) {
+            float* d = D + dr * ldd + dc;
+            *d = fmaxf(*d, tile[tr][tc]);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, int64_t rows, const float* Z,
+                       int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine, hipStream_t s)
+{
+    if (rows <= 0 || ncols <= 0) return hipSuccess;
+    if (combine == 2) {
+        const int64_t row_tiles = (rows + TR - 1) / TR, col_tiles = (ncols + TC - 1) / TC;
+        const int64_t grid = row_tiles * col_tiles;
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        k_spmm_tmax<<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, row_tiles);
+        return hipGetLastError();
+    }
+    const bool vec = (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 64;
+    const int W = vec ? 4 : 1;
+    const int64_t strips = (ncols + 64 * W - 1) / (64 * W);
+    const int64_t grid = (rows * strips + 3) / 4;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (vec) {
+        if (combine == 0) k_spmm_rows<4, 0><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
+        else k_spmm_rows<4, 1><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
+    } else {
+        if (combine == 0) k_spmm_rows<1, 0><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
+        else k_spmm_rows<1, 1><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lcrwmd

@@ -1,0 +1,315 @@
+// Support kernels of the LC-RWMD path: squared row norms of E, vocabulary reduction
+// (Sec. IV: words that do not occur in the resident set are dropped), the padded token list
+// of a batch of histograms (the stacked T matrix of the many-to-many form, kept as word ids),
+// the exact-zero fix-up for words that occur in the histogram itself, and CSR validation.
+#include "lcrwmd_internal.h"
+
+namespace lcrwmd {
+
+namespace {
+
+constexpr int kScanThreads = 1024;
+
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t value)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = value;
+}
+
+// One wavefront per row: normE[w] = sum_t E[w][t]^2 in fp32.
+__global__ __launch_bounds__(256) void k_row_norms_f32(const float* __restrict__ E, int64_t v, int32_t m,
+                                                       int64_t ld, float* __restrict__ normE)
+{
+    const int lane = threadIdx.x & 63;
+    int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= v) return;
+    const float* row = E + w * ld;
+    float s = 0.f;
+    for (int t = lane; t < m; t += 64) { float x = row[t]; s = fmaf(x, x, s); }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) normE[w] = s;
+}
+
+__global__ void k_mark_words(const int32_t* __restrict__ col_idx, int64_t nnz, int32_t* __restrict__ flags)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < nnz; i += stride) flags[col_idx[i]] = 1;   // benign race: every writer stores 1
+}
+
+// Exclusive block scan helper: returns the exclusive prefix of x over the block and the block total.
+__device__ inline int32_t block_exclusive_scan(int32_t x, int32_t* wave_sums, int32_t& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t incl = x;
+    for (int o = 1; o < 64; o <<= 1) {
+        int32_t y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t run = 0;
+        for (int k = 0; k < kScanThreads / 64; ++k) { int32_t t = wave_sums[k]; wave_sums[k] = run; run += t; }
+        wave_sums[kScanThreads / 64] = run;
+    }
+    __syncthreads();
+    int32_t excl = wave_sums[wave] + incl - x;
+    total = wave_sums[kScanThreads / 64];
+    __syncthreads();   // wave_sums is reused by the next strip
+    return excl;
+}
+
+// Single workgroup: stream compaction of the flagged words, in increasing word id.
+__global__ __launch_bounds__(kScanThreads) void k_compact_words(const int32_t* __restrict__ flags, int64_t v,
+                                                                int32_t* __restrict__ list,
+                                                                int32_t* __restrict__ map,
+                                                                int32_t* __restrict__ count)
+{
+    __shared__ int32_t wave_sums[kScanThreads / 64 + 1];
+    int32_t carry = 0;
+    for (int64_t base = 0; base < v; base += kScanThreads) {
+        int64_t w = base + threadIdx.x;
+        int32_t f = (w < v && flags[w] != 0) ? 1 : 0;
+        int32_t total;
+        int32_t pos = carry + block_exclusive_scan(f, wave_sums, total);
+        if (w < v) {
+            if (f) list[pos] = (int32_t)w;
+            if (map) map[w] = f ? pos : -1;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) *count = carry;
+}
+
+__global__ void k_remap_cols(const int32_t* __restrict__ col_idx, int64_t nnz, const int32_t* __restrict__ map,
+                             int32_t* __restrict__ out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < nnz; i += stride) out[i] = map[col_idx[i]];
+}
+
+// Single workgroup: pofs[s] = sum_{r<s} roundup8(len_r); pofs[nseg] = padded total.
+__global__ __launch_bounds__(kScanThreads) void k_seg_offsets(const int64_t* __restrict__ rp, int64_t nseg,
+                                                              int32_t* __restrict__ pofs)
+{
+    __shared__ int32_t wave_sums[kScanThreads / 64 + 1];
+    int32_t carry = 0;
+    for (int64_t base = 0; base < nseg; base += kScanThreads) {
+        int64_t s = base + threadIdx.x;
+        int32_t len = 0;
+        if (s < nseg) {
+            int64_t l = rp[s + 1] - rp[s];
+            if (l < 0) l = 0;
+            len = (int32_t)((l + (kGroup - 1)) & ~(int64_t)(kGroup - 1));
+        }
+        int32_t total;
+        int32_t pos = carry + block_exclusive_scan(len, wave_sums, total);
+        if (s < nseg) pofs[s] = pos;
+        carry += total;
+    }
+    if (threadIdx.x == 0) pofs[nseg] = carry;
+}
+
+// Largest s in [0, nseg] with pofs[s] <= x (pofs is non-decreasing, pofs[0] == 0 <= x).
+__device__ inline int32_t last_le(const int32_t* pofs, int32_t nseg, int32_t x)
+{
+    int32_t lo = 0, hi = nseg + 1;   // invariant: pofs[lo] <= x, (hi == nseg+1 or pofs[hi] > x)
+    while (hi - lo > 1) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (pofs[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// One thread per group of 8 padded tokens.
+__global__ void k_fill_tokens(const int64_t* __restrict__ rp, const int32_t* __restrict__ col_idx, int32_t nseg,
+                              const int32_t* __restrict__ pofs, const float* __restrict__ normE,
+                              int32_t* __restrict__ tok_ids, float* __restrict__ tok_hn,
+                              int32_t* __restrict__ grp_seg, int64_t ngroups_alloc)
+{
+    int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= ngroups_alloc) return;
+    const int32_t total = pofs[nseg];
+    const int64_t start = g * kGroup;
+    if (start >= total) {
+        grp_seg[g] = -1;
+        for (int t = 0; t < kGroup; ++t) { tok_ids[start + t] = 0; tok_hn[start + t] = 0.f; }
+        return;
+    }
+    const int32_t seg = last_le(pofs, nseg, (int32_t)start);   // equal offsets: the last one is the non-empty one
+    const int64_t base = rp[seg];
+    const int64_t len = rp[seg + 1] - base;
+    const int64_t pos0 = start - pofs[seg];
+    grp_seg[g] = seg;
+    for (int t = 0; t < kGroup; ++t) {
+        int64_t pos = pos0 + t;
+        if (pos > len - 1) pos = len - 1;                       // pad by repeating the last word
+        int32_t id = col_idx[base + pos];
+        tok_ids[start + t] = id;
+        tok_hn[start + t] = -0.5f * normE[id];
+    }
+}
+
+// chunk_seg[c] = first segment whose padded offset is >= c * chunk_tokens (nseg when there is none).
+__global__ void k_chunk_bounds(const int32_t* __restrict__ pofs, int32_t nseg, int32_t chunk_tokens,
+                               int32_t nchunks, int32_t* __restrict__ chunk_seg)
+{
+    int32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > nchunks) return;
+    int64_t x = (int64_t)c * chunk_tokens;
+    int32_t lo = 0, hi = nseg;      // answer in [0, nseg]
+    while (lo < hi) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if ((int64_t)pofs[mid] >= x) hi = mid; else lo = mid + 1;
+    }
+    chunk_seg[c] = lo;
+}
+
+// One wavefront per histogram.
+__global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict__ rp,
+                                                      const int32_t* __restrict__ col_idx, int64_t nseg,
+                                                      const int32_t* __restrict__ map, float* __restrict__ Z,
+                                                      int64_t ldz)
+{
+    const int lane = threadIdx.x & 63;
+    int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (seg >= nseg) return;
+    for (int64_t p = rp[seg] + lane; p < rp[seg + 1]; p += 64) {
+        int32_t w = col_idx[p];
+        int32_t row = map ? map[w] : w;
+        if (row >= 0) Z[(int64_t)row * ldz + seg] = 0.f;
+    }
+}
+
+__global__ void k_validate_csr(const int64_t* __restrict__ rp, const int32_t* __restrict__ col_idx,
+                               const float* __restrict__ val, int64_t rows, int64_t cols, int64_t nnz,
+                               int32_t* __restrict__ status)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0 && (rp[0] != 0 || rp[rows] != nnz)) atomicMax(status, (int32_t)LCRWMD_EBADCSR);
+    if (i >= rows) return;
+    int64_t a = rp[i], b = rp[i + 1];
+    if (a < 0 || b > nnz || b < a) { atomicMax(status, (int32_t)LCRWMD_EBADCSR); return; }
+    if (b == a) { atomicMax(status, (int32_t)LCRWMD_EEMPTYDOC); return; }
+    int32_t prev = -1;
+    bool bad = false;
+    for (int64_t p = a; p < b; ++p) {
+        int32_t c = col_idx[p];
+        if (c <= prev || c >= cols) bad = true;
+        if (val && !(val[p] > 0.f)) bad = true;
+        prev = c;
+    }
+    if (bad) atomicMax(status, (int32_t)LCRWMD_EBADCSR);   // EEMPTYDOC (3) outranks EBADCSR (2) only in number
+}
+
+inline int grid_for(int64_t n, int threads, int cap = 1 << 20)
+{
+    int64_t g = (n + threads - 1) / threads;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+}  // namespace
+
+hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    k_fill_i32<<<grid_for(n, 256, 8192), 256, 0, s>>>(p, n, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_norms_f32(const float* E, int64_t v, int32_t m, int64_t ld, float* normE, hipStream_t s)
+{
+    if (v <= 0) return hipSuccess;
+    k_row_norms_f32<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, v, m, ld, normE);
+    return hipGetLastError();
+}
+
+hipError_t launch_mark_words(const int32_t* col_idx, int64_t nnz, int32_t* flags, hipStream_t s)
+{
+    if (nnz <= 0) return hipSuccess;
+    k_mark_words<<<grid_for(nnz, 256, 8192), 256, 0, s>>>(col_idx, nnz, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_words(const int32_t* flags, int64_t v, int32_t* list, int32_t* map, int32_t* count,
+                                hipStream_t s)
+{
+    k_compact_words<<<1, kScanThreads, 0, s>>>(flags, v, list, map, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_remap_cols(const int32_t* col_idx, int64_t nnz, const int32_t* map, int32_t* out, hipStream_t s)
+{
+    if (nnz <= 0) return hipSuccess;
+    k_remap_cols<<<grid_for(nnz, 256, 8192), 256, 0, s>>>(col_idx, nnz, map, out);
+    return hipGetLastError();
+}
+
+size_t token_plan_bytes(int64_t nseg, int64_t nnz_batch)
+{
+    Bump b((void*)256, (size_t)1 << 60);   // dry run: only the byte count matters
+    TokenPlan tp;
+    carve_token_plan(b, tp, nseg, nnz_batch, 1);
+    return b.used + 256;
+}
+
+bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles)
+{
+    tp.nseg = nseg;
+    tp.tok_bound = nnz_batch + (kGroup - 1) * nseg;
+    tp.tok_alloc = ((tp.tok_bound + kTileTokens - 1) / kTileTokens + 1) * kTileTokens;
+    // Aim at a few thousand workgroups (vocabulary tiles x chunks) so that 256 CUs stay busy and the
+    // tail is short, while each chunk still spans many token tiles.
+    int64_t want_chunks = (4096 + nvoc_tiles - 1) / (nvoc_tiles > 0 ? nvoc_tiles : 1);
+    if (want_chunks < 1) want_chunks = 1;
+    int64_t ct = (tp.tok_bound + want_chunks - 1) / want_chunks;
+    ct = ((ct + kTileTokens - 1) / kTileTokens) * kTileTokens;
+    if (ct < 4 * kTileTokens) ct = 4 * kTileTokens;
+    if (ct > 64 * kTileTokens) ct = 64 * kTileTokens;
+    tp.chunk_tokens = (int32_t)ct;
+    tp.nchunks = (int32_t)((tp.tok_bound + ct - 1) / ct);
+    if (tp.nchunks < 1) tp.nchunks = 1;
+    // the dry run used for sizing passes nvoc_tiles = 1, which yields the largest chunk count it can
+    // ever need only if chunks never get smaller than the floor: size for the floor.
+    int64_t chunks_alloc = (tp.tok_bound + 4 * kTileTokens - 1) / (4 * kTileTokens) + 2;
+    tp.pofs = b.take_n<int32_t>((size_t)nseg + 1);
+    tp.tok_ids = b.take_n<int32_t>((size_t)tp.tok_alloc);
+    tp.tok_hn = b.take_n<float>((size_t)tp.tok_alloc);
+    tp.grp_seg = b.take_n<int32_t>((size_t)(tp.tok_alloc / kGroup));
+    tp.chunk_seg = b.take_n<int32_t>((size_t)chunks_alloc);
+    return b.ok;
+}
+
+hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, const int32_t* col_idx,
+                             const float* normE, hipStream_t s)
+{
+    k_seg_offsets<<<1, kScanThreads, 0, s>>>(row_ptr_batch, tp.nseg, tp.pofs);
+    int64_t ngroups = tp.tok_alloc / kGroup;
+    k_fill_tokens<<<grid_for(ngroups, 256), 256, 0, s>>>(row_ptr_batch, col_idx, (int32_t)tp.nseg, tp.pofs, normE,
+                                                         tp.tok_ids, tp.tok_hn, tp.grp_seg, ngroups);
+    k_chunk_bounds<<<grid_for(tp.nchunks + 1, 256), 256, 0, s>>>(tp.pofs, (int32_t)tp.nseg, tp.chunk_tokens,
+                                                                 tp.nchunks, tp.chunk_seg);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg,
+                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s)
+{
+    if (nseg <= 0) return hipSuccess;
+    k_zero_matches<<<(unsigned)((nseg + 3) / 4), 256, 0, s>>>(row_ptr_batch, col_idx, nseg, map, Z, ldz);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_csr(const lcrwmd_csr& X, int32_t* status, hipStream_t s)
+{
+    k_validate_csr<<<grid_for(X.rows > 0 ? X.rows : 1, 256), 256, 0, s>>>(X.row_ptr, X.col_idx, X.val, X.rows,
+                                                                          X.cols, X.nnz, status);
+    return hipGetLastError();
+}
+
+}  // namespace lcrwmd

@@ -1,0 +1,174 @@
+// Top-k per query (Sec. III: the k smallest distances of a row of the result and the positions of the
+// respective database histograms, stored in the n2 x k matrix R).  D is n x q row-major here, so a query
+// is a column; lanes run along 32 neighbouring columns to keep the reads of D contiguous, and the rows
+// are split over workgroups.  Order everywhere: (distance, row index) ascending.
+#include <float.h>
+#include <limits.h>
+
+#include "lcrwmd_internal.h"
+
+namespace lcrwmd {
+
+namespace {
+
+constexpr int COLS = 32;     // query columns per workgroup
+constexpr int LISTS = 8;     // row lanes per column (256 threads = 32 x 8)
+
+struct TopkPlan {
+    int64_t col_strips;
+    int32_t nsplit;
+    int64_t rows_per_split;
+};
+
+TopkPlan plan_topk(int64_t n, int64_t q, int k, size_t ws_bytes)
+{
+    TopkPlan p;
+    p.col_strips = (q + COLS - 1) / COLS;
+    int64_t want = (2048 + p.col_strips - 1) / p.col_strips;    // aim at ~2k workgroups
+    int64_t by_rows = n / 2048 > 0 ? n / 2048 : 1;                 // at least ~2k rows per split
+    int64_t ns = want < by_rows ? want : by_rows;
+    if (ns > 64) ns = 64;
+    if (ns < 1) ns = 1;
+    size_t need = (size_t)ns * (size_t)q * (size_t)k * 8;
+    if (ns > 1 && need > ws_bytes) ns = 1;
+    p.nsplit = (int32_t)ns;
+    p.rows_per_split = (n + ns - 1) / ns;
+    return p;
+}
+
+__device__ inline bool before(float d, int32_t i, float bd, int32_t bi) { return d < bd || (d == bd && i < bi); }
+
+// Partial top-k of rows [split * rows_per_split, ...) for 32 columns.
+__global__ __launch_bounds__(256) void k_topk_partial(const float* __restrict__ D, int64_t n, int64_t q,
+                                                      int64_t ldd, int k, int64_t rows_per_split,
+                                                      int64_t col_strips, float* __restrict__ out_d,
+                                                      int32_t* __restrict__ out_i)
+{
+    extern __shared__ unsigned char smem[];
+    float* kd = reinterpret_cast<float*>(smem);                          // [k][256]
+    int32_t* ki = reinterpret_cast<int32_t*>(smem + (size_t)k * 256 * 4);  // [k][256]
+    int32_t* cnt_s = reinterpret_cast<int32_t*>(smem + (size_t)k * 256 * 8);
+
+    const int tid = threadIdx.x;
+    const int jj = tid & (COLS - 1), rg = tid / COLS;
+    const int64_t strip = blockIdx.x % col_strips;
+    const int64_t split = blockIdx.x / col_strips;
+    const int64_t j = strip * COLS + jj;
+    const int64_t r_begin = split * rows_per_split;
+    int64_t r_end = r_begin + rows_per_split;
+    if (r_end > n) r_end = n;
+
+    int cnt = 0;
+    float worst = FLT_MAX;
+    if (j < q) {
+        for (int64_t i = r_begin + rg; i < r_end; i += LISTS) {
+            const float d = D[i * ldd + j];
+            int pos;
+            if (cnt < k) pos = cnt++;
+            else if (d < worst) pos = k - 1;
+            else continue;
+            while (pos > 0 && d < kd[(pos - 1) * 256 + tid]) {
+                kd[pos * 256 + tid] = kd[(pos - 1) * 256 + tid];
+                ki[pos * 256 + tid] = ki[(pos - 1) * 256 + tid];
+                --pos;
+            }
+            kd[pos * 256 + tid] = d;
+            ki[pos * 256 + tid] = (int32_t)i;
+            if (cnt == k) worst = kd[(k - 1) * 256 + tid];
+        }
+    }
+    cnt_s[tid] = cnt;
+    __syncthreads();
+    if (rg == 0 && j < q) {
+        int h[LISTS];
+#pragma unroll
+        for (int g = 0; g < LISTS; ++g) h[g] = 0;
+        float* od = out_d + ((size_t)split * q + j) * k;
+        int32_t* oi = out_i + ((size_t)split * q + j) * k;
+        for (int r = 0; r < k; ++r) {
+            int best = -1;
+            float bd = FLT_MAX;
+            int32_t bi = INT_MAX;
+#pragma unroll
+            for (int g = 0; g < LISTS; ++g) {
+                const int t = jj + COLS * g;
+                if (h[g] < cnt_s[t]) {
+                    const float d = kd[h[g] * 256 + t];
+                    const int32_t i = ki[h[g] * 256 + t];
+                    if (best < 0 || before(d, i, bd, bi)) { best = g; bd = d; bi = i; }
+                }
+            }
+            od[r] = bd;      // FLT_MAX / INT_MAX mark a slot this split could not fill
+            oi[r] = bi;
+#pragma unroll
+            for (int g = 0; g < LISTS; ++g)
+                if (best == g) ++h[g];
+        }
+    }
+}
+
+// One wavefront per query merges the nsplit (<= 64) sorted partial lists.
+__global__ __launch_bounds__(64) void k_topk_merge(const float* __restrict__ part_d, const int32_t* __restrict__ part_i,
+                                                   int64_t q, int k, int nsplit, float* __restrict__ R_dist,
+                                                   int32_t* __restrict__ R_idx)
+{
+    const int64_t j = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float* ld = part_d + ((size_t)lane * q + j) * k;
+    const int32_t* li = part_i + ((size_t)lane * q + j) * k;
+    int h = 0;
+    for (int r = 0; r < k; ++r) {
+        float d = FLT_MAX;
+        int32_t i = INT_MAX;
+        if (lane < nsplit && h < k) { d = ld[h]; i = li[h]; }
+        float bd = d;
+        int32_t bi = i;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float od = __shfl_xor(bd, o);
+            const int32_t oi = __shfl_xor(bi, o);
+            if (before(od, oi, bd, bi)) { bd = od; bi = oi; }
+        }
+        if (lane == 0) { R_dist[j * k + r] = bd; R_idx[j * k + r] = bi; }
+        if (d == bd && i == bi && bi != INT_MAX) ++h;   // row indices are unique, so exactly one lane advances
+    }
+}
+
+}  // namespace
+
+size_t topk_bytes(int64_t n, int64_t q, int k)
+{
+    TopkPlan p = plan_topk(n, q, k, (size_t)-1);
+    return p.nsplit > 1 ? (size_t)p.nsplit * (size_t)q * (size_t)k * 8 + 512 : 0;
+}
+
+hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
+                       void* ws, size_t ws_bytes, hipStream_t s)
+{
+    if (q <= 0) return hipSuccess;
+    Bump b(ws, ws ? ws_bytes : 0);
+    TopkPlan p = plan_topk(n, q, k, ws ? ws_bytes - (ws_bytes > 512 ? 512 : ws_bytes) : 0);
+    float* pd = R_dist;
+    int32_t* pi = R_idx;
+    if (p.nsplit > 1) {
+        pd = b.take_n<float>((size_t)p.nsplit * q * k);
+        pi = b.take_n<int32_t>((size_t)p.nsplit * q * k);
+        if (!b.ok) { p.nsplit = 1; p.rows_per_split = n; pd = R_dist; pi = R_idx; }
+    }
+    const size_t smem = (size_t)k * 256 * 8 + 256 * 4;
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_topk_partial),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    const int64_t grid = p.col_strips * p.nsplit;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    k_topk_partial<<<(unsigned)grid, 256, smem, s>>>(D, n, q, ldd, k, p.rows_per_split, p.col_strips, pd, pi);
+    if (p.nsplit > 1) {
+        if (q > 0x7fffffffLL) return hipErrorInvalidValue;
+        k_topk_merge<<<(unsigned)q, 64, 0, s>>>(pd, pi, q, k, p.nsplit, R_dist, R_idx);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lcrwmd

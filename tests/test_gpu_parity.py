@@ -1,0 +1,271 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1711_07227_amd import binding, synth
+from helpers import ATOL_ZERO, RTOL_F32, assert_close, run_rwmd, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+def problem(v, m, n, q, h_lo, h_hi, seed, s=1.1):
+    E = synth.embeddings(v, m, seed)
+    db = synth.corpus(n, v, h_lo, h_hi, s, seed + 1)
+    qs = synth.corpus(q, v, h_lo, h_hi, s, seed + 2)
+    return {"E": E, "db": db, "queries": qs}
+
+
+# ------------------------------------------------------------------------------------------- phase 1
+@pytest.mark.parametrize("v,m,q,h_lo,h_hi", [
+    (700, 300, 9, 1, 40),       # several vocabulary tiles with a ragged last one, histograms of 1..40 words
+    (130, 300, 70, 3, 9),       # more histograms than tokens per tile
+    (257, 7, 5, 2, 12),         # m not a multiple of 4: scalar load path, single K piece
+    (300, 64, 3, 100, 200),     # histograms longer than one token tile
+])
+def test_phase1_matches_oracle(ctx, v, m, q, h_lo, h_hi):
+    print(f"phase1 v={v} m={m} q={q} h={h_lo}..{h_hi}", flush=True)
+    E = synth.embeddings(v, m, 5)
+    qs = synth.corpus(q, v, h_lo, h_hi, 1.1, 6)
+    ref = oracle.phase1(E, qs)
+    Ed = torch.from_numpy(E).cuda()
+    Q = binding.Csr.from_numpy(qs, v)
+    ldz = q + 3
+    Z = torch.full((v, ldz), -7.0, dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, 0, 0, q, Q.nnz))
+    ctx.phase1_mindist(Ed, Q, Z, ws)
+    torch.cuda.synchronize()
+    Zh = Z.cpu().numpy()
+    assert np.all(Zh[:, q:] == -7.0)                         # padding columns untouched
+    assert_close(Zh[:, :q], ref, what="Z")
+    ptr, col, _ = qs
+    for j in range(q):
+        assert np.all(Zh[col[ptr[j]:ptr[j + 1]], j] == 0.0)  # exact zeros for the histogram's own words
+
+
+def test_phase1_with_row_pitch_and_unnormalised_embeddings(ctx):
+    rng = np.random.default_rng(3)
+    v, m, q = 200, 300, 6
+    E = (rng.standard_normal((v, m)) * rng.uniform(0.2, 3.0, size=(v, 1))).astype(np.float32)
+    qs = synth.corpus(q, v, 2, 30, 1.1, 8)
+    ref = oracle.phase1(E, qs)
+    big = torch.zeros((v, 304), dtype=torch.float32, device="cuda")
+    big[:, :m] = torch.from_numpy(E).cuda()
+    Ed = big[:, :m]                                          # ld = 304 > m
+    Z = torch.empty((v, q), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, 0, 0, q, len(qs[1])))
+    ctx.phase1_mindist(Ed, binding.Csr.from_numpy(qs, v), Z, ws)
+    torch.cuda.synchronize()
+    assert_close(Z.cpu().numpy(), ref, rtol=2e-4, what="Z unnormalised")
+
+
+# ------------------------------------------------------------------------------------------- phase 2
+@pytest.mark.parametrize("rows,v,ncols", [(90, 400, 10), (333, 1000, 64), (200, 500, 517), (5, 50, 1)])
+def test_phase2_store_and_max(ctx, rows, v, ncols):
+    print(f"phase2 rows={rows} v={v} ncols={ncols}", flush=True)
+    rng = np.random.default_rng(rows)
+    X = synth.corpus(rows, v, 1, min(60, v), 1.1, 2)
+    Zh = rng.random((v, ncols)).astype(np.float32)
+    ref = oracle.phase2(X, Zh.astype(np.float64))
+    Xd = binding.Csr.from_numpy(X, v)
+    ldz = (ncols + 3) // 4 * 4
+    Z = torch.zeros((v, ldz), dtype=torch.float32, device="cuda")
+    Z[:, :ncols] = torch.from_numpy(Zh).cuda()
+    D = torch.full((rows, ncols + 2), -1.0, dtype=torch.float32, device="cuda")
+    ctx.phase2_spmm(Xd, Z, ncols, D, combine=0)
+    torch.cuda.synchronize()
+    Dh = D.cpu().numpy()
+    assert np.all(Dh[:, ncols:] == -1.0)
+    assert_close(Dh[:, :ncols], ref, rtol=1e-5, what="X*Z")
+    # maximum with existing content
+    prev = rng.random((rows, ncols)).astype(np.float32)
+    D2 = torch.from_numpy(prev).cuda()
+    ctx.phase2_spmm(Xd, Z, ncols, D2, combine=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(D2.cpu().numpy(), np.maximum(prev, Dh[:, :ncols]))
+    # transposed maximum
+    prevT = rng.random((ncols, rows)).astype(np.float32)
+    D3 = torch.from_numpy(prevT).cuda()
+    ctx.phase2_spmm(Xd, Z, ncols, D3, combine=2)
+    torch.cuda.synchronize()
+    assert_close(D3.cpu().numpy(), np.maximum(prevT.astype(np.float64), ref.T), rtol=1e-5, what="transposed max")
+
+
+# ------------------------------------------------------------------------------------------- full bound
+def test_rwmd_tiny_config_full_matrix(ctx, tiny):
+    ref = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    E, db, qs = upload(tiny)
+    got = run_rwmd(ctx, E, db, qs)
+    assert_close(got, ref, what="tiny D")
+
+
+def test_rwmd_without_host_row_pointers(ctx, tiny):
+    ref = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    E, db, qs = upload(tiny, host_rows=False)
+    assert_close(run_rwmd(ctx, E, db, qs), ref, what="tiny D (row_ptr fetched by the library)")
+
+
+def test_rwmd_ragged_mid_size_and_batch_independence(ctx):
+    p = problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    E, db, qs = upload(p)
+    whole = run_rwmd(ctx, E, db, qs)
+    assert_close(whole, ref, what="mid D")
+    ctx.set_options(max_query_batch=5, max_db_batch=64)
+    try:
+        batched = run_rwmd(ctx, E, db, qs)
+    finally:
+        ctx.set_options()
+    assert_close(batched, ref, what="mid D in small batches")
+    assert np.max(np.abs(batched - whole)) <= 2e-6           # same sums, same order: batches change nothing
+
+
+def test_rwmd_self_distance_zero_and_symmetry(ctx, tiny):
+    sub = synth.csr_rows(*tiny["db"], np.arange(150))
+    p = {"E": tiny["E"], "db": sub, "queries": sub}
+    E, db, qs = upload(p)
+    got = run_rwmd(ctx, E, db, qs)
+    assert np.all(np.diag(got) == 0.0)
+    assert np.max(np.abs(got - got.T)) <= 1e-5
+    assert_close(got, oracle.rwmd_table(tiny["E"], sub, sub), what="self D")
+
+
+def test_rwmd_degenerate_shapes(ctx):
+    # one database doc, one query, single-word documents
+    E = synth.embeddings(50, 300, 1)
+    one = (np.array([0, 1], np.int64), np.array([7], np.int32), np.array([1.0], np.float32))
+    other = (np.array([0, 1], np.int64), np.array([9], np.int32), np.array([1.0], np.float32))
+    p = {"E": E, "db": one, "queries": other}
+    got = run_rwmd(ctx, *upload(p))
+    ref = np.linalg.norm(E[7].astype(np.float64) - E[9].astype(np.float64))
+    assert got.shape == (1, 1) and abs(got[0, 0] - ref) <= RTOL_F32 * ref
+    p = {"E": E, "db": one, "queries": one}
+    assert run_rwmd(ctx, *upload(p))[0, 0] == 0.0
+    # orthonormal embeddings: closed form sqrt(2) * weight outside the other document
+    v = 64
+    p = {"E": np.eye(v, dtype=np.float32), "db": synth.corpus(40, v, 2, 20, 1.0, 4),
+         "queries": synth.corpus(9, v, 2, 20, 1.0, 5)}
+    assert_close(run_rwmd(ctx, *upload(p)), oracle.rwmd_bruteforce(p["E"], p["db"], p["queries"]), what="eye D")
+
+
+def test_empty_inputs_are_noops(ctx):
+    E = torch.from_numpy(synth.embeddings(20, 300, 1)).cuda()
+    empty = binding.Csr(torch.zeros(1, dtype=torch.int64, device="cuda"), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                        torch.zeros(0, dtype=torch.float32, device="cuda"), 20, torch.zeros(1, dtype=torch.int64))
+    db = binding.Csr.from_numpy(synth.corpus(5, 20, 1, 5, 1.0, 1), 20)
+    D = torch.zeros((5, 1), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(1 << 20)
+    ctx.rwmd(empty, db, E, D, ws)
+    ctx.phase1_mindist(E, empty, D, ws)
+    ctx.phase2_spmm(empty, D, 1, D)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------- top-k
+@pytest.mark.parametrize("n,q,k", [(1000, 10, 16), (5000, 70, 5), (300, 33, 64), (40, 3, 40)])
+def test_topk_of_a_matrix_is_exact(ctx, n, q, k):
+    rng = np.random.default_rng(n + k)
+    Dh = rng.random((n, q)).astype(np.float32)
+    Dh[rng.integers(0, n, 50), rng.integers(0, q, 50)] = 0.25      # ties across rows
+    D = torch.from_numpy(Dh).cuda()
+    ridx, rdist = oracle.topk(Dh.astype(np.float64), k)
+    for ws in (None, binding.alloc_workspace(1 << 24)):
+        R_idx = torch.empty((q, k), dtype=torch.int32, device="cuda")
+        R_dist = torch.empty((q, k), dtype=torch.float32, device="cuda")
+        ctx.topk(D, k, R_idx, R_dist, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(R_idx.cpu().numpy().astype(np.int64), ridx)
+        assert np.array_equal(R_dist.cpu().numpy().astype(np.float64), rdist)
+
+
+def test_rwmd_topk_matches_oracle_on_tiny(ctx, tiny):
+    k = 16
+    E, db, qs = upload(tiny)
+    n, q = db.rows, qs.rows
+    R_idx = torch.empty((q, k), dtype=torch.int32, device="cuda")
+    R_dist = torch.empty((q, k), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(ctx.workspace_bytes(E.shape[0], E.shape[1], n, db.nnz, q, qs.nnz, k=k))
+    ctx.rwmd_topk(qs, db, E, k, R_idx, R_dist, ws)
+    torch.cuda.synchronize()
+    ref = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    ridx, rdist = oracle.topk(ref, k + 1)
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    assert_close(gd, rdist[:, :k], what="top-k distances")
+    # indices must agree wherever the oracle's neighbouring gaps exceed the fp32 error bound
+    gap_ok = np.diff(rdist, axis=1) > 8e-6 * rdist[:, 1:]
+    for j in range(q):
+        for r in range(k):
+            left_ok = r == 0 or gap_ok[j, r - 1]
+            if left_ok and gap_ok[j, r]:
+                assert gi[j, r] == ridx[j, r], (j, r)
+    assert (~gap_ok).sum() <= 2, "tiny config should be nearly ties-free at fp32 resolution"
+    # batches of queries give the same answer
+    ctx.set_options(max_query_batch=4)
+    try:
+        R2 = torch.empty_like(R_idx)
+        ctx.rwmd_topk(qs, db, E, k, R2, R_dist, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_options()
+    assert np.array_equal(R2.cpu().numpy(), gi)
+
+
+# ------------------------------------------------------------------------------------------- error paths
+def test_error_codes_never_crash(ctx, tiny):
+    E, db, qs = upload(tiny)
+    D = torch.empty((db.rows, qs.rows), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(1 << 26)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.rwmd(qs, db, E, D, None)
+    assert e.value.status == binding.EWORKSPACE
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.rwmd(qs, db, E, D, ws[:4096])
+    assert e.value.status == binding.EWORKSPACE and "workspace" in str(e.value)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.rwmd(qs, db, E, torch.empty((db.rows, 5), dtype=torch.float32, device="cuda"), ws)   # ldd < q
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.rwmd(qs, db, E[:100], D, ws)                      # columns != v
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.topk(D, 65, torch.empty((qs.rows, 65), dtype=torch.int32, device="cuda"),
+                 torch.empty((qs.rows, 65), dtype=torch.float32, device="cuda"))
+    assert e.value.status == binding.EUNSUPPORTED
+    # device-side validation of malformed histograms
+    ctx.set_options(validate=1)
+    try:
+        v = E.shape[0]
+        ptr, col, val = [a.copy() for a in tiny["queries"]]
+        col[3] = col[2]                                        # duplicate word inside a row
+        with pytest.raises(binding.LcrwmdError) as e:
+            ctx.rwmd(binding.Csr.from_numpy((ptr, col, val), v), db, E, D, ws)
+        assert e.value.status == binding.EBADCSR
+        ptr2 = tiny["queries"][0].copy()
+        ptr2[4] = ptr2[3]                                      # an empty histogram
+        with pytest.raises(binding.LcrwmdError) as e:
+            ctx.rwmd(binding.Csr.from_numpy((ptr2, tiny["queries"][1], tiny["queries"][2]), v), db, E, D, ws)
+        assert e.value.status == binding.EEMPTYDOC
+        col3 = tiny["queries"][1].copy()
+        col3[-1] = v + 5                                       # word id outside the vocabulary
+        with pytest.raises(binding.LcrwmdError) as e:
+            ctx.rwmd(binding.Csr.from_numpy((tiny["queries"][0], col3, tiny["queries"][2]), v), db, E, D, ws)
+        assert e.value.status == binding.EBADCSR
+        ctx.rwmd(qs, db, E, D, binding.alloc_workspace(ctx.workspace_bytes(v, 300, db.rows, db.nnz, qs.rows, qs.nnz)))
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_options()
+
+
+def test_results_are_deterministic(ctx, tiny):
+    E, db, qs = upload(tiny)
+    a = run_rwmd(ctx, E, db, qs)
+    b = run_rwmd(ctx, E, db, qs)
+    assert np.array_equal(a, b)
