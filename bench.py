@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "long"])
     ap.add_argument("--compute", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
+                         "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--cpu-queries", type=int, default=24, help="queries in the CPU oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -57,6 +60,13 @@ def main():
     ctx.set_options(compute=compute)
     ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, binding.F32))
     D = torch.empty((n, q), dtype=torch.float32, device="cuda")
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         ctx.rwmd(qs, db, E, D, ws)

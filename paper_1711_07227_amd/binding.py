@@ -11,8 +11,11 @@ import pathlib
 
 import torch
 
+import os
+
 _HERE = pathlib.Path(__file__).resolve().parent
-LIB_PATH = _HERE / "liblcrwmd.so"
+# LCRWMD_LIB lets a developer point the binding at another build of the same library
+LIB_PATH = pathlib.Path(os.environ.get("LCRWMD_LIB", _HERE / "liblcrwmd.so"))
 
 OK, EINVAL, EBADCSR, EEMPTYDOC, EWORKSPACE, EUNSUPPORTED, EHIP = range(7)
 F32, BF16 = 0, 1
