@@ -76,7 +76,8 @@ typedef struct {
     int compute;                    /* lcrwmd_dtype the first-phase contraction multiplies in.
                                        LCRWMD_F32 (default for fp32 E): fp32 MFMA.  LCRWMD_BF16: E is
                                        rounded to bf16 (round-to-nearest-even) unless already bf16,
-                                       products accumulate in fp32.  bf16 E always computes in bf16.  */
+                                       products accumulate in fp32.  bf16 E always computes in bf16.
+                                       The bf16 path needs m <= 300 (LCRWMD_EUNSUPPORTED otherwise).  */
     int64_t max_query_batch;        /* upper limit on histograms of X2 per pass (Sec. IV, many-to-many:
                                        X2 is divided into batches); 0 = chosen from the workspace     */
     int64_t max_db_batch;           /* same for the database rows handled per pass of the swapped

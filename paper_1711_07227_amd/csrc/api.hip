@@ -128,6 +128,8 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
     ep.normE = b.take_n<float>((size_t)E->v);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the word norms");
     if (ep.bf16) {
+        if (!bf16_supported((int32_t)E->m))
+            return fail(ctx, LCRWMD_EUNSUPPORTED, "the bf16 path supports m <= 300 (got %lld)", (long long)E->m);
         void* packed = b.take(pack_bf16_bytes(E->v, (int32_t)E->m));
         if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the bf16 copy of E");
         HIP_TRY(launch_pack_bf16(E->data, E->dtype, E->v, (int32_t)E->m, E->ld, packed, ep.normE, s));

@@ -104,7 +104,7 @@ hipError_t launch_validate_csr(const lcrwmd_csr& X, int32_t* status, hipStream_t
 hipError_t launch_phase1_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 
 // phase1_bf16.hip
-constexpr int kBf16Pitch = 320;   // elements per packed bf16 row: 300 values padded for 16-wide K steps
+bool bf16_supported(int32_t m);    // the register-resident vocabulary operand holds m + 4 <= 304 columns
 size_t pack_bf16_bytes(int64_t v, int32_t m);
 int32_t bf16_pitch(int32_t m);
 hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_t m, int64_t ld, void* packed,

@@ -269,3 +269,60 @@ def test_results_are_deterministic(ctx, tiny):
     a = run_rwmd(ctx, E, db, qs)
     b = run_rwmd(ctx, E, db, qs)
     assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------- bf16 path
+def bf16_round(E):
+    return synth.bf16_bits_to_f32(synth.to_bf16_bits(E))
+
+
+@pytest.mark.parametrize("v,m,q,h_lo,h_hi", [(700, 300, 9, 1, 40), (300, 64, 3, 100, 200), (515, 290, 20, 2, 30),
+                                             (200, 13, 4, 1, 9)])
+def test_phase1_bf16_matches_oracle_on_rounded_embeddings(ctx, v, m, q, h_lo, h_hi):
+    print(f"phase1 bf16 v={v} m={m} q={q}", flush=True)
+    E = synth.embeddings(v, m, 15)
+    Er = bf16_round(E)
+    qs = synth.corpus(q, v, h_lo, h_hi, 1.1, 16)
+    ref_rounded = oracle.phase1(Er, qs)
+    ref_exact = oracle.phase1(E, qs)
+    Q = binding.Csr.from_numpy(qs, v)
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, 0, 0, q, Q.nnz, binding.BF16))
+    # (a) fp32 E, bf16 compute requested through the options: the library rounds to nearest even itself
+    ctx.set_options(compute=binding.BF16)
+    try:
+        Z = torch.full((v, q), -3.0, dtype=torch.float32, device="cuda")
+        ctx.phase1_mindist(torch.from_numpy(E).cuda(), Q, Z, ws)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_options()
+    Za = Z.cpu().numpy()
+    assert_close(Za, ref_rounded, rtol=1e-4, what="bf16 Z vs oracle on bf16-rounded E")
+    assert_close(Za, ref_exact, rtol=2e-2, atol=1e-5, what="bf16 Z vs oracle on fp32 E")
+    # (b) E handed over as bf16
+    Z2 = torch.full((v, q), -3.0, dtype=torch.float32, device="cuda")
+    ctx.phase1_mindist(torch.from_numpy(Er).cuda().to(torch.bfloat16), Q, Z2, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(Z2.cpu().numpy(), Za)
+    ptr, col, _ = qs
+    for j in range(q):
+        assert np.all(Za[col[ptr[j]:ptr[j + 1]], j] == 0.0)
+
+
+def test_rwmd_bf16_tiny_and_ragged(ctx, tiny):
+    for p in (tiny, problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)):
+        Er = bf16_round(p["E"])
+        ref_rounded = oracle.rwmd_table(Er, p["db"], p["queries"])
+        ref_exact = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+        E, db, qs = upload({"E": Er, "db": p["db"], "queries": p["queries"]}, dtype=torch.bfloat16)
+        got = run_rwmd(ctx, E, db, qs, emb_dtype=binding.BF16)
+        assert_close(got, ref_rounded, rtol=1e-4, what="bf16 D vs oracle on bf16-valued E")
+        assert_close(got, ref_exact, rtol=2e-2, what="bf16 D vs oracle on fp32 E")
+
+
+def test_bf16_rejects_wide_embeddings(ctx):
+    E = torch.zeros((10, 400), dtype=torch.bfloat16, device="cuda")
+    qs = binding.Csr.from_numpy(synth.corpus(2, 10, 1, 3, 1.0, 1), 10)
+    Z = torch.zeros((10, 2), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.phase1_mindist(E, qs, Z, binding.alloc_workspace(1 << 20))
+    assert e.value.status == binding.EUNSUPPORTED
