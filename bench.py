@@ -25,6 +25,19 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X, dense bf16 matrix
 PEAK_HBM_GBS = 8000.0
 
 
+def recorded_traffic(workload, compute):
+    """HBM bytes per launch of the first-phase kernel from the committed rocprofv3 counter runs, or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 5 and not line.startswith("#") and f[0] == workload and f[1] == compute:
+                return (float(f[3]) + float(f[4])) * 1e9
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,7 +138,8 @@ def main():
         "config": {"workload": f"{cfg.name}: v={v} m={m} n={n} q={q} h={cfg.h_lo}-{cfg.h_hi} zipf={cfg.zipf_s}",
                    "nnz_db": db.nnz, "nnz_q": qs.nnz, "data_gen_s": round(t_gen, 1)},
         "roofline": {"bound": "mfma", "kernel": f"phase1_{args.compute}", "achieved": achieved_tflops, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved_tflops / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved_tflops / peak,
+                     "traffic": recorded_traffic(args.workload, args.compute),
                      "launches_per_step": prof["phase1_launches"] / args.steps, "avg_launch_ms": p1_ms,
                      "flops_per_launch": p1_flops,
                      "share_of_step": prof["phase1_ms"] / (1e3 * sec)},
