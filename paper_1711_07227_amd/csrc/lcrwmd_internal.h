@@ -111,6 +111,11 @@ hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_
                             float* normE, hipStream_t s);
 hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 
+// phase1_tiles.hip: the direct-to-LDS tile kernel for both precisions
+bool tiles_f32_supported(const Phase1Args& a);
+hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, int32_t nsteps, const TokenPlan& tp, hipStream_t s);
+
 // phase2.hip
 hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,
                        const float* Z, int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine,

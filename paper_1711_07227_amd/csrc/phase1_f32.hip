@@ -424,6 +424,7 @@ __global__ __launch_bounds__(256, 1) void k_phase1_f32_regb(P1Dev p)
 hipError_t launch_phase1_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
 {
     if (a.nvoc <= 0 || tp.nseg <= 0) return hipSuccess;
+    if (tiles_f32_supported(a)) return launch_phase1_tiles_f32(a, tp, s);   // 16-byte aligned rows, m <= 300
     P1Dev d;
     d.E = (const float*)a.E;
     d.ld = a.ld;

@@ -326,3 +326,32 @@ def test_bf16_rejects_wide_embeddings(ctx):
     with pytest.raises(binding.LcrwmdError) as e:
         ctx.phase1_mindist(E, qs, Z, binding.alloc_workspace(1 << 20))
     assert e.value.status == binding.EUNSUPPORTED
+
+
+# ------------------------------------------------------------------------------------------- full-size workload
+def test_medium_workload_at_full_size_sampled_pairs(ctx):
+    """The benchmark's workload and launch configuration; the oracle evaluates sampled pairs one by one."""
+    cfg = synth.CONFIGS["medium"]
+    print("generating medium", flush=True)
+    p = synth.make(cfg)
+    E, db, qs = upload(p)
+    n, q = db.rows, qs.rows
+    assert (n, q, E.shape[0]) == (100000, 1000, 100000)
+    ws = binding.alloc_workspace(ctx.workspace_bytes(E.shape[0], 300, n, db.nnz, q, qs.nnz))
+    D = torch.full((n, q), float("nan"), dtype=torch.float32, device="cuda")
+    print("running lcrwmd_rwmd", flush=True)
+    ctx.rwmd(qs, db, E, D, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(D).all())
+    assert float(D.min()) >= 0.0 and float(D.max()) <= 2.0 + 1e-4           # unit vectors
+    rng = np.random.default_rng(7)
+    pi = np.concatenate([rng.integers(0, n, 3000), [0, n - 1, 0, n - 1]])
+    pj = np.concatenate([rng.integers(0, q, 3000), [0, q - 1, q - 1, 0]])
+    print("oracle on sampled pairs", flush=True)
+    ref = oracle.rwmd_pairs(p["E"], p["db"], p["queries"], pi, pj)
+    got = D[torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()].cpu().numpy()
+    assert_close(got, ref, what="medium sampled pairs")
+    # two full columns through the per-query table oracle
+    cols = np.array([3, q - 1])
+    ref_cols = oracle.rwmd_table(p["E"], p["db"], synth.csr_rows(*p["queries"], cols))
+    assert_close(D[:, torch.from_numpy(cols).cuda()].cpu().numpy(), ref_cols, what="medium full columns")
