@@ -226,6 +226,14 @@ lcrwmd_status host_row_ptr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, HostPtr& out, h
     return LCRWMD_OK;
 }
 
+// Exact padded token count of histograms [a, b): every histogram rounded up to a multiple of 8 tokens.
+int64_t padded_tokens(const int64_t* rp, int64_t a, int64_t b)
+{
+    int64_t t = 0;
+    for (int64_t r = a; r < b; ++r) t += (rp[r + 1] - rp[r] + (kGroup - 1)) & ~(int64_t)(kGroup - 1);
+    return t;
+}
+
 int64_t max_tokens_per_batch(const int64_t* rp, int64_t rows, int64_t batch)
 {
     int64_t mx = 0;
@@ -291,7 +299,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], nvt_f);
+        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], nvt_f, padded_tokens(rq, j0, j1));
         const int64_t ldz = round_up(j1 - j0, 4);
         float* Z = bb.take_n<float>((size_t)v * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
@@ -314,7 +322,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t i1 = i0 + nb < n ? i0 + nb : n;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], nvt_r);
+        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], nvt_r, padded_tokens(rdb, i0, i1));
         const int64_t ldz = round_up(i1 - i0, 4);
         float* Z = bb.take_n<float>((size_t)vq * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");

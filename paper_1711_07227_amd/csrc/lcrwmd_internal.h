@@ -69,7 +69,10 @@ struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
     template <class T> T* take_n(size_t count) { return (T*)take(count * sizeof(T)); }
 };
 
-bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles);
+// padded_exact: the exact padded token count when the caller knows the row lengths (else -1: the bound is used,
+// and the last chunks may turn out empty)
+bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles,
+                      int64_t padded_exact = -1);
 
 // Operand description of one first-phase launch.
 struct Phase1Args {

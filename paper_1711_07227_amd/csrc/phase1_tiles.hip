@@ -23,6 +23,8 @@
 // K step sigma covers pieces 2 sigma and 2 sigma + 1: lane half h multiplies piece 2 sigma + h of its token row
 // with the same piece of its vocabulary word.  bf16: one v_mfma_f32_32x32x16_bf16 per step; fp32: four
 // v_mfma_f32_32x32x2_f32 (one per float of the piece).
+#include <type_traits>
+
 #include "lcrwmd_internal.h"
 
 namespace lcrwmd {
@@ -32,6 +34,30 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1.
+template <int B, int E, class F>
+__device__ inline void static_for(F&& f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
+// Issue one 16-byte LDS read WITHOUT waiting for it.  The destination registers are written asynchronously; the
+// caller waits with s_waitcnt lgkmcnt before using them.  The compiler is deliberately not told about the latency:
+// its own wait insertion drains the whole LDS queue before every use, which exposes a full LDS round trip per K step.
+template <int OFF>
+__device__ inline f32x4 lds_read16_nowait(uint32_t addr)
+{
+    f32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+// s_waitcnt that only constrains the LDS/scalar queue: at most N operations still outstanding
+#define LCRWMD_WAIT_LGKM(N) __builtin_amdgcn_s_waitcnt(0xC07F | ((N) << 8))
 
 struct P1T {
     const unsigned char* Eb;   // operand rows (fp32: caller's E; bf16: packed copy)
@@ -228,28 +254,62 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     int gsv = load_gs(t0), gsv_next = 0;
     if (!BF16) load_hn(t0, hn);
     int buf = 0;
+#ifdef DBG_TIMING
+    long long tacc[6] = {0, 0, 0, 0, 0, 0};
+    long long tprev = clock64();
+#define DBG_T(k) { long long tn = clock64(); tacc[k] += tn - tprev; tprev = tn; }
+#else
+#define DBG_T(k)
+#endif
     for (int tb = t0; tb < t1; tb += ROWS) {
         __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0): this wavefront's copies of the tile have landed
+        DBG_T(0)
         __syncthreads();                        // ... and everyone's; everyone has left the other buffer
+        DBG_T(1)
         if (tb + ROWS < t1) {
+#ifndef DBG_NO_COPY
             issue_tile_copy(buf ^ 1);                           // word ids were fetched during the previous tile
+#endif
             if (tb + 2 * ROWS < t1) load_words(tb + 2 * ROWS);
             gsv_next = load_gs(tb + ROWS);
             if (!BF16) load_hn(tb + ROWS, hn_next);
         }
+        DBG_T(2)
 
-        const unsigned char* A = smem + buf * tbytes;
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            if (s < nsteps) {
-                const bool in_half = half_quad && (s == nsteps - 1);
-                const unsigned char* base =
-                    in_half ? A + full_quads * QUAD_BYTES + off_half : A + (s >> 1) * QUAD_BYTES + ((s & 1) ? off_odd : off_even);
-                const int rstride = in_half ? 1024 : 2048;
-                f32x4 a[NRT];
-#pragma unroll
-                for (int rt = 0; rt < NRT; ++rt) a[rt] = *reinterpret_cast<const f32x4*>(base + rt * rstride);
-                if (BF16) {
+        // Software pipeline over the K steps: the LDS reads of step s + 1 are issued before the MFMAs of step s,
+        // into the other of two fragment register sets.
+        if constexpr (NS > 0) {
+            constexpr bool HALFQ = (NS & 1) != 0;                 // 2 NS pieces: a half quad iff NS is odd
+            constexpr int FULLQ = (2 * NS) >> 2;
+            const uint32_t abase =
+                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)(buf * tbytes);
+            const uint32_t addr_even = abase + off_even, addr_odd = abase + off_odd, addr_half = abase + off_half;
+            f32x4 afrag[2][NRT];
+            auto issue_reads = [&](auto s_c) {
+                constexpr int s = decltype(s_c)::value;
+                constexpr bool in_half = HALFQ && (s == NS - 1);
+                constexpr int region = in_half ? FULLQ * QUAD_BYTES : (s >> 1) * QUAD_BYTES;
+                constexpr int stride = in_half ? 1024 : 2048;
+                static_for<0, NRT>([&](auto rt_c) {
+                    constexpr int rt = decltype(rt_c)::value;
+                    constexpr int total = region + rt * stride;
+                    constexpr int win = total / 32768;             // keep the immediate offset below 2^15
+                    const uint32_t base = (in_half ? addr_half : ((s & 1) ? addr_odd : addr_even)) + win * 32768;
+                    afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+                });
+            };
+            issue_reads(std::integral_constant<int, 0>{});
+            static_for<0, NS>([&](auto s_c) {
+                constexpr int s = decltype(s_c)::value;
+                if constexpr (s + 1 < NS) {
+                    issue_reads(std::integral_constant<int, s + 1>{});
+                    LCRWMD_WAIT_LGKM(NRT);          // everything but the reads just issued has arrived
+                } else {
+                    LCRWMD_WAIT_LGKM(0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const f32x4* a = afrag[s & 1];
+                if constexpr (BF16) {
 #pragma unroll
                     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
@@ -267,6 +327,39 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                                 acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
                                     a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else {
+            const unsigned char* A = smem + buf * tbytes;
+#pragma unroll
+            for (int s = 0; s < MAXS; ++s) {
+                if (s < nsteps) {
+                    const bool in_half = half_quad && (s == nsteps - 1);
+                    const unsigned char* base = in_half ? A + full_quads * QUAD_BYTES + off_half
+                                                        : A + (s >> 1) * QUAD_BYTES + ((s & 1) ? off_odd : off_even);
+                    const int rstride = in_half ? 1024 : 2048;
+                    f32x4 a[NRT];
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt) a[rt] = *reinterpret_cast<const f32x4*>(base + rt * rstride);
+                    if (BF16) {
+#pragma unroll
+                        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                            for (int ct = 0; ct < NCT; ++ct)
+                                acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                    __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                                    s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                                for (int ct = 0; ct < NCT; ++ct)
+                                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                        a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
+                    }
+                }
             }
         }
         if (!BF16) {
@@ -279,9 +372,20 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(half == 0 ? hn[rt] : 0.f, one, acc[rt][ct], 0, 0, 0);
         }
 
+        DBG_T(3)
         // Epilogue: registers 4g'..4g'+3 of row tile rt hold token rows 32 rt + 8 g' + 4 half + {0..3}: group 4 rt + g'.
         int ng = (t1 - tb) >> 3;
         if (ng > NG) ng = NG;
+#ifdef DBG_NO_EPI
+        cur = s0;
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) run[ct] = fmaxf(run[ct], acc[rt][ct][r]);
+        ng = 0;
+#endif
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             if (g < ng) {
@@ -308,8 +412,15 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
             for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
         }
         buf ^= 1;
+        DBG_T(4)
     }
     flush();
+#ifdef DBG_TIMING
+    if (blockIdx.x == 0 && tid == 0) {
+        for (int k = 0; k < 5; ++k) p.Z[k] = (float)tacc[k];
+        p.Z[5] = (float)((t1 - t0) / ROWS);
+    }
+#endif
 }
 
 template <bool BF16, int NRT, int NCT, int WGS_PER_CU, int NS>
@@ -366,6 +477,9 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.nreal = a.m / 4;
     d.npieces = (d.nreal + 1) & ~1;
     d.nzero_from = a.m;
+#ifdef DBG_F32_NCT1
+    if (d.npieces == 76) return launch_tiles<false, 2, 1, 1, 38>(d, s);
+#endif
     if (d.npieces == 76) return launch_tiles<false, 2, 2, 1, 38>(d, s);   // m = 300
     return launch_tiles<false, 2, 2, 1, 0>(d, s);
 }

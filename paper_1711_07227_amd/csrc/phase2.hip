@@ -12,7 +12,10 @@ namespace lcrwmd {
 
 namespace {
 
-// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers.
+// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
+// Units are ordered strip-major and workgroup ids follow that order, so at any time the whole chip works on
+// one strip of columns: the strip of Z (rows of 256 W bytes) is what has to stay in the L2s / Infinity Cache,
+// not the full rows.
 template <int W, int COMBINE>
 __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
                                                    const float* __restrict__ xv, int64_t rows,
@@ -21,54 +24,54 @@ __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ r
 {
     const int lane = threadIdx.x & 63;
     const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    // strips vary fastest: neighbouring wavefronts read the same CSR row and adjacent pieces of Z rows
-    const int64_t i = unit / strips;
-    const int64_t strip = unit - i * strips;
-    if (i >= rows) return;
+    const int64_t strip = unit / rows;
+    const int64_t i = unit - strip * rows;
+    if (strip >= strips) return;
     const int64_t j = strip * (64 * W) + (int64_t)lane * W;
-    const int64_t a = rp[i], b = rp[i + 1];
+    // row bounds are wave-uniform: keep them scalar so that the loop control and the row addresses of Z are scalar too
+    const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
+    const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
     float acc[W];
 #pragma unroll
     for (int t = 0; t < W; ++t) acc[t] = 0.f;
+    const bool full = j + W - 1 < ncols;
+    const float* zj = Z + j;
+    typedef float vecw __attribute__((ext_vector_type(W)));
 
-    if (W == 4) {
-        const bool full = j + 3 < ncols;
-        int64_t p = a;
-        for (; p + 1 < b; p += 2) {     // two gathers in flight per lane
-            const int32_t c0 = ci[p], c1 = ci[p + 1];
-            const float x0 = xv[p], x1 = xv[p + 1];
-            if (full) {
-                const float4 z0 = *reinterpret_cast<const float4*>(Z + (int64_t)c0 * ldz + j);
-                const float4 z1 = *reinterpret_cast<const float4*>(Z + (int64_t)c1 * ldz + j);
-                acc[0] = fmaf(x0, z0.x, acc[0]); acc[1] = fmaf(x0, z0.y, acc[1]);
-                acc[2] = fmaf(x0, z0.z, acc[2]); acc[3] = fmaf(x0, z0.w, acc[3]);
-                acc[0] = fmaf(x1, z1.x, acc[0]); acc[1] = fmaf(x1, z1.y, acc[1]);
-                acc[2] = fmaf(x1, z1.z, acc[2]); acc[3] = fmaf(x1, z1.w, acc[3]);
-            } else {
+    // 64 stored entries at a time: one coalesced load of (column, weight) per lane, then each entry is broadcast
+    // with readlane and its row segment of Z gathered; the gathers of a batch are independent of one another.
+    for (int64_t p0 = a; p0 < b; p0 += 64) {
+        const int cnt = (int)(b - p0 < 64 ? b - p0 : 64);
+        int cv = 0;
+        float xl = 0.f;
+        if (lane < cnt) { cv = ci[p0 + lane]; xl = xv[p0 + lane]; }
+        // lanes past the end repeat the batch's first column with weight 0: the batch can then be walked in
+        // full groups of 8 (a repeated row is a valid, finite row of Z; it contributes nothing)
+        const int c_first = __builtin_amdgcn_readfirstlane(cv);
+        if (lane >= cnt) cv = c_first;
+        const int cnt8 = (cnt + 7) & ~7;
+        if (full) {
+            for (int u = 0; u < cnt8; u += 8) {
+                vecw z[8];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (j + t < ncols) {
-                        acc[t] = fmaf(x0, Z[(int64_t)c0 * ldz + j + t], acc[t]);
-                        acc[t] = fmaf(x1, Z[(int64_t)c1 * ldz + j + t], acc[t]);
-                    }
+                for (int k = 0; k < 8; ++k)
+                    z[k] = *reinterpret_cast<const vecw*>(zj + (int64_t)__builtin_amdgcn_readlane(cv, u + k) * ldz);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xl), u + k));
+#pragma unroll
+                    for (int t = 0; t < W; ++t) acc[t] = fmaf(x, z[k][t], acc[t]);
+                }
+            }
+        } else {
+            for (int u = 0; u < cnt; ++u) {
+                const float* zr = zj + (int64_t)__builtin_amdgcn_readlane(cv, u) * ldz;
+                const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xl), u));
+#pragma unroll
+                for (int t = 0; t < W; ++t)
+                    if (j + t < ncols) acc[t] = fmaf(x, zr[t], acc[t]);
             }
         }
-        if (p < b) {
-            const int32_t c0 = ci[p];
-            const float x0 = xv[p];
-            if (full) {
-                const float4 z0 = *reinterpret_cast<const float4*>(Z + (int64_t)c0 * ldz + j);
-                acc[0] = fmaf(x0, z0.x, acc[0]); acc[1] = fmaf(x0, z0.y, acc[1]);
-                acc[2] = fmaf(x0, z0.z, acc[2]); acc[3] = fmaf(x0, z0.w, acc[3]);
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (j + t < ncols) acc[t] = fmaf(x0, Z[(int64_t)c0 * ldz + j + t], acc[t]);
-            }
-        }
-    } else {
-        if (j < ncols)
-            for (int64_t p = a; p < b; ++p) acc[0] = fmaf(xv[p], Z[(int64_t)ci[p] * ldz + j], acc[0]);
     }
 
 #pragma unroll
@@ -146,18 +149,18 @@ hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, in
         k_spmm_tmax<<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, row_tiles);
         return hipGetLastError();
     }
-    const bool vec = (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 64;
-    const int W = vec ? 4 : 1;
+    // strip width: 16-byte gathers need 16-byte aligned rows of Z; narrower strips keep more rows of the strip in cache
+    int W = 1;
+    if ((ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 256) W = 4;
+    else if ((ldz % 2 == 0) && (((uintptr_t)Z & 7) == 0) && ncols >= 128) W = 2;
     const int64_t strips = (ncols + 64 * W - 1) / (64 * W);
     const int64_t grid = (rows * strips + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (vec) {
-        if (combine == 0) k_spmm_rows<4, 0><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
-        else k_spmm_rows<4, 1><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
-    } else {
-        if (combine == 0) k_spmm_rows<1, 0><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
-        else k_spmm_rows<1, 1><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips);
-    }
+#define LAUNCH_ROWS(WW, CC) k_spmm_rows<WW, CC><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips)
+    if (W == 4) { if (combine == 0) LAUNCH_ROWS(4, 0); else LAUNCH_ROWS(4, 1); }
+    else if (W == 2) { if (combine == 0) LAUNCH_ROWS(2, 0); else LAUNCH_ROWS(2, 1); }
+    else { if (combine == 0) LAUNCH_ROWS(1, 0); else LAUNCH_ROWS(1, 1); }
+#undef LAUNCH_ROWS
     return hipGetLastError();
 }
 

@@ -258,7 +258,7 @@ size_t token_plan_bytes(int64_t nseg, int64_t nnz_batch)
     return b.used + 256;
 }
 
-bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles)
+bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles, int64_t padded_exact)
 {
     tp.nseg = nseg;
     tp.tok_bound = nnz_batch + (kGroup - 1) * nseg;
@@ -272,7 +272,8 @@ bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, i
     if (ct < 4 * kTileTokens) ct = 4 * kTileTokens;
     if (ct > 64 * kTileTokens) ct = 64 * kTileTokens;
     tp.chunk_tokens = (int32_t)ct;
-    tp.nchunks = (int32_t)((tp.tok_bound + ct - 1) / ct);
+    const int64_t tok_for_chunks = padded_exact >= 0 ? padded_exact : tp.tok_bound;
+    tp.nchunks = (int32_t)((tok_for_chunks + ct - 1) / ct);
     if (tp.nchunks < 1) tp.nchunks = 1;
     // the dry run used for sizing passes nvoc_tiles = 1, which yields the largest chunk count it can
     // ever need only if chunks never get smaller than the floor: size for the floor.
