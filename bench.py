@@ -43,7 +43,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "long"])
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "long", "short", "knn"],
+                    help="medium is the benchmark's workload; the others are the remaining workload families "
+                         "(short: one step = one batch of 4,096 database rows used as queries; knn: fused top-16)")
     ap.add_argument("--compute", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -59,6 +61,9 @@ def main():
     from paper_1711_07227_amd import binding, synth
 
     cfg = synth.CONFIGS[args.workload]
+    bf16_in = cfg.precision == "bf16"
+    if bf16_in:
+        args.compute = "bf16"
     t_gen = time.perf_counter()
     prob = synth.make(cfg)
     t_gen = time.perf_counter() - t_gen
@@ -66,13 +71,39 @@ def main():
 
     torch.cuda.set_device(0)
     E = torch.from_numpy(prob["E"]).cuda()
+    if bf16_in:
+        E = E.to(torch.bfloat16)          # the generator already rounded the values to bf16
     db = binding.Csr.from_numpy(prob["db"], v)
-    qs = binding.Csr.from_numpy(prob["queries"], v)
     ctx = binding.Context(0)
     compute = binding.BF16 if args.compute == "bf16" else binding.F32
     ctx.set_options(compute=compute)
-    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, binding.F32))
-    D = torch.empty((n, q), dtype=torch.float32, device="cuda")
+    emb_dtype = binding.BF16 if bf16_in else binding.F32
+    if cfg.queries_from_db:
+        # all-pairs sweep: step i uses database rows [i*q, (i+1)*q) as the queries
+        nb = max(args.steps + args.warmup, 1)
+        batches = []
+        for i in range(nb):
+            rows = (np.arange(q) + i * q) % n
+            batches.append(binding.Csr.from_numpy(synth.csr_rows(*prob["db"], rows), v))
+        qs = batches[0]
+        prob["queries"] = synth.csr_rows(*prob["db"], (np.arange(q) + (nb - 1) * q) % n)   # the last timed batch
+    else:
+        qs = binding.Csr.from_numpy(prob["queries"], v)
+        batches = None
+    k = cfg.topk
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, emb_dtype, k))
+    if k:
+        R_idx = torch.empty((q, k), dtype=torch.int32, device="cuda")
+        R_dist = torch.empty((q, k), dtype=torch.float32, device="cuda")
+        D = None
+    else:
+        D = torch.empty((n, q), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        if k:
+            ctx.rwmd_topk(qs, db, E, k, R_idx, R_dist, ws)
+        else:
+            ctx.rwmd(batches[i] if batches else qs, db, E, D, ws)
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -81,13 +112,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        ctx.rwmd(qs, db, E, D, ws)
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     ctx.profile_begin()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ctx.rwmd(qs, db, E, D, ws)
+    for i in range(args.steps):
+        step(args.warmup + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_end()
@@ -111,8 +142,14 @@ def main():
         rng = np.random.default_rng(1)
         pi = rng.integers(0, n, 512)
         pj = rng.integers(0, q, 512)
+        if k:    # the returned neighbours' distances, recomputed pair by pair
+            pj = rng.integers(0, q, 128)
+            pr = rng.integers(0, k, 128)
+            pi = R_idx[torch.from_numpy(pj).cuda(), torch.from_numpy(pr).cuda()].cpu().numpy().astype(np.int64)
+            got = R_dist[torch.from_numpy(pj).cuda(), torch.from_numpy(pr).cuda()].cpu().numpy().astype(np.float64)
+        else:
+            got = D[torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()].cpu().numpy().astype(np.float64)
         ref = oracle.rwmd_pairs(prob["E"], prob["db"], prob["queries"], pi, pj)
-        got = D[torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()].cpu().numpy().astype(np.float64)
         check = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-6)))
         qn = max(1, min(args.cpu_queries, q))
         sub = synth.csr_rows(*prob["queries"], np.arange(qn))
@@ -134,6 +171,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": args.compute,
+        "all_pairs_sweep_s": (n / q) * sec / args.steps if cfg.queries_from_db else None,
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: v={v} m={m} n={n} q={q} h={cfg.h_lo}-{cfg.h_hi} zipf={cfg.zipf_s}",
                    "nnz_db": db.nnz, "nnz_q": qs.nnz, "data_gen_s": round(t_gen, 1)},
