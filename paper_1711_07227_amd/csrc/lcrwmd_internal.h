@@ -117,7 +117,7 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStrea
 // phase1_tiles.hip: the direct-to-LDS tile kernel for both precisions
 bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
-hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, int32_t nsteps, const TokenPlan& tp, hipStream_t s);
+hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 
 // phase2.hip
 hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,

@@ -1,10 +1,9 @@
 // Operand packing for the bf16-in / fp32-accumulate first phase of LC-RWMD (Sec. IV, Fig. 6); the contraction
 // itself is the tile kernel in phase1_tiles.hip.
 //
-// Packed operand (pack kernel below): one row per word, `pitch` bf16 values (a multiple of 32, i.e. whole
-// 64-byte lines): columns [0, m) hold the embedding rounded to bf16 (round-to-nearest-even), then zeros,
-// and the three columns just before the end of the last 16-wide K step hold -|row|^2/2 split into three
-// bf16 terms.  A word used as a TOKEN brings these along; for a word used as VOCABULARY the kernel
+// Packed operand (pack kernel below): one row per word, 320 bf16 values (five 128-byte lines): columns [0, m)
+// hold the embedding rounded to bf16 (round-to-nearest-even), then zeros, and columns 300..302 hold -|row|^2/2
+// split into three bf16 terms.  A word used as a TOKEN brings these along; for a word used as VOCABULARY the kernel
 // overwrites the same three positions of its register copy with 1.0, so the contraction itself adds the
 // -|T_a|^2/2 term and the epilogue is a plain maximum.
 //
@@ -13,14 +12,6 @@
 namespace lcrwmd {
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int kMaxSteps = 19;            // K steps of 16 held in registers: m + 4 <= 304
-constexpr int kVocabPerWave = 64;
-constexpr int kVocabPerBlock = 256;      // 4 wavefronts
-constexpr int kRows = kTileTokens;       // 128 token rows per tile
 
 __device__ inline uint16_t f32_to_bf16_rne(float x)
 {
@@ -66,19 +57,19 @@ __global__ __launch_bounds__(256) void k_pack_bf16(const void* __restrict__ E, i
 
 }  // namespace
 
-// K steps needed for m values plus the three norm columns, and the packed row pitch in elements.
-static int32_t steps_for(int32_t m) { return (m + 4 + 15) / 16; }   // the last four columns of the last step are reserved
-bool bf16_supported(int32_t m) { return steps_for(m) <= kMaxSteps; }
-int32_t bf16_pitch(int32_t m) { return ((steps_for(m) * 16 + 31) / 32) * 32; }
-size_t pack_bf16_bytes(int64_t v, int32_t m) { return (size_t)v * (size_t)bf16_pitch(m) * 2; }
+// The packed row always has the tile kernel's shape: 320 columns, values in [0, m), zeros up to column 300, the three
+// norm terms in columns 300..302 (the last K step's upper half, elements 4..6).
+constexpr int32_t kPackPitch = 320, kNormCol = 300;
+bool bf16_supported(int32_t m) { return m <= kNormCol; }
+int32_t bf16_pitch(int32_t) { return kPackPitch; }
+size_t pack_bf16_bytes(int64_t v, int32_t) { return (size_t)v * kPackPitch * 2; }
 
 hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_t m, int64_t ld, void* packed,
                             float* normE, hipStream_t s)
 {
     if (v <= 0) return hipSuccess;
-    if (steps_for(m) > kMaxSteps) return hipErrorNotSupported;
-    const int32_t norm_col = steps_for(m) * 16 - 4;
-    k_pack_bf16<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, dtype == LCRWMD_BF16 ? 1 : 0, v, m, ld, bf16_pitch(m), norm_col,
+    if (!bf16_supported(m)) return hipErrorNotSupported;
+    k_pack_bf16<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, dtype == LCRWMD_BF16 ? 1 : 0, v, m, ld, kPackPitch, kNormCol,
                                                        (uint16_t*)packed, normE);
     return hipGetLastError();
 }
@@ -86,8 +77,8 @@ hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_
 hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
 {
     if (a.nvoc <= 0 || tp.nseg <= 0) return hipSuccess;
-    if (steps_for(a.m) > kMaxSteps) return hipErrorNotSupported;
-    return launch_phase1_tiles_bf16(a, steps_for(a.m), tp, s);
+    if (!bf16_supported(a.m)) return hipErrorNotSupported;
+    return launch_phase1_tiles_bf16(a, tp, s);
 }
 
 }  // namespace lcrwmd

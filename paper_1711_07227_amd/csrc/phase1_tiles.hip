@@ -1,5 +1,5 @@
 // First phase of LC-RWMD (Sec. IV, Fig. 6, many-to-many form): the tile kernel shared by the fp32 and the
-// bf16-in / fp32-accumulate paths.
+// bf16-in / fp32-accumulate paths, for embedding dimensions up to 300.
 //
 //   Z[w][j] = sqrt(max(|E_w|^2 - 2 * max_{a in histogram j} (T_a . E_w - |T_a|^2 / 2), 0))
 //
@@ -10,19 +10,23 @@
 // wave-uniform.  The pairwise matrix C = E o T of the paper exists only in accumulators.
 //
 // Data movement
-//   * vocabulary operand: NCT x 32 words per wavefront, the whole K extent in registers (16 bytes per K step
-//     and column tile), loaded once per workgroup;
-//   * token operand: tiles of NRT x 32 rows x the whole K extent, copied global -> LDS with
-//     global_load_lds_dwordx4 (no registers), double buffered, ONE barrier per tile.
-// Rows are handled as 16-byte pieces.  A copy instruction moves one "quad" (4 consecutive pieces = 64 bytes)
-// of 16 rows: the four lanes of a lane quad fetch 64 contiguous bytes, and lane (row r, slot s) fetches piece
-// s ^ ((r >> 2) & 3), so that the 16-byte LDS reads of 16 consecutive rows of one piece hit all 64 banks.
-// When the number of pieces is 2 mod 4 the last two pieces form a half quad (32 rows x 32 bytes per
-// instruction, swizzled with bit 3 of the row).
+//   * vocabulary operand: NCT x 32 words per wavefront, the whole K extent (304 columns) in registers, loaded
+//     once per workgroup;
+//   * token operand: tiles of 64 rows x the whole K extent, copied global -> LDS with global_load_lds_dwordx4
+//     (no registers), double buffered, ONE barrier per tile; the copy instructions of the next tile are
+//     spread over the K steps of the current one so that they never queue up behind each other.
 //
-// K step sigma covers pieces 2 sigma and 2 sigma + 1: lane half h multiplies piece 2 sigma + h of its token row
-// with the same piece of its vocabulary word.  bf16: one v_mfma_f32_32x32x16_bf16 per step; fp32: four
-// v_mfma_f32_32x32x2_f32 (one per float of the piece).
+// Rows are handled as 16-byte pieces, 8 pieces (one 128-byte cache line) to an "octet": bf16 rows are 5 octets
+// (the whole 640-byte packed row), fp32 rows 10 octets (1200 bytes = 75 pieces; the pieces past the end of the row
+// re-read piece 74 and meet zeros on the vocabulary side).  One copy instruction moves one octet of 8 rows = 1 KiB:
+// the 8 lanes of a row fetch one full line, and lane (row r, slot s) fetches piece s ^ ((r >> 1) & 7), so that the
+// later 16-byte LDS reads of 16 consecutive rows of one piece hit all 64 banks.  A tile is 40 KiB (bf16) or 80 KiB
+// (fp32); with two buffers, two bf16 workgroups or one fp32 workgroup fill the CU's 160 KiB of LDS exactly.
+//
+// K step s covers pieces 2 s and 2 s + 1: lane half h multiplies piece 2 s + h of its token row with the same
+// piece of its vocabulary word.  bf16: one v_mfma_f32_32x32x16_bf16 per step and tile; fp32: four
+// v_mfma_f32_32x32x2_f32 (one per float of the piece).  The LDS reads of step s + 1 are issued before the MFMAs
+// of step s and waited for with a partial lgkmcnt.
 #include <type_traits>
 
 #include "lcrwmd_internal.h"
@@ -47,7 +51,7 @@ __device__ inline void static_for(F&& f)
 
 // Issue one 16-byte LDS read WITHOUT waiting for it.  The destination registers are written asynchronously; the
 // caller waits with s_waitcnt lgkmcnt before using them.  The compiler is deliberately not told about the latency:
-// its own wait insertion drains the whole LDS queue before every use, which exposes a full LDS round trip per K step.
+// its own wait insertion drains the whole LDS queue before every use.
 template <int OFF>
 __device__ inline f32x4 lds_read16_nowait(uint32_t addr)
 {
@@ -62,8 +66,7 @@ __device__ inline f32x4 lds_read16_nowait(uint32_t addr)
 struct P1T {
     const unsigned char* Eb;   // operand rows (fp32: caller's E; bf16: packed copy)
     int64_t pitch_b;           // bytes per row
-    int32_t npieces;           // 16-byte pieces copied per row (even)
-    int32_t nreal;             // pieces that exist in memory; copies of later pieces re-read piece nreal - 1
+    int32_t nreal;             // 16-byte pieces that exist in a row; later pieces re-read piece nreal - 1
     int32_t nzero_from;        // fp32: vocabulary values at K index >= this are zero (= m)
     const float* normE;
     const int32_t* voc_rows;
@@ -80,19 +83,24 @@ struct P1T {
     int64_t ldz;
 };
 
-// NS > 0 fixes the number of K steps at compile time (the m = 300 case): every guard on the step count folds away
-// and a tile's contraction becomes one straight-line block, which lets the LDS reads of the next steps be issued
-// under the MFMAs of the current one.  NS = 0 reads the step count from the arguments.
-template <bool BF16, int NRT, int NCT, int WGS_PER_CU, int NS>
+constexpr int ROWS = 64;      // token rows per tile
+constexpr int NRT = 2;        // 32-row MFMA tiles per token tile
+
+template <bool BF16>
+struct Layout {
+    static constexpr int NS = BF16 ? 19 : 38;                 // K steps (pairs of pieces): 304 columns
+    static constexpr int NOCT = BF16 ? 5 : 10;                // octets copied per row
+    static constexpr int OCT_BYTES = (ROWS / 8) * 1024;       // one octet of all rows of the tile
+    static constexpr int TILE_BYTES = NOCT * OCT_BYTES;
+    static constexpr int NJOBS = NOCT * (ROWS / 8) / 4;       // copy instructions per wavefront and tile
+};
+
+template <bool BF16, int NCT, int WGS_PER_CU>
 __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 {
-    constexpr int ROWS = NRT * 32;
-    constexpr int RB = ROWS / 16;              // 16-row blocks per tile
-    constexpr int NR = RB / 4;                 // token rows a lane copies per quad pass (RB = 4 or 8)
-    constexpr int QUAD_BYTES = RB * 1024;
-    constexpr int MAXS = BF16 ? 19 : 38;       // K steps held in registers (304 columns)
+    using L = Layout<BF16>;
+    constexpr int NS = L::NS;
     constexpr int NG = ROWS / 8;               // token groups per tile
-    static_assert(RB == 4 || RB == 8, "tiles of 64 or 128 rows");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -115,18 +123,13 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     const int t0 = p.pofs[s0], t1 = p.pofs[s1];
     if (t0 >= t1) return;
 
-    const int npieces = NS ? 2 * NS : p.npieces;
-    const int nsteps = npieces >> 1;
-    const int full_quads = npieces >> 2;
-    const bool half_quad = (npieces & 3) != 0;
-    const int tbytes = full_quads * QUAD_BYTES + (half_quad ? NRT * 1024 : 0);
     const unsigned char* Eb = p.Eb;
 
     // ---- vocabulary operand -> registers ----
     bool col_ok[NCT];
     float nEw[NCT];
-    float* zout[NCT];
-    f32x4 breg[MAXS][NCT];
+    int32_t zrow[NCT];          // row of Z this lane writes (pointer formed at flush time: registers are scarce)
+    f32x4 breg[NS][NCT];
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct) {
         const int64_t col = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
@@ -134,19 +137,16 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         const int64_t colc = col_ok[ct] ? col : p.nvoc - 1;
         const int32_t wid = p.voc_rows ? p.voc_rows[colc] : (int32_t)colc;
         nEw[ct] = p.normE[wid];
-        zout[ct] = p.Z + (p.z_by_position ? colc : (int64_t)wid) * p.ldz;
+        zrow[ct] = p.z_by_position ? (int32_t)colc : wid;
         const unsigned char* row = Eb + (int64_t)wid * p.pitch_b;
 #pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            f32x4 x = {0.f, 0.f, 0.f, 0.f};
-            if (s < nsteps) {
-                const int piece = 2 * s + half;
-                x = *reinterpret_cast<const f32x4*>(row + (piece < p.nreal ? piece : p.nreal - 1) * 16);
-                if (!BF16) {   // zero beyond the embedding dimension (a re-read piece, or the tail of the last one)
+        for (int s = 0; s < NS; ++s) {
+            const int piece = 2 * s + half;
+            f32x4 x = *reinterpret_cast<const f32x4*>(row + (piece < p.nreal ? piece : p.nreal - 1) * 16);
+            if (!BF16) {   // zero beyond the embedding dimension (a re-read piece, or the tail of the last one)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        if (piece * 4 + t >= p.nzero_from) x[t] = 0.f;
-                }
+                for (int t = 0; t < 4; ++t)
+                    if (piece * 4 + t >= p.nzero_from) x[t] = 0.f;
             }
             breg[s][ct] = x;
         }
@@ -156,70 +156,44 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         // vocabulary side those positions multiply by one
         if (half == 1) {
 #pragma unroll
-            for (int s = 0; s < MAXS; ++s) {
-                if (s == nsteps - 1) {
-#pragma unroll
-                    for (int ct = 0; ct < NCT; ++ct) {
-                        breg[s][ct][2] = __uint_as_float(0x3F803F80u);   // elements 4, 5 = 1.0
-                        breg[s][ct][3] = __uint_as_float(0x00003F80u);   // element 6 = 1.0, element 7 = 0
-                    }
-                }
+            for (int ct = 0; ct < NCT; ++ct) {
+                breg[NS - 1][ct][2] = __uint_as_float(0x3F803F80u);   // elements 4, 5 = 1.0
+                breg[NS - 1][ct][3] = __uint_as_float(0x00003F80u);   // element 6 = 1.0, element 7 = 0
             }
         }
     }
 
-    // ---- copy jobs of this wavefront: job j = 4 i + wave; full quads: quad j / RB, row block j % RB ----
-    const int njobs_full = full_quads * RB;
-    const int pieceF = (lane & 3) ^ ((lane >> 4) & 3);
-    const int pieceH = (lane & 1) ^ ((lane >> 4) & 1);
-    const int rowF = wave * 16 + (lane >> 2);           // + 64 for the second row of a lane when RB == 8
-    const int rowH = (wave % NRT) * 32 + (lane >> 1);   // half quad: waves 0 .. NRT-1 each copy one 32-row block
+    // ---- copy jobs of this wavefront ----
+    // job J -> octet J / 2, row block (of 8 rows) wave + 4 (J % 2); lane -> row lane / 8, slot lane % 8
+    const int rowA = wave * 8 + (lane >> 3);                       // J even; J odd: + 32
+    const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
+    const uint32_t offO = pieceO * 16;
+    // the last octet may reach past the end of the row (fp32: pieces 75..79): re-read the last real piece
+    const int last_piece = (L::NOCT - 1) * 8 + pieceO;
+    const uint32_t off_last = (last_piece < p.nreal ? last_piece : p.nreal - 1) * 16;
 
-    // word ids of the token rows this lane copies, fetched one tile ahead of the copy that uses them
-    int32_t wF[NR], wH = 0;
+    // Word ids of the two token rows this lane copies.  They are fetched when the previous tile's copy jobs have
+    // all been issued (one pair of registers serves both) and are multiplied out to byte offsets job by job.
+    int32_t wA = 0, wB = 0;
     auto load_words = [&](int tb) {
-#pragma unroll
-        for (int k = 0; k < NR; ++k) wF[k] = p.tok_ids[tb + rowF + 64 * k];
-        if (half_quad) wH = p.tok_ids[tb + rowH];
+        wA = p.tok_ids[tb + rowA];
+        wB = p.tok_ids[tb + rowA + 32];
     };
-    // Job i of this wavefront is (quad, row block) = ((4 i + wave) / RB, (4 i + wave) % RB): with RB = 4 that is
-    // (i, wave), with RB = 8 it is (i / 2, wave + 4 (i % 2)) - static per i, so the loop unrolls into straight code.
-    constexpr int MAXJ = (RB == 4) ? 19 : 18;   // at most 19 full quads (RB = 4) or 9 (RB = 8)
-    const int offF = pieceF * 16;
-    // pieces past the end of the row (fp32 with an odd piece count) re-read the last real piece
-    const int last_piece = (full_quads - 1) * 4 + pieceF;
-    const int off_last = (last_piece < p.nreal ? last_piece : p.nreal - 1) * 16;
-    auto issue_tile_copy = [&](int buf) {
-        const unsigned char* g[NR];
-#pragma unroll
-        for (int k = 0; k < NR; ++k) g[k] = Eb + (int64_t)wF[k] * p.pitch_b;
-        unsigned char* lbase = smem + buf * tbytes + wave * 1024;
-#pragma unroll
-        for (int i = 0; i < MAXJ; ++i) {
-            const int quad = (RB == 4) ? i : (i >> 1);
-            if (quad < full_quads) {
-                const int rbk = (RB == 4) ? 0 : (i & 1);
-                const int off = (quad == full_quads - 1) ? off_last : quad * 64 + offF;
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(g[rbk] + off),
-                    (__attribute__((address_space(3))) void*)(lbase + (quad * RB + rbk * 4) * 1024), 16, 0, 0);
-            }
-        }
-        if (half_quad && wave < NRT) {
-            int piece = full_quads * 4 + pieceH;
-            if (piece >= p.nreal) piece = p.nreal - 1;
-            const unsigned char* src = Eb + (int64_t)wH * p.pitch_b + piece * 16;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(lbase + njobs_full * 1024), 16, 0, 0);
-        }
+    const uint32_t pitch32 = (uint32_t)p.pitch_b;     // the host guarantees rows * pitch < 2^32
+    // copy job J (compile time) of this wavefront into buffer `lbase`
+    auto copy_job = [&](auto j_c, unsigned char* lbase) {
+        constexpr int J = decltype(j_c)::value;
+        constexpr int oct = J >> 1;
+        const uint32_t off = (uint32_t)((J & 1) ? wB : wA) * pitch32 + (oct == L::NOCT - 1 ? off_last : offO + oct * 128);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + off),
+                                         (__attribute__((address_space(3))) void*)(lbase + (oct * 8 + (J & 1) * 4 + wave) * 1024),
+                                         16, 0, 0);
     };
 
-    // ---- LDS read offsets of this lane (bytes) for even / odd K steps and for the half quad ----
-    const int rsw = (lane >> 2) & 3;
-    const int row_off = (((lane >> 4) & 1) * 64 + 4 * (lane & 15)) * 16;
-    const int off_even = row_off + ((0 + half) ^ rsw) * 16;
-    const int off_odd = row_off + ((2 + half) ^ rsw) * 16;
-    const int off_half = (2 * l31 + (half ^ ((lane >> 3) & 1))) * 16;
+    // ---- LDS read address of this lane (bytes) ----
+    // row block (l31 >> 3), row (l31 & 7), slot (2 k + half) ^ ((l31 >> 1) & 7) for k = s & 3: k enters as an XOR of bits 5..6
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    uint32_t a_oct = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
 
     f32x16 acc[NRT][NCT];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -231,11 +205,12 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         if (cur >= 0) {
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                // both lane halves hold 8 of the 16 rows of a group pair: exchange and combine
+                // both lane halves hold 4 of the 8 rows of every group: exchange and combine
                 const unsigned r = __float_as_uint(run[ct]);
                 const auto sw = __builtin_amdgcn_permlane32_swap(r, r, false, false);
                 const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                if (half == 0 && col_ok[ct]) zout[ct][cur] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * best, 0.f));
+                if (half == 0 && col_ok[ct])
+                    p.Z[(int64_t)zrow[ct] * p.ldz + cur] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * best, 0.f));
             }
         }
     };
@@ -248,12 +223,14 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         for (int rt = 0; rt < NRT; ++rt) h[rt] = p.tok_hn[tb + rt * 32 + l31];
     };
 
+    // first tile: copy it in one go
     load_words(t0);
-    issue_tile_copy(0);
+    static_for<0, L::NJOBS>([&](auto j_c) { copy_job(j_c, smem); });
     if (t0 + ROWS < t1) load_words(t0 + ROWS);
     int gsv = load_gs(t0), gsv_next = 0;
     if (!BF16) load_hn(t0, hn);
     int buf = 0;
+
 #ifdef DBG_TIMING
     long long tacc[6] = {0, 0, 0, 0, 0, 0};
     long long tprev = clock64();
@@ -266,102 +243,68 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         DBG_T(0)
         __syncthreads();                        // ... and everyone's; everyone has left the other buffer
         DBG_T(1)
-        if (tb + ROWS < t1) {
-#ifndef DBG_NO_COPY
-            issue_tile_copy(buf ^ 1);                           // word ids were fetched during the previous tile
-#endif
-            if (tb + 2 * ROWS < t1) load_words(tb + 2 * ROWS);
+        const bool more = tb + ROWS < t1;
+        unsigned char* next_buf = smem + (buf ^ 1) * L::TILE_BYTES;
+        if (more) {
             gsv_next = load_gs(tb + ROWS);
             if (!BF16) load_hn(tb + ROWS, hn_next);
         }
         DBG_T(2)
 
         // Software pipeline over the K steps: the LDS reads of step s + 1 are issued before the MFMAs of step s,
-        // into the other of two fragment register sets.
-        if constexpr (NS > 0) {
-            constexpr bool HALFQ = (NS & 1) != 0;                 // 2 NS pieces: a half quad iff NS is odd
-            constexpr int FULLQ = (2 * NS) >> 2;
-            const uint32_t abase =
-                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem + (uint32_t)(buf * tbytes);
-            const uint32_t addr_even = abase + off_even, addr_odd = abase + off_odd, addr_half = abase + off_half;
-            f32x4 afrag[2][NRT];
-            auto issue_reads = [&](auto s_c) {
-                constexpr int s = decltype(s_c)::value;
-                constexpr bool in_half = HALFQ && (s == NS - 1);
-                constexpr int region = in_half ? FULLQ * QUAD_BYTES : (s >> 1) * QUAD_BYTES;
-                constexpr int stride = in_half ? 1024 : 2048;
-                static_for<0, NRT>([&](auto rt_c) {
-                    constexpr int rt = decltype(rt_c)::value;
-                    constexpr int total = region + rt * stride;
-                    constexpr int win = total / 32768;             // keep the immediate offset below 2^15
-                    const uint32_t base = (in_half ? addr_half : ((s & 1) ? addr_odd : addr_even)) + win * 32768;
-                    afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
-                });
-            };
-            issue_reads(std::integral_constant<int, 0>{});
-            static_for<0, NS>([&](auto s_c) {
-                constexpr int s = decltype(s_c)::value;
-                if constexpr (s + 1 < NS) {
-                    issue_reads(std::integral_constant<int, s + 1>{});
-                    LCRWMD_WAIT_LGKM(NRT);          // everything but the reads just issued has arrived
-                } else {
-                    LCRWMD_WAIT_LGKM(0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                const f32x4* a = afrag[s & 1];
-                if constexpr (BF16) {
+        // into the other of two fragment register sets; one copy instruction of the next tile rides along every
+        // COPY_EVERY steps.
+        f32x4 afrag[2][NRT];
+        auto issue_reads = [&](auto s_c) {
+            constexpr int s = decltype(s_c)::value;
+            static_for<0, NRT>([&](auto rt_c) {
+                constexpr int rt = decltype(rt_c)::value;
+                constexpr int total = (s >> 2) * L::OCT_BYTES + rt * 4096;
+                constexpr int win = total / 32768;             // keep the immediate offset below 2^15
+                const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
+                afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+            });
+        };
+        constexpr int COPY_EVERY = NS / L::NJOBS;
+        issue_reads(std::integral_constant<int, 0>{});
+        static_for<0, NS>([&](auto s_c) {
+            constexpr int s = decltype(s_c)::value;
+            if constexpr (s + 1 < NS) {
+                issue_reads(std::integral_constant<int, s + 1>{});
+                LCRWMD_WAIT_LGKM(NRT);          // everything but the reads just issued has arrived
+            } else {
+                LCRWMD_WAIT_LGKM(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const f32x4* a = afrag[s & 1];
+            if constexpr (BF16) {
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ++ct)
+                        acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                            s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
                         for (int ct = 0; ct < NCT; ++ct)
-                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
-                                s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-                            for (int ct = 0; ct < NCT; ++ct)
-                                acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                    a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        } else {
-            const unsigned char* A = smem + buf * tbytes;
-#pragma unroll
-            for (int s = 0; s < MAXS; ++s) {
-                if (s < nsteps) {
-                    const bool in_half = half_quad && (s == nsteps - 1);
-                    const unsigned char* base = in_half ? A + full_quads * QUAD_BYTES + off_half
-                                                        : A + (s >> 1) * QUAD_BYTES + ((s & 1) ? off_odd : off_even);
-                    const int rstride = in_half ? 1024 : 2048;
-                    f32x4 a[NRT];
-#pragma unroll
-                    for (int rt = 0; rt < NRT; ++rt) a[rt] = *reinterpret_cast<const f32x4*>(base + rt * rstride);
-                    if (BF16) {
-#pragma unroll
-                        for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-                            for (int ct = 0; ct < NCT; ++ct)
-                                acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                    __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
-                                    s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t)
-#pragma unroll
-                            for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-                                for (int ct = 0; ct < NCT; ++ct)
-                                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                        a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
-                    }
-                }
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
             }
-        }
+#ifndef DBG_NO_COPY
+            if constexpr (s % COPY_EVERY == 0 && s / COPY_EVERY < L::NJOBS) {
+                if (more) copy_job(std::integral_constant<int, s / COPY_EVERY>{}, next_buf);
+            }
+            if constexpr (s == COPY_EVERY * (L::NJOBS - 1) + 1) {     // all copy jobs issued: fetch the ids for the tile after next
+                if (tb + 2 * ROWS < t1) load_words(tb + 2 * ROWS);
+            }
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+        });
         if (!BF16) {
             // one more rank-1 step adds -|T_a|^2/2 to every element of token row a
             const float one = half == 0 ? 1.f : 0.f;
@@ -371,8 +314,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 for (int ct = 0; ct < NCT; ++ct)
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(half == 0 ? hn[rt] : 0.f, one, acc[rt][ct], 0, 0, 0);
         }
-
         DBG_T(3)
+
         // Epilogue: registers 4g'..4g'+3 of row tile rt hold token rows 32 rt + 8 g' + 4 half + {0..3}: group 4 rt + g'.
         int ng = (t1 - tb) >> 3;
         if (ng > NG) ng = NG;
@@ -411,6 +354,9 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #pragma unroll
             for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
         }
+        {   // the other buffer is read next
+            a_oct += buf ? -L::TILE_BYTES : L::TILE_BYTES;
+        }
         buf ^= 1;
         DBG_T(4)
     }
@@ -423,23 +369,22 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #endif
 }
 
-template <bool BF16, int NRT, int NCT, int WGS_PER_CU, int NS>
+template <bool BF16, int NCT, int WGS_PER_CU>
 hipError_t launch_tiles(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
     const int64_t items = (int64_t)d.nvt * d.nchunks;
     const int64_t grid = (items + 7) / 8 * 8;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int full_quads = d.npieces >> 2;
-    const size_t smem = 2 * ((size_t)full_quads * (NRT * 2 * 1024) + ((d.npieces & 3) ? NRT * 1024 : 0));
-    static size_t attr_set = 0;
-    if (smem > attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NRT, NCT, WGS_PER_CU, NS>),
+    const size_t smem = 2 * (size_t)Layout<BF16>::TILE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NCT, WGS_PER_CU>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_set = smem;
+        attr_set = true;
     }
-    k_phase1_tiles<BF16, NRT, NCT, WGS_PER_CU, NS><<<(unsigned)grid, 256, smem, s>>>(d);
+    k_phase1_tiles<BF16, NCT, WGS_PER_CU><<<(unsigned)grid, 256, smem, s>>>(d);
     return hipGetLastError();
 }
 
@@ -465,9 +410,11 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
 
 }  // namespace
 
+// fp32 rows are read in place: 300 values (75 whole 16-byte pieces; the 76th piece of the layout re-reads the 75th)
+// in 16-byte aligned rows.  Other shapes take the register-staged kernels of phase1_f32.hip.
 bool tiles_f32_supported(const Phase1Args& a)
 {
-    return a.m <= 300 && a.m % 4 == 0 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0;
+    return a.m == 300 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0;
 }
 
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
@@ -475,25 +422,18 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     P1T d = common_args(a, tp);
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
-    d.npieces = (d.nreal + 1) & ~1;
     d.nzero_from = a.m;
-#ifdef DBG_F32_NCT1
-    if (d.npieces == 76) return launch_tiles<false, 2, 1, 1, 38>(d, s);
-#endif
-    if (d.npieces == 76) return launch_tiles<false, 2, 2, 1, 38>(d, s);   // m = 300
-    return launch_tiles<false, 2, 2, 1, 0>(d, s);
+    return launch_tiles<false, 2, 1>(d, s);
 }
 
-// a.E is the packed bf16 copy, a.ld its pitch in elements; nsteps K steps of 16 are in use
-hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, int32_t nsteps, const TokenPlan& tp, hipStream_t s)
+// a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
+hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
 {
     P1T d = common_args(a, tp);
     d.pitch_b = a.ld * 2;
-    d.npieces = 2 * nsteps;
-    d.nreal = d.npieces;
+    d.nreal = Layout<true>::NOCT * 8;
     d.nzero_from = 0;
-    if (nsteps == 19) return launch_tiles<true, 2, 2, 2, 19>(d, s);       // m = 300
-    return launch_tiles<true, 2, 2, 2, 0>(d, s);
+    return launch_tiles<true, 2, 2>(d, s);
 }
 
 }  // namespace lcrwmd
