@@ -187,12 +187,13 @@ lcrwmd_status run_spmm(lcrwmd_ctx* ctx, const int64_t* rp, const int32_t* ci, co
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
-size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, bool bf16)
+size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, bool bf16)
 {
     size_t b = emb_prep_bytes(v, m, bf16);
-    b += 3 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position map of the queries
+    b += 4 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position maps of both sets
     b += (size_t)(v < nnz_q ? v : nnz_q) * 4 + 256;   // word list of the queries
     b += (size_t)nnz_q * 4 + 256;             // query columns renumbered to positions
+    b += (size_t)nnz_db * 4 + 256;            // database columns renumbered to positions
     b += 1024;                                // counters
     return b;
 }
@@ -263,6 +264,8 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     // swapped pass only the words of the queries.
     int32_t* flags = b.take_n<int32_t>((size_t)v);
     int32_t* list_db = b.take_n<int32_t>((size_t)v);
+    int32_t* map_db = b.take_n<int32_t>((size_t)v);
+    int32_t* dbcol_pos = b.take_n<int32_t>((size_t)DB->nnz);
     int32_t* map_q = b.take_n<int32_t>((size_t)v);
     int32_t* list_q = b.take_n<int32_t>((size_t)(v < nnz_q ? v : nnz_q));
     int32_t* qcol_pos = b.take_n<int32_t>((size_t)nnz_q);
@@ -270,7 +273,8 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
 
     HIP_TRY(launch_fill_i32(flags, v, 0, s));
     HIP_TRY(launch_mark_words(DB->col_idx, DB->nnz, flags, s));
-    HIP_TRY(launch_compact_words(flags, v, list_db, nullptr, counters + 0, s));
+    HIP_TRY(launch_compact_words(flags, v, list_db, map_db, counters + 0, s));
+    HIP_TRY(launch_remap_cols(DB->col_idx, DB->nnz, map_db, dbcol_pos, s));
     HIP_TRY(launch_fill_i32(flags, v, 0, s));
     HIP_TRY(launch_mark_words(Q->col_idx + qoff, nnz_q, flags, s));
     HIP_TRY(launch_compact_words(flags, v, list_q, map_q, counters + 1, s));
@@ -301,11 +305,11 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         TokenPlan tp;
         carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], nvt_f, padded_tokens(rq, j0, j1));
         const int64_t ldz = round_up(j1 - j0, 4);
-        float* Z = bb.take_n<float>((size_t)v * ldz);
+        float* Z = bb.take_n<float>((size_t)ve * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
-        ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/0, /*zero_map=*/nullptr, Q->row_ptr + j0,
+        ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/1, /*zero_map=*/map_db, Q->row_ptr + j0,
                           Q->col_idx, rq[j1] - rq[j0], tp, Z, ldz, s));
-        ST_TRY(run_spmm(ctx, DB->row_ptr, DB->col_idx, DB->val, n, DB->nnz, ve, Z, ldz, j1 - j0, D + (j0 - jq0), ldd, 0, s));
+        ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, j1 - j0, D + (j0 - jq0), ldd, 0, s));
     }
 
     // ---- swapped: cost of moving the queries onto database docs, D = max(D1, (X2 * Z')^T) ----
@@ -462,7 +466,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     int64_t nb = n < 16384 ? n : 16384;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
     const int64_t vq = v < nnz_q ? v : nnz_q;
-    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, bf16);
+    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16);
     size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
     size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
     size_t total = fixed + (f > r ? f : r) + 4096;
@@ -579,7 +583,7 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     const bool bf16 = use_bf16(ctx, E);
     for (;;) {
         size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
-        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, bf16) +
+        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16) +
                       fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
         if (need <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query tile of D");

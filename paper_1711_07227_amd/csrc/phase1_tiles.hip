@@ -71,7 +71,6 @@ struct P1T {
     const float* normE;
     const int32_t* voc_rows;
     int64_t nvoc;
-    int32_t z_by_position;
     int32_t nvt;
     int32_t nchunks;
     const int32_t* pofs;
@@ -126,18 +125,17 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     const unsigned char* Eb = p.Eb;
 
     // ---- vocabulary operand -> registers ----
-    bool col_ok[NCT];
+    // Lanes past the end of the vocabulary repeat its last word: they compute and store the same value to the same
+    // place as the lane that owns it.  Z is written by position in the vocabulary list (registers are scarce: the
+    // row pointer is formed at flush time from the lane id).
     float nEw[NCT];
-    int32_t zrow[NCT];          // row of Z this lane writes (pointer formed at flush time: registers are scarce)
     f32x4 breg[NS][NCT];
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct) {
         const int64_t col = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
-        col_ok[ct] = col < p.nvoc;
-        const int64_t colc = col_ok[ct] ? col : p.nvoc - 1;
+        const int64_t colc = col < p.nvoc ? col : p.nvoc - 1;
         const int32_t wid = p.voc_rows ? p.voc_rows[colc] : (int32_t)colc;
         nEw[ct] = p.normE[wid];
-        zrow[ct] = p.z_by_position ? (int32_t)colc : wid;
         const unsigned char* row = Eb + (int64_t)wid * p.pitch_b;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
@@ -165,19 +163,20 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 
     // ---- copy jobs of this wavefront ----
     // job J -> octet J / 2, row block (of 8 rows) wave + 4 (J % 2); lane -> row lane / 8, slot lane % 8
-    const int rowA = wave * 8 + (lane >> 3);                       // J even; J odd: + 32
+    const int lane8 = lane >> 3;                                   // row within an 8-row block; also this lane's token group
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
     const uint32_t offO = pieceO * 16;
-    // the last octet may reach past the end of the row (fp32: pieces 75..79): re-read the last real piece
+    // fp32: the last octet reaches past the end of the row (pieces 75..79): re-read the last real piece
     const int last_piece = (L::NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = (last_piece < p.nreal ? last_piece : p.nreal - 1) * 16;
+    const uint32_t off_last = BF16 ? offO + (L::NOCT - 1) * 128 : (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16);
 
     // Word ids of the two token rows this lane copies.  They are fetched when the previous tile's copy jobs have
     // all been issued (one pair of registers serves both) and are multiplied out to byte offsets job by job.
     int32_t wA = 0, wB = 0;
     auto load_words = [&](int tb) {
-        wA = p.tok_ids[tb + rowA];
-        wB = p.tok_ids[tb + rowA + 32];
+        const int32_t* t = p.tok_ids + (tb + wave * 8);             // scalar part of the address
+        wA = t[lane8];
+        wB = t[lane8 + 32];
     };
     const uint32_t pitch32 = (uint32_t)p.pitch_b;     // the host guarantees rows * pitch < 2^32
     // copy job J (compile time) of this wavefront into buffer `lbase`
@@ -209,14 +208,17 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 const unsigned r = __float_as_uint(run[ct]);
                 const auto sw = __builtin_amdgcn_permlane32_swap(r, r, false, false);
                 const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                if (half == 0 && col_ok[ct])
-                    p.Z[(int64_t)zrow[ct] * p.ldz + cur] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * best, 0.f));
+                if (half == 0) {
+                    int64_t pos = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
+                    if (pos >= p.nvoc) pos = p.nvoc - 1;
+                    p.Z[pos * p.ldz + cur] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * best, 0.f));
+                }
             }
         }
     };
 
     // per-tile side data, fetched one tile ahead: group -> histogram (lane g < NG) and, fp32, -|T|^2/2 per row
-    auto load_gs = [&](int tb) { return p.grp_seg[(tb >> 3) + (lane & (NG - 1))]; };
+    auto load_gs = [&](int tb) { return (p.grp_seg + (tb >> 3))[lane8]; };      // lanes 8 g .. 8 g + 7 hold group g
     float hn[NRT], hn_next[NRT];
     auto load_hn = [&](int tb, float* h) {
 #pragma unroll
@@ -227,13 +229,14 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     load_words(t0);
     static_for<0, L::NJOBS>([&](auto j_c) { copy_job(j_c, smem); });
     if (t0 + ROWS < t1) load_words(t0 + ROWS);
-    int gsv = load_gs(t0), gsv_next = 0;
+    int gsv = load_gs(t0);
     if (!BF16) load_hn(t0, hn);
     int buf = 0;
 
 #ifdef DBG_TIMING
     long long tacc[6] = {0, 0, 0, 0, 0, 0};
     long long tprev = clock64();
+    const long long dbg_c0 = tprev, dbg_w0 = wall_clock64();
 #define DBG_T(k) { long long tn = clock64(); tacc[k] += tn - tprev; tprev = tn; }
 #else
 #define DBG_T(k)
@@ -246,7 +249,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         const bool more = tb + ROWS < t1;
         unsigned char* next_buf = smem + (buf ^ 1) * L::TILE_BYTES;
         if (more) {
-            gsv_next = load_gs(tb + ROWS);
             if (!BF16) load_hn(tb + ROWS, hn_next);
         }
         DBG_T(2)
@@ -319,6 +321,11 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         // Epilogue: registers 4g'..4g'+3 of row tile rt hold token rows 32 rt + 8 g' + 4 half + {0..3}: group 4 rt + g'.
         int ng = (t1 - tb) >> 3;
         if (ng > NG) ng = NG;
+        // the groups' histograms move to scalar registers; the register then takes the next tile's (one tile ahead)
+        int sgs[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) sgs[g] = __builtin_amdgcn_readlane(gsv, 8 * g);
+        if (more) gsv = load_gs(tb + ROWS);
 #ifdef DBG_NO_EPI
         cur = s0;
 #pragma unroll
@@ -332,7 +339,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             if (g < ng) {
-                const int sg = __builtin_amdgcn_readlane(gsv, g);
+                const int sg = sgs[g];
                 const int rt = g >> 2, r0 = (g & 3) * 4;
                 float mg[NCT];
 #pragma unroll
@@ -349,7 +356,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 }
             }
         }
-        gsv = gsv_next;
         if (!BF16) {
 #pragma unroll
             for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
@@ -365,6 +371,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     if (blockIdx.x == 0 && tid == 0) {
         for (int k = 0; k < 5; ++k) p.Z[k] = (float)tacc[k];
         p.Z[5] = (float)((t1 - t0) / ROWS);
+        p.Z[6] = (float)(clock64() - dbg_c0);
+        p.Z[7] = (float)(wall_clock64() - dbg_w0);
     }
 #endif
 }
@@ -395,7 +403,6 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
     d.normE = a.normE;
     d.voc_rows = a.voc_rows;
     d.nvoc = a.nvoc;
-    d.z_by_position = a.z_by_position;
     d.nvt = 0;
     d.nchunks = tp.nchunks;
     d.pofs = tp.pofs;
