@@ -82,6 +82,16 @@ typedef struct {
                                        X2 is divided into batches); 0 = chosen from the workspace     */
     int64_t max_db_batch;           /* same for the database rows handled per pass of the swapped
                                        direction; 0 = chosen from the workspace                      */
+    int dedup;                      /* 1: lcrwmd_rwmd / lcrwmd_rwmd_topk use the de-duplicated form: the
+                                       Euclidean distances between the distinct words of the database and
+                                       the distinct words of a query batch are computed once, as one
+                                       table (the operator of Sec. III on the two reduced vocabularies),
+                                       and both passes take their minima from it.  Same result as the
+                                       default up to fp32 summation order.  The table lives in the
+                                       workspace (4 bytes x distinct database words x distinct query
+                                       words); when it does not fit, or for fp32 E with m != 300, the call
+                                       silently runs the default form.  0 (default): distances are
+                                       recomputed per stored entry, as the paper's two phases do.      */
 } lcrwmd_options;
 
 /* Create a context bound to HIP device `device`.  No device memory is allocated. */
@@ -91,7 +101,7 @@ void lcrwmd_destroy(lcrwmd_ctx* ctx);
 /* Text for the last non-OK status returned on this context (owned by the context; "" if none). */
 const char* lcrwmd_last_error(const lcrwmd_ctx* ctx);
 
-/* Copy the options in / out.  Defaults: validate 0, compute LCRWMD_F32, batches 0. */
+/* Copy the options in / out.  Defaults: validate 0, compute LCRWMD_F32, batches 0, dedup 0. */
 lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt);
 lcrwmd_status lcrwmd_get_options(const lcrwmd_ctx* ctx, lcrwmd_options* opt);
 
@@ -100,6 +110,8 @@ lcrwmd_status lcrwmd_get_options(const lcrwmd_ctx* ctx, lcrwmd_options* opt);
  * preferred batch sizes.  lcrwmd_rwmd and lcrwmd_rwmd_topk also run with less, in smaller
  * batches, down to a floor below which they return LCRWMD_EWORKSPACE.
  * nnz_db / nnz_q are the stored entries of X1 / X2; k = 0 when no top-k is wanted.
+ * With the dedup option set the figure includes the word-pair table at its upper bound
+ * (distinct words <= stored entries); any size that suffices without the option still works.
  */
 lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db,
                                      int64_t q, int64_t nnz_q, lcrwmd_dtype emb_dtype, int k,
@@ -186,6 +198,10 @@ lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q,
 typedef struct {
     double phase1_ms;  int64_t phase1_launches;  double phase1_flops;
     double phase2_ms;  int64_t phase2_launches;  double phase2_bytes;  double phase2_gather_bytes;
+    /* dedup option: the table build counts as first-phase work (2 * distinct database words * distinct query
+       words * m flops); the two table passes are timed here, bytes = table rows streamed + outputs. */
+    double table_fwd_ms;  int64_t table_fwd_launches;  double table_fwd_bytes;
+    double table_rev_ms;  int64_t table_rev_launches;  double table_rev_bytes;
 } lcrwmd_profile;
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);

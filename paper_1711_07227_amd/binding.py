@@ -41,13 +41,15 @@ class EmbStruct(ctypes.Structure):
 
 class OptionsStruct(ctypes.Structure):
     _fields_ = [("validate", ctypes.c_int), ("compute", ctypes.c_int),
-                ("max_query_batch", ctypes.c_int64), ("max_db_batch", ctypes.c_int64)]
+                ("max_query_batch", ctypes.c_int64), ("max_db_batch", ctypes.c_int64), ("dedup", ctypes.c_int)]
 
 
 class ProfileStruct(ctypes.Structure):
     _fields_ = [("phase1_ms", ctypes.c_double), ("phase1_launches", ctypes.c_int64), ("phase1_flops", ctypes.c_double),
                 ("phase2_ms", ctypes.c_double), ("phase2_launches", ctypes.c_int64), ("phase2_bytes", ctypes.c_double),
-                ("phase2_gather_bytes", ctypes.c_double)]
+                ("phase2_gather_bytes", ctypes.c_double),
+                ("table_fwd_ms", ctypes.c_double), ("table_fwd_launches", ctypes.c_int64), ("table_fwd_bytes", ctypes.c_double),
+                ("table_rev_ms", ctypes.c_double), ("table_rev_launches", ctypes.c_int64), ("table_rev_bytes", ctypes.c_double)]
 
 
 class LcrwmdError(RuntimeError):
@@ -166,15 +168,16 @@ class Context:
     def last_error(self) -> str:
         return self._lib.lcrwmd_last_error(self._h).decode()
 
-    def set_options(self, validate: int = 0, compute: int = F32, max_query_batch: int = 0, max_db_batch: int = 0):
-        o = OptionsStruct(validate, compute, max_query_batch, max_db_batch)
+    def set_options(self, validate: int = 0, compute: int = F32, max_query_batch: int = 0, max_db_batch: int = 0,
+                    dedup: int = 0):
+        o = OptionsStruct(validate, compute, max_query_batch, max_db_batch, dedup)
         self._check(self._lib.lcrwmd_set_options(self._h, ctypes.byref(o)))
 
     def get_options(self) -> dict:
         o = OptionsStruct()
         self._check(self._lib.lcrwmd_get_options(self._h, ctypes.byref(o)))
         return {"validate": o.validate, "compute": o.compute, "max_query_batch": o.max_query_batch,
-                "max_db_batch": o.max_db_batch}
+                "max_db_batch": o.max_db_batch, "dedup": o.dedup}
 
     def workspace_bytes(self, v, m, n, nnz_db, q, nnz_q, emb_dtype=F32, k=0) -> int:
         out = ctypes.c_size_t()

@@ -62,6 +62,7 @@ struct ProfScope {
 };
 
 constexpr int64_t kMaxTokens = (int64_t)1 << 30;   // padded tokens per launch (int32 offsets)
+constexpr int64_t kTableQueries = 4096;            // queries per pass of the de-duplicated form
 
 lcrwmd_status check_csr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, bool need_val)
 {
@@ -289,6 +290,46 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     if (region_off >= b.size) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
     const size_t region = b.size - region_off;
 
+    // ---- de-duplicated form: one word-pair table for the batch, both passes read it ----
+    if (ctx->opt.dedup && ve > 0 && vq > 0 && q <= table_max_queries()) {
+        Phase1Args a;
+        a.E = ep.data;
+        a.ld = ep.ld;
+        a.m = m;
+        a.normE = ep.normE;
+        a.voc_rows = list_q;
+        a.nvoc = vq;
+        a.z_by_position = 1;
+        const int64_t ldw = round_up(vq, 4), ldz = round_up(q, 4);
+        const int64_t tok_count = round_up(ve, kTileTokens) + kTileTokens;
+        Bump bb(b.base + region_off, region);
+        float* W = bb.take_n<float>((size_t)ve * ldw);
+        float* Z = bb.take_n<float>((size_t)ve * ldz);
+        int32_t* tok_ids = bb.take_n<int32_t>((size_t)tok_count);
+        float* tok_hn = bb.take_n<float>((size_t)tok_count);
+        a.Z = W;
+        a.ldz = ldw;
+        if (bb.ok && distance_table_supported(a, ep.bf16)) {
+            HIP_TRY(launch_table_tokens(list_db, ve, ep.normE, tok_ids, tok_hn, tok_count, s));
+            {
+                ProfScope ps(ctx, s, 1, 2.0 * (double)ve * (double)vq * (double)m);
+                HIP_TRY(launch_distance_table(a, ep.bf16, tok_ids, tok_hn, ve, s));
+            }
+            HIP_TRY(launch_table_zero_same(list_q, vq, map_db, W, ldw, s));
+            {   // forward: every table row once, Z once
+                ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);
+                HIP_TRY(launch_table_fwd(W, ldw, ve, vq, Q->row_ptr + jq0, qcol_pos - qoff, q, Z, ldz, s));
+            }
+            ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, q, D, ldd, 0, s));
+            {   // swapped: one table row per stored database entry, D read and written once
+                ProfScope ps(ctx, s, 4, 4.0 * (double)DB->nnz * (double)vq + 8.0 * (double)n * (double)q + 4.0 * (double)DB->nnz);
+                HIP_TRY(launch_table_rev(W, ldw, vq, DB->row_ptr, dbcol_pos, n, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, D, ldd, s));
+            }
+            return LCRWMD_OK;
+        }
+        // the table does not fit the workspace (or the embedding shape has no table kernel): per-entry passes below
+    }
+
     // ---- forward: cost of moving database docs onto the queries, D1 = X1 * Z ----
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
@@ -384,7 +425,7 @@ lcrwmd_status lcrwmd_create(lcrwmd_ctx** out, int device)
     if (!c) return LCRWMD_EINVAL;
     c->err[0] = 0;
     c->profiling = false;
-    c->opt = lcrwmd_options{0, LCRWMD_F32, 0, 0};
+    c->opt = lcrwmd_options{0, LCRWMD_F32, 0, 0, 0};
     c->device = device;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
@@ -426,6 +467,8 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
         (void)hipEventDestroy(r.stop);
         if (e != hipSuccess) continue;
         if (r.kind == 1) { out->phase1_ms += ms; out->phase1_launches += 1; out->phase1_flops += r.work; }
+        else if (r.kind == 3) { out->table_fwd_ms += ms; out->table_fwd_launches += 1; out->table_fwd_bytes += r.work; }
+        else if (r.kind == 4) { out->table_rev_ms += ms; out->table_rev_launches += 1; out->table_rev_bytes += r.work; }
         else { out->phase2_ms += ms; out->phase2_launches += 1; out->phase2_bytes += r.work; out->phase2_gather_bytes += r.work2; }
     }
     ctx->prof.clear();
@@ -439,7 +482,7 @@ lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt)
     if (!ctx) return LCRWMD_EINVAL;
     if (!opt) return fail(ctx, LCRWMD_EINVAL, "options are NULL");
     if ((opt->validate != 0 && opt->validate != 1) || (opt->compute != LCRWMD_F32 && opt->compute != LCRWMD_BF16) ||
-        opt->max_query_batch < 0 || opt->max_db_batch < 0)
+        opt->max_query_batch < 0 || opt->max_db_batch < 0 || (opt->dedup != 0 && opt->dedup != 1))
         return fail(ctx, LCRWMD_EINVAL, "option out of range");
     ctx->opt = *opt;
     return LCRWMD_OK;
@@ -470,6 +513,13 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
     size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
     size_t total = fixed + (f > r ? f : r) + 4096;
+    if (ctx->opt.dedup) {
+        // room for the word-pair table and the forward Z at their upper bounds (distinct words <= stored entries)
+        const int64_t qt = qb < kTableQueries ? qb : kTableQueries;
+        const int64_t ve_max = v < nnz_db ? v : nnz_db;
+        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 4) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 + 4096;
+        if (t > (f > r ? f : r)) total = fixed + t + 4096;
+    }
     if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
     // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
     size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
@@ -539,6 +589,14 @@ lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrw
     HIP_TRY(hipSetDevice(ctx->device));
     HostPtr rq, rdb;
     ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    if (ctx->opt.dedup && queries->rows > kTableQueries) {
+        // the table kernels keep one value per query in LDS: hand them the queries in ranges
+        for (int64_t j0 = 0; j0 < queries->rows; j0 += kTableQueries) {
+            const int64_t j1 = j0 + kTableQueries < queries->rows ? j0 + kTableQueries : queries->rows;
+            ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, D + j0, ldd, ws, ws_bytes, s));
+        }
+        return LCRWMD_OK;
+    }
     return rwmd_core(ctx, queries, rq.p, 0, queries->rows, database, rdb.p, E, D, ldd, ws, ws_bytes, s);
 }
 

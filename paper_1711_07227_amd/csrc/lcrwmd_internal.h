@@ -118,6 +118,20 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStrea
 bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+bool distance_table_supported(const Phase1Args& a, bool bf16);
+hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
+                                 int64_t ntok, hipStream_t s);
+// table.hip: the two passes of the de-duplicated form over a word-pair table W (rows: distinct database words)
+int64_t table_max_queries();
+hipError_t launch_table_tokens(const int32_t* list_db, int64_t ve, const float* normE, int32_t* tok_ids, float* tok_hn,
+                               int64_t count, hipStream_t s);
+hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32_t* map_db, float* W, int64_t ldw,
+                                  hipStream_t s);
+hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int64_t* q_rp, const int32_t* q_pos,
+                            int64_t q, float* Z, int64_t ldz, hipStream_t s);
+hipError_t launch_table_rev(const float* W, int64_t ldw, int64_t vq, const int64_t* db_rp, const int32_t* db_pos,
+                            int64_t rows, const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q,
+                            float* D, int64_t ldd, hipStream_t s);
 
 // phase2.hip
 hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,

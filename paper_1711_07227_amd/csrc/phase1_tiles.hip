@@ -73,6 +73,8 @@ struct P1T {
     int64_t nvoc;
     int32_t nvt;
     int32_t nchunks;
+    int32_t ntok;              // table mode: number of token rows (tok_ids is readable up to the next multiple of 64 + 64)
+    int32_t chunk_tokens;      // table mode: token rows per chunk (a multiple of 64)
     const int32_t* pofs;
     const int32_t* tok_ids;
     const float* tok_hn;
@@ -94,7 +96,10 @@ struct Layout {
     static constexpr int NJOBS = NOCT * (ROWS / 8) / 4;       // copy instructions per wavefront and tile
 };
 
-template <bool BF16, int NCT, int WGS_PER_CU>
+// TABLE = true turns the kernel into the plain pairwise-distance operation C = T o E of Sec. III: no minimum, every
+// element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0)) is stored, row t (token) x column u (vocabulary position) with
+// pitch ldz.  Tokens are then simply the rows tok_ids[0 .. ntok) cut into chunks of chunk_tokens.
+template <bool BF16, int NCT, int WGS_PER_CU, bool TABLE>
 __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 {
     using L = Layout<BF16>;
@@ -117,10 +122,19 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     if (slot >= per_xcd || item >= items) return;
     const int chunk = (int)(item / p.nvt);
     const int vt = (int)(item - (int64_t)chunk * p.nvt);
-    const int s0 = p.chunk_seg[chunk], s1 = p.chunk_seg[chunk + 1];
-    if (s0 >= s1) return;
-    const int t0 = p.pofs[s0], t1 = p.pofs[s1];
+    int s0 = 0, t0, t1;
+    if (TABLE) {
+        t0 = chunk * p.chunk_tokens;
+        t1 = t0 + p.chunk_tokens < p.ntok ? t0 + p.chunk_tokens : p.ntok;
+    } else {
+        s0 = p.chunk_seg[chunk];
+        const int s1 = p.chunk_seg[chunk + 1];
+        if (s0 >= s1) return;
+        t0 = p.pofs[s0];
+        t1 = p.pofs[s1];
+    }
     if (t0 >= t1) return;
+    (void)s0;
 
     const unsigned char* Eb = p.Eb;
 
@@ -218,7 +232,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     };
 
     // per-tile side data, fetched one tile ahead: group -> histogram (lane g < NG) and, fp32, -|T|^2/2 per row
-    auto load_gs = [&](int tb) { return (p.grp_seg + (tb >> 3))[lane8]; };      // lanes 8 g .. 8 g + 7 hold group g
+    auto load_gs = [&](int tb) { return TABLE ? 0 : (p.grp_seg + (tb >> 3))[lane8]; };   // lanes 8 g .. 8 g + 7 hold group g
     float hn[NRT], hn_next[NRT];
     auto load_hn = [&](int tb, float* h) {
 #pragma unroll
@@ -318,8 +332,25 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         }
         DBG_T(3)
 
+        if constexpr (TABLE) {
+            // every element is a result: register r of row tile rt is token row 32 rt + 8 (r / 4) + 4 half + r % 4
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const int64_t pos = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
+                if (pos < p.nvoc) {
+                    float* out = p.Z + pos;
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int row = tb + rt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                            if (row < t1) out[(int64_t)row * p.ldz] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * acc[rt][ct][r], 0.f));
+                        }
+                }
+            }
+        }
         // Epilogue: registers 4g'..4g'+3 of row tile rt hold token rows 32 rt + 8 g' + 4 half + {0..3}: group 4 rt + g'.
-        int ng = (t1 - tb) >> 3;
+        int ng = TABLE ? 0 : (t1 - tb) >> 3;
         if (ng > NG) ng = NG;
         // the groups' histograms move to scalar registers; the register then takes the next tile's (one tile ahead)
         int sgs[NG];
@@ -366,7 +397,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         buf ^= 1;
         DBG_T(4)
     }
-    flush();
+    if (!TABLE) flush();
 #ifdef DBG_TIMING
     if (blockIdx.x == 0 && tid == 0) {
         for (int k = 0; k < 5; ++k) p.Z[k] = (float)tacc[k];
@@ -377,7 +408,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #endif
 }
 
-template <bool BF16, int NCT, int WGS_PER_CU>
+template <bool BF16, int NCT, int WGS_PER_CU, bool TABLE>
 hipError_t launch_tiles(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
@@ -387,12 +418,12 @@ hipError_t launch_tiles(P1T d, hipStream_t s)
     const size_t smem = 2 * (size_t)Layout<BF16>::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NCT, WGS_PER_CU>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NCT, WGS_PER_CU, TABLE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    k_phase1_tiles<BF16, NCT, WGS_PER_CU><<<(unsigned)grid, 256, smem, s>>>(d);
+    k_phase1_tiles<BF16, NCT, WGS_PER_CU, TABLE><<<(unsigned)grid, 256, smem, s>>>(d);
     return hipGetLastError();
 }
 
@@ -405,6 +436,8 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
     d.nvoc = a.nvoc;
     d.nvt = 0;
     d.nchunks = tp.nchunks;
+    d.ntok = 0;
+    d.chunk_tokens = tp.chunk_tokens;
     d.pofs = tp.pofs;
     d.tok_ids = tp.tok_ids;
     d.tok_hn = tp.tok_hn;
@@ -430,7 +463,7 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<false, 2, 1>(d, s);
+    return launch_tiles<false, 2, 1, false>(d, s);
 }
 
 // a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
@@ -440,7 +473,50 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hi
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<true>::NOCT * 8;
     d.nzero_from = 0;
-    return launch_tiles<true, 2, 2>(d, s);
+    return launch_tiles<true, 2, 2, false>(d, s);
+}
+
+// Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
+// tok_ids / tok_hn: the token rows' word ids and -|.|^2/2 (fp32 path), readable up to roundup(ntok, 64) + 64 entries.
+bool distance_table_supported(const Phase1Args& a, bool bf16) { return bf16 || tiles_f32_supported(a); }
+
+hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
+                                 int64_t ntok, hipStream_t s)
+{
+    if (a.nvoc <= 0 || ntok <= 0) return hipSuccess;
+    if (!distance_table_supported(a, bf16) || ntok > 0x7fffffffLL - 128) return hipErrorNotSupported;
+    P1T d;
+    d.Eb = (const unsigned char*)a.E;
+    d.normE = a.normE;
+    d.voc_rows = a.voc_rows;
+    d.nvoc = a.nvoc;
+    d.nvt = 0;
+    d.ntok = (int32_t)ntok;
+    // a few thousand work items (vocabulary tiles x chunks of token rows), each chunk 4 .. 64 tiles of 64 rows
+    const int64_t nvt = (a.nvoc + 255) / 256;
+    const int64_t want_chunks = (4096 + nvt - 1) / nvt;
+    int64_t ct = ((ntok + want_chunks - 1) / want_chunks + ROWS - 1) / ROWS * ROWS;
+    if (ct < 4 * ROWS) ct = 4 * ROWS;
+    if (ct > 64 * ROWS) ct = 64 * ROWS;
+    d.chunk_tokens = (int32_t)ct;
+    d.nchunks = (int32_t)((ntok + ct - 1) / ct);
+    d.pofs = nullptr;
+    d.tok_ids = tok_ids;
+    d.tok_hn = tok_hn;
+    d.grp_seg = nullptr;
+    d.chunk_seg = nullptr;
+    d.Z = a.Z;
+    d.ldz = a.ldz;
+    if (bf16) {
+        d.pitch_b = a.ld * 2;
+        d.nreal = Layout<true>::NOCT * 8;
+        d.nzero_from = 0;
+        return launch_tiles<true, 2, 2, true>(d, s);
+    }
+    d.pitch_b = a.ld * 4;
+    d.nreal = a.m / 4;
+    d.nzero_from = a.m;
+    return launch_tiles<false, 2, 1, true>(d, s);
 }
 
 }  // namespace lcrwmd

@@ -1,0 +1,164 @@
+"""GPU parity of the de-duplicated form (option dedup = 1): one word-pair table per query batch, both passes read it.
+Same checks as the default form: the CPU oracle on the same seeded inputs, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1711_07227_amd import binding, synth
+from helpers import RTOL_F32, assert_close, run_rwmd, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def ctx():
+    c = binding.Context(0)
+    c.set_options(dedup=1)
+    yield c
+    c.close()
+
+
+def problem(v, m, n, q, h_lo, h_hi, seed, s=1.1):
+    return {"E": synth.embeddings(v, m, seed), "db": synth.corpus(n, v, h_lo, h_hi, s, seed + 1),
+            "queries": synth.corpus(q, v, h_lo, h_hi, s, seed + 2)}
+
+
+def table_was_used(ctx, E, db, qs, emb_dtype=binding.F32):
+    """Run once under the profiler hooks and report whether the table passes ran."""
+    ws = binding.alloc_workspace(ctx.workspace_bytes(E.shape[0], E.shape[1], db.rows, db.nnz, qs.rows, qs.nnz, emb_dtype))
+    D = torch.zeros((db.rows, qs.rows), dtype=torch.float32, device="cuda")
+    ctx.profile_begin()
+    ctx.rwmd(qs, db, E, D, ws)
+    prof = ctx.profile_end()
+    return prof["table_rev_launches"] > 0 and prof["table_fwd_launches"] > 0
+
+
+def test_dedup_tiny_full_matrix_and_agreement_with_default_form(ctx, tiny):
+    ref = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    E, db, qs = upload(tiny)
+    got = run_rwmd(ctx, E, db, qs)
+    assert_close(got, ref, what="tiny D (dedup)")
+    assert table_was_used(ctx, E, db, qs)
+    plain = binding.Context(0)
+    try:
+        base = run_rwmd(plain, E, db, qs)
+    finally:
+        plain.close()
+    assert np.max(np.abs(got - base)) <= 1e-5            # same distances; only the summation order differs
+
+
+def test_dedup_ragged_documents_and_single_words(ctx):
+    p = problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    assert_close(run_rwmd(ctx, *upload(p)), ref, what="mid D (dedup)")
+    # one document, one query, one word each; then identical documents
+    E = synth.embeddings(50, 300, 1)
+    one = (np.array([0, 1], np.int64), np.array([7], np.int32), np.array([1.0], np.float32))
+    other = (np.array([0, 1], np.int64), np.array([9], np.int32), np.array([1.0], np.float32))
+    got = run_rwmd(ctx, *upload({"E": E, "db": one, "queries": other}))
+    d = np.linalg.norm(E[7].astype(np.float64) - E[9].astype(np.float64))
+    assert got.shape == (1, 1) and abs(got[0, 0] - d) <= RTOL_F32 * d
+    assert run_rwmd(ctx, *upload({"E": E, "db": one, "queries": one}))[0, 0] == 0.0
+
+
+def test_dedup_self_distance_is_exactly_zero(ctx, tiny):
+    sub = synth.csr_rows(*tiny["db"], np.arange(150))
+    got = run_rwmd(ctx, *upload({"E": tiny["E"], "db": sub, "queries": sub}))
+    assert np.all(np.diag(got) == 0.0)
+    assert_close(got, oracle.rwmd_table(tiny["E"], sub, sub), what="self D (dedup)")
+
+
+def test_dedup_more_query_words_than_one_slab(ctx):
+    """Over 32768 distinct query words: the table rows pass through LDS in several slabs."""
+    v = 90000
+    p = {"E": synth.embeddings(v, 300, 5), "db": synth.corpus(300, v, 1, 90, 1.0, 6),
+         "queries": synth.corpus(900, v, 60, 140, 0.8, 7)}
+    assert len(np.unique(p["queries"][1])) > 32768
+    E, db, qs = upload(p)
+    got = run_rwmd(ctx, E, db, qs)
+    assert table_was_used(ctx, E, db, qs)
+    rng = np.random.default_rng(3)
+    pi = np.concatenate([rng.integers(0, 300, 1500), [0, 299]])
+    pj = np.concatenate([rng.integers(0, 900, 1500), [899, 0]])
+    assert_close(got[pi, pj], oracle.rwmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="multi-slab sampled pairs")
+    plain = binding.Context(0)
+    try:
+        base = run_rwmd(plain, E, db, qs)
+    finally:
+        plain.close()
+    assert np.max(np.abs(got - base)) <= 1e-5
+
+
+def test_dedup_query_ranges_beyond_one_pass(ctx):
+    """More than 4096 queries: the library walks them in ranges, each with its own table."""
+    p = problem(v=500, m=300, n=60, q=4300, h_lo=1, h_hi=6, seed=33)
+    got = run_rwmd(ctx, *upload(p))
+    assert_close(got, oracle.rwmd_bruteforce(p["E"], p["db"], p["queries"]), what="4300 queries (dedup)")
+
+
+def test_dedup_falls_back_when_the_table_does_not_fit_or_has_no_kernel(ctx, tiny):
+    E, db, qs = upload(tiny)
+    plain = binding.Context(0)
+    try:
+        small = plain.workspace_bytes(E.shape[0], 300, db.rows, db.nnz, qs.rows, qs.nnz)
+        base = run_rwmd(plain, E, db, qs)
+    finally:
+        plain.close()
+    # tiny: 5000 x ~500 x 4 bytes of table do fit the default workspace or not; force the issue with the floor
+    got = run_rwmd(ctx, E, db, qs, ws_bytes=small)
+    assert_close(got, oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"]), what="tiny D (dedup, default workspace)")
+    assert np.max(np.abs(got - base)) <= 1e-5
+    # fp32 embeddings of another width have no table kernel: the default form runs
+    p = problem(v=400, m=64, n=90, q=7, h_lo=2, h_hi=30, seed=8)
+    assert_close(run_rwmd(ctx, *upload(p)), oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="m = 64 (dedup asked)")
+
+
+def test_dedup_bf16_and_topk(ctx, tiny):
+    bits = synth.to_bf16_bits(tiny["E"])
+    Er = synth.bf16_bits_to_f32(bits)
+    ref = oracle.rwmd_table(Er, tiny["db"], tiny["queries"])
+    E, db, qs = upload({"E": Er, "db": tiny["db"], "queries": tiny["queries"]}, dtype=torch.bfloat16)
+    got = run_rwmd(ctx, E, db, qs, emb_dtype=binding.BF16)
+    assert_close(got, ref, rtol=1e-4, what="bf16 D (dedup) vs oracle on bf16-valued E")
+    # fused entry point with the option set
+    E32, db, qs = upload(tiny)
+    k = 16
+    ws = binding.alloc_workspace(ctx.workspace_bytes(E32.shape[0], 300, db.rows, db.nnz, qs.rows, qs.nnz, binding.F32, k))
+    R_idx = torch.zeros((qs.rows, k), dtype=torch.int32, device="cuda")
+    R_dist = torch.zeros((qs.rows, k), dtype=torch.float32, device="cuda")
+    ctx.rwmd_topk(qs, db, E32, k, R_idx, R_dist, ws)
+    torch.cuda.synchronize()
+    full = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    ref_idx, ref_dist = oracle.topk(full, k)
+    assert_close(R_dist.cpu().numpy(), ref_dist, what="top-k distances (dedup)")
+    gi = R_idx.cpu().numpy()
+    for j in range(qs.rows):
+        # positions must agree wherever the oracle's neighbouring distances are further apart than the tolerance
+        srt = np.sort(full[:, j])[: k + 1]
+        if np.min(np.diff(srt)) > 1e-5:
+            assert np.array_equal(gi[j], ref_idx[j])
+        assert_close(full[gi[j], j], ref_dist[j], what="top-k positions point at the reported distances")
+
+
+def test_dedup_medium_workload_at_full_size_sampled_pairs(ctx):
+    cfg = synth.CONFIGS["medium"]
+    print("generating medium", flush=True)
+    p = synth.make(cfg)
+    E, db, qs = upload(p)
+    n, q = db.rows, qs.rows
+    ws = binding.alloc_workspace(ctx.workspace_bytes(E.shape[0], 300, n, db.nnz, q, qs.nnz))
+    D = torch.full((n, q), float("nan"), dtype=torch.float32, device="cuda")
+    print("running lcrwmd_rwmd with dedup", flush=True)
+    ctx.profile_begin()
+    ctx.rwmd(qs, db, E, D, ws)
+    prof = ctx.profile_end()
+    assert prof["table_rev_launches"] == 1 and prof["table_fwd_launches"] == 1
+    assert bool(torch.isfinite(D).all())
+    rng = np.random.default_rng(11)
+    pi = np.concatenate([rng.integers(0, n, 3000), [0, n - 1, 0, n - 1]])
+    pj = np.concatenate([rng.integers(0, q, 3000), [0, q - 1, q - 1, 0]])
+    print("oracle on sampled pairs", flush=True)
+    ref = oracle.rwmd_pairs(p["E"], p["db"], p["queries"], pi, pj)
+    got = D[torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()].cpu().numpy()
+    assert_close(got, ref, what="medium sampled pairs (dedup)")

@@ -27,7 +27,8 @@ def test_struct_layouts_match_header():
     # int64 x3 + 4 pointers; pointer + int64 x3 + enum (padded); int x2 + int64 x2
     assert ctypes.sizeof(binding.CsrStruct) == 56
     assert ctypes.sizeof(binding.EmbStruct) == 40
-    assert ctypes.sizeof(binding.OptionsStruct) == 24
+    assert ctypes.sizeof(binding.OptionsStruct) == 32
+    assert ctypes.sizeof(binding.ProfileStruct) == 104
 
 
 def test_no_oracle_in_product_path():
