@@ -62,7 +62,6 @@ struct ProfScope {
 };
 
 constexpr int64_t kMaxTokens = (int64_t)1 << 30;   // padded tokens per launch (int32 offsets)
-constexpr int64_t kTableQueries = 4096;            // queries per pass of the de-duplicated form
 
 lcrwmd_status check_csr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, bool need_val)
 {
@@ -300,13 +299,22 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         a.voc_rows = list_q;
         a.nvoc = vq;
         a.z_by_position = 1;
-        const int64_t ldw = round_up(vq, 4), ldz = round_up(q, 4);
+        const int64_t ldw = round_up(vq, 32), ldz = round_up(q, 4);     // table rows start on 128-byte lines
         const int64_t tok_count = round_up(ve, kTileTokens) + kTileTokens;
         Bump bb(b.base + region_off, region);
         float* W = bb.take_n<float>((size_t)ve * ldw);
         float* Z = bb.take_n<float>((size_t)ve * ldz);
         int32_t* tok_ids = bb.take_n<int32_t>((size_t)tok_count);
         float* tok_hn = bb.take_n<float>((size_t)tok_count);
+        int32_t ws_cols, nstrip;
+        table_strips(vq, &ws_cols, &nstrip);
+        const size_t nsq = (size_t)nstrip * (size_t)q + 1;
+        int32_t* bcnt = bb.take_n<int32_t>(nsq);
+        int32_t* boffs = bb.take_n<int32_t>(nsq);
+        int32_t* bcur = bb.take_n<int32_t>(nsq);
+        int32_t* bpos = bb.take_n<int32_t>((size_t)nnz_q);
+        float* bval = bb.take_n<float>((size_t)nnz_q);
+        float* D2 = nstrip > 1 ? bb.take_n<float>((size_t)n * ldz) : nullptr;     // partial sums between strips
         a.Z = W;
         a.ldz = ldw;
         if (bb.ok && distance_table_supported(a, ep.bf16)) {
@@ -316,14 +324,15 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
                 HIP_TRY(launch_distance_table(a, ep.bf16, tok_ids, tok_hn, ve, s));
             }
             HIP_TRY(launch_table_zero_same(list_q, vq, map_db, W, ldw, s));
+            HIP_TRY(launch_table_buckets(Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, vq, bcnt, boffs, bcur, bpos, bval, s));
             {   // forward: every table row once, Z once
                 ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);
-                HIP_TRY(launch_table_fwd(W, ldw, ve, vq, Q->row_ptr + jq0, qcol_pos - qoff, q, Z, ldz, s));
+                HIP_TRY(launch_table_fwd(W, ldw, ve, vq, boffs, bpos, q, Z, ldz, s));
             }
             ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, q, D, ldd, 0, s));
             {   // swapped: one table row per stored database entry, D read and written once
                 ProfScope ps(ctx, s, 4, 4.0 * (double)DB->nnz * (double)vq + 8.0 * (double)n * (double)q + 4.0 * (double)DB->nnz);
-                HIP_TRY(launch_table_rev(W, ldw, vq, DB->row_ptr, dbcol_pos, n, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, D, ldd, s));
+                HIP_TRY(launch_table_rev(W, ldw, vq, DB->row_ptr, dbcol_pos, n, boffs, bpos, bval, q, D2, ldz, D, ldd, s));
             }
             return LCRWMD_OK;
         }
@@ -515,9 +524,10 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     size_t total = fixed + (f > r ? f : r) + 4096;
     if (ctx->opt.dedup) {
         // room for the word-pair table and the forward Z at their upper bounds (distinct words <= stored entries)
-        const int64_t qt = qb < kTableQueries ? qb : kTableQueries;
+        const int64_t qt = qb < table_max_queries() ? qb : table_max_queries();
         const int64_t ve_max = v < nnz_db ? v : nnz_db;
-        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 4) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 + 4096;
+        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 +
+                         table_bucket_bytes(vq, qt, nnz_q) + (size_t)n * (size_t)round_up(qt, 4) * 4 + 8192;
         if (t > (f > r ? f : r)) total = fixed + t + 4096;
     }
     if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
@@ -589,10 +599,11 @@ lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrw
     HIP_TRY(hipSetDevice(ctx->device));
     HostPtr rq, rdb;
     ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
-    if (ctx->opt.dedup && queries->rows > kTableQueries) {
+    const int64_t qr = table_max_queries();
+    if (ctx->opt.dedup && queries->rows > qr) {
         // the table kernels keep one value per query in LDS: hand them the queries in ranges
-        for (int64_t j0 = 0; j0 < queries->rows; j0 += kTableQueries) {
-            const int64_t j1 = j0 + kTableQueries < queries->rows ? j0 + kTableQueries : queries->rows;
+        for (int64_t j0 = 0; j0 < queries->rows; j0 += qr) {
+            const int64_t j1 = j0 + qr < queries->rows ? j0 + qr : queries->rows;
             ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, D + j0, ldd, ws, ws_bytes, s));
         }
         return LCRWMD_OK;

@@ -127,11 +127,15 @@ hipError_t launch_table_tokens(const int32_t* list_db, int64_t ve, const float* 
                                int64_t count, hipStream_t s);
 hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32_t* map_db, float* W, int64_t ldw,
                                   hipStream_t s);
-hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int64_t* q_rp, const int32_t* q_pos,
+void table_strips(int64_t vq, int32_t* ws, int32_t* nstrip);
+size_t table_bucket_bytes(int64_t vq, int64_t q, int64_t nnz_q);
+hipError_t launch_table_buckets(const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q, int64_t vq,
+                                int32_t* cnt, int32_t* offs, int32_t* cursor, int32_t* bpos, float* bval, hipStream_t s);
+hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int32_t* offs, const int32_t* bpos,
                             int64_t q, float* Z, int64_t ldz, hipStream_t s);
 hipError_t launch_table_rev(const float* W, int64_t ldw, int64_t vq, const int64_t* db_rp, const int32_t* db_pos,
-                            int64_t rows, const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q,
-                            float* D, int64_t ldd, hipStream_t s);
+                            int64_t rows, const int32_t* offs, const int32_t* bpos, const float* bval, int64_t q,
+                            float* D2, int64_t ld2, float* D, int64_t ldd, hipStream_t s);
 
 // phase2.hip
 hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,

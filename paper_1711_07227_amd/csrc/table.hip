@@ -9,6 +9,13 @@
 //   swapped   Z'[u][i] = min_{p in database row i} W[p][u],  D[i][j] = max(D[i][j], sum_a y_ja Z'[u_a][i])
 //                                                                         (k_table_rev: both steps fused, Z' stays in LDS)
 // The swapped pass is a stream of table rows: 4 * (stored database entries) * (query words) bytes, bandwidth bound.
+//
+// Strips.  The columns u are cut into strips of at most 768 (3 KiB per table row) and the queries' entries are
+// regrouped by strip once per call (k_bucket_*).  The swapped pass is launched strip by strip: while one strip is
+// being worked on, the strip of the frequent database words' rows stays in the L2s and the strip of the whole table
+// fits the Infinity Cache, so most of the stream never reaches HBM; per-strip partial sums accumulate in a buffer
+// D2 (always in strip order: the result does not depend on timing).  One wavefront owns one database row: its
+// minima live in a private 3 KiB of LDS and no workgroup barrier is needed.
 #include "lcrwmd_internal.h"
 
 namespace lcrwmd {
@@ -17,9 +24,10 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 1024;            // 16 wavefronts: one workgroup per CU
-constexpr int kWaves = kThreads / 64;
-constexpr int kSlabMax = 32768;           // floats of a table row held in LDS at a time (128 KiB)
+constexpr int kStrip = 768;               // columns per strip: 3 float4 per lane
+constexpr int kPieces = kStrip / 256;     // float4 per lane and table row
+constexpr int kWaves = 4;                 // wavefronts per workgroup, each on its own row(s)
+constexpr int kMaxQueries = 4096;         // queries per pass: at most 64 per lane in the forward kernel
 
 // Identical words are at distance exactly 0; the norm expansion only gets there up to cancellation error.
 __global__ void k_table_zero_same(const int32_t* __restrict__ list_q, int32_t vq, const int32_t* __restrict__ map_db,
@@ -42,158 +50,254 @@ __global__ void k_table_tokens(const int32_t* __restrict__ list_db, int32_t ve, 
     tok_hn[t] = -0.5f * normE[id];
 }
 
-__device__ inline float wave_sum(float x)
+// ---- the queries' entries regrouped by strip ----
+// offs[s * q + j] = start of the entries of query j that fall into strip s, in (strip, query) order; offs[nstrip * q]
+// = their number.  bpos = column - strip start, bval = weight; the entries of one (strip, query) keep their order.
+
+// One thread per query: counts per strip.
+__global__ void k_bucket_count(const int64_t* __restrict__ q_rp, const int32_t* __restrict__ q_pos, int32_t q,
+                               int32_t ws, int32_t nstrip, int32_t* __restrict__ cnt)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
-    return x;
-}
-__device__ inline float wave_min(float x)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fminf(x, __shfl_xor(x, o));
-    return x;
+    const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= q) return;
+    for (int32_t s = 0; s < nstrip; ++s) cnt[(int64_t)s * q + j] = 0;
+    for (int64_t e = q_rp[j]; e < q_rp[j + 1]; ++e) cnt[(int64_t)(q_pos[e] / ws) * q + j] += 1;
 }
 
-// Swapped pass, one workgroup per database row i.  The query words are cut into slabs of `slab` (a multiple of 4, at
-// most R * 4096) columns.  Per slab: (A) every thread keeps R float4 running minima over the table rows of the
-// words of row i (each table row is read as one contiguous, fully coalesced stream); the minima go to LDS; (B) one
-// wavefront per query sums weight * minimum over the query's words that fall into the slab.  At the end
-// D[i][j] = max(D[i][j], sum_j).  LDS: slab floats + q floats.
-template <int R>
-__global__ __launch_bounds__(kThreads) void k_table_rev(const float* __restrict__ W, int64_t ldw, int32_t vq,
-                                                        int32_t slab, const int64_t* __restrict__ db_rp,
-                                                        const int32_t* __restrict__ db_pos,
-                                                        const int64_t* __restrict__ q_rp,
-                                                        const int32_t* __restrict__ q_pos,
-                                                        const float* __restrict__ q_val, int32_t q,
-                                                        float* __restrict__ D, int64_t ldd)
+// Single workgroup: offs = exclusive prefix sums of cnt[0 .. count), offs[count] = total; cursor = copy of offs.
+__global__ __launch_bounds__(1024) void k_bucket_scan(const int32_t* __restrict__ cnt, int64_t count,
+                                                      int32_t* __restrict__ offs, int32_t* __restrict__ cursor)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    float* zrow = lds;             // [slab]
-    float* sums = lds + slab;      // [q]
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t i = blockIdx.x;
+    __shared__ int32_t wsum[17];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t carry = 0;
+    for (int64_t base = 0; base < count; base += 1024) {
+        const int64_t k = base + threadIdx.x;
+        const int32_t x = k < count ? cnt[k] : 0;
+        int32_t incl = x;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t y = __shfl_up(incl, o);
+            if (lane >= o) incl += y;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int32_t run = 0;
+            for (int w = 0; w < 16; ++w) { const int32_t t = wsum[w]; wsum[w] = run; run += t; }
+            wsum[16] = run;
+        }
+        __syncthreads();
+        const int32_t excl = carry + wsum[wave] + incl - x;
+        if (k < count) { offs[k] = excl; cursor[k] = excl; }
+        carry += wsum[16];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) offs[count] = carry;
+}
+
+// One thread per query: entries to their places.  cursor[s * q + j] is private to the thread.
+__global__ void k_bucket_scatter(const int64_t* __restrict__ q_rp, const int32_t* __restrict__ q_pos,
+                                 const float* __restrict__ q_val, int32_t q, int32_t ws, int32_t* __restrict__ cursor,
+                                 int32_t* __restrict__ bpos, float* __restrict__ bval)
+{
+    const int32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= q) return;
+    int32_t cur_s = -1, cur = 0;
+    for (int64_t e = q_rp[j]; e < q_rp[j + 1]; ++e) {
+        const int32_t c = q_pos[e], s = c / ws;
+        if (s != cur_s) {
+            if (cur_s >= 0) cursor[(int64_t)cur_s * q + j] = cur;
+            cur_s = s;
+            cur = cursor[(int64_t)s * q + j];
+        }
+        bpos[cur] = c - s * ws;
+        bval[cur] = q_val[e];
+        ++cur;
+    }
+}
+
+// Make this wavefront's LDS writes visible to its own later reads (one wavefront = one owner of the region).
+__device__ inline void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Swapped pass over one strip [c0, c0 + 4 * npiece) of the columns; one wavefront per database row i.
+//   (A) lanes keep float4 running minima over the table rows of the words of row i (each row segment is read as
+//       one contiguous piece), then park them in LDS;
+//   (B) lane = query: sum of weight * minimum over the query's entries in this strip, added to the partial sum of
+//       the strips before (D2); the last strip applies the maximum with D instead.
+__global__ __launch_bounds__(64 * kWaves) void k_table_rev(const float* __restrict__ W, int64_t ldw, int32_t c0,
+                                                          int32_t npiece, const int64_t* __restrict__ db_rp,
+                                                          const int32_t* __restrict__ db_pos, int64_t n,
+                                                          const int32_t* __restrict__ brp,
+                                                          const int32_t* __restrict__ bpos,
+                                                          const float* __restrict__ bval, int32_t q,
+                                                          float* __restrict__ D2, int64_t ld2, float* __restrict__ D,
+                                                          int64_t ldd, int first, int last)
+{
+    __shared__ __attribute__((aligned(16))) float zs[kWaves][kStrip];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t i = (int64_t)blockIdx.x * kWaves + wave;
+    if (i >= n) return;                       // whole wavefronts leave; there is no workgroup barrier below
     const int64_t a = db_rp[i], b = db_rp[i + 1];
 
-    for (int j = tid; j < q; j += kThreads) sums[j] = 0.f;
-
-    for (int32_t u0 = 0; u0 < vq; u0 += slab) {
-        const int32_t width = vq - u0 < slab ? vq - u0 : slab;     // real columns; the row pitch covers the next multiple of 4
-        const int32_t npiece = (width + 3) >> 2;
-        // ---- (A) column minima over the row's words ----
-        f32x4 best[R];
-        bool own[R];
-        const float* col[R];
+    const float* col[kPieces];
+    f32x4 best[kPieces];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int k = tid + r * kThreads;
-            own[r] = k < npiece;
-            col[r] = W + u0 + 4 * (own[r] ? k : 0);
-            best[r] = f32x4{INFINITY, INFINITY, INFINITY, INFINITY};
-        }
-        int64_t p = a;
-        for (; p + 1 < b; p += 2) {
-            const int64_t o0 = (int64_t)db_pos[p] * ldw, o1 = (int64_t)db_pos[p + 1] * ldw;
-            f32x4 x0[R], x1[R];
+    for (int r = 0; r < kPieces; ++r) {
+        const int piece = lane + 64 * r;
+        col[r] = W + c0 + 4 * (piece < npiece ? piece : 0);      // lanes without a piece re-read piece 0
+        best[r] = f32x4{INFINITY, INFINITY, INFINITY, INFINITY};
+    }
+    int64_t p = a;
+    for (; p + 3 < b; p += 4) {
+        int64_t o[4];
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (own[r]) {
-                    x0[r] = *reinterpret_cast<const f32x4*>(col[r] + o0);
-                    x1[r] = *reinterpret_cast<const f32x4*>(col[r] + o1);
-                }
+        for (int t = 0; t < 4; ++t) o[t] = (int64_t)db_pos[p + t] * ldw;
+        f32x4 x[4][kPieces];
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (own[r]) {
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) best[r][t] = fminf(best[r][t], fminf(x0[r][t], x1[r][t]));
-                }
-        }
-        if (p < b) {
-            const int64_t o0 = (int64_t)db_pos[p] * ldw;
+            for (int r = 0; r < kPieces; ++r) x[t][r] = *reinterpret_cast<const f32x4*>(col[r] + o[t]);
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (own[r]) {
-                    const f32x4 x = *reinterpret_cast<const f32x4*>(col[r] + o0);
+        for (int r = 0; r < kPieces; ++r)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) best[r][t] = fminf(best[r][t], x[t]);
-                }
-        }
-        __syncthreads();          // the previous slab's minima are no longer being read
+            for (int c = 0; c < 4; ++c)
+                best[r][c] = fminf(fminf(best[r][c], fminf(x[0][r][c], x[1][r][c])), fminf(x[2][r][c], x[3][r][c]));
+    }
+    for (; p < b; ++p) {
+        const int64_t o = (int64_t)db_pos[p] * ldw;
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (own[r]) *reinterpret_cast<f32x4*>(zrow + 4 * (tid + r * kThreads)) = best[r];
-        __syncthreads();
-        // ---- (B) weighted sums of the queries over this slab ----
-        for (int j = wave; j < q; j += kWaves) {
-            const int64_t qa = q_rp[j], qb = q_rp[j + 1];
-            float part = 0.f;
-            for (int64_t e = qa + lane; e < qb; e += 64) {
-                const uint32_t c = (uint32_t)(q_pos[e] - u0);
-                if (c < (uint32_t)width) part = fmaf(q_val[e], zrow[c], part);
-            }
-            part = wave_sum(part);
-            if (lane == 0) sums[j] += part;       // query j always belongs to this wavefront
+        for (int r = 0; r < kPieces; ++r) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(col[r] + o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) best[r][c] = fminf(best[r][c], x[c]);
         }
     }
-    __syncthreads();
-    float* drow = D + i * ldd;
-    for (int j = tid; j < q; j += kThreads) drow[j] = fmaxf(drow[j], sums[j]);
-}
+#pragma unroll
+    for (int r = 0; r < kPieces; ++r)
+        if (lane + 64 * r < npiece) *reinterpret_cast<f32x4*>(&zs[wave][4 * (lane + 64 * r)]) = best[r];
+    wave_lds_sync();
 
-// Forward pass, one workgroup per distinct database word p: the table row goes to LDS slab by slab and one
-// wavefront per query takes the minimum over the query's words; Z[p][j] is written once, along the row.
-__global__ __launch_bounds__(kThreads) void k_table_fwd(const float* __restrict__ W, int64_t ldw, int32_t vq,
-                                                        int32_t slab, const int64_t* __restrict__ q_rp,
-                                                        const int32_t* __restrict__ q_pos, int32_t q,
-                                                        float* __restrict__ Z, int64_t ldz)
-{
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    float* wrow = lds;             // [slab]
-    float* mins = lds + slab;      // [q]
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t p = blockIdx.x;
-    const float* row = W + p * ldw;
-
-    for (int j = tid; j < q; j += kThreads) mins[j] = INFINITY;
-
-    for (int32_t u0 = 0; u0 < vq; u0 += slab) {
-        const int32_t width = vq - u0 < slab ? vq - u0 : slab;
-        const int32_t npiece = (width + 3) >> 2;
-        __syncthreads();
-        for (int k = tid; k < npiece; k += kThreads)
-            *reinterpret_cast<f32x4*>(wrow + 4 * k) = *reinterpret_cast<const f32x4*>(row + u0 + 4 * k);
-        __syncthreads();
-        for (int j = wave; j < q; j += kWaves) {
-            const int64_t qa = q_rp[j], qb = q_rp[j + 1];
-            float part = INFINITY;
-            for (int64_t e = qa + lane; e < qb; e += 64) {
-                const uint32_t c = (uint32_t)(q_pos[e] - u0);
-                if (c < (uint32_t)width) part = fminf(part, wrow[c]);
+    const float* z = zs[wave];
+    float* d2 = D2 + i * ld2;
+    float* d = D + i * ldd;
+    for (int32_t j0 = 0; j0 < q; j0 += 64) {
+        const int32_t j = j0 + lane;
+        if (j < q) {
+            float acc = 0.f;
+            const int32_t ea = brp[j], eb = brp[j + 1];
+            for (int32_t e = ea; e < eb; e += 4) {          // four entries' loads in flight; the sum keeps entry order
+                int32_t c[4];
+                float w[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const bool ok = e + t < eb;
+                    c[t] = bpos[ok ? e + t : e];
+                    w[t] = ok ? bval[e + t] : 0.f;
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc = fmaf(w[t], z[c[t]], acc);
             }
-            part = wave_min(part);
-            if (lane == 0) mins[j] = fminf(mins[j], part);
+            if (!first) acc += d2[j];
+            if (last) d[j] = fmaxf(d[j], acc);
+            else d2[j] = acc;
         }
     }
-    __syncthreads();
-    float* zrow = Z + p * ldz;
-    for (int j = tid; j < q; j += kThreads) zrow[j] = mins[j];
 }
 
-// Slab width for vq columns: the fewest slabs that fit, of equal width (a multiple of 4).
-int32_t slab_for(int64_t vq)
+// Forward pass: one wavefront per RW table rows, all strips in turn.  Lane l owns the queries l, l + 64, ...
+// (QPL of them) and keeps their running minima for the RW rows in registers; a strip of the RW rows is parked in
+// LDS, then every owned query walks its entries of that strip.  Z[p][j] is written once, along the row.
+template <int QPL, int RW>
+__global__ __launch_bounds__(64 * kWaves) void k_table_fwd(const float* __restrict__ W, int64_t ldw, int64_t ve,
+                                                          int32_t vq, int32_t ws, int32_t nstrip,
+                                                          const int32_t* __restrict__ offs,
+                                                          const int32_t* __restrict__ bpos, int32_t q,
+                                                          float* __restrict__ Z, int64_t ldz)
 {
-    const int64_t nslab = (vq + kSlabMax - 1) / kSlabMax;
-    int64_t w = (vq + nslab - 1) / nslab;
-    w = (w + 3) & ~(int64_t)3;
-    return (int32_t)w;
+    __shared__ __attribute__((aligned(16))) float zs[kWaves][RW][kStrip];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t p0 = ((int64_t)blockIdx.x * kWaves + wave) * RW;
+    if (p0 >= ve) return;
+    const float* row[RW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) row[r] = W + (p0 + r < ve ? p0 + r : ve - 1) * ldw;
+    float acc[RW][QPL];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int jj = 0; jj < QPL; ++jj) acc[r][jj] = INFINITY;
+
+    for (int32_t s = 0; s < nstrip; ++s) {
+        const int32_t c0 = s * ws;
+        const int32_t width = vq - c0 < ws ? vq - c0 : ws;
+        const int32_t npiece = (width + 3) >> 2;
+        wave_lds_sync();                       // the previous strip has been read
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int k = 0; k < kPieces; ++k) {
+                const int piece = lane + 64 * k;
+                if (piece < npiece)
+                    *reinterpret_cast<f32x4*>(&zs[wave][r][4 * piece]) = *reinterpret_cast<const f32x4*>(row[r] + c0 + 4 * piece);
+            }
+        wave_lds_sync();
+        const int32_t* brp = offs + (int64_t)s * q;
+#pragma unroll
+        for (int jj = 0; jj < QPL; ++jj) {
+            const int32_t j = lane + 64 * jj;
+            if (j < q) {
+                const int32_t ea = brp[j], eb = brp[j + 1];
+                for (int32_t e = ea; e < eb; e += 4) {      // four entries' loads in flight; a repeated entry changes no minimum
+                    int32_t c[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) c[t] = bpos[e + t < eb ? e + t : e];
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+                        acc[r][jj] = fminf(fminf(acc[r][jj], fminf(zs[wave][r][c[0]], zs[wave][r][c[1]])),
+                                           fminf(zs[wave][r][c[2]], zs[wave][r][c[3]]));
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+        if (p0 + r < ve) {
+            float* zrow = Z + (p0 + r) * ldz;
+#pragma unroll
+            for (int jj = 0; jj < QPL; ++jj)
+                if (lane + 64 * jj < q) zrow[lane + 64 * jj] = acc[r][jj];
+        }
 }
 
 }  // namespace
 
-int64_t table_max_queries() { return (160 * 1024 / 4) - kSlabMax; }   // q floats beside a full slab in 160 KiB of LDS
+int64_t table_max_queries() { return kMaxQueries; }
+
+// Strips for vq columns: equal widths, multiples of 32, at most kStrip.
+void table_strips(int64_t vq, int32_t* ws, int32_t* nstrip)
+{
+    const int64_t ns = vq > 0 ? (vq + kStrip - 1) / kStrip : 1;
+    int64_t w = (vq + ns - 1) / ns;
+    w = (w + 31) & ~(int64_t)31;            // strips start on 128-byte lines of the table rows
+    if (w < 32) w = 32;
+    *ws = (int32_t)w;
+    *nstrip = (int32_t)((vq + w - 1) / w > 0 ? (vq + w - 1) / w : 1);
+}
+
+// Bytes of the regrouped query entries (offs, cursor / counts, bpos, bval) for q queries with nnz_q entries.
+size_t table_bucket_bytes(int64_t vq, int64_t q, int64_t nnz_q)
+{
+    int32_t ws, ns;
+    table_strips(vq, &ws, &ns);
+    return 3 * (((size_t)ns * (size_t)q + 1) * 4 + 256) + 2 * ((size_t)nnz_q * 4 + 256);
+}
 
 hipError_t launch_table_tokens(const int32_t* list_db, int64_t ve, const float* normE, int32_t* tok_ids, float* tok_hn,
                                int64_t count, hipStream_t s)
@@ -211,61 +315,62 @@ hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32
     return hipGetLastError();
 }
 
-hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int64_t* q_rp, const int32_t* q_pos,
+// Regroup the entries of q queries (q_rp indexed from the first query of the batch, offsets into q_pos / q_val).
+// cnt, offs and cursor hold nstrip * q + 1 values each.
+hipError_t launch_table_buckets(const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q, int64_t vq,
+                                int32_t* cnt, int32_t* offs, int32_t* cursor, int32_t* bpos, float* bval, hipStream_t s)
+{
+    if (q <= 0) return hipSuccess;
+    int32_t ws, ns;
+    table_strips(vq, &ws, &ns);
+    const unsigned grid = (unsigned)((q + 63) / 64);
+    k_bucket_count<<<grid, 64, 0, s>>>(q_rp, q_pos, (int32_t)q, ws, ns, cnt);
+    k_bucket_scan<<<1, 1024, 0, s>>>(cnt, (int64_t)ns * q, offs, cursor);
+    k_bucket_scatter<<<grid, 64, 0, s>>>(q_rp, q_pos, q_val, (int32_t)q, ws, cursor, bpos, bval);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int32_t* offs, const int32_t* bpos,
                             int64_t q, float* Z, int64_t ldz, hipStream_t s)
 {
     if (ve <= 0 || q <= 0 || vq <= 0) return hipSuccess;
-    if (q > table_max_queries() || ve > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int32_t slab = slab_for(vq);
-    const size_t smem = ((size_t)slab + (size_t)q) * 4;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_table_fwd), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    k_table_fwd<<<(unsigned)ve, kThreads, smem, s>>>(W, ldw, (int32_t)vq, slab, q_rp, q_pos, (int32_t)q, Z, ldz);
+    if (q > kMaxQueries || (ldw & 3) != 0 || ((uintptr_t)W & 15) != 0) return hipErrorInvalidValue;
+    int32_t ws, ns;
+    table_strips(vq, &ws, &ns);
+#define FWD(QPL, RW)                                                                                                   \
+    do {                                                                                                               \
+        const int64_t grid = (ve + (int64_t)kWaves * RW - 1) / ((int64_t)kWaves * RW);                                 \
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;                                                          \
+        k_table_fwd<QPL, RW><<<(unsigned)grid, 64 * kWaves, 0, s>>>(W, ldw, ve, (int32_t)vq, ws, ns, offs, bpos, (int32_t)q, Z, ldz); \
+    } while (0)
+    if (q <= 4 * 64) FWD(4, 4);
+    else if (q <= 16 * 64) FWD(16, 4);
+    else if (q <= 32 * 64) FWD(32, 2);
+    else FWD(64, 1);
+#undef FWD
     return hipGetLastError();
 }
 
-template <int R>
-static hipError_t launch_rev_r(const float* W, int64_t ldw, int32_t vq, int32_t slab, const int64_t* db_rp,
-                               const int32_t* db_pos, int64_t rows, const int64_t* q_rp, const int32_t* q_pos,
-                               const float* q_val, int32_t q, float* D, int64_t ldd, size_t smem, hipStream_t s)
-{
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_table_rev<R>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    k_table_rev<R><<<(unsigned)rows, kThreads, smem, s>>>(W, ldw, vq, slab, db_rp, db_pos, q_rp, q_pos, q_val, q, D, ldd);
-    return hipGetLastError();
-}
-
-// D[i][j] = max(D[i][j], sum_a q_val[a] * min_{p in row i} W[db_pos[p]][q_pos[a]]) for i in [0, rows), j in [0, q).
-// db_rp is indexed from the first row of the batch and holds offsets into db_pos; the same for q_rp / q_pos / q_val.
+// D[i][j] = max(D[i][j], sum_a bval[a] * min_{p in row i} W[db_pos[p]][column of a]) for i in [0, rows), j in [0, q).
+// db_rp is indexed from the first row of the batch and holds offsets into db_pos.  D2 (rows x ld2) holds the partial
+// sums between the strips' launches.
 hipError_t launch_table_rev(const float* W, int64_t ldw, int64_t vq, const int64_t* db_rp, const int32_t* db_pos,
-                            int64_t rows, const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q,
-                            float* D, int64_t ldd, hipStream_t s)
+                            int64_t rows, const int32_t* offs, const int32_t* bpos, const float* bval, int64_t q,
+                            float* D2, int64_t ld2, float* D, int64_t ldd, hipStream_t s)
 {
     if (rows <= 0 || q <= 0 || vq <= 0) return hipSuccess;
-    if (q > table_max_queries() || rows > 0x7fffffffLL || (ldw & 3) != 0 || ((uintptr_t)W & 15) != 0) return hipErrorInvalidValue;
-    const int32_t slab = slab_for(vq);
-    const size_t smem = ((size_t)slab + (size_t)q) * 4;
-    const int r = (slab / 4 + kThreads - 1) / kThreads;
-#define REV(RR) return launch_rev_r<RR>(W, ldw, (int32_t)vq, slab, db_rp, db_pos, rows, q_rp, q_pos, q_val, (int32_t)q, D, ldd, smem, s)
-    switch (r) {
-        case 1: REV(1);
-        case 2: REV(2);
-        case 3: REV(3);
-        case 4: REV(4);
-        case 5: REV(5);
-        case 6: REV(6);
-        case 7: REV(7);
-        default: REV(8);
+    if (q > kMaxQueries || (ldw & 3) != 0 || ((uintptr_t)W & 15) != 0) return hipErrorInvalidValue;
+    int32_t ws, ns;
+    table_strips(vq, &ws, &ns);
+    const int64_t grid = (rows + kWaves - 1) / kWaves;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    for (int32_t st = 0; st < ns; ++st) {
+        const int32_t c0 = st * ws;
+        const int32_t width = (int32_t)(vq - c0 < ws ? vq - c0 : ws);
+        k_table_rev<<<(unsigned)grid, 64 * kWaves, 0, s>>>(W, ldw, c0, (width + 3) >> 2, db_rp, db_pos, rows, offs + (int64_t)st * q,
+                                                          bpos, bval, (int32_t)q, D2, ld2, D, ldd, st == 0, st == ns - 1);
     }
-#undef REV
+    return hipGetLastError();
 }
 
 }  // namespace lcrwmd
