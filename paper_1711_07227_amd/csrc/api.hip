@@ -160,6 +160,7 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     a.z_by_position = z_by_position;
     a.Z = Z;
     a.ldz = ldz;
+    a.num_cu = ctx->num_cu;
     {
         ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m);
         if (ep.bf16) HIP_TRY(launch_phase1_bf16(a, tp, s));
@@ -185,6 +186,10 @@ lcrwmd_status run_spmm(lcrwmd_ctx* ctx, const int64_t* rp, const int32_t* ci, co
 }
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Vocabulary tile count the token plan sizes its chunks for (it aims at a few thousand (tile, chunk) pairs).  The
+// bf16 kernel balances its load in units of chunks, so it gets eight times as many, shorter chunks.
+int64_t plan_tiles(int64_t nvt, bool bf16) { return bf16 ? (nvt + 7) / 8 : nvt; }
 
 // Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
 size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, bool bf16)
@@ -353,7 +358,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], nvt_f, padded_tokens(rq, j0, j1));
+        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1));
         const int64_t ldz = round_up(j1 - j0, 4);
         float* Z = bb.take_n<float>((size_t)ve * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
@@ -376,7 +381,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t i1 = i0 + nb < n ? i0 + nb : n;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], nvt_r, padded_tokens(rdb, i0, i1));
+        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], plan_tiles(nvt_r, ep.bf16), padded_tokens(rdb, i0, i1));
         const int64_t ldz = round_up(i1 - i0, 4);
         float* Z = bb.take_n<float>((size_t)vq * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");
@@ -563,7 +568,7 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     EmbPrep ep;
     ST_TRY(prepare_emb(ctx, E, b, ep, s));
     TokenPlan tp;
-    carve_token_plan(b, tp, queries->rows, queries->nnz, (E->v + kTileVocab - 1) / kTileVocab);
+    carve_token_plan(b, tp, queries->rows, queries->nnz, plan_tiles((E->v + kTileVocab - 1) / kTileVocab, ep.bf16));
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
                            emb_prep_bytes(E->v, (int32_t)E->m, ep.bf16) + token_plan_bytes(queries->rows, queries->nnz));
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,

@@ -85,6 +85,7 @@ struct Phase1Args {
     int z_by_position;        // 1: Z row = position in voc_rows; 0: Z row = word id
     float* Z;
     int64_t ldz;
+    int32_t num_cu = 256;     // compute units of the device (the bf16 kernel launches one workgroup per CU)
 };
 
 // prep.hip
@@ -117,7 +118,7 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStrea
 // phase1_tiles.hip: the direct-to-LDS tile kernel for both precisions
 bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
-hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s);
 bool distance_table_supported(const Phase1Args& a, bool bf16);
 hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
                                  int64_t ntok, hipStream_t s);

@@ -78,7 +78,7 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStrea
 {
     if (a.nvoc <= 0 || tp.nseg <= 0) return hipSuccess;
     if (!bf16_supported(a.m)) return hipErrorNotSupported;
-    return launch_phase1_tiles_bf16(a, tp, s);
+    return launch_phase1_tiles_bf16(a, tp, a.num_cu, s);
 }
 
 }  // namespace lcrwmd

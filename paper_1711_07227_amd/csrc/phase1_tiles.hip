@@ -12,16 +12,18 @@
 // Data movement
 //   * vocabulary operand: NCT x 32 words per wavefront, the whole K extent (304 columns) in registers, loaded
 //     once per workgroup;
-//   * token operand: tiles of 64 rows x the whole K extent, copied global -> LDS with global_load_lds_dwordx4
-//     (no registers), double buffered, ONE barrier per tile; the copy instructions of the next tile are
-//     spread over the K steps of the current one so that they never queue up behind each other.
+//   * token operand: tiles of ROWS rows x the whole K extent, copied global -> LDS with global_load_lds_dwordx4
+//     (no registers) into a ring of NBUF buffers, ONE barrier per tile; the copy instructions of the tile
+//     NBUF - 1 ahead are spread over the K steps of the current one so that they never queue up behind each
+//     other.  fp32: 64-row tiles, 2 buffers (a tile is ~44k MFMA clocks, far more than the memory latency);
+//     bf16: 32-row tiles, 4 buffers (a tile is only ~1.2k MFMA clocks: copies have to be three tiles ahead).
 //
 // Rows are handled as 16-byte pieces, 8 pieces (one 128-byte cache line) to an "octet": bf16 rows are 5 octets
 // (the whole 640-byte packed row), fp32 rows 10 octets (1200 bytes = 75 pieces; the pieces past the end of the row
 // re-read piece 74 and meet zeros on the vocabulary side).  One copy instruction moves one octet of 8 rows = 1 KiB:
 // the 8 lanes of a row fetch one full line, and lane (row r, slot s) fetches piece s ^ ((r >> 1) & 7), so that the
-// later 16-byte LDS reads of 16 consecutive rows of one piece hit all 64 banks.  A tile is 40 KiB (bf16) or 80 KiB
-// (fp32); with two buffers, two bf16 workgroups or one fp32 workgroup fill the CU's 160 KiB of LDS exactly.
+// later 16-byte LDS reads of 16 consecutive rows of one piece hit all 64 banks.  A tile is 20 KiB (bf16) or 80 KiB
+// (fp32); two bf16 workgroups (4 buffers each) or one fp32 workgroup (2 buffers) fill the CU's 160 KiB of LDS exactly.
 //
 // K step s covers pieces 2 s and 2 s + 1: lane half h multiplies piece 2 s + h of its token row with the same
 // piece of its vocabulary word.  bf16: one v_mfma_f32_32x32x16_bf16 per step and tile; fp32: four
@@ -84,17 +86,21 @@ struct P1T {
     int64_t ldz;
 };
 
-constexpr int ROWS = 64;      // token rows per tile
-constexpr int NRT = 2;        // 32-row MFMA tiles per token tile
-
+// Tile shape per path: ROWS token rows (NRT 32-row MFMA tiles) and NBUF LDS buffers.
 template <bool BF16>
 struct Layout {
+    static constexpr int ROWS = BF16 ? 32 : 64;
+    static constexpr int NRT = ROWS / 32;
+    static constexpr int NBUF = BF16 ? 4 : 2;
+    static constexpr int PD = NBUF - 1;                       // tiles between a copy and its use
+    static constexpr int LA = BF16 ? 3 : 1;                   // K steps between an LDS read and its use
     static constexpr int NS = BF16 ? 19 : 38;                 // K steps (pairs of pieces): 304 columns
     static constexpr int NOCT = BF16 ? 5 : 10;                // octets copied per row
     static constexpr int OCT_BYTES = (ROWS / 8) * 1024;       // one octet of all rows of the tile
     static constexpr int TILE_BYTES = NOCT * OCT_BYTES;
     static constexpr int NJOBS = NOCT * (ROWS / 8) / 4;       // copy instructions per wavefront and tile
 };
+constexpr int kMaxRows = 64;
 
 // TABLE = true turns the kernel into the plain pairwise-distance operation C = T o E of Sec. III: no minimum, every
 // element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0)) is stored, row t (token) x column u (vocabulary position) with
@@ -104,6 +110,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 {
     using L = Layout<BF16>;
     constexpr int NS = L::NS;
+    constexpr int ROWS = L::ROWS, NRT = L::NRT, NBUF = L::NBUF, PD = L::PD;
     constexpr int NG = ROWS / 8;               // token groups per tile
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -113,15 +120,27 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: keep it scalar
     const int l31 = lane & 31, half = lane >> 5;
 
-    // Work item -> (chunk, vocabulary tile); each XCD (workgroup id mod 8) gets a contiguous range of items so
-    // that its CUs work on the same chunk and share its token rows in that XCD's L2.
-    const int64_t items = (int64_t)p.nvt * p.nchunks;
-    const int64_t per_xcd = (items + 7) >> 3;
-    const int64_t slot = blockIdx.x >> 3;
-    const int64_t item = (int64_t)(blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || item >= items) return;
-    const int chunk = (int)(item / p.nvt);
-    const int vt = (int)(item - (int64_t)chunk * p.nvt);
+    // Work item -> (chunk, vocabulary tile).  XCD x (workgroup id mod 8) takes, of chunk c, the vocabulary tiles
+    // congruent to x - c mod 8, chunk after chunk: whatever the number of tiles and the chunks' lengths, all XCDs
+    // carry the same load (the residues rotate), and the CUs of an XCD work on the same chunk at the same time,
+    // sharing its token rows in that XCD's L2.  Eight consecutive chunks hold exactly nvt items of every XCD.
+    int chunk, vt;
+    {
+        const int xcd = blockIdx.x & 7;
+        const int64_t slot = blockIdx.x >> 3;
+        const int64_t period = slot / p.nvt;
+        int rem = (int)(slot - period * p.nvt);
+        chunk = -1;
+        vt = 0;
+#pragma unroll 1
+        for (int k = 0; k < 8; ++k) {
+            const int r = (xcd - k) & 7;                          // residue of this XCD in chunk 8 * period + k
+            const int n = r < p.nvt ? (p.nvt - r + 7) >> 3 : 0;
+            if (rem < n) { chunk = (int)(period * 8) + k; vt = r + 8 * rem; break; }
+            rem -= n;
+        }
+        if (chunk < 0 || chunk >= p.nchunks) return;
+    }
     int s0 = 0, t0, t1;
     if (TABLE) {
         t0 = chunk * p.chunk_tokens;
@@ -176,7 +195,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     }
 
     // ---- copy jobs of this wavefront ----
-    // job J -> octet J / 2, row block (of 8 rows) wave + 4 (J % 2); lane -> row lane / 8, slot lane % 8
+    // job J -> octet J / NRT, row block (of 8 rows) wave + 4 (J % NRT); lane -> row lane / 8, slot lane % 8
     const int lane8 = lane >> 3;                                   // row within an 8-row block; also this lane's token group
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
     const uint32_t offO = pieceO * 16;
@@ -190,23 +209,23 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     auto load_words = [&](int tb) {
         const int32_t* t = p.tok_ids + (tb + wave * 8);             // scalar part of the address
         wA = t[lane8];
-        wB = t[lane8 + 32];
+        if (NRT == 2) wB = t[lane8 + 32];
     };
     const uint32_t pitch32 = (uint32_t)p.pitch_b;     // the host guarantees rows * pitch < 2^32
     // copy job J (compile time) of this wavefront into buffer `lbase`
     auto copy_job = [&](auto j_c, unsigned char* lbase) {
         constexpr int J = decltype(j_c)::value;
-        constexpr int oct = J >> 1;
-        const uint32_t off = (uint32_t)((J & 1) ? wB : wA) * pitch32 + (oct == L::NOCT - 1 ? off_last : offO + oct * 128);
+        constexpr int oct = J / NRT, blk = J % NRT;
+        const uint32_t off = (uint32_t)(blk ? wB : wA) * pitch32 + (oct == L::NOCT - 1 ? off_last : offO + oct * 128);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + off),
-                                         (__attribute__((address_space(3))) void*)(lbase + (oct * 8 + (J & 1) * 4 + wave) * 1024),
+                                         (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + blk * 4 + wave) * 1024),
                                          16, 0, 0);
     };
 
     // ---- LDS read address of this lane (bytes) ----
     // row block (l31 >> 3), row (l31 & 7), slot (2 k + half) ^ ((l31 >> 1) & 7) for k = s & 3: k enters as an XOR of bits 5..6
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    uint32_t a_oct = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
+    const uint32_t a_oct0 = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
 
     f32x16 acc[NRT][NCT];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -239,13 +258,18 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         for (int rt = 0; rt < NRT; ++rt) h[rt] = p.tok_hn[tb + rt * 32 + l31];
     };
 
-    // first tile: copy it in one go
-    load_words(t0);
-    static_for<0, L::NJOBS>([&](auto j_c) { copy_job(j_c, smem); });
-    if (t0 + ROWS < t1) load_words(t0 + ROWS);
+    // the first PD tiles: copy each in one go
+    static_for<0, PD>([&](auto k_c) {
+        constexpr int k = decltype(k_c)::value;
+        if (t0 + k * ROWS < t1) {
+            load_words(t0 + k * ROWS);
+            static_for<0, L::NJOBS>([&](auto j_c) { copy_job(j_c, smem + k * L::TILE_BYTES); });
+        }
+    });
+    if (t0 + PD * ROWS < t1) load_words(t0 + PD * ROWS);
     int gsv = load_gs(t0);
     if (!BF16) load_hn(t0, hn);
-    int buf = 0;
+    int buf = 0;                               // ring position of the tile being multiplied
 
 #ifdef DBG_TIMING
     long long tacc[6] = {0, 0, 0, 0, 0, 0};
@@ -256,21 +280,29 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #define DBG_T(k)
 #endif
     for (int tb = t0; tb < t1; tb += ROWS) {
-        __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0): this wavefront's copies of the tile have landed
+        // This wavefront's copies of the tile have landed.  Vector memory operations complete in issue order and the
+        // copies of the PD - 1 later tiles were issued after this tile's: while those are all still to come, at most
+        // (PD - 1) * NJOBS operations may remain outstanding; at the end of the chunk everything is waited for.
+        if (PD > 1 && tb + (PD - 1) * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | ((PD - 1) * L::NJOBS));
+        else __builtin_amdgcn_s_waitcnt(0x0f70);
         DBG_T(0)
-        __syncthreads();                        // ... and everyone's; everyone has left the other buffer
+        __syncthreads();                        // ... and everyone's; everyone has left the buffer refilled next
         DBG_T(1)
         const bool more = tb + ROWS < t1;
-        unsigned char* next_buf = smem + (buf ^ 1) * L::TILE_BYTES;
+        const bool more_copy = tb + PD * ROWS < t1;
+        const int buf_copy = buf == 0 ? NBUF - 1 : buf - 1;          // = (buf + PD) mod NBUF
+        unsigned char* next_buf = smem + buf_copy * L::TILE_BYTES;
+        const uint32_t a_oct = a_oct0 + buf * L::TILE_BYTES;
         if (more) {
             if (!BF16) load_hn(tb + ROWS, hn_next);
         }
         DBG_T(2)
 
-        // Software pipeline over the K steps: the LDS reads of step s + 1 are issued before the MFMAs of step s,
-        // into the other of two fragment register sets; one copy instruction of the next tile rides along every
-        // COPY_EVERY steps.
-        f32x4 afrag[2][NRT];
+        // Software pipeline over the K steps: the LDS reads of step s + LA are issued before the MFMAs of step s,
+        // into a ring of LA + 1 fragment register sets (LA steps of MFMAs have to cover the LDS latency: a bf16 step
+        // is only 64 MFMA clocks); one copy instruction of a later tile rides along every COPY_EVERY steps.
+        constexpr int LA = L::LA;
+        f32x4 afrag[LA + 1][NRT];
         auto issue_reads = [&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
             static_for<0, NRT>([&](auto rt_c) {
@@ -278,21 +310,28 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 constexpr int total = (s >> 2) * L::OCT_BYTES + rt * 4096;
                 constexpr int win = total / 32768;             // keep the immediate offset below 2^15
                 const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
-                afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+                afrag[s % (LA + 1)][rt] = lds_read16_nowait<total - win * 32768>(base);
             });
         };
         constexpr int COPY_EVERY = NS / L::NJOBS;
-        issue_reads(std::integral_constant<int, 0>{});
+        static_for<0, LA>([&](auto s_c) { issue_reads(s_c); });
         static_for<0, NS>([&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
-            if constexpr (s + 1 < NS) {
-                issue_reads(std::integral_constant<int, s + 1>{});
-                LCRWMD_WAIT_LGKM(NRT);          // everything but the reads just issued has arrived
-            } else {
-                LCRWMD_WAIT_LGKM(0);
+            if constexpr (WGS_PER_CU > 1) {
+                // Two wavefronts share a SIMD's matrix pipe.  Priority rises through the K loop, so of two wavefronts
+                // that multiply at the same time the one further along wins the pipe and pulls ahead: the pair
+                // settles into one multiplying while the other runs its epilogue, instead of both doing the same.
+                if constexpr (s == 0) __builtin_amdgcn_s_setprio(0);
+                if constexpr (s == NS / 3) __builtin_amdgcn_s_setprio(1);
+                if constexpr (s == (2 * NS) / 3) __builtin_amdgcn_s_setprio(2);
+            }
+            if constexpr (s + LA < NS) issue_reads(std::integral_constant<int, s + LA>{});
+            {
+                constexpr int later = (NS - 1 - s < LA ? NS - 1 - s : LA) * NRT;     // reads issued after step s's
+                LCRWMD_WAIT_LGKM(later);
             }
             __builtin_amdgcn_sched_barrier(0);
-            const f32x4* a = afrag[s & 1];
+            const f32x4* a = afrag[s % (LA + 1)];
             if constexpr (BF16) {
 #pragma unroll
                 for (int rt = 0; rt < NRT; ++rt)
@@ -313,14 +352,15 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
             }
 #ifndef DBG_NO_COPY
             if constexpr (s % COPY_EVERY == 0 && s / COPY_EVERY < L::NJOBS) {
-                if (more) copy_job(std::integral_constant<int, s / COPY_EVERY>{}, next_buf);
+                if (more_copy) copy_job(std::integral_constant<int, s / COPY_EVERY>{}, next_buf);
             }
-            if constexpr (s == COPY_EVERY * (L::NJOBS - 1) + 1) {     // all copy jobs issued: fetch the ids for the tile after next
-                if (tb + 2 * ROWS < t1) load_words(tb + 2 * ROWS);
+            if constexpr (s == COPY_EVERY * (L::NJOBS - 1) + 1) {     // all copy jobs issued: fetch the ids for the next tile to copy
+                if (tb + (PD + 1) * ROWS < t1) load_words(tb + (PD + 1) * ROWS);
             }
 #endif
             __builtin_amdgcn_sched_barrier(0);
         });
+        if constexpr (WGS_PER_CU > 1) __builtin_amdgcn_s_setprio(3);      // the epilogue's few instructions go first
         if (!BF16) {
             // one more rank-1 step adds -|T_a|^2/2 to every element of token row a
             const float one = half == 0 ? 1.f : 0.f;
@@ -391,10 +431,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #pragma unroll
             for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
         }
-        {   // the other buffer is read next
-            a_oct += buf ? -L::TILE_BYTES : L::TILE_BYTES;
-        }
-        buf ^= 1;
+        buf = buf == NBUF - 1 ? 0 : buf + 1;
         DBG_T(4)
     }
     if (!TABLE) flush();
@@ -408,14 +445,263 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// bf16 first phase, "ping-pong" form.  A bf16 tile is so short (76 MFMAs, ~2.4k clocks) that neither its epilogue nor
+// the barrier around it can be hidden behind the MFMAs of the same wavefront.  Here one workgroup of EIGHT wavefronts
+// owns a CU: two groups of four (one wavefront of each group per SIMD), each group covering 256 vocabulary words, both
+// reading the same token tiles.  The groups run half a period apart: while one group multiplies a tile, the other one
+// runs the epilogue of the tile it multiplied before and issues its share of the copies; a workgroup barrier ends
+// every half period.  The matrix pipe of a SIMD is then always owned by exactly one wavefront, and everything that is
+// not an MFMA happens in the other wavefront's shadow.
+//
+// Token tiles: 64 rows, the layout of the kernel above, in a ring of four buffers (160 KiB).  The five copy
+// instructions a wavefront contributes to tile t + 3 ride along its K loop over tile t.  It waits for its own copies
+// of tile t + 1 at the end of that K loop with a partial vmcnt: vector memory operations complete in issue order,
+// and the ten copy instructions of tiles t + 2 and t + 3 were issued later, so "at most ten outstanding" means the
+// copies of tile t + 1 (and everything older) have landed.  The barrier that follows publishes them.
+namespace pp {
+constexpr int ROWS = 64, NRT = 2, NCT = 2, NS = 19, NOCT = 5, NBUF = 4, PD = 3;
+constexpr int OCT_BYTES = (ROWS / 8) * 1024, TILE_BYTES = NOCT * OCT_BYTES;
+constexpr int NG = ROWS / 8;
+constexpr int WG_COLS = 2 * 4 * NCT * 32;      // vocabulary words per workgroup
+}  // namespace pp
+
+// Workgroup barrier WITHOUT the memory fences of __syncthreads(): a fence would wait for every outstanding vector
+// memory operation, i.e. for the copies just issued for a tile three periods away and for the stores of Z.  What a
+// barrier has to order here is waited for explicitly: LDS reads with lgkmcnt(0) at the end of a K loop, a
+// wavefront's own copies with vmcnt(0) at the start of its next epilogue.
+__device__ inline void pp_barrier() { __builtin_amdgcn_s_barrier(); }
+
+//
+// The per-tile side tables (word ids of the rows to copy, histogram of every group of 8 rows) are read with uniform
+// addresses through restrict-qualified arguments, i.e. as scalar loads: they are then not part of the vector memory
+// queue whose order the copy waits rely on, and they cost no vector registers.
+__global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t* __restrict__ tok_ids,
+                                                            const int32_t* __restrict__ grp_seg)
+{
+    using namespace pp;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..7
+    const int grp = wave >> 2;                                    // 0: multiplies first; 1: half a period later
+    const int l31 = lane & 31, half = lane >> 5;
+
+    // Work: the (vocabulary tile, chunk) pairs in vocabulary-major order, cut into gridDim.x equal runs, one per
+    // workgroup (the grid is one workgroup per CU).  Chunks are short and end at histogram boundaries; a run of
+    // chunks of one vocabulary tile is one uninterrupted stream of token tiles, so the load is balanced to within a
+    // chunk and the vocabulary operand is reloaded only where a run crosses into the next vocabulary tile.
+    // Workgroups of one XCD (workgroup id mod 8) take neighbouring runs.
+    const int64_t total = (int64_t)p.nvt * p.nchunks;
+    const int64_t wg = (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int64_t item = wg * total / gridDim.x;
+    const int64_t item_end = (wg + 1) * total / gridDim.x;
+
+    const unsigned char* Eb = p.Eb;
+    const int lane8 = lane >> 3;
+    const uint32_t offO = (uint32_t)(((lane & 7) ^ ((wave & 1) * 4 + (lane >> 4))) * 16);
+    const uint32_t pitch32 = (uint32_t)p.pitch_b;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    const uint32_t a_oct0 = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    while (item < item_end) {
+    const int vt = (int)(item / p.nchunks);
+    const int c0 = (int)(item - (int64_t)vt * p.nchunks);
+    const int c1 = (int)(item_end - item < p.nchunks - c0 ? c0 + (item_end - item) : p.nchunks);
+    item += c1 - c0;
+    const int t0 = p.pofs[p.chunk_seg[c0]], t1 = p.pofs[p.chunk_seg[c1]];
+    if (t0 >= t1) continue;
+    const int64_t col0 = (int64_t)vt * WG_COLS + wave * (32 * NCT);      // first vocabulary position of this wavefront
+
+    // ---- vocabulary operand -> registers (lanes past the end repeat the last word) ----
+    float nEw[NCT];
+    f32x4 breg[NS][NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int64_t col = col0 + ct * 32 + l31;
+        const int64_t colc = col < p.nvoc ? col : p.nvoc - 1;
+        const int32_t wid = p.voc_rows ? p.voc_rows[colc] : (int32_t)colc;
+        nEw[ct] = p.normE[wid];
+        const unsigned char* row = Eb + (int64_t)wid * p.pitch_b;
+#pragma unroll
+        for (int s = 0; s < NS; ++s) breg[s][ct] = *reinterpret_cast<const f32x4*>(row + (2 * s + half) * 16);
+    }
+    if (half == 1) {          // the three -|row|^2/2 terms of the token side multiply by one here
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            breg[NS - 1][ct][2] = __uint_as_float(0x3F803F80u);
+            breg[NS - 1][ct][3] = __uint_as_float(0x00003F80u);
+        }
+    }
+
+    // ---- copies: wavefront w moves row block w (rows 8 w .. 8 w + 7) of a tile, one octet per instruction ----
+    // word ids of the 8 rows this wavefront copies (uniform), and this lane's pick
+    struct Ids { int32_t v[8]; };
+    auto load_ids = [&](int tb) {
+        Ids r;
+        const int32_t* t = tok_ids + (tb + wave * 8);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r.v[k] = t[k];
+        return r;
+    };
+    // byte offset of this lane's piece of its row, from the row block's 8 word ids
+    auto row_offset = [&](const Ids& ids) {
+        // lane l < 8 takes id l, then every lane fetches the id of its row from lane (row within the block)
+        int32_t spread = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) asm("v_writelane_b32 %0, %1, %2" : "+v"(spread) : "s"(ids.v[k]), "n"(k));
+        const int32_t wA = __builtin_amdgcn_ds_bpermute(lane8 << 2, spread);
+        return (uint32_t)wA * pitch32 + offO;
+    };
+    auto copy_octet = [&](auto o_c, uint32_t off, unsigned char* lbase) {
+        constexpr int oct = decltype(o_c)::value;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + off + oct * 128),
+                                         (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
+                                         16, 0, 0);
+    };
+    auto copy_tile = [&](const Ids& ids, unsigned char* lbase) {
+        const uint32_t off = row_offset(ids);
+        static_for<0, NOCT>([&](auto o_c) { copy_octet(o_c, off, lbase); });
+    };
+
+    f32x16 acc[NRT][NCT];
+    // Running maximum of the histogram being walked (`cur`), per column tile and lane half; a histogram's value is
+    // complete when the next one starts.  The running maximum is updated with selects; the only branch per group of 8
+    // rows is the one around the store (taken when a histogram ends).
+    int cur = -1;
+    float run[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) run[ct] = 0.f;
+    const float nEsel = half ? nEw[1] : nEw[0];
+    float* zrow;
+    {
+        int64_t pos = col0 + lane;                 // lower lanes: column tile 0, upper lanes: column tile 1
+        if (pos >= p.nvoc) pos = p.nvoc - 1;
+        zrow = p.Z + pos * p.ldz;
+    }
+    // Store the value of histogram `cur`.  One exchange hands the lower lanes both halves' maxima of column tile 0
+    // and the upper lanes those of column tile 1, so one store serves 64 words.
+    auto flush = [&]() {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(run[0]), __float_as_uint(run[1]), false, false);
+        const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        zrow[cur] = __builtin_amdgcn_sqrtf(fmaxf(nEsel - 2.f * best, 0.f));
+    };
+
+    struct Grp { int32_t v[NG]; };
+    auto load_gs = [&](int tb) {
+        Grp r;
+        const int32_t* g = grp_seg + (tb >> 3);
+#pragma unroll
+        for (int k = 0; k < NG; ++k) r.v[k] = g[k];
+        return r;
+    };
+
+    // ---- the first PD tiles ----
+    static_for<0, PD>([&](auto k_c) {
+        constexpr int k = decltype(k_c)::value;
+        if (t0 + k * ROWS < t1) copy_tile(load_ids(t0 + k * ROWS), smem + k * TILE_BYTES);
+    });
+    // copies of tile t + PD ride along the K loop of tile t; their source offsets are formed one epilogue earlier
+    uint32_t off_next = row_offset(load_ids(t0 + PD * ROWS < t1 ? t0 + PD * ROWS : t0));
+    Ids ids_next = load_ids(t0 + (PD + 1) * ROWS < t1 ? t0 + (PD + 1) * ROWS : t0);
+    Grp grp_next = load_gs(t0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): this wavefront's share of the first tiles has landed
+    pp_barrier();
+    if (grp == 1) pp_barrier();                // the second group starts half a period later
+
+    int buf = 0;
+    for (int tb = t0; tb < t1; tb += ROWS) {
+        // ================= half period 1: multiply =================
+        {
+            const uint32_t a_oct = a_oct0 + buf * TILE_BYTES;
+            const bool more_copy = tb + PD * ROWS < t1;
+            unsigned char* copy_buf = smem + (buf == 0 ? NBUF - 1 : buf - 1) * TILE_BYTES;   // (buf + PD) mod NBUF: the tile before this one is done with
+            f32x4 afrag[2][NRT];
+            auto issue_reads = [&](auto s_c) {
+                constexpr int s = decltype(s_c)::value;
+                static_for<0, NRT>([&](auto rt_c) {
+                    constexpr int rt = decltype(rt_c)::value;
+                    constexpr int total = (s >> 2) * OCT_BYTES + rt * 4096;
+                    constexpr int win = total / 32768;
+                    const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
+                    afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+                });
+            };
+            issue_reads(std::integral_constant<int, 0>{});
+            static_for<0, NS>([&](auto s_c) {
+                constexpr int s = decltype(s_c)::value;
+                if constexpr (s + 1 < NS) {
+                    issue_reads(std::integral_constant<int, s + 1>{});
+                    LCRWMD_WAIT_LGKM(NRT);
+                } else {
+                    LCRWMD_WAIT_LGKM(0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const f32x4* a = afrag[s & 1];
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ++ct)
+                        acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                            s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
+                if constexpr (s % 4 == 1 && s / 4 < NOCT) {          // a copy instruction stalls at issue for a while: in the MFMAs' shadow it is free
+                    if (more_copy) copy_octet(std::integral_constant<int, s / 4>{}, off_next, copy_buf);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+        // this wavefront's copies of the next tile have landed (see the head of the kernel)
+        if (tb + PD * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * NOCT));
+        else if (tb + 2 * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | NOCT);
+        else __builtin_amdgcn_s_waitcnt(0x0f70);
+        pp_barrier();
+        // ================= half period 2: everything else =================
+        {
+            int ng = (t1 - tb) >> 3;
+            if (ng > NG) ng = NG;
+            const Grp sgsv = grp_next;
+            const Ids ids = ids_next;
+            const int32_t* sgs = sgsv.v;
+            if (tb + (PD + 1) * ROWS < t1) off_next = row_offset(ids);
+            // the next epilogue's tables: requested only now, so that the wait for the lane exchange above does not
+            // include them, and early enough to be back before the next K loop counts its LDS reads
+            __builtin_amdgcn_sched_barrier(0);
+            if (tb + ROWS < t1) grp_next = load_gs(tb + ROWS);
+            if (tb + (PD + 2) * ROWS < t1) ids_next = load_ids(tb + (PD + 2) * ROWS);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const bool live = g < ng;                      // groups past the end of the chunk are someone else's
+                const int sg = live ? sgs[g] : cur;
+                const bool is_new = sg != cur;
+                const int rt = g >> 2, r0 = (g & 3) * 4;
+                if (is_new && cur >= 0) flush();
+                cur = sg;
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct) {
+                    const float mg = fmaxf(fmaxf(acc[rt][ct][r0], acc[rt][ct][r0 + 1]), fmaxf(acc[rt][ct][r0 + 2], acc[rt][ct][r0 + 3]));
+                    run[ct] = fmaxf(live ? mg : -INFINITY, is_new ? -INFINITY : run[ct]);
+                }
+            }
+        }
+        pp_barrier();
+        buf = buf == NBUF - 1 ? 0 : buf + 1;
+    }
+    if (grp == 0) pp_barrier();             // both groups pass the same number of barriers; nobody reads LDS any more
+    if (cur >= 0) flush();
+    }   // runs of this workgroup
+}
+
 template <bool BF16, int NCT, int WGS_PER_CU, bool TABLE>
 hipError_t launch_tiles(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
-    const int64_t items = (int64_t)d.nvt * d.nchunks;
-    const int64_t grid = (items + 7) / 8 * 8;
+    const int64_t grid = 8 * (int64_t)d.nvt * ((d.nchunks + 7) / 8);       // per XCD: nvt items in every 8 chunks
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    const size_t smem = 2 * (size_t)Layout<BF16>::TILE_BYTES;
+    const size_t smem = (size_t)Layout<BF16>::NBUF * (size_t)Layout<BF16>::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NCT, WGS_PER_CU, TABLE>),
@@ -467,13 +753,27 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
 }
 
 // a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
-hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
+hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s)
 {
     P1T d = common_args(a, tp);
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<true>::NOCT * 8;
     d.nzero_from = 0;
-    return launch_tiles<true, 2, 2, false>(d, s);
+    d.nvt = (int32_t)((d.nvoc + pp::WG_COLS - 1) / pp::WG_COLS);
+    // one workgroup per CU (it takes all of a CU's LDS), fewer when there is less work than that
+    const int64_t total = (int64_t)d.nvt * d.nchunks;
+    int64_t grid = num_cu > 8 ? num_cu / 8 * 8 : 8;
+    while (grid > 8 && grid > total) grid -= 8;
+    const size_t smem = (size_t)pp::NBUF * pp::TILE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_pingpong),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    k_phase1_pingpong<<<(unsigned)grid, 512, smem, s>>>(d, d.tok_ids, d.grp_seg);
+    return hipGetLastError();
 }
 
 // Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
@@ -495,9 +795,9 @@ hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* 
     // a few thousand work items (vocabulary tiles x chunks of token rows), each chunk 4 .. 64 tiles of 64 rows
     const int64_t nvt = (a.nvoc + 255) / 256;
     const int64_t want_chunks = (4096 + nvt - 1) / nvt;
-    int64_t ct = ((ntok + want_chunks - 1) / want_chunks + ROWS - 1) / ROWS * ROWS;
-    if (ct < 4 * ROWS) ct = 4 * ROWS;
-    if (ct > 64 * ROWS) ct = 64 * ROWS;
+    int64_t ct = ((ntok + want_chunks - 1) / want_chunks + kMaxRows - 1) / kMaxRows * kMaxRows;
+    if (ct < 4 * kMaxRows) ct = 4 * kMaxRows;
+    if (ct > 64 * kMaxRows) ct = 64 * kMaxRows;
     d.chunk_tokens = (int32_t)ct;
     d.nchunks = (int32_t)((ntok + ct - 1) / ct);
     d.pofs = nullptr;
