@@ -456,9 +456,9 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 //
 // Token tiles: 64 rows, the layout of the kernel above, in a ring of four buffers (160 KiB).  The five copy
 // instructions a wavefront contributes to tile t + 3 ride along its K loop over tile t.  It waits for its own copies
-// of tile t + 1 at the end of that K loop with a partial vmcnt: vector memory operations complete in issue order,
-// and the ten copy instructions of tiles t + 2 and t + 3 were issued later, so "at most ten outstanding" means the
-// copies of tile t + 1 (and everything older) have landed.  The barrier that follows publishes them.
+// of tile t + 2 at the end of that K loop with a partial vmcnt: vector memory operations complete in issue order,
+// and the five copy instructions of tile t + 3 were issued later, so "at most five outstanding" means the copies of
+// tile t + 2 (and everything older) have landed.  The barrier that follows publishes them.
 namespace pp {
 constexpr int ROWS = 64, NRT = 2, NCT = 2, NS = 19, NOCT = 5, NBUF = 4, PD = 3;
 constexpr int OCT_BYTES = (ROWS / 8) * 1024, TILE_BYTES = NOCT * OCT_BYTES;
@@ -611,85 +611,93 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     pp_barrier();
     if (grp == 1) pp_barrier();                // the second group starts half a period later
 
-    int buf = 0;
-    for (int tb = t0; tb < t1; tb += ROWS) {
-        // ================= half period 1: multiply =================
-        {
-            const uint32_t a_oct = a_oct0 + buf * TILE_BYTES;
-            const bool more_copy = tb + PD * ROWS < t1;
-            unsigned char* copy_buf = smem + (buf == 0 ? NBUF - 1 : buf - 1) * TILE_BYTES;   // (buf + PD) mod NBUF: the tile before this one is done with
-            f32x4 afrag[2][NRT];
-            auto issue_reads = [&](auto s_c) {
-                constexpr int s = decltype(s_c)::value;
-                static_for<0, NRT>([&](auto rt_c) {
-                    constexpr int rt = decltype(rt_c)::value;
-                    constexpr int total = (s >> 2) * OCT_BYTES + rt * 4096;
-                    constexpr int win = total / 32768;
-                    const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
-                    afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
-                });
-            };
-            issue_reads(std::integral_constant<int, 0>{});
-            static_for<0, NS>([&](auto s_c) {
-                constexpr int s = decltype(s_c)::value;
-                if constexpr (s + 1 < NS) {
-                    issue_reads(std::integral_constant<int, s + 1>{});
-                    LCRWMD_WAIT_LGKM(NRT);
-                } else {
-                    LCRWMD_WAIT_LGKM(0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                const f32x4* a = afrag[s & 1];
+    // The epilogue of a tile: histogram maxima of its 8 groups, the stores of the histograms that end in it, the
+    // source offsets of the copies two K loops ahead and the scalar table loads for the epilogue after this one.
+    auto epilogue = [&](int tb) {
+        int ng = (t1 - tb) >> 3;
+        if (ng > NG) ng = NG;
+        const Grp sgsv = grp_next;
+        const Ids ids = ids_next;
+        const int32_t* sgs = sgsv.v;
+        if (tb + (PD + 1) * ROWS < t1) off_next = row_offset(ids);
+        // the next epilogue's tables: requested only now, so that the wait for the lane exchange above does not
+        // include them, and early enough to be back before the next K loop counts its LDS reads
+        __builtin_amdgcn_sched_barrier(0);
+        if (tb + ROWS < t1) grp_next = load_gs(tb + ROWS);
+        if (tb + (PD + 2) * ROWS < t1) ids_next = load_ids(tb + (PD + 2) * ROWS);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int rt = 0; rt < NRT; ++rt)
+        for (int g = 0; g < NG; ++g) {
+            const bool live = g < ng;                      // groups past the end of the chunk are someone else's
+            const int sg = live ? sgs[g] : cur;
+            const bool is_new = sg != cur;
+            const int rt = g >> 2, r0 = (g & 3) * 4;
+            if (is_new && cur >= 0) flush();
+            cur = sg;
 #pragma unroll
-                    for (int ct = 0; ct < NCT; ++ct)
-                        acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
-                            s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
-                if constexpr (s % 4 == 1 && s / 4 < NOCT) {          // a copy instruction stalls at issue for a while: in the MFMAs' shadow it is free
-                    if (more_copy) copy_octet(std::integral_constant<int, s / 4>{}, off_next, copy_buf);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        }
-        // this wavefront's copies of the next tile have landed (see the head of the kernel)
-        if (tb + PD * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * NOCT));
-        else if (tb + 2 * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | NOCT);
-        else __builtin_amdgcn_s_waitcnt(0x0f70);
-        pp_barrier();
-        // ================= half period 2: everything else =================
-        {
-            int ng = (t1 - tb) >> 3;
-            if (ng > NG) ng = NG;
-            const Grp sgsv = grp_next;
-            const Ids ids = ids_next;
-            const int32_t* sgs = sgsv.v;
-            if (tb + (PD + 1) * ROWS < t1) off_next = row_offset(ids);
-            // the next epilogue's tables: requested only now, so that the wait for the lane exchange above does not
-            // include them, and early enough to be back before the next K loop counts its LDS reads
-            __builtin_amdgcn_sched_barrier(0);
-            if (tb + ROWS < t1) grp_next = load_gs(tb + ROWS);
-            if (tb + (PD + 2) * ROWS < t1) ids_next = load_ids(tb + (PD + 2) * ROWS);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const bool live = g < ng;                      // groups past the end of the chunk are someone else's
-                const int sg = live ? sgs[g] : cur;
-                const bool is_new = sg != cur;
-                const int rt = g >> 2, r0 = (g & 3) * 4;
-                if (is_new && cur >= 0) flush();
-                cur = sg;
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct) {
-                    const float mg = fmaxf(fmaxf(acc[rt][ct][r0], acc[rt][ct][r0 + 1]), fmaxf(acc[rt][ct][r0 + 2], acc[rt][ct][r0 + 3]));
-                    run[ct] = fmaxf(live ? mg : -INFINITY, is_new ? -INFINITY : run[ct]);
-                }
+            for (int ct = 0; ct < NCT; ++ct) {
+                const float mg = fmaxf(fmaxf(acc[rt][ct][r0], acc[rt][ct][r0 + 1]), fmaxf(acc[rt][ct][r0 + 2], acc[rt][ct][r0 + 3]));
+                run[ct] = fmaxf(live ? mg : -INFINITY, is_new ? -INFINITY : run[ct]);
             }
         }
+    };
+
+    // One loop iteration = [epilogue of the previous tile] [first LDS reads of this tile] barrier [K loop] barrier.
+    // The reads are issued BEFORE the barrier that starts the K loop, so the matrix pipe does not wait for the LDS
+    // latency at the start of every half period; they are legal there because every wavefront waits, at the end of
+    // its K loop over tile t, for its copies of tile t + 2 (not t + 1): a tile is complete in LDS, and published by a
+    // barrier, a full period before its first read.
+    int buf = 0;
+    for (int tb = t0; tb < t1; tb += ROWS) {
+        if (tb > t0) epilogue(tb - ROWS);
+        const uint32_t a_oct = a_oct0 + buf * TILE_BYTES;
+        const bool more_copy = tb + PD * ROWS < t1;
+        unsigned char* copy_buf = smem + (buf == 0 ? NBUF - 1 : buf - 1) * TILE_BYTES;   // (buf + PD) mod NBUF: the tile before this one is done with
+        // Two fragment register sets: the reads of step s + 1 are issued before the MFMAs of step s.
+        f32x4 afrag[2][NRT];
+        auto issue_reads = [&](auto s_c) {
+            constexpr int s = decltype(s_c)::value;
+            static_for<0, NRT>([&](auto rt_c) {
+                constexpr int rt = decltype(rt_c)::value;
+                constexpr int total = (s >> 2) * OCT_BYTES + rt * 4096;
+                constexpr int win = total / 32768;
+                const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
+                afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+            });
+        };
+        issue_reads(std::integral_constant<int, 0>{});
+        if (tb > t0) pp_barrier();              // ends the half period of the epilogue above
+        // ================= multiply =================
+        static_for<0, NS>([&](auto s_c) {
+            constexpr int s = decltype(s_c)::value;
+            if constexpr (s + 1 < NS) {
+                issue_reads(std::integral_constant<int, s + 1>{});
+                LCRWMD_WAIT_LGKM(NRT);
+            } else {
+                LCRWMD_WAIT_LGKM(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const f32x4* a = afrag[s & 1];
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct)
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                        s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
+            if constexpr (s % 4 == 1 && s / 4 < NOCT) {          // a copy instruction stalls at issue for a while: in the MFMAs' shadow it is free
+                if (more_copy) copy_octet(std::integral_constant<int, s / 4>{}, off_next, copy_buf);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // this wavefront's copies of the tile after next have landed (see the head of the kernel)
+        if (tb + PD * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | NOCT);
+        else __builtin_amdgcn_s_waitcnt(0x0f70);
         pp_barrier();
         buf = buf == NBUF - 1 ? 0 : buf + 1;
     }
+    epilogue(t1 - 1 - ((t1 - 1 - t0) % ROWS));      // the last tile's
+    pp_barrier();
     if (grp == 0) pp_barrier();             // both groups pass the same number of barriers; nobody reads LDS any more
     if (cur >= 0) flush();
     }   // runs of this workgroup
