@@ -137,6 +137,28 @@ def main():
     p2_gbs = prof["phase2_bytes"] / max(prof["phase2_ms"], 1e-9) / 1e6
     p2_gather_gbs = prof["phase2_gather_bytes"] / max(prof["phase2_ms"], 1e-9) / 1e6
 
+    # The de-duplicated form of the same job, timed next to the default one (reported, never `value`).
+    variant = None
+    if not args.dedup and not k and not cfg.queries_from_db:
+        try:
+            ctx.set_options(compute=compute, dedup=1)
+            ws2 = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, emb_dtype, 0))
+            D2 = torch.empty((n, q), dtype=torch.float32, device="cuda")
+            ctx.rwmd(qs, db, E, D2, ws2)
+            torch.cuda.synchronize()
+            tv = time.perf_counter()
+            for _ in range(args.steps):
+                ctx.rwmd(qs, db, E, D2, ws2)
+            torch.cuda.synchronize()
+            tv = (time.perf_counter() - tv) / args.steps
+            variant = {"form": "dedup (word-pair table per query batch, same result)", "ms_per_step": 1e3 * tv,
+                       "pairs_per_s": n * q / tv, "max_abs_diff_vs_default": float((D2 - D).abs().max())}
+            del ws2, D2
+        except (RuntimeError, binding.LcrwmdError) as e:      # e.g. not enough device memory for the table
+            variant = {"form": "dedup", "skipped": str(e)[:200]}
+        finally:
+            ctx.set_options(compute=compute, dedup=0)
+
     # sampled check of the timed result against the oracle's per-pair brute force
     cpu = None
     check = None
@@ -206,6 +228,12 @@ def main():
                    "gather_GBps": p2_gather_gbs, "launches_per_step": prof["phase2_launches"] / args.steps,
                    "avg_launch_ms": p2_ms, "share_of_step": prof["phase2_ms"] / (1e3 * sec)},
         "cpu_baseline": cpu,
+        "dedup_variant": variant,
+        "time_split_ms_per_step": {"phase1": prof["phase1_ms"] / args.steps, "phase2": prof["phase2_ms"] / args.steps,
+                                   "table_passes": (prof["table_fwd_ms"] + prof["table_rev_ms"]) / args.steps,
+                                   "rest": ms_per_step - (prof["phase1_ms"] + prof["phase2_ms"] + prof["table_fwd_ms"] +
+                                                          prof["table_rev_ms"]) / args.steps},
+        "numpy": np.__version__,
         "max_rel_err_vs_oracle_512_pairs": check,
     }
     print(json.dumps(out))
