@@ -12,34 +12,20 @@ namespace lcrwmd {
 
 namespace {
 
-// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
-// Units are ordered strip-major and workgroup ids follow that order, so at any time the whole chip works on
-// one strip of columns: the strip of Z (rows of 256 W bytes) is what has to stay in the L2s / Infinity Cache,
-// not the full rows.
-template <int W, int COMBINE>
-__global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
-                                                   const float* __restrict__ xv, int64_t rows,
-                                                   const float* __restrict__ Z, int64_t ldz, int64_t ncols,
-                                                   float* __restrict__ D, int64_t ldd, int64_t strips)
+// acc[t] = sum over the stored entries p in [a, b) of xv[p] * Z[ci[p]][j + t], t < W, for this lane's columns
+// j .. j + W - 1 (a, b wave-uniform).
+// 64 stored entries at a time: one coalesced load of (column, weight) per lane, then each entry is broadcast
+// with readlane and its row segment of Z gathered; the gathers of a batch are independent of one another.
+template <int W>
+__device__ inline void row_times_strip(int64_t a, int64_t b, const int32_t* __restrict__ ci, const float* __restrict__ xv,
+                                       const float* __restrict__ Z, int64_t ldz, int64_t ncols, int64_t j, int lane,
+                                       float* acc)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t strip = unit / rows;
-    const int64_t i = unit - strip * rows;
-    if (strip >= strips) return;
-    const int64_t j = strip * (64 * W) + (int64_t)lane * W;
-    // row bounds are wave-uniform: keep them scalar so that the loop control and the row addresses of Z are scalar too
-    const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
-    const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
-    float acc[W];
 #pragma unroll
     for (int t = 0; t < W; ++t) acc[t] = 0.f;
     const bool full = j + W - 1 < ncols;
     const float* zj = Z + j;
     typedef float vecw __attribute__((ext_vector_type(W)));
-
-    // 64 stored entries at a time: one coalesced load of (column, weight) per lane, then each entry is broadcast
-    // with readlane and its row segment of Z gathered; the gathers of a batch are independent of one another.
     for (int64_t p0 = a; p0 < b; p0 += 64) {
         const int cnt = (int)(b - p0 < 64 ? b - p0 : 64);
         int cv = 0;
@@ -73,6 +59,29 @@ __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ r
             }
         }
     }
+}
+
+// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
+// Units are ordered strip-major and workgroup ids follow that order, so at any time the whole chip works on
+// one strip of columns: the strip of Z (rows of 256 W bytes) is what has to stay in the L2s / Infinity Cache,
+// not the full rows.
+template <int W, int COMBINE>
+__global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                                                   const float* __restrict__ xv, int64_t rows,
+                                                   const float* __restrict__ Z, int64_t ldz, int64_t ncols,
+                                                   float* __restrict__ D, int64_t ldd, int64_t strips)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t strip = unit / rows;
+    const int64_t i = unit - strip * rows;
+    if (strip >= strips) return;
+    const int64_t j = strip * (64 * W) + (int64_t)lane * W;
+    // row bounds are wave-uniform: keep them scalar so that the loop control and the row addresses of Z are scalar too
+    const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
+    const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
+    float acc[W];
+    row_times_strip<W>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
 
 #pragma unroll
     for (int t = 0; t < W; ++t) {
@@ -136,12 +145,63 @@ __global__ __launch_bounds__(256) void k_spmm_tmax(const int64_t* __restrict__ r
     }
 }
 
+// Transposed maximum, wide form: a workgroup computes a 32 (rows of X) x 256 (columns) tile of S, every wavefront
+// 8 rows with 16-byte gathers exactly as k_spmm_rows does, and turns the tile through LDS so that the
+// read-modify-write of D runs along D's rows (32 consecutive floats = one 128-byte line per column of the tile).
+// Needs 16-byte aligned rows of Z.  Row tiles vary fastest, so the workgroups that share a strip of columns of Z
+// run together.
+constexpr int WR = 32, WC = 256;
+
+__global__ __launch_bounds__(256) void k_spmm_tmax_wide(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                                                        const float* __restrict__ xv, int64_t rows,
+                                                        const float* __restrict__ Z, int64_t ldz, int64_t ncols,
+                                                        float* __restrict__ D, int64_t ldd, int64_t row_tiles)
+{
+    __shared__ float tile[WR][WC + 1];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t ct = blockIdx.x / row_tiles;
+    const int64_t rt = blockIdx.x - ct * row_tiles;
+    const int64_t r0 = rt * WR, c0 = ct * WC;
+    const int64_t j = c0 + (int64_t)lane * 4;
+
+    for (int k = 0; k < WR / 4; ++k) {
+        const int rr = wave * (WR / 4) + k;
+        const int64_t r = r0 + rr;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r < rows) {
+            const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[r]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r] >> 32)) << 32);
+            const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[r + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r + 1] >> 32)) << 32);
+            row_times_strip<4>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) tile[rr][4 * lane + t] = acc[t];
+    }
+    __syncthreads();
+    // thread -> (row of the tile = position along D's row, column of the tile = row of D)
+    const int tr = threadIdx.x & (WR - 1);
+    for (int tc = threadIdx.x / WR; tc < WC; tc += 256 / WR) {
+        const int64_t dr = c0 + tc, dc = r0 + tr;
+        if (dr < ncols && dc < rows) {
+            float* d = D + dr * ldd + dc;
+            *d = fmaxf(*d, tile[tr][tc]);
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, int64_t rows, const float* Z,
                        int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine, hipStream_t s)
 {
     if (rows <= 0 || ncols <= 0) return hipSuccess;
+    if (combine == 2 && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 128) {
+        const int64_t row_tiles = (rows + WR - 1) / WR, col_tiles = (ncols + WC - 1) / WC;
+        const int64_t grid = row_tiles * col_tiles;
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        k_spmm_tmax_wide<<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, row_tiles);
+        return hipGetLastError();
+    }
     if (combine == 2) {
         const int64_t row_tiles = (rows + TR - 1) / TR, col_tiles = (ncols + TC - 1) / TC;
         const int64_t grid = row_tiles * col_tiles;
