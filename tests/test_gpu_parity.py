@@ -308,6 +308,37 @@ def test_phase1_bf16_matches_oracle_on_rounded_embeddings(ctx, v, m, q, h_lo, h_
         assert np.all(Za[col[ptr[j]:ptr[j + 1]], j] == 0.0)
 
 
+@pytest.mark.parametrize("compute", ["f32", "bf16"])
+def test_phase1_tile_and_pipeline_boundaries(ctx, compute):
+    """Token counts around the tile sizes (32 / 64 rows), the depth of the copy pipeline (1..5 tiles per chunk) and the
+    chunk length; vocabulary sizes around the workgroup widths (256 / 512 words)."""
+    bf16 = compute == "bf16"
+    rng = np.random.default_rng(11)
+    ctx.set_options(compute=binding.BF16 if bf16 else binding.F32)
+    try:
+        for v, lens in [(1, [1]), (255, [8]), (256, [7, 1]), (257, [64]), (511, [63, 9]), (512, [128]), (513, [65, 64, 63]),
+                        (1025, [200, 56]), (300, [320]), (600, [31] * 17), (700, [8] * 70), (530, [1] * 300),
+                        (520, [100] * 6), (1100, [3, 250, 2, 260, 1])]:
+            print(f"boundaries {compute} v={v} lens={lens[:6]}", flush=True)
+            E = synth.embeddings(v, 300, 100 + v)
+            Er = bf16_round(E) if bf16 else E
+            lens = [min(l, v) for l in lens]
+            ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+            col = np.concatenate([np.sort(rng.choice(v, size=l, replace=False)) for l in lens]).astype(np.int32)
+            val = np.concatenate([np.full(l, 1.0 / l) for l in lens]).astype(np.float32)
+            qs = (ptr, col, val)
+            q = len(lens)
+            ref = oracle.phase1(Er, qs)
+            Z = torch.full((v, q), -5.0, dtype=torch.float32, device="cuda")
+            dt = binding.BF16 if bf16 else binding.F32
+            ws = binding.alloc_workspace(ctx.workspace_bytes(v, 300, 0, 0, q, len(col), dt))
+            ctx.phase1_mindist(torch.from_numpy(E).cuda(), binding.Csr.from_numpy(qs, v), Z, ws)
+            torch.cuda.synchronize()
+            assert_close(Z.cpu().numpy(), ref, what=f"Z {compute} v={v} q={q}")
+    finally:
+        ctx.set_options()
+
+
 def test_rwmd_bf16_tiny_and_ragged(ctx, tiny):
     for p in (tiny, problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)):
         Er = bf16_round(p["E"])
