@@ -50,7 +50,9 @@ typedef enum {
 } lcrwmd_status;
 
 /* Storage type of embedding values.  Accumulation is always fp32. */
-typedef enum { LCRWMD_F32 = 0, LCRWMD_BF16 = 1 } lcrwmd_dtype;
+typedef enum { LCRWMD_F32 = 0, LCRWMD_BF16 = 1,
+               LCRWMD_BF16X3 = 2   /* only as lcrwmd_options.compute, never as a storage type */
+} lcrwmd_dtype;
 
 /* A set of histograms X (Sec. III, Fig. 2): one sparse row per document. */
 typedef struct {
@@ -77,7 +79,13 @@ typedef struct {
                                        LCRWMD_F32 (default for fp32 E): fp32 MFMA.  LCRWMD_BF16: E is
                                        rounded to bf16 (round-to-nearest-even) unless already bf16,
                                        products accumulate in fp32.  bf16 E always computes in bf16.
-                                       The bf16 path needs m <= 300 (LCRWMD_EUNSUPPORTED otherwise).  */
+                                       The bf16 path needs m <= 300 (LCRWMD_EUNSUPPORTED otherwise).
+                                       LCRWMD_BF16X3 (fp32 E, m <= 300, dedup 0; otherwise it means
+                                       LCRWMD_F32): every fp32 value x is split into hi = bf16(x) and
+                                       lo = bf16(x - hi) and a product is taken as hi*hi + hi*lo + lo*hi
+                                       on the bf16 matrix units with fp32 accumulation; norms stay fp32.
+                                       The dropped lo*lo term is 2^-16 relative: distances agree with
+                                       fp32 arithmetic to about 1e-6 relative for unit-norm rows.      */
     int64_t max_query_batch;        /* upper limit on histograms of X2 per pass (Sec. IV, many-to-many:
                                        X2 is divided into batches); 0 = chosen from the workspace     */
     int64_t max_db_batch;           /* same for the database rows handled per pass of the swapped

@@ -18,7 +18,7 @@ _HERE = pathlib.Path(__file__).resolve().parent
 LIB_PATH = pathlib.Path(os.environ.get("LCRWMD_LIB", _HERE / "liblcrwmd.so"))
 
 OK, EINVAL, EBADCSR, EEMPTYDOC, EWORKSPACE, EUNSUPPORTED, EHIP = range(7)
-F32, BF16 = 0, 1
+F32, BF16, BF16X3 = 0, 1, 2     # BF16X3: only as the compute option
 STATUS_NAMES = {0: "OK", 1: "EINVAL", 2: "EBADCSR", 3: "EEMPTYDOC", 4: "EWORKSPACE", 5: "EUNSUPPORTED", 6: "EHIP"}
 
 EXPORTS = (

@@ -96,6 +96,15 @@ lcrwmd_status check_ws(lcrwmd_ctx* ctx, const void* ws, size_t ws_bytes)
 
 bool use_bf16(const lcrwmd_ctx* ctx, const lcrwmd_emb* E) { return E->dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16; }
 
+// Arithmetic of the first phase: 0 fp32, 1 bf16, 2 split bf16 (three products per fp32 product).  The split form
+// exists for fp32 E with m <= 300 in the default (per-entry) form; anything else that asks for it computes in fp32.
+int prec_mode(const lcrwmd_ctx* ctx, const lcrwmd_emb* E)
+{
+    if (use_bf16(ctx, E)) return 1;
+    if (ctx->opt.compute == LCRWMD_BF16X3 && E->m <= 300 && !ctx->opt.dedup) return 2;
+    return 0;
+}
+
 lcrwmd_status validate_on_device(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, int32_t* dev_status,
                                  hipStream_t s)
 {
@@ -114,19 +123,29 @@ struct EmbPrep {
     const void* data;
     int64_t ld;
     float* normE;
-    bool bf16;
+    bool bf16;     // mode 1
+    int mode;      // see prec_mode
 };
 
-size_t emb_prep_bytes(int64_t v, int32_t m, bool bf16)
+size_t emb_prep_bytes(int64_t v, int32_t m, int mode)
 {
-    return (size_t)v * 4 + 256 + (bf16 ? pack_bf16_bytes(v, m) + 256 : 0);
+    return (size_t)v * 4 + 256 + (mode == 1 ? pack_bf16_bytes(v, m) + 256 : mode == 2 ? pack_x3_bytes(v) + 256 : 0);
 }
 
 lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep& ep, hipStream_t s)
 {
-    ep.bf16 = use_bf16(ctx, E);
+    ep.mode = prec_mode(ctx, E);
+    ep.bf16 = ep.mode == 1;
     ep.normE = b.take_n<float>((size_t)E->v);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the word norms");
+    if (ep.mode == 2) {
+        void* packed = b.take(pack_x3_bytes(E->v));
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the split copy of E");
+        HIP_TRY(launch_pack_x3((const float*)E->data, E->v, (int32_t)E->m, E->ld, packed, ep.normE, s));
+        ep.data = packed;
+        ep.ld = x3_pitch();
+        return LCRWMD_OK;
+    }
     if (ep.bf16) {
         if (!bf16_supported((int32_t)E->m))
             return fail(ctx, LCRWMD_EUNSUPPORTED, "the bf16 path supports m <= 300 (got %lld)", (long long)E->m);
@@ -163,7 +182,8 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     a.num_cu = ctx->num_cu;
     {
         ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m);
-        if (ep.bf16) HIP_TRY(launch_phase1_bf16(a, tp, s));
+        if (ep.mode == 2) HIP_TRY(launch_phase1_tiles_x3(a, tp, s));
+        else if (ep.bf16) HIP_TRY(launch_phase1_bf16(a, tp, s));
         else HIP_TRY(launch_phase1_f32(a, tp, s));
     }
     // a word that occurs in the histogram is at distance exactly 0 from it; the norm expansion
@@ -192,9 +212,9 @@ int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 int64_t plan_tiles(int64_t nvt, bool bf16) { return bf16 ? (nvt + 7) / 8 : nvt; }
 
 // Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
-size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, bool bf16)
+size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int mode)
 {
-    size_t b = emb_prep_bytes(v, m, bf16);
+    size_t b = emb_prep_bytes(v, m, mode);
     b += 4 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position maps of both sets
     b += (size_t)(v < nnz_q ? v : nnz_q) * 4 + 256;   // word list of the queries
     b += (size_t)nnz_q * 4 + 256;             // query columns renumbered to positions
@@ -495,7 +515,8 @@ lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt)
 {
     if (!ctx) return LCRWMD_EINVAL;
     if (!opt) return fail(ctx, LCRWMD_EINVAL, "options are NULL");
-    if ((opt->validate != 0 && opt->validate != 1) || (opt->compute != LCRWMD_F32 && opt->compute != LCRWMD_BF16) ||
+    if ((opt->validate != 0 && opt->validate != 1) ||
+        (opt->compute != LCRWMD_F32 && opt->compute != LCRWMD_BF16 && opt->compute != LCRWMD_BF16X3) ||
         opt->max_query_batch < 0 || opt->max_db_batch < 0 || (opt->dedup != 0 && opt->dedup != 1))
         return fail(ctx, LCRWMD_EINVAL, "option out of range");
     ctx->opt = *opt;
@@ -516,7 +537,8 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
     if (v <= 0 || m <= 0 || n < 0 || nnz_db < 0 || q < 0 || nnz_q < 0 || k < 0)
         return fail(ctx, LCRWMD_EINVAL, "negative size");
-    const bool bf16 = emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16;
+    const int bf16 = (emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16) ? 1
+                     : (ctx->opt.compute == LCRWMD_BF16X3 && m <= 300 && !ctx->opt.dedup) ? 2 : 0;     // see prec_mode
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     if (k > 0 && qb > 2048) qb = 2048;
@@ -570,7 +592,7 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     TokenPlan tp;
     carve_token_plan(b, tp, queries->rows, queries->nnz, plan_tiles((E->v + kTileVocab - 1) / kTileVocab, ep.bf16));
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
-                           emb_prep_bytes(E->v, (int32_t)E->m, ep.bf16) + token_plan_bytes(queries->rows, queries->nnz));
+                           emb_prep_bytes(E->v, (int32_t)E->m, ep.mode) + token_plan_bytes(queries->rows, queries->nnz));
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,
                       queries->nnz, tp, Z, ldz, s);
 }
@@ -654,7 +676,7 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
     int64_t qb = q < 2048 ? q : 2048;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
-    const bool bf16 = use_bf16(ctx, E);
+    const int bf16 = prec_mode(ctx, E);
     for (;;) {
         size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
         size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16) +

@@ -119,6 +119,11 @@ hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStrea
 bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s);
+hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+// split-bf16 operand copy: 640 bf16 per row (304 hi values, 304 lo values, zeros)
+size_t pack_x3_bytes(int64_t v);
+int32_t x3_pitch();
+hipError_t launch_pack_x3(const float* E, int64_t v, int32_t m, int64_t ld, void* packed, float* normE, hipStream_t s);
 bool distance_table_supported(const Phase1Args& a, bool bf16);
 hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
                                  int64_t ntok, hipStream_t s);

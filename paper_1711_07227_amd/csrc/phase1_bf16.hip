@@ -55,6 +55,32 @@ __global__ __launch_bounds__(256) void k_pack_bf16(const void* __restrict__ E, i
     }
 }
 
+// Split copy for the three-product form: value x -> hi = bf16(x), lo = bf16(x - hi); a row holds the 304 hi values
+// (zeros beyond m), then the 304 lo values, then zeros up to 640.  The norms are those of the fp32 values.
+__global__ __launch_bounds__(256) void k_pack_x3(const float* __restrict__ E, int64_t v, int32_t m, int64_t ld,
+                                                 uint16_t* __restrict__ packed, float* __restrict__ normE)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= v) return;
+    uint16_t* out = packed + w * 640;
+    float s = 0.f;
+    for (int t = lane; t < 320; t += 64) {
+        uint16_t hi = 0, lo = 0;
+        if (t < m) {
+            const float x = E[w * ld + t];
+            hi = f32_to_bf16_rne(x);
+            lo = f32_to_bf16_rne(x - bf16_to_f32(hi));
+            s = fmaf(x, x, s);
+        }
+        if (t < 304) { out[t] = hi; out[304 + t] = lo; }
+        else out[304 + t] = 0;            // columns 608 .. 623
+    }
+    if (lane < 16) out[624 + lane] = 0;
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) normE[w] = s;
+}
+
 }  // namespace
 
 // The packed row always has the tile kernel's shape: 320 columns, values in [0, m), zeros up to column 300, the three
@@ -71,6 +97,17 @@ hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_
     if (!bf16_supported(m)) return hipErrorNotSupported;
     k_pack_bf16<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, dtype == LCRWMD_BF16 ? 1 : 0, v, m, ld, kPackPitch, kNormCol,
                                                        (uint16_t*)packed, normE);
+    return hipGetLastError();
+}
+
+size_t pack_x3_bytes(int64_t v) { return (size_t)v * 640 * 2; }
+int32_t x3_pitch() { return 640; }
+
+hipError_t launch_pack_x3(const float* E, int64_t v, int32_t m, int64_t ld, void* packed, float* normE, hipStream_t s)
+{
+    if (v <= 0) return hipSuccess;
+    if (m > kNormCol) return hipErrorNotSupported;
+    k_pack_x3<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, v, m, ld, (uint16_t*)packed, normE);
     return hipGetLastError();
 }
 

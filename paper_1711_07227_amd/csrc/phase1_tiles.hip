@@ -86,16 +86,26 @@ struct P1T {
     int64_t ldz;
 };
 
+// Arithmetic of the contraction.
+//   F32:  fp32 operands, v_mfma_f32_32x32x2_f32.
+//   BF16: operands rounded to bf16, v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+//   X3:   every fp32 operand value x is split into two bf16 terms, hi = bf16(x) and lo = bf16(x - hi), and the product
+//         of two values is taken as hi*hi + hi*lo + lo*hi (three bf16 MFMAs, fp32 accumulation; the lo*lo term, 2^-16
+//         relative, is dropped).  The operand rows hold the 304 hi values followed by the 304 lo values: the row has
+//         the shape of an fp32 row (76 pieces), K step s < 19 is the hi piece pair and step s + 19 its lo pair.
+enum : int { kF32 = 0, kBF16 = 1, kX3 = 2 };
+
 // Tile shape per path: ROWS token rows (NRT 32-row MFMA tiles) and NBUF LDS buffers.
-template <bool BF16>
+template <int MODE>
 struct Layout {
-    static constexpr int ROWS = BF16 ? 32 : 64;
+    static constexpr int ROWS = MODE == kBF16 ? 32 : 64;
     static constexpr int NRT = ROWS / 32;
-    static constexpr int NBUF = BF16 ? 4 : 2;
+    static constexpr int NBUF = MODE == kBF16 ? 4 : 2;
     static constexpr int PD = NBUF - 1;                       // tiles between a copy and its use
-    static constexpr int LA = BF16 ? 3 : 1;                   // K steps between an LDS read and its use
-    static constexpr int NS = BF16 ? 19 : 38;                 // K steps (pairs of pieces): 304 columns
-    static constexpr int NOCT = BF16 ? 5 : 10;                // octets copied per row
+    static constexpr int LA = MODE == kBF16 ? 3 : 1;           // K-loop iterations between an LDS read and its use
+    static constexpr int NS = MODE == kBF16 ? 19 : 38;         // pairs of 16-byte pieces per operand row (registers, LDS reads)
+    static constexpr int NITER = MODE == kX3 ? 19 : NS;        // K-loop iterations (X3: a hi and a lo pair per iteration)
+    static constexpr int NOCT = MODE == kBF16 ? 5 : 10;        // octets copied per row
     static constexpr int OCT_BYTES = (ROWS / 8) * 1024;       // one octet of all rows of the tile
     static constexpr int TILE_BYTES = NOCT * OCT_BYTES;
     static constexpr int NJOBS = NOCT * (ROWS / 8) / 4;       // copy instructions per wavefront and tile
@@ -105,11 +115,12 @@ constexpr int kMaxRows = 64;
 // TABLE = true turns the kernel into the plain pairwise-distance operation C = T o E of Sec. III: no minimum, every
 // element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0)) is stored, row t (token) x column u (vocabulary position) with
 // pitch ldz.  Tokens are then simply the rows tok_ids[0 .. ntok) cut into chunks of chunk_tokens.
-template <bool BF16, int NCT, int WGS_PER_CU, bool TABLE>
+template <int MODE, int NCT, int WGS_PER_CU, bool TABLE>
 __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 {
-    using L = Layout<BF16>;
-    constexpr int NS = L::NS;
+    using L = Layout<MODE>;
+    constexpr bool BF16 = MODE == kBF16, X3 = MODE == kX3;
+    constexpr int NS = L::NS, NITER = L::NITER;
     constexpr int ROWS = L::ROWS, NRT = L::NRT, NBUF = L::NBUF, PD = L::PD;
     constexpr int NG = ROWS / 8;               // token groups per tile
 
@@ -174,7 +185,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         for (int s = 0; s < NS; ++s) {
             const int piece = 2 * s + half;
             f32x4 x = *reinterpret_cast<const f32x4*>(row + (piece < p.nreal ? piece : p.nreal - 1) * 16);
-            if (!BF16) {   // zero beyond the embedding dimension (a re-read piece, or the tail of the last one)
+            if (!BF16 && !X3) {   // zero beyond the embedding dimension (a re-read piece, or the tail of the last one)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     if (piece * 4 + t >= p.nzero_from) x[t] = 0.f;
@@ -201,7 +212,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     const uint32_t offO = pieceO * 16;
     // fp32: the last octet reaches past the end of the row (pieces 75..79): re-read the last real piece
     const int last_piece = (L::NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = BF16 ? offO + (L::NOCT - 1) * 128 : (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16);
+    const uint32_t off_last = (BF16 || X3) ? offO + (L::NOCT - 1) * 128 : (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16);
 
     // Word ids of the two token rows this lane copies.  They are fetched when the previous tile's copy jobs have
     // all been issued (one pair of registers serves both) and are multiplied out to byte offsets job by job.
@@ -302,43 +313,60 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         // into a ring of LA + 1 fragment register sets (LA steps of MFMAs have to cover the LDS latency: a bf16 step
         // is only 64 MFMA clocks); one copy instruction of a later tile rides along every COPY_EVERY steps.
         constexpr int LA = L::LA;
-        f32x4 afrag[LA + 1][NRT];
+        constexpr int NF = X3 ? 2 : 1;                   // fragments per iteration and row tile (X3: hi and lo)
+        f32x4 afrag[LA + 1][NRT][NF];
         auto issue_reads = [&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
             static_for<0, NRT>([&](auto rt_c) {
                 constexpr int rt = decltype(rt_c)::value;
-                constexpr int total = (s >> 2) * L::OCT_BYTES + rt * 4096;
-                constexpr int win = total / 32768;             // keep the immediate offset below 2^15
-                const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
-                afrag[s % (LA + 1)][rt] = lds_read16_nowait<total - win * 32768>(base);
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int step = s + decltype(f_c)::value * 19;            // piece pair read
+                    constexpr int total = (step >> 2) * L::OCT_BYTES + rt * 4096;
+                    constexpr int win = total / 32768;             // keep the immediate offset below 2^15
+                    const uint32_t base = (a_oct ^ ((step & 3) << 5)) + win * 32768;
+                    afrag[s % (LA + 1)][rt][decltype(f_c)::value] = lds_read16_nowait<total - win * 32768>(base);
+                });
             });
         };
-        constexpr int COPY_EVERY = NS / L::NJOBS;
+        constexpr int COPY_EVERY = NITER >= L::NJOBS ? NITER / L::NJOBS : 1;
         static_for<0, LA>([&](auto s_c) { issue_reads(s_c); });
-        static_for<0, NS>([&](auto s_c) {
+        static_for<0, NITER>([&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
             if constexpr (WGS_PER_CU > 1) {
                 // Two wavefronts share a SIMD's matrix pipe.  Priority rises through the K loop, so of two wavefronts
                 // that multiply at the same time the one further along wins the pipe and pulls ahead: the pair
                 // settles into one multiplying while the other runs its epilogue, instead of both doing the same.
                 if constexpr (s == 0) __builtin_amdgcn_s_setprio(0);
-                if constexpr (s == NS / 3) __builtin_amdgcn_s_setprio(1);
-                if constexpr (s == (2 * NS) / 3) __builtin_amdgcn_s_setprio(2);
+                if constexpr (s == NITER / 3) __builtin_amdgcn_s_setprio(1);
+                if constexpr (s == (2 * NITER) / 3) __builtin_amdgcn_s_setprio(2);
             }
-            if constexpr (s + LA < NS) issue_reads(std::integral_constant<int, s + LA>{});
+            if constexpr (s + LA < NITER) issue_reads(std::integral_constant<int, s + LA>{});
             {
-                constexpr int later = (NS - 1 - s < LA ? NS - 1 - s : LA) * NRT;     // reads issued after step s's
+                constexpr int later = (NITER - 1 - s < LA ? NITER - 1 - s : LA) * NRT * NF;     // reads issued after step s's
                 LCRWMD_WAIT_LGKM(later);
             }
             __builtin_amdgcn_sched_barrier(0);
-            const f32x4* a = afrag[s % (LA + 1)];
-            if constexpr (BF16) {
+            const auto& a = afrag[s % (LA + 1)];
+            if constexpr (X3) {
+                // hi*hi, hi*lo, lo*hi: the four accumulators take turns, so dependent MFMAs are four apart
+                static_for<0, 3>([&](auto term_c) {
+                    constexpr int term = decltype(term_c)::value;
+                    constexpr int fa = term == 2 ? 1 : 0, sb = term == 1 ? s + 19 : s;
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < NCT; ++ct)
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, a[rt][fa]), __builtin_bit_cast(bf16x8, breg[sb][ct]),
+                                (s == 0 && term == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
+                });
+            } else if constexpr (BF16) {
 #pragma unroll
                 for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
                     for (int ct = 0; ct < NCT; ++ct)
                         acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                            __builtin_bit_cast(bf16x8, a[rt][0]), __builtin_bit_cast(bf16x8, breg[s][ct]),
                             s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
             } else {
 #pragma unroll
@@ -348,13 +376,20 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #pragma unroll
                         for (int ct = 0; ct < NCT; ++ct)
                             acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
-                                a[rt][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
+                                a[rt][0][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
             }
 #ifndef DBG_NO_COPY
-            if constexpr (s % COPY_EVERY == 0 && s / COPY_EVERY < L::NJOBS) {
-                if (more_copy) copy_job(std::integral_constant<int, s / COPY_EVERY>{}, next_buf);
-            }
-            if constexpr (s == COPY_EVERY * (L::NJOBS - 1) + 1) {     // all copy jobs issued: fetch the ids for the next tile to copy
+            // copy jobs of a later tile, spread over the iterations (X3: 20 jobs over 19 iterations, the last takes two)
+            static_for<0, L::NJOBS>([&](auto j_c) {
+                constexpr int j = decltype(j_c)::value;
+                constexpr int at = j * COPY_EVERY < NITER ? j * COPY_EVERY : NITER - 1;
+                if constexpr (at == s) {
+                    if (more_copy) copy_job(j_c, next_buf);
+                }
+            });
+            if constexpr (s == ((L::NJOBS - 1) * COPY_EVERY < NITER ? (L::NJOBS - 1) * COPY_EVERY + 1 : NITER) ||
+                          (s == NITER - 1 && (L::NJOBS - 1) * COPY_EVERY + 1 >= NITER)) {
+                // all copy jobs issued: fetch the ids for the next tile to copy
                 if (tb + (PD + 1) * ROWS < t1) load_words(tb + (PD + 1) * ROWS);
             }
 #endif
@@ -703,21 +738,21 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     }   // runs of this workgroup
 }
 
-template <bool BF16, int NCT, int WGS_PER_CU, bool TABLE>
+template <int MODE, int NCT, int WGS_PER_CU, bool TABLE>
 hipError_t launch_tiles(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
     const int64_t grid = 8 * (int64_t)d.nvt * ((d.nchunks + 7) / 8);       // per XCD: nvt items in every 8 chunks
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    const size_t smem = (size_t)Layout<BF16>::NBUF * (size_t)Layout<BF16>::TILE_BYTES;
+    const size_t smem = (size_t)Layout<MODE>::NBUF * (size_t)Layout<MODE>::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<BF16, NCT, WGS_PER_CU, TABLE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    k_phase1_tiles<BF16, NCT, WGS_PER_CU, TABLE><<<(unsigned)grid, 256, smem, s>>>(d);
+    k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE><<<(unsigned)grid, 256, smem, s>>>(d);
     return hipGetLastError();
 }
 
@@ -757,7 +792,17 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<false, 2, 1, false>(d, s);
+    return launch_tiles<kF32, 2, 1, false>(d, s);
+}
+
+// a.E is the split copy: 640 bf16 per row (304 hi, 304 lo, zeros); norms and -|T|^2/2 stay fp32 as in the fp32 path
+hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
+{
+    P1T d = common_args(a, tp);
+    d.pitch_b = a.ld * 2;
+    d.nreal = Layout<kX3>::NOCT * 8;
+    d.nzero_from = 0;
+    return launch_tiles<kX3, 2, 1, false>(d, s);
 }
 
 // a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
@@ -765,7 +810,7 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
 {
     P1T d = common_args(a, tp);
     d.pitch_b = a.ld * 2;
-    d.nreal = Layout<true>::NOCT * 8;
+    d.nreal = Layout<kBF16>::NOCT * 8;
     d.nzero_from = 0;
     d.nvt = (int32_t)((d.nvoc + pp::WG_COLS - 1) / pp::WG_COLS);
     // one workgroup per CU (it takes all of a CU's LDS), fewer when there is less work than that
@@ -817,14 +862,14 @@ hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* 
     d.ldz = a.ldz;
     if (bf16) {
         d.pitch_b = a.ld * 2;
-        d.nreal = Layout<true>::NOCT * 8;
+        d.nreal = Layout<kBF16>::NOCT * 8;
         d.nzero_from = 0;
-        return launch_tiles<true, 2, 2, true>(d, s);
+        return launch_tiles<kBF16, 2, 2, true>(d, s);
     }
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<false, 2, 1, true>(d, s);
+    return launch_tiles<kF32, 2, 1, true>(d, s);
 }
 
 }  // namespace lcrwmd

@@ -308,13 +308,13 @@ def test_phase1_bf16_matches_oracle_on_rounded_embeddings(ctx, v, m, q, h_lo, h_
         assert np.all(Za[col[ptr[j]:ptr[j + 1]], j] == 0.0)
 
 
-@pytest.mark.parametrize("compute", ["f32", "bf16"])
+@pytest.mark.parametrize("compute", ["f32", "bf16", "bf16x3"])
 def test_phase1_tile_and_pipeline_boundaries(ctx, compute):
     """Token counts around the tile sizes (32 / 64 rows), the depth of the copy pipeline (1..5 tiles per chunk) and the
     chunk length; vocabulary sizes around the workgroup widths (256 / 512 words)."""
     bf16 = compute == "bf16"
     rng = np.random.default_rng(11)
-    ctx.set_options(compute=binding.BF16 if bf16 else binding.F32)
+    ctx.set_options(compute={"f32": binding.F32, "bf16": binding.BF16, "bf16x3": binding.BF16X3}[compute])
     try:
         for v, lens in [(1, [1]), (255, [8]), (256, [7, 1]), (257, [64]), (511, [63, 9]), (512, [128]), (513, [65, 64, 63]),
                         (1025, [200, 56]), (300, [320]), (600, [31] * 17), (700, [8] * 70), (530, [1] * 300),
@@ -335,6 +335,37 @@ def test_phase1_tile_and_pipeline_boundaries(ctx, compute):
             ctx.phase1_mindist(torch.from_numpy(E).cuda(), binding.Csr.from_numpy(qs, v), Z, ws)
             torch.cuda.synchronize()
             assert_close(Z.cpu().numpy(), ref, what=f"Z {compute} v={v} q={q}")
+    finally:
+        ctx.set_options()
+
+
+def test_split_bf16_compute_keeps_fp32_tolerance(ctx, tiny):
+    """compute = BF16X3 (hi*hi + hi*lo + lo*hi on the bf16 units): same tolerance as fp32 against the oracle on the
+    unrounded embeddings, for one phase and for the whole bound, also with m < 300 and unnormalised rows."""
+    ctx.set_options(compute=binding.BF16X3)
+    try:
+        for v, m, q, h_lo, h_hi in [(700, 300, 9, 1, 40), (515, 290, 20, 2, 30), (300, 64, 3, 100, 200)]:
+            E = synth.embeddings(v, m, 25)
+            qs = synth.corpus(q, v, h_lo, h_hi, 1.1, 26)
+            Q = binding.Csr.from_numpy(qs, v)
+            Z = torch.full((v, q), -3.0, dtype=torch.float32, device="cuda")
+            ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, 0, 0, q, Q.nnz))
+            ctx.phase1_mindist(torch.from_numpy(E).cuda(), Q, Z, ws)
+            torch.cuda.synchronize()
+            assert_close(Z.cpu().numpy(), oracle.phase1(E, qs), what=f"split-bf16 Z v={v} m={m}")
+        rng = np.random.default_rng(4)
+        E = (rng.standard_normal((400, 300)) * rng.uniform(0.2, 3.0, size=(400, 1))).astype(np.float32)
+        qs = synth.corpus(8, 400, 2, 30, 1.1, 27)
+        Z = torch.empty((400, 8), dtype=torch.float32, device="cuda")
+        ws = binding.alloc_workspace(ctx.workspace_bytes(400, 300, 0, 0, 8, len(qs[1])))
+        ctx.phase1_mindist(torch.from_numpy(E).cuda(), binding.Csr.from_numpy(qs, 400), Z, ws)
+        torch.cuda.synchronize()
+        assert_close(Z.cpu().numpy(), oracle.phase1(E, qs), rtol=2e-4, what="split-bf16 Z unnormalised")
+        for p in (tiny, problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)):
+            got = run_rwmd(ctx, *upload(p))
+            assert_close(got, oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="split-bf16 D")
+        sub = synth.csr_rows(*tiny["db"], np.arange(100))
+        assert np.all(np.diag(run_rwmd(ctx, *upload({"E": tiny["E"], "db": sub, "queries": sub}))) == 0.0)
     finally:
         ctx.set_options()
 
