@@ -24,8 +24,8 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kStrip = 768;               // columns per strip: 3 float4 per lane
-constexpr int kPieces = kStrip / 256;     // float4 per lane and table row
+constexpr int kStrip = 512;               // columns per strip: 2 float4 per lane (measured best of 256 .. 1024 on Medium)
+constexpr int kPieces = (kStrip + 255) / 256;     // float4 per lane and table row
 constexpr int kWaves = 4;                 // wavefronts per workgroup, each on its own row(s)
 constexpr int kMaxQueries = 4096;         // queries per pass: at most 64 per lane in the forward kernel
 
@@ -154,20 +154,25 @@ __global__ __launch_bounds__(64 * kWaves) void k_table_rev(const float* __restri
         best[r] = f32x4{INFINITY, INFINITY, INFINITY, INFINITY};
     }
     int64_t p = a;
-    for (; p + 3 < b; p += 4) {
-        int64_t o[4];
+    constexpr int UN = 4;                       // table rows in flight per lane and piece (8 measured slower)
+    for (; p + UN - 1 < b; p += UN) {
+        int64_t o[UN];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = (int64_t)db_pos[p + t] * ldw;
-        f32x4 x[4][kPieces];
+        for (int t = 0; t < UN; ++t) o[t] = (int64_t)db_pos[p + t] * ldw;
+        f32x4 x[UN][kPieces];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < UN; ++t)
 #pragma unroll
             for (int r = 0; r < kPieces; ++r) x[t][r] = *reinterpret_cast<const f32x4*>(col[r] + o[t]);
 #pragma unroll
         for (int r = 0; r < kPieces; ++r)
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                best[r][c] = fminf(fminf(best[r][c], fminf(x[0][r][c], x[1][r][c])), fminf(x[2][r][c], x[3][r][c]));
+            for (int c = 0; c < 4; ++c) {
+                float m = best[r][c];
+#pragma unroll
+                for (int t = 0; t < UN; ++t) m = fminf(m, x[t][r][c]);
+                best[r][c] = m;
+            }
     }
     for (; p < b; ++p) {
         const int64_t o = (int64_t)db_pos[p] * ldw;
