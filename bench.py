@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--dedup", action="store_true",
                     help="de-duplicated form: one word-pair table per query batch instead of one distance per stored "
                          "entry (same result); the dominant kernel is then the bandwidth-bound swapped table pass")
+    ap.add_argument("--permute-vocab", action="store_true",
+                    help="stress variant: renumber the vocabulary at random, so that word id is no longer frequency rank")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
@@ -70,7 +72,7 @@ def main():
     if bf16_in:
         args.compute = "bf16"
     t_gen = time.perf_counter()
-    prob = synth.make(cfg)
+    prob = synth.make(cfg, permute_vocab=args.permute_vocab)
     t_gen = time.perf_counter() - t_gen
     v, m, n, q = prob["v"], cfg.m, prob["n"], prob["q"]
 
@@ -224,6 +226,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: v={v} m={m} n={n} q={q} h={cfg.h_lo}-{cfg.h_hi} zipf={cfg.zipf_s}",
                    "variant": "dedup (word-pair table)" if table else "per-entry distances (the paper's two phases)",
+                   "vocabulary": "renumbered at random" if args.permute_vocab else "word id = frequency rank",
                    "nnz_db": db.nnz, "nnz_q": qs.nnz, "data_gen_s": round(t_gen, 1)},
         "roofline": table if table else p1_roof,
         "phase1": p1_roof if table else None,

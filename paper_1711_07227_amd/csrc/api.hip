@@ -321,43 +321,48 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         a.ld = ep.ld;
         a.m = m;
         a.normE = ep.normE;
-        a.voc_rows = list_q;
-        a.nvoc = vq;
         a.z_by_position = 1;
-        const int64_t ldw = round_up(vq, 32), ldz = round_up(q, 4);     // table rows start on 128-byte lines
+        // columns of the table: the query words dealt out over the column strips (vc places, a few of them unused)
+        int32_t ws_cols, nstrip;
+        table_strips(vq, &ws_cols, &nstrip);
+        const int64_t vc = (int64_t)ws_cols * nstrip;
+        const int64_t ldw = vc, ldz = round_up(q, 4);                  // ws_cols is a multiple of 32: rows start on 128-byte lines
         const int64_t tok_count = round_up(ve, kTileTokens) + kTileTokens;
         Bump bb(b.base + region_off, region);
         float* W = bb.take_n<float>((size_t)ve * ldw);
         float* Z = bb.take_n<float>((size_t)ve * ldz);
         int32_t* tok_ids = bb.take_n<int32_t>((size_t)tok_count);
         float* tok_hn = bb.take_n<float>((size_t)tok_count);
-        int32_t ws_cols, nstrip;
-        table_strips(vq, &ws_cols, &nstrip);
         const size_t nsq = (size_t)nstrip * (size_t)q + 1;
         int32_t* bcnt = bb.take_n<int32_t>(nsq);
         int32_t* boffs = bb.take_n<int32_t>(nsq);
         int32_t* bcur = bb.take_n<int32_t>(nsq);
         int32_t* bpos = bb.take_n<int32_t>((size_t)nnz_q);
         float* bval = bb.take_n<float>((size_t)nnz_q);
+        int32_t* col_word = bb.take_n<int32_t>((size_t)vc);
+        int32_t* qcol = bb.take_n<int32_t>((size_t)nnz_q);
         float* D2 = nstrip > 1 ? bb.take_n<float>((size_t)n * ldz) : nullptr;     // partial sums between strips
+        a.voc_rows = col_word;
+        a.nvoc = vc;
         a.Z = W;
         a.ldz = ldw;
         if (bb.ok && distance_table_supported(a, ep.bf16)) {
+            HIP_TRY(launch_table_spread(list_q, vq, qcol_pos, nnz_q, col_word, qcol, s));
             HIP_TRY(launch_table_tokens(list_db, ve, ep.normE, tok_ids, tok_hn, tok_count, s));
             {
                 ProfScope ps(ctx, s, 1, 2.0 * (double)ve * (double)vq * (double)m);
                 HIP_TRY(launch_distance_table(a, ep.bf16, tok_ids, tok_hn, ve, s));
             }
-            HIP_TRY(launch_table_zero_same(list_q, vq, map_db, W, ldw, s));
-            HIP_TRY(launch_table_buckets(Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, vq, bcnt, boffs, bcur, bpos, bval, s));
+            HIP_TRY(launch_table_zero_same(col_word, vc, map_db, W, ldw, s));
+            HIP_TRY(launch_table_buckets(Q->row_ptr + jq0, qcol - qoff, Q->val, q, vc, bcnt, boffs, bcur, bpos, bval, s));
             {   // forward: every table row once, Z once
                 ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);
-                HIP_TRY(launch_table_fwd(W, ldw, ve, vq, boffs, bpos, q, Z, ldz, s));
+                HIP_TRY(launch_table_fwd(W, ldw, ve, vc, boffs, bpos, q, Z, ldz, s));
             }
             ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, q, D, ldd, 0, s));
             {   // swapped: one table row per stored database entry, D read and written once
                 ProfScope ps(ctx, s, 4, 4.0 * (double)DB->nnz * (double)vq + 8.0 * (double)n * (double)q + 4.0 * (double)DB->nnz);
-                HIP_TRY(launch_table_rev(W, ldw, vq, DB->row_ptr, dbcol_pos, n, boffs, bpos, bval, q, D2, ldz, D, ldd, s));
+                HIP_TRY(launch_table_rev(W, ldw, vc, DB->row_ptr, dbcol_pos, n, boffs, bpos, bval, q, D2, ldz, D, ldd, s));
             }
             return LCRWMD_OK;
         }
@@ -553,7 +558,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
         // room for the word-pair table and the forward Z at their upper bounds (distinct words <= stored entries)
         const int64_t qt = qb < table_max_queries() ? qb : table_max_queries();
         const int64_t ve_max = v < nnz_db ? v : nnz_db;
-        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 +
+        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + 32 * ((vq + 255) / 256) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 +
                          table_bucket_bytes(vq, qt, nnz_q) + (size_t)n * (size_t)round_up(qt, 4) * 4 + 8192;
         if (t > (f > r ? f : r)) total = fixed + t + 4096;
     }

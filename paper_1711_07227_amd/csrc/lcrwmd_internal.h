@@ -135,6 +135,8 @@ hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32
                                   hipStream_t s);
 void table_strips(int64_t vq, int32_t* ws, int32_t* nstrip);
 size_t table_bucket_bytes(int64_t vq, int64_t q, int64_t nnz_q);
+hipError_t launch_table_spread(const int32_t* list_q, int64_t vq, const int32_t* pos_in, int64_t nnz, int32_t* col_word,
+                               int32_t* pos_out, hipStream_t s);
 hipError_t launch_table_buckets(const int64_t* q_rp, const int32_t* q_pos, const float* q_val, int64_t q, int64_t vq,
                                 int32_t* cnt, int32_t* offs, int32_t* cursor, int32_t* bpos, float* bval, hipStream_t s);
 hipError_t launch_table_fwd(const float* W, int64_t ldw, int64_t ve, int64_t vq, const int32_t* offs, const int32_t* bpos,

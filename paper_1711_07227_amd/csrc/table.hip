@@ -39,6 +39,29 @@ __global__ void k_table_zero_same(const int32_t* __restrict__ list_q, int32_t vq
     if (p >= 0) W[(int64_t)p * ldw + u] = 0.f;
 }
 
+// Columns of the table: query word number u (in increasing word id) goes to strip u mod nstrip, place u / nstrip.
+// Word ids grow with rarity in real vocabularies, so this deals the frequent words out over all strips: every
+// strip then sees about the same number of entries per query (with the words in id order the first strip held
+// nearly all of them and its per-query loops dominated).  Unused places at the end of a strip repeat word 0 of
+// the list; no entry points at them.
+__global__ void k_spread_columns(const int32_t* __restrict__ list_q, int32_t vq, int32_t ws, int32_t nstrip,
+                                 int32_t* __restrict__ col_word)
+{
+    const int32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= ws * nstrip) return;
+    const int32_t u = (c % ws) * nstrip + c / ws;
+    col_word[c] = list_q[u < vq ? u : 0];
+}
+
+__global__ void k_spread_entries(const int32_t* __restrict__ pos_in, int64_t nnz, int32_t ws, int32_t nstrip,
+                                 int32_t* __restrict__ pos_out)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t u = pos_in[e];
+    pos_out[e] = (u % nstrip) * ws + u / nstrip;
+}
+
 // Token list of the table launch: the distinct database words, padded with the last one.
 __global__ void k_table_tokens(const int32_t* __restrict__ list_db, int32_t ve, const float* __restrict__ normE,
                                int32_t* __restrict__ tok_ids, float* __restrict__ tok_hn, int32_t count)
@@ -301,7 +324,21 @@ size_t table_bucket_bytes(int64_t vq, int64_t q, int64_t nnz_q)
 {
     int32_t ws, ns;
     table_strips(vq, &ws, &ns);
-    return 3 * (((size_t)ns * (size_t)q + 1) * 4 + 256) + 2 * ((size_t)nnz_q * 4 + 256);
+    return 3 * (((size_t)ns * (size_t)q + 1) * 4 + 256) + 3 * ((size_t)nnz_q * 4 + 256) + (size_t)ws * ns * 4 + 256;
+}
+
+// Deal the vq query words out over the strips: col_word[ws * nstrip] = word of every table column, pos_out = the
+// entries' columns (pos_in holds their numbers in the word list).
+hipError_t launch_table_spread(const int32_t* list_q, int64_t vq, const int32_t* pos_in, int64_t nnz, int32_t* col_word,
+                               int32_t* pos_out, hipStream_t s)
+{
+    if (vq <= 0) return hipSuccess;
+    int32_t ws, ns;
+    table_strips(vq, &ws, &ns);
+    const int64_t cols = (int64_t)ws * ns;
+    k_spread_columns<<<(unsigned)((cols + 255) / 256), 256, 0, s>>>(list_q, (int32_t)vq, ws, ns, col_word);
+    if (nnz > 0) k_spread_entries<<<(unsigned)((nnz + 255) / 256), 256, 0, s>>>(pos_in, nnz, ws, ns, pos_out);
+    return hipGetLastError();
 }
 
 hipError_t launch_table_tokens(const int32_t* list_db, int64_t ve, const float* normE, int32_t* tok_ids, float* tok_hn,

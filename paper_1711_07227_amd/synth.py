@@ -158,7 +158,24 @@ def csr_rows(row_ptr, col_idx, val, rows):
     return rp, col_idx[idx].copy(), val[idx].copy()
 
 
-def make(cfg: Config, *, n: int | None = None, q: int | None = None, v: int | None = None):
+def permute_vocabulary(E, sets, seed: int):
+    """The same problem under a random renumbering of the vocabulary: word w becomes perm[w] in E's rows and in
+    every histogram (rows re-sorted by the new ids).  Distances are unchanged; what changes is that word id no
+    longer equals frequency rank, i.e. the frequent words are scattered over E instead of sharing its first rows."""
+    v = E.shape[0]
+    perm = np.random.Generator(np.random.PCG64(seed)).permutation(v).astype(np.int32)
+    E2 = np.empty_like(E)
+    E2[perm] = E
+    out = []
+    for row_ptr, col_idx, val in sets:
+        c = perm[col_idx]
+        rows = np.repeat(np.arange(len(row_ptr) - 1, dtype=np.int64), np.diff(row_ptr))
+        order = np.lexsort((c, rows))
+        out.append((row_ptr.copy(), c[order].astype(np.int32), val[order].copy()))
+    return E2, out
+
+
+def make(cfg: Config, *, n: int | None = None, q: int | None = None, v: int | None = None, permute_vocab: bool = False):
     """All inputs of a configuration; n, q, v may be overridden to scale it down."""
     n = cfg.n if n is None else n
     q = cfg.q if q is None else q
@@ -169,4 +186,6 @@ def make(cfg: Config, *, n: int | None = None, q: int | None = None, v: int | No
         qs = csr_rows(*db, np.arange(min(q, n)))
     else:
         qs = corpus(q, v, cfg.h_lo, cfg.h_hi, cfg.zipf_s, seed_for(cfg.index, 2))
+    if permute_vocab:
+        E, (db, qs) = permute_vocabulary(E, [db, qs], seed_for(cfg.index, 3))
     return {"cfg": cfg, "E": E, "db": db, "queries": qs, "v": v, "n": n, "q": qs[0].shape[0] - 1}

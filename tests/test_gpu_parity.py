@@ -138,6 +138,16 @@ def test_rwmd_self_distance_zero_and_symmetry(ctx, tiny):
     assert_close(got, oracle.rwmd_table(tiny["E"], sub, sub), what="self D")
 
 
+def test_rwmd_is_invariant_under_vocabulary_renumbering(ctx, tiny):
+    """A consistent permutation of the word ids (rows of E and every histogram) changes no distance; it does change
+    which words share a vocabulary tile and the order of the sums, hence a tolerance of a few ulps."""
+    E2, (db2, qs2) = synth.permute_vocabulary(tiny["E"], [tiny["db"], tiny["queries"]], 99)
+    a = run_rwmd(ctx, *upload(tiny))
+    b = run_rwmd(ctx, *upload({"E": E2, "db": db2, "queries": qs2}))
+    assert np.max(np.abs(a - b)) <= 2e-6
+    assert_close(b, oracle.rwmd_table(E2, db2, qs2), what="tiny D, renumbered vocabulary")
+
+
 def test_rwmd_degenerate_shapes(ctx):
     # one database doc, one query, single-word documents
     E = synth.embeddings(50, 300, 1)

@@ -49,3 +49,21 @@ def test_config_table_matches_workloads():
     assert c["short"].queries_from_db and c["short"].precision == "bf16" and c["short"].q == 4096
     assert c["knn"].topk == 16 and c["knn"].v == 1000000
     assert all(x.m == 300 for x in c.values())
+
+
+def test_permuted_vocabulary_is_the_same_problem():
+    cfg = synth.CONFIGS["tiny"]
+    a = synth.make(cfg, n=60, q=5)
+    b = synth.make(cfg, n=60, q=5, permute_vocab=True)
+    assert a["E"].shape == b["E"].shape and not np.array_equal(a["E"], b["E"])
+    for key in ("db", "queries"):
+        pa, ca, va = a[key]
+        pb, cb, vb = b[key]
+        assert np.array_equal(pa, pb)
+        for r in range(len(pa) - 1):
+            sa, sb = slice(pa[r], pa[r + 1]), slice(pb[r], pb[r + 1])
+            assert np.all(np.diff(cb[sb]) > 0)                                   # still strictly increasing
+            # the same multiset of (embedding row, weight) pairs
+            ka = sorted((a["E"][w].tobytes(), float(x)) for w, x in zip(ca[sa], va[sa]))
+            kb = sorted((b["E"][w].tobytes(), float(x)) for w, x in zip(cb[sb], vb[sb]))
+            assert ka == kb
