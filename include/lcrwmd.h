@@ -80,7 +80,7 @@ typedef struct {
                                        rounded to bf16 (round-to-nearest-even) unless already bf16,
                                        products accumulate in fp32.  bf16 E always computes in bf16.
                                        The bf16 path needs m <= 300 (LCRWMD_EUNSUPPORTED otherwise).
-                                       LCRWMD_BF16X3 (fp32 E, m <= 300, dedup 0; otherwise it means
+                                       LCRWMD_BF16X3 (fp32 E, m <= 300; otherwise it means
                                        LCRWMD_F32): every fp32 value x is split into hi = bf16(x) and
                                        lo = bf16(x - hi) and a product is taken as hi*hi + hi*lo + lo*hi
                                        on the bf16 matrix units with fp32 accumulation; norms stay fp32.

@@ -97,11 +97,11 @@ lcrwmd_status check_ws(lcrwmd_ctx* ctx, const void* ws, size_t ws_bytes)
 bool use_bf16(const lcrwmd_ctx* ctx, const lcrwmd_emb* E) { return E->dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16; }
 
 // Arithmetic of the first phase: 0 fp32, 1 bf16, 2 split bf16 (three products per fp32 product).  The split form
-// exists for fp32 E with m <= 300 in the default (per-entry) form; anything else that asks for it computes in fp32.
+// exists for fp32 E with m <= 300; anything else that asks for it computes in fp32.
 int prec_mode(const lcrwmd_ctx* ctx, const lcrwmd_emb* E)
 {
     if (use_bf16(ctx, E)) return 1;
-    if (ctx->opt.compute == LCRWMD_BF16X3 && E->m <= 300 && !ctx->opt.dedup) return 2;
+    if (ctx->opt.compute == LCRWMD_BF16X3 && E->m <= 300) return 2;
     return 0;
 }
 
@@ -346,12 +346,12 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         a.nvoc = vc;
         a.Z = W;
         a.ldz = ldw;
-        if (bb.ok && distance_table_supported(a, ep.bf16)) {
+        if (bb.ok && distance_table_supported(a, ep.mode)) {
             HIP_TRY(launch_table_spread(list_q, vq, qcol_pos, nnz_q, col_word, qcol, s));
             HIP_TRY(launch_table_tokens(list_db, ve, ep.normE, tok_ids, tok_hn, tok_count, s));
             {
                 ProfScope ps(ctx, s, 1, 2.0 * (double)ve * (double)vq * (double)m);
-                HIP_TRY(launch_distance_table(a, ep.bf16, tok_ids, tok_hn, ve, s));
+                HIP_TRY(launch_distance_table(a, ep.mode, tok_ids, tok_hn, ve, s));
             }
             HIP_TRY(launch_table_zero_same(col_word, vc, map_db, W, ldw, s));
             HIP_TRY(launch_table_buckets(Q->row_ptr + jq0, qcol - qoff, Q->val, q, vc, bcnt, boffs, bcur, bpos, bval, s));
@@ -543,7 +543,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     if (v <= 0 || m <= 0 || n < 0 || nnz_db < 0 || q < 0 || nnz_q < 0 || k < 0)
         return fail(ctx, LCRWMD_EINVAL, "negative size");
     const int bf16 = (emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16) ? 1
-                     : (ctx->opt.compute == LCRWMD_BF16X3 && m <= 300 && !ctx->opt.dedup) ? 2 : 0;     // see prec_mode
+                     : (ctx->opt.compute == LCRWMD_BF16X3 && m <= 300) ? 2 : 0;     // see prec_mode
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     if (k > 0 && qb > 2048) qb = 2048;

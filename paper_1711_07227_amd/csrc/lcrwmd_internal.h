@@ -124,8 +124,9 @@ hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipS
 size_t pack_x3_bytes(int64_t v);
 int32_t x3_pitch();
 hipError_t launch_pack_x3(const float* E, int64_t v, int32_t m, int64_t ld, void* packed, float* normE, hipStream_t s);
-bool distance_table_supported(const Phase1Args& a, bool bf16);
-hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
+// mode: 0 fp32 rows, 1 packed bf16 rows, 2 split-bf16 rows
+bool distance_table_supported(const Phase1Args& a, int mode);
+hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* tok_ids, const float* tok_hn,
                                  int64_t ntok, hipStream_t s);
 // table.hip: the two passes of the de-duplicated form over a word-pair table W (rows: distinct database words)
 int64_t table_max_queries();

@@ -831,13 +831,13 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
 
 // Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
 // tok_ids / tok_hn: the token rows' word ids and -|.|^2/2 (fp32 path), readable up to roundup(ntok, 64) + 64 entries.
-bool distance_table_supported(const Phase1Args& a, bool bf16) { return bf16 || tiles_f32_supported(a); }
+bool distance_table_supported(const Phase1Args& a, int mode) { return mode != 0 || tiles_f32_supported(a); }
 
-hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* tok_ids, const float* tok_hn,
+hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* tok_ids, const float* tok_hn,
                                  int64_t ntok, hipStream_t s)
 {
     if (a.nvoc <= 0 || ntok <= 0) return hipSuccess;
-    if (!distance_table_supported(a, bf16) || ntok > 0x7fffffffLL - 128) return hipErrorNotSupported;
+    if (!distance_table_supported(a, mode) || ntok > 0x7fffffffLL - 128) return hipErrorNotSupported;
     P1T d;
     d.Eb = (const unsigned char*)a.E;
     d.normE = a.normE;
@@ -860,11 +860,17 @@ hipError_t launch_distance_table(const Phase1Args& a, bool bf16, const int32_t* 
     d.chunk_seg = nullptr;
     d.Z = a.Z;
     d.ldz = a.ldz;
-    if (bf16) {
+    if (mode == 1) {
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kBF16>::NOCT * 8;
         d.nzero_from = 0;
         return launch_tiles<kBF16, 2, 2, true>(d, s);
+    }
+    if (mode == 2) {
+        d.pitch_b = a.ld * 2;
+        d.nreal = Layout<kX3>::NOCT * 8;
+        d.nzero_from = 0;
+        return launch_tiles<kX3, 2, 1, true>(d, s);
     }
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;

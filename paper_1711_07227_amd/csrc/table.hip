@@ -214,26 +214,54 @@ __global__ __launch_bounds__(64 * kWaves) void k_table_rev(const float* __restri
     const float* z = zs[wave];
     float* d2 = D2 + i * ld2;
     float* d = D + i * ldd;
-    for (int32_t j0 = 0; j0 < q; j0 += 64) {
-        const int32_t j = j0 + lane;
-        if (j < q) {
+    // Eight slices of 64 queries at a time: their entry ranges, the partial sums so far and the values of D are all
+    // requested before the first is used, and the first four entries of every slice are in flight together.
+    constexpr int SL = 8;
+    for (int32_t jb = 0; jb < q; jb += 64 * SL) {
+        int32_t ea[SL], eb[SL];
+        float prev[SL], dold[SL];
+#pragma unroll
+        for (int k = 0; k < SL; ++k) {
+            const int32_t j = jb + 64 * k + lane;
+            const bool ok = j < q;
+            ea[k] = ok ? brp[j] : 0;
+            eb[k] = ok ? brp[j + 1] : 0;
+            prev[k] = (ok && !first) ? d2[j] : 0.f;
+            dold[k] = (ok && last) ? d[j] : 0.f;
+        }
+        int32_t c[SL][4];
+        float w[SL][4];
+#pragma unroll
+        for (int k = 0; k < SL; ++k)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bool ok = ea[k] + t < eb[k];
+                c[k][t] = ok ? bpos[ea[k] + t] : 0;
+                w[k][t] = ok ? bval[ea[k] + t] : 0.f;
+            }
+#pragma unroll
+        for (int k = 0; k < SL; ++k) {
+            const int32_t j = jb + 64 * k + lane;
             float acc = 0.f;
-            const int32_t ea = brp[j], eb = brp[j + 1];
-            for (int32_t e = ea; e < eb; e += 4) {          // four entries' loads in flight; the sum keeps entry order
-                int32_t c[4];
-                float w[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc = fmaf(w[k][t], z[c[k][t]], acc);      // entry order, as in the loop below
+            for (int32_t e = ea[k] + 4; e < eb[k]; e += 4) {
+                int32_t cc[4];
+                float ww[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const bool ok = e + t < eb;
-                    c[t] = bpos[ok ? e + t : e];
-                    w[t] = ok ? bval[e + t] : 0.f;
+                    const bool ok = e + t < eb[k];
+                    cc[t] = bpos[ok ? e + t : e];
+                    ww[t] = ok ? bval[e + t] : 0.f;
                 }
 #pragma unroll
-                for (int t = 0; t < 4; ++t) acc = fmaf(w[t], z[c[t]], acc);
+                for (int t = 0; t < 4; ++t) acc = fmaf(ww[t], z[cc[t]], acc);
             }
-            if (!first) acc += d2[j];
-            if (last) d[j] = fmaxf(d[j], acc);
-            else d2[j] = acc;
+            acc += prev[k];
+            if (j < q) {
+                if (last) d[j] = fmaxf(dold[k], acc);
+                else d2[j] = acc;
+            }
         }
     }
 }

@@ -70,7 +70,7 @@ def test_dedup_self_distance_is_exactly_zero(ctx, tiny):
 
 
 def test_dedup_more_query_words_than_one_slab(ctx):
-    """Over 32768 distinct query words: the table rows pass through LDS in several slabs."""
+    """Tens of thousands of distinct query words: many column strips, queries with entries in all of them."""
     v = 90000
     p = {"E": synth.embeddings(v, 300, 5), "db": synth.corpus(300, v, 1, 90, 1.0, 6),
          "queries": synth.corpus(900, v, 60, 140, 0.8, 7)}
@@ -112,6 +112,14 @@ def test_dedup_falls_back_when_the_table_does_not_fit_or_has_no_kernel(ctx, tiny
     # fp32 embeddings of another width have no table kernel: the default form runs
     p = problem(v=400, m=64, n=90, q=7, h_lo=2, h_hi=30, seed=8)
     assert_close(run_rwmd(ctx, *upload(p)), oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="m = 64 (dedup asked)")
+
+
+def test_dedup_with_split_bf16_table(ctx, tiny):
+    ctx.set_options(dedup=1, compute=binding.BF16X3)
+    for p in (tiny, problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)):
+        E, db, qs = upload(p)
+        assert_close(run_rwmd(ctx, E, db, qs), oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="D (dedup, split bf16)")
+        assert table_was_used(ctx, E, db, qs)
 
 
 def test_dedup_bf16_and_topk(ctx, tiny):
