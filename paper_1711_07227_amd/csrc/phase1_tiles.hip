@@ -494,12 +494,26 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 // of tile t + 2 at the end of that K loop with a partial vmcnt: vector memory operations complete in issue order,
 // and the five copy instructions of tile t + 3 were issued later, so "at most five outstanding" means the copies of
 // tile t + 2 (and everything older) have landed.  The barrier that follows publishes them.
-namespace pp {
-constexpr int ROWS = 64, NRT = 2, NCT = 2, NS = 19, NOCT = 5, NBUF = 4, PD = 3;
-constexpr int OCT_BYTES = (ROWS / 8) * 1024, TILE_BYTES = NOCT * OCT_BYTES;
-constexpr int NG = ROWS / 8;
-constexpr int WG_COLS = 2 * 4 * NCT * 32;      // vocabulary words per workgroup
-}  // namespace pp
+//
+// The same schedule serves the fp32 and the split-bf16 arithmetic (one 32-word column tile per wavefront instead of
+// two, so that eight wavefronts fit the register file; 80 KiB tiles in two buffers, copies one tile ahead): their
+// tiles are long enough to hide a barrier, but not the copy instructions' issue stalls and the epilogue, which cost
+// a wavefront that owns its SIMD alone a tenth of its time.
+template <int MODE>
+struct PP {
+    static constexpr int ROWS = 64, NRT = 2;
+    static constexpr int NCT = MODE == kBF16 ? 2 : 1;          // 32-word column tiles per wavefront
+    static constexpr int NS = MODE == kBF16 ? 19 : 38;         // pairs of 16-byte pieces per operand row
+    static constexpr int NITER = MODE == kF32 ? 38 : 19;       // K-loop iterations
+    static constexpr int NF = MODE == kX3 ? 2 : 1;             // fragments per iteration and row tile (hi, lo)
+    static constexpr int NOCT = MODE == kBF16 ? 5 : 10;
+    static constexpr int NBUF = MODE == kBF16 ? 4 : 2;
+    static constexpr int PD = NBUF - 1;
+    static constexpr int OCT_BYTES = (ROWS / 8) * 1024, TILE_BYTES = NOCT * OCT_BYTES;
+    static constexpr int NG = ROWS / 8;
+    static constexpr int WG_COLS = 2 * 4 * NCT * 32;           // vocabulary words per workgroup
+    static constexpr int COPY_EVERY = NITER / NOCT >= 1 ? NITER / NOCT : 1;
+};
 
 // Workgroup barrier WITHOUT the memory fences of __syncthreads(): a fence would wait for every outstanding vector
 // memory operation, i.e. for the copies just issued for a tile three periods away and for the stores of Z.  What a
@@ -511,10 +525,15 @@ __device__ inline void pp_barrier() { __builtin_amdgcn_s_barrier(); }
 // The per-tile side tables (word ids of the rows to copy, histogram of every group of 8 rows) are read with uniform
 // addresses through restrict-qualified arguments, i.e. as scalar loads: they are then not part of the vector memory
 // queue whose order the copy waits rely on, and they cost no vector registers.
+template <int MODE>
 __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t* __restrict__ tok_ids,
                                                             const int32_t* __restrict__ grp_seg)
 {
-    using namespace pp;
+    using C = PP<MODE>;
+    constexpr bool BF16 = MODE == kBF16, X3 = MODE == kX3, F32 = MODE == kF32;
+    constexpr int ROWS = C::ROWS, NRT = C::NRT, NCT = C::NCT, NS = C::NS, NITER = C::NITER, NF = C::NF, NOCT = C::NOCT;
+    constexpr int NBUF = C::NBUF, PD = C::PD, OCT_BYTES = C::OCT_BYTES, TILE_BYTES = C::TILE_BYTES, NG = C::NG;
+    constexpr int WG_COLS = C::WG_COLS;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -535,7 +554,12 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
 
     const unsigned char* Eb = p.Eb;
     const int lane8 = lane >> 3;
-    const uint32_t offO = (uint32_t)(((lane & 7) ^ ((wave & 1) * 4 + (lane >> 4))) * 16);
+    const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
+    const uint32_t offO = (uint32_t)(pieceO * 16);
+    // fp32 rows end inside the last octet (pieces 75..79 do not exist): those lanes re-read the last real piece,
+    // which meets zeros on the vocabulary side
+    const int last_piece = (NOCT - 1) * 8 + pieceO;
+    const uint32_t off_last = (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16) - offO;
     const uint32_t pitch32 = (uint32_t)p.pitch_b;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t a_oct0 = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
@@ -561,9 +585,18 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
         nEw[ct] = p.normE[wid];
         const unsigned char* row = Eb + (int64_t)wid * p.pitch_b;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) breg[s][ct] = *reinterpret_cast<const f32x4*>(row + (2 * s + half) * 16);
+        for (int s = 0; s < NS; ++s) {
+            const int piece = 2 * s + half;
+            f32x4 x = *reinterpret_cast<const f32x4*>(row + (piece < p.nreal ? piece : p.nreal - 1) * 16);
+            if (F32) {        // zero beyond the embedding dimension (a re-read piece, or the tail of the last one)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (piece * 4 + t >= p.nzero_from) x[t] = 0.f;
+            }
+            breg[s][ct] = x;
+        }
     }
-    if (half == 1) {          // the three -|row|^2/2 terms of the token side multiply by one here
+    if (BF16 && half == 1) {          // the three -|row|^2/2 terms of the token side multiply by one here
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct) {
             breg[NS - 1][ct][2] = __uint_as_float(0x3F803F80u);
@@ -592,7 +625,8 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     };
     auto copy_octet = [&](auto o_c, uint32_t off, unsigned char* lbase) {
         constexpr int oct = decltype(o_c)::value;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + off + oct * 128),
+        const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 128));
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + o),
                                          (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
                                          16, 0, 0);
     };
@@ -609,17 +643,19 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     float run[NCT];
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct) run[ct] = 0.f;
-    const float nEsel = half ? nEw[1] : nEw[0];
+    const float nEsel = (NCT == 2 && half) ? nEw[NCT - 1] : nEw[0];
     float* zrow;
     {
-        int64_t pos = col0 + lane;                 // lower lanes: column tile 0, upper lanes: column tile 1
+        // two column tiles: lower lanes own tile 0, upper lanes tile 1; one: both halves own the same 32 words
+        int64_t pos = col0 + (NCT == 2 ? lane : l31);
         if (pos >= p.nvoc) pos = p.nvoc - 1;
         zrow = p.Z + pos * p.ldz;
     }
     // Store the value of histogram `cur`.  One exchange hands the lower lanes both halves' maxima of column tile 0
-    // and the upper lanes those of column tile 1, so one store serves 64 words.
+    // and the upper lanes those of column tile 1, so one store serves 64 words (with a single column tile both
+    // halves end up with the same value and store it to the same place).
     auto flush = [&]() {
-        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(run[0]), __float_as_uint(run[1]), false, false);
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(run[0]), __float_as_uint(run[NCT - 1]), false, false);
         const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         zrow[cur] = __builtin_amdgcn_sqrtf(fmaxf(nEsel - 2.f * best, 0.f));
     };
@@ -642,6 +678,13 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     uint32_t off_next = row_offset(load_ids(t0 + PD * ROWS < t1 ? t0 + PD * ROWS : t0));
     Ids ids_next = load_ids(t0 + (PD + 1) * ROWS < t1 ? t0 + (PD + 1) * ROWS : t0);
     Grp grp_next = load_gs(t0);
+    // fp32 and split bf16: -|T_a|^2/2 of this lane's two token rows, added by a rank-1 fp32 MFMA step per tile
+    float hn[NRT] = {}, hn_next[NRT] = {};
+    auto load_hn = [&](int tb, float* h) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) h[rt] = p.tok_hn[tb + rt * 32 + l31];
+    };
+    if (!BF16) load_hn(t0, hn);
     __builtin_amdgcn_s_waitcnt(0x0f70);        // vmcnt(0): this wavefront's share of the first tiles has landed
     pp_barrier();
     if (grp == 1) pp_barrier();                // the second group starts half a period later
@@ -688,45 +731,90 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
         const uint32_t a_oct = a_oct0 + buf * TILE_BYTES;
         const bool more_copy = tb + PD * ROWS < t1;
         unsigned char* copy_buf = smem + (buf == 0 ? NBUF - 1 : buf - 1) * TILE_BYTES;   // (buf + PD) mod NBUF: the tile before this one is done with
-        // Two fragment register sets: the reads of step s + 1 are issued before the MFMAs of step s.
-        f32x4 afrag[2][NRT];
+        // Two fragment register sets: the reads of iteration s + 1 are issued before the MFMAs of iteration s.
+        f32x4 afrag[2][NRT][NF];
         auto issue_reads = [&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
             static_for<0, NRT>([&](auto rt_c) {
                 constexpr int rt = decltype(rt_c)::value;
-                constexpr int total = (s >> 2) * OCT_BYTES + rt * 4096;
-                constexpr int win = total / 32768;
-                const uint32_t base = (a_oct ^ ((s & 3) << 5)) + win * 32768;
-                afrag[s & 1][rt] = lds_read16_nowait<total - win * 32768>(base);
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int step = s + decltype(f_c)::value * 19;            // piece pair read (split bf16: hi, lo)
+                    constexpr int total = (step >> 2) * OCT_BYTES + rt * 4096;
+                    constexpr int win = total / 32768;                              // keep the immediate offset below 2^15
+                    const uint32_t base = (a_oct ^ ((step & 3) << 5)) + win * 32768;
+                    afrag[s & 1][rt][decltype(f_c)::value] = lds_read16_nowait<total - win * 32768>(base);
+                });
             });
         };
-        issue_reads(std::integral_constant<int, 0>{});
+        // With copies three tiles ahead a tile is published a full period before its first read, and the first reads
+        // may precede the barrier; with copies one tile ahead (fp32, split bf16) the other group's share of this tile
+        // is published by this very barrier.
+        if (PD >= 3) issue_reads(std::integral_constant<int, 0>{});
         if (tb > t0) pp_barrier();              // ends the half period of the epilogue above
+        if (PD < 3) issue_reads(std::integral_constant<int, 0>{});
+        if (!BF16 && tb + ROWS < t1) load_hn(tb + ROWS, hn_next);     // before this K loop's copies: never waits for them
         // ================= multiply =================
-        static_for<0, NS>([&](auto s_c) {
+        static_for<0, NITER>([&](auto s_c) {
             constexpr int s = decltype(s_c)::value;
-            if constexpr (s + 1 < NS) {
+            if constexpr (s + 1 < NITER) {
                 issue_reads(std::integral_constant<int, s + 1>{});
-                LCRWMD_WAIT_LGKM(NRT);
+                LCRWMD_WAIT_LGKM(NRT * NF);
             } else {
                 LCRWMD_WAIT_LGKM(0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            const f32x4* a = afrag[s & 1];
+            const auto& a = afrag[s & 1];
+            if constexpr (X3) {
+                // hi*hi, hi*lo, lo*hi; the accumulators take turns, so dependent MFMAs are two apart
+                static_for<0, 3>([&](auto term_c) {
+                    constexpr int term = decltype(term_c)::value;
+                    constexpr int fa = term == 2 ? 1 : 0, sb = term == 1 ? s + 19 : s;
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < NCT; ++ct)
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, a[rt][fa]), __builtin_bit_cast(bf16x8, breg[sb][ct]),
+                                (s == 0 && term == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
+                });
+            } else if constexpr (BF16) {
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < NCT; ++ct)
+                        acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, a[rt][0]), __builtin_bit_cast(bf16x8, breg[s][ct]),
+                            s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < NCT; ++ct)
+                            acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                                a[rt][0][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
+            }
+            // a copy instruction stalls at issue for a while: in the MFMAs' shadow of the other group it is free
+            if constexpr (s % C::COPY_EVERY == 1 % C::COPY_EVERY && s / C::COPY_EVERY < NOCT) {
+                if (more_copy) copy_octet(std::integral_constant<int, s / C::COPY_EVERY>{}, off_next, copy_buf);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (!BF16) {
+            // one more rank-1 step adds -|T_a|^2/2 to every element of token row a
+            const float one = half == 0 ? 1.f : 0.f;
 #pragma unroll
             for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
                 for (int ct = 0; ct < NCT; ++ct)
-                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, a[rt]), __builtin_bit_cast(bf16x8, breg[s][ct]),
-                        s == 0 ? zero16 : acc[rt][ct], 0, 0, 0);
-            if constexpr (s % 4 == 1 && s / 4 < NOCT) {          // a copy instruction stalls at issue for a while: in the MFMAs' shadow it is free
-                if (more_copy) copy_octet(std::integral_constant<int, s / 4>{}, off_next, copy_buf);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        // this wavefront's copies of the tile after next have landed (see the head of the kernel)
-        if (tb + PD * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | NOCT);
+                    acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(half == 0 ? hn[rt] : 0.f, one, acc[rt][ct], 0, 0, 0);
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
+        }
+        // This wavefront's copies have landed: with copies three tiles ahead, those of the tile after next (the five of
+        // the tile beyond were issued later, see the head of the kernel); with copies one tile ahead, all of them.
+        if (PD >= 3 && tb + PD * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | NOCT);
         else __builtin_amdgcn_s_waitcnt(0x0f70);
         pp_barrier();
         buf = buf == NBUF - 1 ? 0 : buf + 1;
@@ -786,13 +874,34 @@ bool tiles_f32_supported(const Phase1Args& a)
     return a.m == 300 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0;
 }
 
+// One workgroup of eight wavefronts per CU (it takes all of a CU's LDS), fewer when there is less work than that.
+template <int MODE>
+hipError_t launch_pingpong(P1T d, int num_cu, hipStream_t s)
+{
+    using C = PP<MODE>;
+    d.nvt = (int32_t)((d.nvoc + C::WG_COLS - 1) / C::WG_COLS);
+    const int64_t total = (int64_t)d.nvt * d.nchunks;
+    int64_t grid = num_cu > 8 ? num_cu / 8 * 8 : 8;
+    while (grid > 8 && grid > total) grid -= 8;
+    const size_t smem = (size_t)C::NBUF * C::TILE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_pingpong<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    k_phase1_pingpong<MODE><<<(unsigned)grid, 512, smem, s>>>(d, d.tok_ids, d.grp_seg);
+    return hipGetLastError();
+}
+
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s)
 {
     P1T d = common_args(a, tp);
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<kF32, 2, 1, false>(d, s);
+    return launch_pingpong<kF32>(d, a.num_cu, s);
 }
 
 // a.E is the split copy: 640 bf16 per row (304 hi, 304 lo, zeros); norms and -|T|^2/2 stay fp32 as in the fp32 path
@@ -802,7 +911,7 @@ hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipS
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<kX3>::NOCT * 8;
     d.nzero_from = 0;
-    return launch_tiles<kX3, 2, 1, false>(d, s);
+    return launch_pingpong<kX3>(d, a.num_cu, s);
 }
 
 // a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
@@ -812,21 +921,7 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<kBF16>::NOCT * 8;
     d.nzero_from = 0;
-    d.nvt = (int32_t)((d.nvoc + pp::WG_COLS - 1) / pp::WG_COLS);
-    // one workgroup per CU (it takes all of a CU's LDS), fewer when there is less work than that
-    const int64_t total = (int64_t)d.nvt * d.nchunks;
-    int64_t grid = num_cu > 8 ? num_cu / 8 * 8 : 8;
-    while (grid > 8 && grid > total) grid -= 8;
-    const size_t smem = (size_t)pp::NBUF * pp::TILE_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_pingpong),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    k_phase1_pingpong<<<(unsigned)grid, 512, smem, s>>>(d, d.tok_ids, d.grp_seg);
-    return hipGetLastError();
+    return launch_pingpong<kBF16>(d, num_cu, s);
 }
 
 // Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
