@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--permute-vocab", action="store_true",
                     help="stress variant: renumber the vocabulary at random, so that word id is no longer frequency rank")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dedup-variant", action="store_true",
+                    help="do not time the de-duplicated form after the default one (keeps a profile to the timed kernels)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -144,7 +146,7 @@ def main():
 
     # The de-duplicated form of the same job, timed next to the default one (reported, never `value`).
     variant = None
-    if not args.dedup and not k and not cfg.queries_from_db:
+    if not args.dedup and not args.no_dedup_variant and not k and not cfg.queries_from_db:
         try:
             ctx.set_options(compute=compute, dedup=1)
             ws2 = binding.alloc_workspace(ctx.workspace_bytes(v, m, n, db.nnz, q, qs.nnz, emb_dtype, 0))
