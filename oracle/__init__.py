@@ -157,3 +157,6 @@ def topk(D, k):
                          idx.ctypes.data_as(_pi64), dist.ctypes.data_as(_pd))
     _check(rc)
     return idx, dist
+
+
+from .wmd import cost_matrix, emd, wmd_pair, wmd_pairs, centroids, wcd, wmd_topk_pruned  # noqa: E402,F401
