@@ -46,7 +46,8 @@ typedef enum {
     LCRWMD_EEMPTYDOC = 3,     /* a histogram without words                                           */
     LCRWMD_EWORKSPACE = 4,    /* workspace missing, misaligned or too small                          */
     LCRWMD_EUNSUPPORTED = 5,  /* e.g. k larger than the supported maximum                            */
-    LCRWMD_EHIP = 6           /* a HIP runtime call failed; see lcrwmd_last_error                    */
+    LCRWMD_EHIP = 6,          /* a HIP runtime call failed; see lcrwmd_last_error                    */
+    LCRWMD_ENOCONVERGE = 7    /* a transport problem used up its augmentation budget (lcrwmd_wmd_*)  */
 } lcrwmd_status;
 
 /* Storage type of embedding values.  Accumulation is always fp32. */
@@ -210,9 +211,84 @@ typedef struct {
        words * m flops); the two table passes are timed here, bytes = table rows streamed + outputs. */
     double table_fwd_ms;  int64_t table_fwd_launches;  double table_fwd_bytes;
     double table_rev_ms;  int64_t table_rev_launches;  double table_rev_bytes;
+    /* lcrwmd_wmd_pairs / lcrwmd_wmd_topk: the transport solver and the kernel that writes its cost matrices */
+    double emd_ms;  int64_t emd_launches;  double emd_pairs;  double emd_cost_ms;
 } lcrwmd_profile;
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Exact WMD behind the RWMD bound (Sec. II, Sec. III).  These calls take fp32 or bf16 E of any m;
+ * cost matrices are evaluated from differences of the stored values in fp32, the transport
+ * problems are solved in fp64, results are returned as fp32.
+ * ------------------------------------------------------------------------------------------- */
+
+/*
+ * Word Centroid Distance (Sec. III, "Word Centroid Distance"): with the centroids C1 = X1 E and
+ * C2 = X2 E (weights as stored),  D[i * ldd + j] = || C1[i] - C2[j] ||_2.   D is n x q fp32.
+ * Workspace: (n + q) * round_up(m, 4) * 4 bytes + 512.  No host synchronisation.
+ */
+lcrwmd_status lcrwmd_wcd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                         const lcrwmd_emb* E, float* D, int64_t ldd, void* ws, size_t ws_bytes,
+                         void* hip_stream);
+
+/*
+ * Workspace of lcrwmd_wmd_pairs for `pairs_in_flight` transport problems at a time, and the part of
+ * lcrwmd_wmd_topk's workspace that holds them: per problem max_h_db * max_h_q * 12 bytes (fp32 costs,
+ * fp64 flows), where max_h_* are the largest stored-entry counts of a database / query histogram.
+ */
+lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db, int64_t max_h_q,
+                                               int64_t pairs_in_flight, size_t* out_bytes);
+
+/*
+ * WMD of listed pairs (Sec. II: EMD(x1, x2) = min sum y[p,q] c[p,q] over y >= 0 with row sums x1
+ * and column sums x2; Sec. III, "Solving the WMD problem": x1 = F1,i, x2 = F2,j, c = T1,i o T2,j):
+ *
+ *     out[t] = EMD( X1[pair_db[t]], X2[pair_q[t]],  C[p,u] = || E[word p] - E[word u] ||_2 ),  t < npairs
+ *
+ * pair_db / pair_q / out (and flags, when not NULL) are device arrays of npairs entries; pair_db[t]
+ * in [0, n), pair_q[t] in [0, q) (checked on the device when the validate option is set).  Both
+ * histograms' weights are divided by their fp64 sums before the solve (stored fp32 weights add up
+ * to 1 only up to rounding, and the two masses must agree).  One wavefront solves one problem by
+ * successive shortest paths; flags[t] = 1 where it ran out of its augmentation budget
+ * (8 (h1 + h2) + 64 paths), in which case out[t] is the cost of a partial flow - none has been
+ * seen to; the call then also returns LCRWMD_ENOCONVERGE when flags is NULL.
+ * The problems are processed as many at a time as the workspace holds (at least one must fit).
+ * Synchronises the stream when it has to fetch row pointers, when validating, and (flags NULL) at
+ * the end to read the failure count.  Histograms of more than about 5,000 words in total per pair
+ * are LCRWMD_EUNSUPPORTED (per-word solver state is kept in LDS).
+ */
+lcrwmd_status lcrwmd_wmd_pairs(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                               const lcrwmd_emb* E, const int32_t* pair_db, const int32_t* pair_q,
+                               int64_t npairs, float* out, int32_t* flags, void* ws, size_t ws_bytes,
+                               void* hip_stream);
+
+/*
+ * Workspace that lets lcrwmd_wmd_topk run with its preferred batch sizes: the RWMD top-k workspace
+ * (lcrwmd_workspace_bytes with k) plus candidate lists and transport problems in flight.
+ */
+lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n,
+                                              int64_t nnz_db, int64_t q, int64_t nnz_q,
+                                              lcrwmd_dtype emb_dtype, int k, int64_t max_h_db,
+                                              int64_t max_h_q, size_t* out_bytes);
+
+/*
+ * The k nearest database histograms of every query by exact WMD, found with the RWMD cut-off
+ * (Sec. III, "Speeding-up WMD using RWMD"): per query, RWMD to every database histogram
+ * (lcrwmd_rwmd), the k nearest by RWMD, WMD to those, the largest of these k values as cut-off L,
+ * WMD to every other histogram whose RWMD is below L, and the k smallest of all WMDs evaluated.
+ * RWMD <= WMD, so nothing that belongs to the result is cut.  The device compares fp32 RWMD values
+ * against fp32 WMD values, so the test is RWMD < L (1 + 1e-5): rounding can only add candidates.
+ * R_idx / R_dist: q x k, ordered by (distance, row index) ascending, as in lcrwmd_rwmd_topk.
+ * evaluated (HOST, q entries, or NULL): WMD evaluations spent on each query (k + survivors).
+ * fp32 E with the LCRWMD_BF16 compute option is refused (LCRWMD_EUNSUPPORTED): a bound rounded to
+ * bf16 may exceed the WMD it is meant to bound.  1 <= k <= min(n, 64).
+ * Synchronises the stream several times per query batch (RWMD vocabulary sizes, survivor counts).
+ * Returns LCRWMD_ENOCONVERGE if any transport problem ran out of budget (results are still written).
+ */
+lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                              const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist,
+                              int64_t* evaluated, void* ws, size_t ws_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -17,14 +17,17 @@ _HERE = pathlib.Path(__file__).resolve().parent
 # LCRWMD_LIB lets a developer point the binding at another build of the same library
 LIB_PATH = pathlib.Path(os.environ.get("LCRWMD_LIB", _HERE / "liblcrwmd.so"))
 
-OK, EINVAL, EBADCSR, EEMPTYDOC, EWORKSPACE, EUNSUPPORTED, EHIP = range(7)
+OK, EINVAL, EBADCSR, EEMPTYDOC, EWORKSPACE, EUNSUPPORTED, EHIP, ENOCONVERGE = range(8)
 F32, BF16, BF16X3 = 0, 1, 2     # BF16X3: only as the compute option
-STATUS_NAMES = {0: "OK", 1: "EINVAL", 2: "EBADCSR", 3: "EEMPTYDOC", 4: "EWORKSPACE", 5: "EUNSUPPORTED", 6: "EHIP"}
+STATUS_NAMES = {0: "OK", 1: "EINVAL", 2: "EBADCSR", 3: "EEMPTYDOC", 4: "EWORKSPACE", 5: "EUNSUPPORTED", 6: "EHIP",
+                7: "ENOCONVERGE"}
 
 EXPORTS = (
     "lcrwmd_create", "lcrwmd_destroy", "lcrwmd_last_error", "lcrwmd_set_options", "lcrwmd_get_options",
     "lcrwmd_workspace_bytes", "lcrwmd_phase1_mindist", "lcrwmd_phase2_spmm", "lcrwmd_rwmd",
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
+    "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
+    "lcrwmd_wmd_topk",
 )
 
 
@@ -49,7 +52,9 @@ class ProfileStruct(ctypes.Structure):
                 ("phase2_ms", ctypes.c_double), ("phase2_launches", ctypes.c_int64), ("phase2_bytes", ctypes.c_double),
                 ("phase2_gather_bytes", ctypes.c_double),
                 ("table_fwd_ms", ctypes.c_double), ("table_fwd_launches", ctypes.c_int64), ("table_fwd_bytes", ctypes.c_double),
-                ("table_rev_ms", ctypes.c_double), ("table_rev_launches", ctypes.c_int64), ("table_rev_bytes", ctypes.c_double)]
+                ("table_rev_ms", ctypes.c_double), ("table_rev_launches", ctypes.c_int64), ("table_rev_bytes", ctypes.c_double),
+                ("emd_ms", ctypes.c_double), ("emd_launches", ctypes.c_int64), ("emd_pairs", ctypes.c_double),
+                ("emd_cost_ms", ctypes.c_double)]
 
 
 class LcrwmdError(RuntimeError):
@@ -84,6 +89,11 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_topk.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+        lib.lcrwmd_wcd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
+        lib.lcrwmd_wmd_pairs_workspace_bytes.argtypes = [vp, i64, i64, i64, P(sz)]
+        lib.lcrwmd_wmd_pairs.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, vp, i64, vp, vp, vp, sz, vp]
+        lib.lcrwmd_wmd_topk_workspace_bytes.argtypes = [vp, i64, i64, i64, i64, i64, i64, i32, i32, i64, i64, P(sz)]
+        lib.lcrwmd_wmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
         lib.lcrwmd_profile_begin.argtypes = [vp]
         lib.lcrwmd_profile_end.argtypes = [vp, P(ProfileStruct)]
         for name in EXPORTS:
@@ -234,6 +244,50 @@ class Context:
         p, nbytes = self._ws(ws)
         self._check(self._lib.lcrwmd_topk(self._h, D.data_ptr(), D.shape[0], D.shape[1], D.stride(0), k,
                                           R_idx.data_ptr(), R_dist.data_ptr(), p, nbytes, _stream()))
+
+    def wcd(self, queries: Csr, database: Csr, E: torch.Tensor, D: torch.Tensor, ws: torch.Tensor):
+        assert D.is_cuda and D.dtype == torch.float32 and D.stride(1) == 1
+        es, qs, ds = _emb_struct(E), queries.struct(), database.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_wcd(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es),
+                                         D.data_ptr(), D.stride(0), p, nbytes, _stream()))
+
+    def wmd_pairs_workspace_bytes(self, max_h_db: int, max_h_q: int, pairs_in_flight: int) -> int:
+        out = ctypes.c_size_t()
+        self._check(self._lib.lcrwmd_wmd_pairs_workspace_bytes(self._h, max_h_db, max_h_q, pairs_in_flight, ctypes.byref(out)))
+        return int(out.value)
+
+    def wmd_pairs(self, queries: Csr, database: Csr, E: torch.Tensor, pair_db: torch.Tensor, pair_q: torch.Tensor,
+                  out: torch.Tensor, ws: torch.Tensor, flags: torch.Tensor | None = None):
+        assert pair_db.dtype == torch.int32 and pair_q.dtype == torch.int32 and out.dtype == torch.float32
+        assert pair_db.is_cuda and pair_q.is_cuda and out.is_cuda
+        assert pair_db.is_contiguous() and pair_q.is_contiguous() and out.is_contiguous()
+        assert pair_q.numel() == pair_db.numel() and out.numel() >= pair_db.numel()
+        assert flags is None or (flags.is_cuda and flags.dtype == torch.int32 and flags.is_contiguous()
+                                 and flags.numel() >= pair_db.numel())
+        es, qs, ds = _emb_struct(E), queries.struct(), database.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_wmd_pairs(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es),
+                                               pair_db.data_ptr(), pair_q.data_ptr(), pair_db.numel(), out.data_ptr(),
+                                               flags.data_ptr() if flags is not None else None, p, nbytes, _stream()))
+
+    def wmd_topk_workspace_bytes(self, v, m, n, nnz_db, q, nnz_q, emb_dtype, k, max_h_db, max_h_q) -> int:
+        out = ctypes.c_size_t()
+        self._check(self._lib.lcrwmd_wmd_topk_workspace_bytes(self._h, v, m, n, nnz_db, q, nnz_q, emb_dtype, k,
+                                                              max_h_db, max_h_q, ctypes.byref(out)))
+        return int(out.value)
+
+    def wmd_topk(self, queries: Csr, database: Csr, E: torch.Tensor, k: int, R_idx: torch.Tensor, R_dist: torch.Tensor,
+                 ws: torch.Tensor, evaluated: torch.Tensor | None = None):
+        """evaluated: optional HOST int64 tensor with one entry per query."""
+        assert R_idx.dtype == torch.int32 and R_dist.dtype == torch.float32 and R_idx.is_contiguous() and R_dist.is_contiguous()
+        assert evaluated is None or (not evaluated.is_cuda and evaluated.dtype == torch.int64 and evaluated.is_contiguous()
+                                     and evaluated.numel() >= queries.rows)
+        es, qs, ds = _emb_struct(E), queries.struct(), database.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_wmd_topk(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es), k,
+                                              R_idx.data_ptr(), R_dist.data_ptr(),
+                                              evaluated.data_ptr() if evaluated is not None else None, p, nbytes, _stream()))
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

@@ -508,6 +508,8 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
         if (r.kind == 1) { out->phase1_ms += ms; out->phase1_launches += 1; out->phase1_flops += r.work; }
         else if (r.kind == 3) { out->table_fwd_ms += ms; out->table_fwd_launches += 1; out->table_fwd_bytes += r.work; }
         else if (r.kind == 4) { out->table_rev_ms += ms; out->table_rev_launches += 1; out->table_rev_bytes += r.work; }
+        else if (r.kind == 5) { out->emd_ms += ms; out->emd_launches += 1; out->emd_pairs += r.work; }
+        else if (r.kind == 6) { out->emd_cost_ms += ms; }
         else { out->phase2_ms += ms; out->phase2_launches += 1; out->phase2_bytes += r.work; out->phase2_gather_bytes += r.work2; }
     }
     ctx->prof.clear();
@@ -702,6 +704,268 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
         ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, (char*)ws + off, ws_bytes - off, s));
         HIP_TRY(launch_topk(tile, n, j1 - j0, ldt, k, R_idx + j0 * k, R_dist + j0 * k, tk, tkb, s));
     }
+    return LCRWMD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ exact WMD, WCD, pruning
+
+lcrwmd_status lcrwmd_wcd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database, const lcrwmd_emb* E,
+                         float* D, int64_t ldd, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    const int64_t n = database->rows, q = queries->rows;
+    if (n == 0 || q == 0) return LCRWMD_OK;
+    if (!D) return fail(ctx, LCRWMD_EINVAL, "D is NULL");
+    if (ldd < q) return fail(ctx, LCRWMD_EINVAL, "ldd < queries.rows");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    Bump b(ws, ws_bytes);
+    if (ctx->opt.validate) {
+        int32_t* st = b.take_n<int32_t>(64);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+        ST_TRY(validate_on_device(ctx, queries, "queries", st, s));
+        ST_TRY(validate_on_device(ctx, database, "database", st, s));
+    }
+    const int64_t ldc = round_up(E->m, 4);
+    float* C1 = b.take_n<float>((size_t)n * ldc);
+    float* C2 = b.take_n<float>((size_t)q * ldc);
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the centroids: need %zu bytes",
+                           (size_t)(n + q) * ldc * 4 + 1024);
+    HIP_TRY(launch_centroids(*E, *database, C1, ldc, s));
+    HIP_TRY(launch_centroids(*E, *queries, C2, ldc, s));
+    HIP_TRY(launch_centroid_dist(C1, n, C2, q, ldc, (int32_t)E->m, D, ldd, s));
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db, int64_t max_h_q, int64_t pairs_in_flight,
+                                               size_t* out_bytes)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
+    if (max_h_db <= 0 || max_h_q <= 0 || pairs_in_flight <= 0) return fail(ctx, LCRWMD_EINVAL, "sizes must be positive");
+    *out_bytes = emd_pair_bytes(max_h_db, max_h_q) * (size_t)pairs_in_flight + 1024;
+    return LCRWMD_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int64_t longest_row(const int64_t* rp, int64_t rows)
+{
+    int64_t mx = 0;
+    for (int64_t r = 0; r < rows; ++r)
+        if (rp[r + 1] - rp[r] > mx) mx = rp[r + 1] - rp[r];
+    return mx;
+}
+
+constexpr int64_t kEmdChunk = 65536;      // transport problems per launch at most
+
+// WMD of `count` listed pairs into out, as many at a time as `slabs` holds.
+lcrwmd_status run_wmd_list(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_csr* DB, const lcrwmd_emb* E,
+                           const int32_t* pair_db, const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max,
+                           void* slabs, size_t slab_bytes, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s)
+{
+    int64_t cap = (int64_t)(slab_bytes / emd_pair_bytes(h1max, h2max));
+    if (cap > kEmdChunk) cap = kEmdChunk;
+    if (cap < 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem (%zu bytes)",
+                             emd_pair_bytes(h1max, h2max));
+    for (int64_t t0 = 0; t0 < count; t0 += cap) {
+        const int64_t c = count - t0 < cap ? count - t0 : cap;
+        {
+            ProfScope ps(ctx, s, 6, (double)c);
+            HIP_TRY(launch_pair_costs(*E, *DB, *Q, pair_db + t0, pair_q + t0, c, h1max, h2max, slabs, s));
+        }
+        ProfScope ps(ctx, s, 5, (double)c);
+        HIP_TRY(launch_emd(*DB, *Q, pair_db + t0, pair_q + t0, c, h1max, h2max, slabs, out + t0, flags ? flags + t0 : nullptr,
+                           fail_count, s));
+    }
+    return LCRWMD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+lcrwmd_status lcrwmd_wmd_pairs(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database, const lcrwmd_emb* E,
+                               const int32_t* pair_db, const int32_t* pair_q, int64_t npairs, float* out, int32_t* flags,
+                               void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    if (npairs < 0) return fail(ctx, LCRWMD_EINVAL, "npairs < 0");
+    if (npairs == 0) return LCRWMD_OK;
+    if (!pair_db || !pair_q || !out) return fail(ctx, LCRWMD_EINVAL, "pair_db, pair_q or out is NULL");
+    if (queries->rows == 0 || database->rows == 0) return fail(ctx, LCRWMD_EINVAL, "pairs listed but a set is empty");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HostPtr rq, rdb;
+    ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    const int64_t h1max = longest_row(rdb.p, database->rows), h2max = longest_row(rq.p, queries->rows);
+    if (!emd_supported(h1max, h2max))
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "histograms of %lld + %lld words exceed the solver's per-word state in LDS",
+                    (long long)h1max, (long long)h2max);
+    Bump b(ws, ws_bytes);
+    int32_t* counters = b.take_n<int32_t>(64);
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+    HIP_TRY(launch_fill_i32(counters, 2, 0, s));
+    if (ctx->opt.validate) {
+        HIP_TRY(launch_check_pairs(pair_db, pair_q, npairs, database->rows, queries->rows, counters + 1, s));
+        int32_t bad = 0;
+        HIP_TRY(hipMemcpyAsync(&bad, counters + 1, sizeof(bad), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (bad) return fail(ctx, LCRWMD_EINVAL, "a listed pair is outside [0, n) x [0, q)");
+    }
+    const size_t off = (b.used + 255) & ~(size_t)255;
+    ST_TRY(run_wmd_list(ctx, queries, database, E, pair_db, pair_q, npairs, h1max, h2max, (char*)ws + off, ws_bytes - off, out,
+                        flags, counters, s));
+    if (!flags) {
+        int32_t failed = 0;
+        HIP_TRY(hipMemcpyAsync(&failed, counters, sizeof(failed), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (failed) return fail(ctx, LCRWMD_ENOCONVERGE, "%d transport problems ran out of their augmentation budget", failed);
+    }
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db, int64_t q,
+                                              int64_t nnz_q, lcrwmd_dtype emb_dtype, int k, int64_t max_h_db,
+                                              int64_t max_h_q, size_t* out_bytes)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
+    if (k < 1 || max_h_db <= 0 || max_h_q <= 0) return fail(ctx, LCRWMD_EINVAL, "k and the histogram sizes must be positive");
+    size_t base = 0;
+    ST_TRY(lcrwmd_workspace_bytes(ctx, v, m, n, nnz_db, q, nnz_q, emb_dtype, k, &base));
+    int64_t qb = q < 2048 ? q : 2048;
+    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+    // per-query arrays, lists for a quarter of all pairs of a batch, 8,192 transport problems in flight
+    const size_t lists = (size_t)qb * (size_t)k * 24 + (size_t)qb * 32 + (size_t)n * (size_t)qb / 4 * 12;
+    const size_t slabs = emd_pair_bytes(max_h_db, max_h_q) * 8192;
+    *out_bytes = base + lists + slabs + 16384;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database, const lcrwmd_emb* E,
+                              int k, int32_t* R_idx, float* R_dist, int64_t* evaluated, void* ws, size_t ws_bytes,
+                              void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    const int64_t n = database->rows, q = queries->rows;
+    if (q == 0) return LCRWMD_OK;
+    if (!R_idx || !R_dist) return fail(ctx, LCRWMD_EINVAL, "R_idx or R_dist is NULL");
+    if (k < 1 || k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    if (n > (int64_t)65535 * 256) return fail(ctx, LCRWMD_EUNSUPPORTED, "more than 16.7 million database rows");
+    if (E->dtype == LCRWMD_F32 && ctx->opt.compute == LCRWMD_BF16)
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "pruning needs a true lower bound: fp32 E with bf16 compute is refused");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HostPtr rq, rdb;
+    ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    const int64_t h1max = longest_row(rdb.p, n), h2max = longest_row(rq.p, q);
+    if (!emd_supported(h1max, h2max))
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "histograms of %lld + %lld words exceed the solver's per-word state in LDS",
+                    (long long)h1max, (long long)h2max);
+    const size_t pair_bytes = emd_pair_bytes(h1max, h2max);
+    const int mode = prec_mode(ctx, E);
+
+    // Query batches.  Front of the workspace: the n x qb tile of RWMD bounds and the per-query arrays; the rest
+    // serves first the RWMD passes and then the candidate lists and the transport problems.
+    int64_t qb = q < 2048 ? q : 2048;
+    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+    auto front_bytes = [&](int64_t b) {
+        return (size_t)n * (size_t)round_up(b, 4) * 4 + topk_bytes(n, b, k) + (size_t)b * (size_t)k * 24 + (size_t)b * 32 + 8192;
+    };
+    for (;;) {
+        const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode) +
+                                 fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
+        const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 64 + 4096;   // first k lists, >= 64 problems in flight
+        if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;
+        if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query batch");
+        qb = (qb + 1) / 2;
+    }
+    std::vector<int64_t> hoff;
+    try {
+        hoff.resize((size_t)qb + 1);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, LCRWMD_EINVAL, "out of host memory");
+    }
+    int32_t failed_total = 0;
+    for (int64_t j0 = 0; j0 < q; j0 += qb) {
+        const int64_t j1 = j0 + qb < q ? j0 + qb : q, nq = j1 - j0;
+        Bump b(ws, ws_bytes);
+        const int64_t ldt = round_up(nq, 4);
+        float* tile = b.take_n<float>((size_t)n * ldt);
+        const size_t tkb = topk_bytes(n, nq, k) + 512;
+        void* tk = b.take(tkb);
+        int32_t* R0 = b.take_n<int32_t>((size_t)nq * k);
+        float* R0d = b.take_n<float>((size_t)nq * k);
+        int32_t* p0_db = b.take_n<int32_t>((size_t)nq * k);
+        int32_t* p0_q = b.take_n<int32_t>((size_t)nq * k);
+        float* wmd0 = b.take_n<float>((size_t)nq * k);
+        float* cut = b.take_n<float>((size_t)nq);
+        int32_t* cnt = b.take_n<int32_t>((size_t)nq);
+        int64_t* off = b.take_n<int64_t>((size_t)nq + 1);
+        int64_t* cursor = b.take_n<int64_t>((size_t)nq);
+        int32_t* counters = b.take_n<int32_t>(64);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: query batch does not fit");
+        const size_t rest_off = (b.used + 255) & ~(size_t)255;
+        char* rest = (char*)ws + rest_off;
+        const size_t rest_bytes = ws_bytes - rest_off;
+
+        // RWMD to every database histogram, the k nearest by RWMD (Sec. III)
+        ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, rest, rest_bytes, s));
+        HIP_TRY(launch_topk(tile, n, nq, ldt, k, R0, R0d, tk, tkb, s));
+        // WMD to those; their largest value is the cut-off
+        HIP_TRY(launch_fill_i32(counters, 1, 0, s));
+        HIP_TRY(launch_first_pairs(R0, nq, k, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
+        ST_TRY(run_wmd_list(ctx, queries, database, E, p0_db, p0_q, nq * k, h1max, h2max, rest, rest_bytes, wmd0, nullptr,
+                            counters, s));
+        HIP_TRY(launch_cutoff(wmd0, nq, k, 1e-5f, cut, s));
+        // survivors: RWMD below the cut-off
+        HIP_TRY(launch_count_below(tile, n, nq, ldt, cut, cnt, off, s));
+        HIP_TRY(hipMemcpyAsync(hoff.data(), off, sizeof(int64_t) * ((size_t)nq + 1), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        if (evaluated)
+            for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k + hoff[j + 1] - hoff[j];
+        // Lists hold 12 bytes per survivor; they share `rest` with the transport problems in flight.
+        size_t slab_part = pair_bytes * 8192;
+        if (slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
+        if (slab_part < pair_bytes) slab_part = pair_bytes;
+        slab_part = slab_part / 256 * 256;
+        if (slab_part < pair_bytes || slab_part + 4096 > rest_bytes)
+            return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem");
+        const int64_t list_cap = (int64_t)((rest_bytes - slab_part - 2048) / 12);
+        for (int64_t ja = 0; ja < nq;) {
+            int64_t jb = ja;
+            while (jb < nq && hoff[jb + 1] - hoff[ja] <= list_cap) ++jb;
+            if (jb == ja)
+                return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: query %lld alone has %lld survivors (%lld fit)",
+                            (long long)(j0 + ja), (long long)(hoff[ja + 1] - hoff[ja]), (long long)list_cap);
+            const int64_t total = hoff[jb] - hoff[ja];
+            Bump lb(rest + slab_part, rest_bytes - slab_part);
+            int32_t* l_db = lb.take_n<int32_t>((size_t)total + 1);
+            int32_t* l_q = lb.take_n<int32_t>((size_t)total + 1);
+            float* l_d = lb.take_n<float>((size_t)total + 1);
+            if (!lb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: survivor lists do not fit");
+            HIP_TRY(launch_fill_below(tile, n, ja, jb, ldt, cut, off, cursor, (int32_t)j0, l_db, l_q, s));
+            ST_TRY(run_wmd_list(ctx, queries, database, E, l_db, l_q, total, h1max, h2max, rest, slab_part, l_d, nullptr, counters, s));
+            HIP_TRY(launch_select_lists(R0, wmd0, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
+            ja = jb;
+        }
+        int32_t failed = 0;
+        HIP_TRY(hipMemcpyAsync(&failed, counters, sizeof(failed), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        failed_total += failed;
+    }
+    if (failed_total)
+        return fail(ctx, LCRWMD_ENOCONVERGE, "%d transport problems ran out of their augmentation budget", failed_total);
     return LCRWMD_OK;
 }
 

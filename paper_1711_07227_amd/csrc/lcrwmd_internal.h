@@ -12,7 +12,7 @@
 
 struct lcrwmd_prof_rec {
     hipEvent_t start, stop;
-    int kind;              // 1: first-phase kernel, 2: second-phase kernel
+    int kind;              // 1: first-phase kernel, 2: second-phase kernel, 3/4: table passes, 5: transport solver, 6: its costs
     double work, work2;
 };
 
@@ -156,5 +156,29 @@ constexpr int kMaxTopK = 64;
 size_t topk_bytes(int64_t n, int64_t q, int k);
 hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
                        void* ws, size_t ws_bytes, hipStream_t s);
+
+// wmd.hip: transport problems (one wavefront each), centroid distances, pruning lists
+size_t emd_pair_bytes(int64_t h1max, int64_t h2max);
+bool emd_supported(int64_t h1max, int64_t h2max);
+hipError_t launch_pair_costs(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
+                             const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, hipStream_t s);
+hipError_t launch_emd(const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db, const int32_t* pair_q,
+                      int64_t count, int64_t h1max, int64_t h2max, void* slabs, float* out, int32_t* flags,
+                      int32_t* fail_count, hipStream_t s);
+hipError_t launch_check_pairs(const int32_t* pair_db, const int32_t* pair_q, int64_t npairs, int64_t n, int64_t q,
+                              int32_t* status, hipStream_t s);
+hipError_t launch_centroids(const lcrwmd_emb& E, const lcrwmd_csr& X, float* C, int64_t ldc, hipStream_t s);
+hipError_t launch_centroid_dist(const float* C1, int64_t n, const float* C2, int64_t q, int64_t ldc, int32_t m, float* D,
+                                int64_t ldd, hipStream_t s);
+hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int k, int32_t j0, float* D, int64_t ldd, int32_t* pair_db,
+                              int32_t* pair_q, hipStream_t s);
+hipError_t launch_cutoff(const float* wmd0, int64_t q, int k, float slack, float* cut, hipStream_t s);
+hipError_t launch_count_below(const float* D, int64_t n, int64_t q, int64_t ldd, const float* cut, int32_t* cnt,
+                              int64_t* off, hipStream_t s);
+hipError_t launch_fill_below(const float* D, int64_t n, int64_t ja, int64_t jb, int64_t ldd, const float* cut,
+                             const int64_t* off, int64_t* cursor, int32_t j0, int32_t* pair_db, int32_t* pair_q,
+                             hipStream_t s);
+hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k, const int64_t* off, int64_t ja, int64_t jb,
+                               const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist, hipStream_t s);
 
 }  // namespace lcrwmd

@@ -1,0 +1,596 @@
+// Exact Word Mover's Distance for lists of histogram pairs, the Word Centroid Distance, and the device side of
+// RWMD-based pruning (Sec. II: EMD as a transport problem; Sec. III: "Solving the WMD problem", "Speeding-up WMD
+// using RWMD", "Word Centroid Distance").
+//
+// The transport problems are small (tens to hundreds of words a side) and there are many of them, so each is given
+// to one wavefront: successive shortest paths with node potentials on the dense bipartite graph, costs in fp32 as
+// produced by the cost kernel, everything the solver itself computes (potentials, path lengths, flows, the
+// objective) in fp64.  Every loop is bounded by the problem's dimensions, so every wavefront ends.
+#include <float.h>
+#include <limits.h>
+
+#include "lcrwmd_internal.h"
+
+namespace lcrwmd {
+
+namespace {
+
+constexpr double kFar = 1e300;        // "no path yet"
+constexpr double kMassEps = 1e-13;    // mass below this is rounding residue of the fp64 normalisation
+
+__device__ inline float emb_val(const void* E, int dtype, int64_t idx)
+{
+    if (dtype == LCRWMD_BF16) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(E)[idx] << 16);
+    return reinterpret_cast<const float*>(E)[idx];
+}
+
+// Order this wavefront's earlier LDS and global accesses before its later ones (lanes hand values to one another).
+__device__ inline void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ inline double wave_sum(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// C = T1 o T2 for every pair of a chunk (Sec. III): c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||,
+// as the square root of the sum of squared differences (no norm expansion: equal words give exactly 0).
+// One workgroup per pair, 32 x 32 output tiles, the embedding dimension staged through LDS 32 values at a time.
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int kCT = 32;
+
+__global__ __launch_bounds__(256) void k_pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+                                                    const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
+                                                    const int64_t* __restrict__ q_rp, const int32_t* __restrict__ q_col,
+                                                    const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q,
+                                                    float* __restrict__ slabs_c, int64_t slab_elems)
+{
+    __shared__ float A[kCT][kCT + 1], B[kCT][kCT + 1];
+    __shared__ int32_t wa[kCT], wb[kCT];
+    const int tid = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int32_t i = pair_db[t], j = pair_q[t];
+    const int64_t a0 = db_rp[i], b0 = q_rp[j];
+    const int h1 = (int)(db_rp[i + 1] - a0), h2 = (int)(q_rp[j + 1] - b0);
+    float* c = slabs_c + t * slab_elems;
+    const int tx = tid & 15, ty = tid >> 4;       // 16 x 16 threads, 2 x 2 outputs each
+    const int lr = tid >> 5, lc = tid & 31;       // loader: rows lr + 8 e, column lc
+    for (int p0 = 0; p0 < h1; p0 += kCT)
+        for (int u0 = 0; u0 < h2; u0 += kCT) {
+            if (tid < kCT) wa[tid] = p0 + tid < h1 ? db_col[a0 + p0 + tid] : -1;
+            else if (tid < 2 * kCT) wb[tid - kCT] = u0 + tid - kCT < h2 ? q_col[b0 + u0 + tid - kCT] : -1;
+            float acc00 = 0.f, acc01 = 0.f, acc10 = 0.f, acc11 = 0.f;
+            for (int k0 = 0; k0 < m; k0 += kCT) {
+                __syncthreads();                   // word ids written; the previous slice has been consumed
+                const int kk = k0 + lc;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int r = lr + 8 * e;
+                    const int32_t w1 = wa[r], w2 = wb[r];
+                    A[r][lc] = (w1 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w1 * ld + kk) : 0.f;
+                    B[r][lc] = (w2 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w2 * ld + kk) : 0.f;
+                }
+                __syncthreads();
+#pragma unroll 8
+                for (int k = 0; k < kCT; ++k) {
+                    const float x0 = A[ty][k], x1 = A[ty + 16][k], y0 = B[tx][k], y1 = B[tx + 16][k];
+                    float d;
+                    d = x0 - y0; acc00 = fmaf(d, d, acc00);
+                    d = x0 - y1; acc01 = fmaf(d, d, acc01);
+                    d = x1 - y0; acc10 = fmaf(d, d, acc10);
+                    d = x1 - y1; acc11 = fmaf(d, d, acc11);
+                }
+            }
+            const int p = p0 + ty, u = u0 + tx;
+            if (p < h1 && u < h2) c[(int64_t)p * h2 + u] = sqrtf(acc00);
+            if (p < h1 && u + 16 < h2) c[(int64_t)p * h2 + u + 16] = sqrtf(acc01);
+            if (p + 16 < h1 && u < h2) c[(int64_t)(p + 16) * h2 + u] = sqrtf(acc10);
+            if (p + 16 < h1 && u + 16 < h2) c[(int64_t)(p + 16) * h2 + u + 16] = sqrtf(acc11);
+            __syncthreads();                       // wa / wb are rewritten by the next tile
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// EMD of one pair per wavefront (Sec. II): minimise sum y[p,u] c[p,u] with row sums x1, column sums x2, y >= 0.
+//
+// Successive shortest paths.  Node potentials phiS (words of X1[i], "sources") and phiT (words of X2[j], "sinks")
+// keep every reduced cost c[p,u] + phiS[p] - phiT[u] non-negative and make it zero on edges that carry flow.  The
+// sources are served one after the other; while source s has mass left, a Dijkstra search over the residual graph
+// finds the nearest sink with unmet demand: forward edges exist between every source and every sink, a backward
+// edge from sink u to source p exists where y[p,u] > 0 and has reduced cost zero, so a source enters the search at
+// the distance of the sink that reaches it.  Mass min(supply left, demand left, smallest flow on a backward edge
+// of the path) is moved, the potentials are shifted by the search distances, and the objective grows by mass x path
+// cost.  Lane l owns sinks and sources l, l + 64, ...; their per-node state sits in LDS, the flow matrix
+// (transposed: one row per sink) and the costs in the pair's slab in device memory.
+// Histogram weights are divided by their fp64 sums first, so both sides carry mass 1.
+// flags[t]: 0 solved; 1 the augmentation budget ran out (the result is then the cost of a partial flow).
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_emd(const int64_t* __restrict__ db_rp, const float* __restrict__ db_val,
+                                            const int64_t* __restrict__ q_rp, const float* __restrict__ q_val,
+                                            const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q,
+                                            const float* __restrict__ slabs_c, int64_t slab_elems, double* slabs_f,
+                                            int32_t h1max, int32_t h2max, float* __restrict__ out,
+                                            int32_t* __restrict__ flags, int32_t* fail_count)
+{
+    extern __shared__ double lds_d[];
+    double* phiS = lds_d;
+    double* dS = phiS + h1max;
+    double* sup = dS + h1max;
+    double* phiT = sup + h1max;
+    double* dT = phiT + h2max;
+    double* dem = dT + h2max;
+    int32_t* par = reinterpret_cast<int32_t*>(dem + h2max);
+    int32_t* vis = par + h1max;
+    int32_t* way = vis + h1max;
+    int32_t* used = way + h2max;
+
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int32_t i = pair_db[t], j = pair_q[t];
+    const int64_t a0 = db_rp[i], b0 = q_rp[j];
+    const int h1 = (int)(db_rp[i + 1] - a0), h2 = (int)(q_rp[j + 1] - b0);
+    const float* c = slabs_c + t * slab_elems;
+    double* f = slabs_f + t * slab_elems;          // f[u * h1 + p] = y[p, u]
+
+    double sa = 0.0, sb = 0.0;
+    for (int p = lane; p < h1; p += 64) sa += (double)db_val[a0 + p];
+    for (int u = lane; u < h2; u += 64) sb += (double)q_val[b0 + u];
+    sa = wave_sum(sa);
+    sb = wave_sum(sb);
+    for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
+    for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
+    for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
+    wave_sync();
+
+    const int budget = 8 * (h1 + h2) + 64;         // augmentations; each empties a source, a sink or a flow entry
+    int naug = 0;
+    bool exhausted = false;
+    double total = 0.0;
+
+    for (int s = 0; s < h1 && !exhausted; ++s) {
+        while (sup[s] > kMassEps) {
+            if (naug >= budget) { exhausted = true; break; }
+            // ---- search from s ----
+            for (int u = lane; u < h2; u += 64) { dT[u] = kFar; used[u] = 0; way[u] = -1; }
+            for (int p = lane; p < h1; p += 64) vis[p] = 0;
+            wave_sync();
+            if (lane == (s & 63)) { vis[s] = 1; dS[s] = 0.0; par[s] = -1; }
+            {
+                const double ps = phiS[s];
+                const float* crow = c + (int64_t)s * h2;
+                for (int u = lane; u < h2; u += 64) {
+                    double rc = (double)crow[u] + ps - phiT[u];
+                    rc = rc > 0.0 ? rc : 0.0;
+                    dT[u] = rc;
+                    way[u] = s;
+                }
+            }
+            int target = -1;
+            double Dt = 0.0;
+            for (int it = 0; it < h2; ++it) {
+                double bv = kFar;
+                int bi = INT_MAX;
+                for (int u = lane; u < h2; u += 64)
+                    if (!used[u] && dT[u] < bv) { bv = dT[u]; bi = u; }
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) {
+                    const double ov = __shfl_xor(bv, o);
+                    const int oi = __shfl_xor(bi, o);
+                    if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                }
+                if (bi == INT_MAX || bv >= kFar) break;        // every reachable sink has been taken
+                const int u = bi;
+                if (lane == (u & 63)) used[u] = 1;
+                if (dem[u] > 0.0) { target = u; Dt = bv; break; }
+                // sources that send flow to u join the search at u's distance
+                const double* frow = f + (int64_t)u * h1;
+                for (int pb = 0; pb < h1; pb += 64) {
+                    const int p = pb + lane;
+                    const bool add = p < h1 && frow[p] > 0.0 && !vis[p];
+                    if (add) { vis[p] = 1; dS[p] = bv; par[p] = u; }
+                    unsigned long long mask = __ballot(add);
+                    while (mask) {
+                        const int pp = pb + __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        const double ps = phiS[pp];
+                        const float* crow = c + (int64_t)pp * h2;
+                        for (int uu = lane; uu < h2; uu += 64)
+                            if (!used[uu]) {
+                                double rc = (double)crow[uu] + ps - phiT[uu];
+                                rc = rc > 0.0 ? rc : 0.0;
+                                const double nd = bv + rc;
+                                if (nd < dT[uu]) { dT[uu] = nd; way[uu] = pp; }
+                            }
+                    }
+                }
+            }
+            wave_sync();
+            if (target < 0) {                                   // only rounding residue is left on this side
+                if (lane == (s & 63)) sup[s] = 0.0;
+                wave_sync();
+                break;
+            }
+            // ---- amount: walk the path from the target back to s ----
+            double delta = sup[s] < dem[target] ? sup[s] : dem[target];
+            {
+                int p = way[target];
+                for (int g = 0; g < h1; ++g) {
+                    const int up = par[p];
+                    if (up < 0) break;
+                    const double fl = f[(int64_t)up * h1 + p];
+                    delta = fl < delta ? fl : delta;
+                    p = way[up];
+                }
+            }
+            const double path_cost = Dt - phiS[s] + phiT[target];
+            total += delta * path_cost;
+            wave_sync();                                         // reads of the old state are done
+            // ---- move the mass ----
+            if (lane == 0) {
+                int u = target, p = way[u];
+                for (int g = 0; g <= h1; ++g) {
+                    f[(int64_t)u * h1 + p] += delta;
+                    const int up = par[p];
+                    if (up < 0) break;
+                    const double nf = f[(int64_t)up * h1 + p] - delta;
+                    f[(int64_t)up * h1 + p] = nf > kMassEps ? nf : 0.0;
+                    u = up;
+                    p = way[u];
+                }
+                double r = sup[s] - delta;
+                sup[s] = r > kMassEps ? r : 0.0;
+                r = dem[target] - delta;
+                dem[target] = r > kMassEps ? r : 0.0;
+            }
+            // ---- potentials: nodes the search settled move by their distance minus the target's ----
+            for (int p = lane; p < h1; p += 64)
+                if (vis[p]) phiS[p] += dS[p] - Dt;
+            for (int u = lane; u < h2; u += 64)
+                if (used[u]) phiT[u] += dT[u] - Dt;
+            wave_sync();
+            ++naug;
+        }
+    }
+    if (lane == 0) {
+        out[t] = (float)total;
+        if (flags) flags[t] = exhausted ? 1 : 0;
+        if (exhausted && fail_count) atomicAdd(fail_count, 1);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Word Centroid Distance (Sec. III): centroids X E, then Euclidean distances between centroids.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_centroids(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+                                                   const int64_t* __restrict__ rp, const int32_t* __restrict__ col,
+                                                   const float* __restrict__ val, float* __restrict__ C, int64_t ldc)
+{
+    const int64_t i = blockIdx.x;
+    const int64_t a = rp[i], b = rp[i + 1];
+    for (int k = threadIdx.x; k < m; k += 256) {
+        float acc = 0.f;
+        for (int64_t e = a; e < b; ++e) acc = fmaf(val[e], emb_val(E, dtype, (int64_t)col[e] * ld + k), acc);
+        C[i * ldc + k] = acc;
+    }
+}
+
+// D[i * ldd + j] = || C1[i] - C2[j] ||: 64 x 64 outputs per workgroup, 4 x 4 per thread, 16 dimensions per LDS slice.
+__global__ __launch_bounds__(256) void k_centroid_dist(const float* __restrict__ C1, int64_t n, const float* __restrict__ C2,
+                                                       int64_t q, int64_t ldc, int32_t m, float* __restrict__ D, int64_t ldd)
+{
+    __shared__ float A[16][64 + 1], B[16][64 + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t i0 = (int64_t)blockIdx.y * 64, j0 = (int64_t)blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < m; k0 += 16) {
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r = (tid >> 4) + 16 * e, k = tid & 15;
+            A[k][r] = (i0 + r < n && k0 + k < m) ? C1[(i0 + r) * ldc + k0 + k] : 0.f;
+            B[k][r] = (j0 + r < q && k0 + k < m) ? C2[(j0 + r) * ldc + k0 + k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            float x[4], y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[e] = A[k][ty + 16 * e]; y[e] = B[k][tx + 16 * e]; }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float d = x[a] - y[b];
+                    acc[a][b] = fmaf(d, d, acc[a][b]);
+                }
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t i = i0 + ty + 16 * a, j = j0 + tx + 16 * b;
+            if (i < n && j < q) D[i * ldd + j] = sqrtf(acc[a][b]);
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Pruning (Sec. III, "Speeding-up WMD using RWMD").  D is the n x q tile of RWMD bounds, R0 the k nearest by RWMD.
+// ---------------------------------------------------------------------------------------------------------------
+// pair lists of the first k candidates of every query, and those entries of D masked so that they are not chosen again
+__global__ void k_first_pairs(const int32_t* __restrict__ R0, int64_t q, int k, int32_t j0, float* __restrict__ D,
+                              int64_t ldd, int32_t* __restrict__ pair_db, int32_t* __restrict__ pair_q)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= q * k) return;
+    const int64_t j = e / k;
+    const int32_t i = R0[e];
+    pair_db[e] = i;
+    pair_q[e] = j0 + (int32_t)j;
+    D[(int64_t)i * ldd + j] = FLT_MAX;
+}
+
+// cut[j] = (largest WMD among the first k) * (1 + slack)
+__global__ void k_cutoff(const float* __restrict__ wmd0, int64_t q, int k, float slack, float* __restrict__ cut)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= q) return;
+    float L = 0.f;
+    for (int r = 0; r < k; ++r) L = fmaxf(L, wmd0[j * k + r]);
+    cut[j] = L * (1.f + slack);
+}
+
+constexpr int kRowsPerBlock = 256;
+
+// cnt[j] += rows of this block with D[i][j] < cut[j]      (thread = query column, so reads of D are contiguous)
+__global__ __launch_bounds__(256) void k_count_below(const float* __restrict__ D, int64_t n, int64_t q, int64_t ldd,
+                                                     const float* __restrict__ cut, int32_t* __restrict__ cnt)
+{
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= q) return;
+    const int64_t i0 = (int64_t)blockIdx.y * kRowsPerBlock;
+    const int64_t i1 = i0 + kRowsPerBlock < n ? i0 + kRowsPerBlock : n;
+    const float L = cut[j];
+    int32_t c = 0;
+    for (int64_t i = i0; i < i1; ++i) c += D[i * ldd + j] < L ? 1 : 0;
+    if (c) atomicAdd(&cnt[j], c);
+}
+
+// exclusive prefix sums of cnt[0..q) into off[0..q]; one workgroup
+__global__ __launch_bounds__(1024) void k_scan_counts(const int32_t* __restrict__ cnt, int64_t q, int64_t* __restrict__ off)
+{
+    __shared__ int64_t part[1024];
+    const int tid = threadIdx.x;
+    const int64_t per = (q + 1023) / 1024;
+    const int64_t a = tid * per, b = a + per < q ? a + per : q;
+    int64_t sum = 0;
+    for (int64_t j = a; j < b; ++j) sum += cnt[j];
+    part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int64_t run = 0;
+        for (int k = 0; k < 1024; ++k) { const int64_t x = part[k]; part[k] = run; run += x; }
+        off[q] = run;
+    }
+    __syncthreads();
+    int64_t run = part[tid];
+    for (int64_t j = a; j < b; ++j) { off[j] = run; run += cnt[j]; }
+}
+
+// cursor[j] = start of query j's list relative to the first query of the range
+__global__ void k_init_cursor(const int64_t* __restrict__ off, int64_t ja, int64_t jb, int64_t* __restrict__ cursor)
+{
+    const int64_t j = ja + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < jb) cursor[j] = off[j] - off[ja];
+}
+
+// second sweep with the same geometry over the query columns [ja, jb): every thread reserves room for its rows in
+// its query's list and fills it
+__global__ __launch_bounds__(256) void k_fill_below(const float* __restrict__ D, int64_t n, int64_t ja, int64_t jb,
+                                                    int64_t ldd, const float* __restrict__ cut, int64_t* __restrict__ cursor,
+                                                    int32_t j0, int32_t* __restrict__ pair_db, int32_t* __restrict__ pair_q)
+{
+    const int64_t j = ja + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= jb) return;
+    const int64_t i0 = (int64_t)blockIdx.y * kRowsPerBlock;
+    const int64_t i1 = i0 + kRowsPerBlock < n ? i0 + kRowsPerBlock : n;
+    const float L = cut[j];
+    int32_t c = 0;
+    for (int64_t i = i0; i < i1; ++i) c += D[i * ldd + j] < L ? 1 : 0;
+    if (!c) return;
+    int64_t at = (int64_t)atomicAdd(reinterpret_cast<unsigned long long*>(&cursor[j]), (unsigned long long)c);
+    for (int64_t i = i0; i < i1; ++i)
+        if (D[i * ldd + j] < L) { pair_db[at] = (int32_t)i; pair_q[at] = j0 + (int32_t)j; ++at; }
+}
+
+__global__ void k_check_pairs(const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q, int64_t npairs,
+                              int64_t n, int64_t q, int32_t* __restrict__ status)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= npairs) return;
+    const int32_t i = pair_db[t], j = pair_q[t];
+    if (i < 0 || i >= n || j < 0 || j >= q) status[0] = 1;
+}
+
+// The k smallest of every query's evaluated WMDs, ordered by (distance, database row): the first k candidates
+// (idx0 / d0, k per query) and the query's list [off[j], off[j + 1]) of the rest.  One workgroup per query.
+__global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict__ idx0, const float* __restrict__ d0, int k,
+                                                      const int64_t* __restrict__ off, int64_t ja, const int32_t* __restrict__ idx1,
+                                                      const float* __restrict__ d1, int32_t* __restrict__ R_idx,
+                                                      float* __restrict__ R_dist)
+{
+    __shared__ float sd[256];
+    __shared__ int32_t si[256];
+    const int tid = threadIdx.x;
+    const int64_t j = ja + blockIdx.x;
+    const int64_t a = off[j] - off[ja], cnt = off[j + 1] - off[j];      // idx1 / d1 start at the range's first query
+    float last_d = -1.f;                 // distances are >= 0, so (-1, -1) precedes every item
+    int32_t last_i = -1;
+    for (int r = 0; r < k; ++r) {
+        float bd = FLT_MAX;
+        int32_t bi = INT_MAX;
+        for (int64_t e = tid; e < k + cnt; e += 256) {
+            const float d = e < k ? d0[j * k + e] : d1[a + e - k];
+            const int32_t i = e < k ? idx0[j * k + e] : idx1[a + e - k];
+            const bool after = d > last_d || (d == last_d && i > last_i);
+            if (after && (d < bd || (d == bd && i < bi))) { bd = d; bi = i; }
+        }
+        sd[tid] = bd;
+        si[tid] = bi;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) {
+                const float od = sd[tid + o];
+                const int32_t oi = si[tid + o];
+                if (od < sd[tid] || (od == sd[tid] && oi < si[tid])) { sd[tid] = od; si[tid] = oi; }
+            }
+            __syncthreads();
+        }
+        last_d = sd[0];
+        last_i = si[0];
+        __syncthreads();
+        if (tid == 0) { R_idx[j * k + r] = last_i; R_dist[j * k + r] = last_d; }
+    }
+}
+
+}  // namespace
+
+// -------------------------------------------------------------------------------------------------------------- host
+static size_t emd_slab_elems(int64_t h1max, int64_t h2max) { return (size_t)h1max * (size_t)h2max; }
+
+size_t emd_pair_bytes(int64_t h1max, int64_t h2max) { return emd_slab_elems(h1max, h2max) * 12; }   // fp32 costs, fp64 flows
+
+static size_t emd_lds_bytes(int64_t h1max, int64_t h2max) { return (size_t)(h1max + h2max) * 32; }
+
+bool emd_supported(int64_t h1max, int64_t h2max) { return emd_lds_bytes(h1max, h2max) <= 159 * 1024; }
+
+// Slab layout for `count` problems in flight: count flow matrices (fp64), then count cost matrices (fp32).
+static float* cost_slabs(void* slabs, int64_t count, size_t elems)
+{
+    return reinterpret_cast<float*>(reinterpret_cast<double*>(slabs) + (size_t)count * elems);
+}
+
+hipError_t launch_pair_costs(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
+                             const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    const size_t elems = emd_slab_elems(h1max, h2max);
+    k_pair_costs<<<dim3((unsigned)count), 256, 0, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx,
+                                                      Q.row_ptr, Q.col_idx, pair_db, pair_q, cost_slabs(slabs, count, elems),
+                                                      (int64_t)elems);
+    return hipGetLastError();
+}
+
+hipError_t launch_emd(const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db, const int32_t* pair_q,
+                      int64_t count, int64_t h1max, int64_t h2max, void* slabs, float* out, int32_t* flags,
+                      int32_t* fail_count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    const size_t elems = emd_slab_elems(h1max, h2max);
+    const size_t lds = emd_lds_bytes(h1max, h2max);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_emd), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    k_emd<<<dim3((unsigned)count), 64, lds, s>>>(DB.row_ptr, DB.val, Q.row_ptr, Q.val, pair_db, pair_q,
+                                                 cost_slabs(slabs, count, elems), (int64_t)elems,
+                                                 reinterpret_cast<double*>(slabs), (int32_t)h1max, (int32_t)h2max, out, flags,
+                                                 fail_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_check_pairs(const int32_t* pair_db, const int32_t* pair_q, int64_t npairs, int64_t n, int64_t q,
+                              int32_t* status, hipStream_t s)
+{
+    if (npairs <= 0) return hipSuccess;
+    k_check_pairs<<<dim3((unsigned)((npairs + 255) / 256)), 256, 0, s>>>(pair_db, pair_q, npairs, n, q, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_centroids(const lcrwmd_emb& E, const lcrwmd_csr& X, float* C, int64_t ldc, hipStream_t s)
+{
+    if (X.rows <= 0) return hipSuccess;
+    k_centroids<<<dim3((unsigned)X.rows), 256, 0, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, X.row_ptr, X.col_idx,
+                                                      X.val, C, ldc);
+    return hipGetLastError();
+}
+
+hipError_t launch_centroid_dist(const float* C1, int64_t n, const float* C2, int64_t q, int64_t ldc, int32_t m, float* D,
+                                int64_t ldd, hipStream_t s)
+{
+    if (n <= 0 || q <= 0) return hipSuccess;
+    const int64_t rows_per_launch = (int64_t)65535 * 64;          // grid.y carries the database rows
+    for (int64_t r0 = 0; r0 < n; r0 += rows_per_launch) {
+        const int64_t rows = n - r0 < rows_per_launch ? n - r0 : rows_per_launch;
+        dim3 grid((unsigned)((q + 63) / 64), (unsigned)((rows + 63) / 64));
+        k_centroid_dist<<<grid, 256, 0, s>>>(C1 + r0 * ldc, rows, C2, q, ldc, m, D + r0 * ldd, ldd);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int k, int32_t j0, float* D, int64_t ldd, int32_t* pair_db,
+                              int32_t* pair_q, hipStream_t s)
+{
+    const int64_t total = q * k;
+    if (total <= 0) return hipSuccess;
+    k_first_pairs<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>(R0, q, k, j0, D, ldd, pair_db, pair_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_cutoff(const float* wmd0, int64_t q, int k, float slack, float* cut, hipStream_t s)
+{
+    if (q <= 0) return hipSuccess;
+    k_cutoff<<<dim3((unsigned)((q + 255) / 256)), 256, 0, s>>>(wmd0, q, k, slack, cut);
+    return hipGetLastError();
+}
+
+// Survivors per query and their prefix sums off[0..q].  n <= 65535 * 256 rows (the caller checks).
+hipError_t launch_count_below(const float* D, int64_t n, int64_t q, int64_t ldd, const float* cut, int32_t* cnt,
+                              int64_t* off, hipStream_t s)
+{
+    if (n <= 0 || q <= 0) return hipSuccess;
+    hipError_t e = launch_fill_i32(cnt, q, 0, s);
+    if (e != hipSuccess) return e;
+    const int64_t row_blocks = (n + kRowsPerBlock - 1) / kRowsPerBlock;
+    k_count_below<<<dim3((unsigned)((q + 255) / 256), (unsigned)row_blocks), 256, 0, s>>>(D, n, q, ldd, cut, cnt);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k_scan_counts<<<1, 1024, 0, s>>>(cnt, q, off);
+    return hipGetLastError();
+}
+
+// Lists of the survivors of queries [ja, jb), query after query, starting at pair_db[0] / pair_q[0].
+hipError_t launch_fill_below(const float* D, int64_t n, int64_t ja, int64_t jb, int64_t ldd, const float* cut,
+                             const int64_t* off, int64_t* cursor, int32_t j0, int32_t* pair_db, int32_t* pair_q,
+                             hipStream_t s)
+{
+    if (n <= 0 || jb <= ja) return hipSuccess;
+    k_init_cursor<<<dim3((unsigned)((jb - ja + 255) / 256)), 256, 0, s>>>(off, ja, jb, cursor);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t row_blocks = (n + kRowsPerBlock - 1) / kRowsPerBlock;
+    k_fill_below<<<dim3((unsigned)((jb - ja + 255) / 256), (unsigned)row_blocks), 256, 0, s>>>(D, n, ja, jb, ldd, cut, cursor,
+                                                                                            j0, pair_db, pair_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k, const int64_t* off, int64_t ja, int64_t jb,
+                               const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist, hipStream_t s)
+{
+    if (jb <= ja) return hipSuccess;
+    k_select_lists<<<dim3((unsigned)(jb - ja)), 256, 0, s>>>(idx0, d0, k, off, ja, idx1, d1, R_idx, R_dist);
+    return hipGetLastError();
+}
+
+}  // namespace lcrwmd

@@ -1,0 +1,245 @@
+"""GPU parity of the exact WMD, the WCD and the pruned top-k against the CPU oracle (LP solver in fp64), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1711_07227_amd import binding, synth
+from helpers import RTOL_F32, assert_close, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def ctx():
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+def longest(csr):
+    return int(np.max(np.diff(csr[0])))
+
+
+def run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=None, flags=False):
+    t = len(pi)
+    ws = binding.alloc_workspace(ctx.wmd_pairs_workspace_bytes(hmax[0], hmax[1], in_flight or max(t, 1)))
+    out = torch.full((max(t, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    fl = torch.full((max(t, 1),), -1, dtype=torch.int32, device="cuda") if flags else None
+    ctx.wmd_pairs(qs, db, E, torch.from_numpy(np.asarray(pi, np.int32)).cuda(), torch.from_numpy(np.asarray(pj, np.int32)).cuda(),
+                  out, ws, fl)
+    torch.cuda.synchronize()
+    if flags:
+        return out.cpu().numpy()[:t], fl.cpu().numpy()[:t]
+    return out.cpu().numpy()[:t]
+
+
+def problem(v, m, n, q, h_lo, h_hi, seed, s=1.1):
+    return {"E": synth.embeddings(v, m, seed), "db": synth.corpus(n, v, h_lo, h_hi, s, seed + 1),
+            "queries": synth.corpus(q, v, h_lo, h_hi, s, seed + 2)}
+
+
+def test_wmd_pairs_small_documents_all_pairs(ctx):
+    p = problem(v=200, m=300, n=12, q=9, h_lo=1, h_hi=12, seed=3)
+    E, db, qs = upload(p)
+    pi, pj = np.divmod(np.arange(12 * 9), 9)
+    got, flags = run_wmd_pairs(ctx, E, db, qs, pi, pj, (longest(p["db"]), longest(p["queries"])), flags=True)
+    assert np.all(flags == 0)
+    assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="WMD of small documents")
+
+
+def test_wmd_pairs_tiny_configuration_sampled(ctx, tiny):
+    """Documents of 20-80 words over a Zipf vocabulary (shared words give zero-cost edges), several tiles a side."""
+    E, db, qs = upload(tiny)
+    rng = np.random.default_rng(5)
+    pi = np.concatenate([rng.integers(0, 1000, 60), [0, 999]])
+    pj = np.concatenate([rng.integers(0, 10, 60), [0, 9]])
+    hmax = (longest(tiny["db"]), longest(tiny["queries"]))
+    got, flags = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, flags=True)
+    assert np.all(flags == 0)
+    ref = oracle.wmd_pairs(tiny["E"], tiny["db"], tiny["queries"], pi, pj)
+    assert_close(got, ref, what="WMD, tiny configuration")
+    # same pairs a few at a time: results do not depend on how many problems share the workspace
+    again = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=7)
+    assert np.array_equal(again, got)
+    # bounds of Sec. III on the device results: RWMD <= WMD
+    rw = oracle.rwmd_pairs(tiny["E"], tiny["db"], tiny["queries"], pi, pj)
+    assert np.all(rw <= got * (1 + 1e-5))
+
+
+def test_wmd_identical_and_single_word_documents(ctx):
+    E = synth.embeddings(60, 300, 1)
+    docs = synth.corpus(20, 60, 1, 9, 1.0, 2)
+    Eg, db, qs = upload({"E": E, "db": docs, "queries": docs})
+    pi = np.arange(20)
+    got = run_wmd_pairs(ctx, Eg, db, qs, pi, pi, (longest(docs), longest(docs)))
+    assert np.all(got == 0.0)                                              # a histogram against itself
+    one = (np.array([0, 1], np.int64), np.array([7], np.int32), np.array([1.0], np.float32))
+    Eg, db, qs = upload({"E": E, "db": docs, "queries": one})
+    got = run_wmd_pairs(ctx, Eg, db, qs, pi, np.zeros(20, np.int64), (longest(docs), 1))
+    ptr, col, val = docs
+    ref = np.array([np.sum(val[ptr[i]:ptr[i + 1]].astype(np.float64) / val[ptr[i]:ptr[i + 1]].astype(np.float64).sum()
+                           * np.linalg.norm(E[col[ptr[i]:ptr[i + 1]]].astype(np.float64) - E[7].astype(np.float64), axis=1))
+                    for i in range(20)])
+    assert_close(got, ref, what="one-word query: every flow is forced")
+
+
+def test_wmd_on_a_line_and_other_embedding_widths(ctx):
+    """m = 1: the closed form is the area between the cumulative distributions; m = 50 and bf16 storage against the LP."""
+    rng = np.random.default_rng(4)
+    v = 40
+    E1 = rng.uniform(-3, 3, (v, 1)).astype(np.float32)
+    docs = synth.corpus(8, v, 2, 9, 1.0, 6)
+    Eg, db, qs = upload({"E": E1, "db": docs, "queries": docs})
+    pi, pj = np.divmod(np.arange(64), 8)
+    got = run_wmd_pairs(ctx, Eg, db, qs, pi, pj, (longest(docs), longest(docs)))
+    ptr, col, val = docs
+    ref = []
+    for i, j in zip(pi, pj):
+        xa, fa = E1[col[ptr[i]:ptr[i + 1]], 0].astype(np.float64), val[ptr[i]:ptr[i + 1]].astype(np.float64)
+        xb, fb = E1[col[ptr[j]:ptr[j + 1]], 0].astype(np.float64), val[ptr[j]:ptr[j + 1]].astype(np.float64)
+        pts = np.unique(np.concatenate([xa, xb]))
+        Fa = np.array([fa[xa <= t].sum() / fa.sum() for t in pts])
+        Fb = np.array([fb[xb <= t].sum() / fb.sum() for t in pts])
+        ref.append(np.sum(np.abs(Fa - Fb)[:-1] * np.diff(pts)))
+    assert_close(got, np.array(ref), what="WMD on a line")
+    p = problem(v=300, m=50, n=6, q=5, h_lo=3, h_hi=40, seed=9)
+    E, db, qs = upload(p)
+    pi, pj = np.divmod(np.arange(30), 5)
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    assert_close(run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax), oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="m = 50")
+    Er = synth.bf16_bits_to_f32(synth.to_bf16_bits(p["E"]))
+    E, db, qs = upload({"E": Er, "db": p["db"], "queries": p["queries"]}, dtype=torch.bfloat16)
+    assert_close(run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax), oracle.wmd_pairs(Er, p["db"], p["queries"], pi, pj), what="bf16 storage")
+
+
+def test_wmd_pairs_medium_sized_documents(ctx):
+    """Documents of the Medium configuration's lengths (50-150 words): the sizes the benchmark solves."""
+    p = synth.make(synth.CONFIGS["medium"], n=40, q=4, v=20000)
+    E, db, qs = upload(p)
+    pi, pj = np.divmod(np.arange(24), 4)
+    got, flags = run_wmd_pairs(ctx, E, db, qs, pi, pj, (longest(p["db"]), longest(p["queries"])), flags=True)
+    assert np.all(flags == 0)
+    assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="WMD of 50-150 word documents")
+
+
+def test_wmd_argument_checks(ctx, tiny):
+    E, db, qs = upload(tiny)
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    pi = torch.tensor([0, 1, 2, 1000], dtype=torch.int32, device="cuda")       # 1000 is one past the last row
+    pj = torch.tensor([0, 1, 2, 3], dtype=torch.int32, device="cuda")
+    ws = binding.alloc_workspace(ctx.wmd_pairs_workspace_bytes(70, 70, 4))
+    ctx.set_options(validate=1)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_pairs(qs, db, E, pi, pj, out, ws)
+    assert e.value.status == binding.EINVAL
+    ctx.set_options(validate=0)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_pairs(qs, db, E, pi[:3], pj[:3], out, binding.alloc_workspace(4096))
+    assert e.value.status == binding.EWORKSPACE
+    ctx.set_options(compute=binding.BF16)
+    R_idx = torch.zeros((10, 4), dtype=torch.int32, device="cuda")
+    R_dist = torch.zeros((10, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_topk(qs, db, E, 4, R_idx, R_dist, binding.alloc_workspace(1 << 20))
+    assert e.value.status == binding.EUNSUPPORTED
+
+
+def test_wcd_against_oracle(ctx, tiny):
+    E, db, qs = upload(tiny)
+    ws = binding.alloc_workspace((db.rows + qs.rows) * 300 * 4 + 1024)
+    D = torch.full((db.rows, qs.rows), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wcd(qs, db, E, D, ws)
+    torch.cuda.synchronize()
+    assert_close(D.cpu().numpy(), oracle.wcd(tiny["E"], tiny["db"], tiny["queries"]), what="WCD, tiny configuration")
+    # ragged sizes that are not multiples of the 64 x 64 tile, another width, a set against itself
+    p = problem(v=500, m=37, n=131, q=67, h_lo=1, h_hi=20, seed=12)
+    E, db, qs = upload(p)
+    D = torch.full((131, 67), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wcd(qs, db, E, D, binding.alloc_workspace((131 + 67) * 40 * 4 + 1024))
+    torch.cuda.synchronize()
+    assert_close(D.cpu().numpy(), oracle.wcd(p["E"], p["db"], p["queries"]), what="WCD, m = 37")
+    S = torch.full((131, 131), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wcd(db, db, E, S, binding.alloc_workspace(2 * 131 * 40 * 4 + 1024))
+    torch.cuda.synchronize()
+    assert np.all(np.diag(S.cpu().numpy()) == 0.0)
+
+
+def check_topk(gi, gd, W):
+    """gi/gd: device result (q x k); W: n x q exact WMD from the oracle."""
+    n, q = W.shape
+    k = gi.shape[1]
+    for j in range(q):
+        order = np.lexsort((np.arange(n), W[:, j]))
+        assert_close(gd[j], W[order[:k], j], what=f"top-k WMD distances of query {j}")
+        assert_close(W[gi[j], j], gd[j], what="reported rows carry the reported distances")
+        assert len(set(gi[j].tolist())) == k
+        gaps = np.diff(W[order[:k + 1], j])
+        if np.min(gaps) > 1e-4 * W[order[k], j]:
+            assert np.array_equal(gi[j], order[:k])
+
+
+def test_wmd_topk_pruned_equals_exhaustive(ctx):
+    """Small enough for the oracle to evaluate every pair: the pruned search must return the true k nearest."""
+    p = problem(v=400, m=300, n=150, q=6, h_lo=2, h_hi=14, seed=17, s=1.0)
+    E, db, qs = upload(p)
+    n, q, k = 150, 6, 5
+    pi, pj = np.divmod(np.arange(n * q), q)
+    W = oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj).reshape(n, q)
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(400, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ev = torch.zeros(q, dtype=torch.int64)
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
+    torch.cuda.synchronize()
+    check_topk(R_idx.cpu().numpy(), R_dist.cpu().numpy(), W)
+    # evaluations: at least what the cut-off rule of Sec. III needs, at most what its slack of 1e-5 can add
+    R = oracle.rwmd_bruteforce(p["E"], p["db"], p["queries"])
+    _, _, need = oracle.wmd_topk_pruned(p["E"], p["db"], p["queries"], k, R)
+    ev = ev.numpy()
+    for j in range(q):
+        first = np.lexsort((np.arange(n), R[:, j]))[:k]
+        L = W[first, j].max()
+        most = len(set(np.nonzero(R[:, j] < L * (1 + 3e-5))[0]) | set(first))
+        assert need[j] - 1 <= ev[j] <= most + 1, (j, need[j], ev[j], most)
+    assert ev.sum() < n * q
+    # every query in a batch of its own, and a small workspace: same result
+    ctx.set_options(max_query_batch=1)
+    R2 = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    D2 = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wmd_topk(qs, db, E, k, R2, D2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(R2, R_idx) and torch.equal(D2, R_dist)
+
+
+def test_wmd_topk_tiny_configuration(ctx, tiny):
+    """Tiny configuration (300 of its 1,000 documents x 10 queries, 20-80 words): the oracle follows the same pruning procedure."""
+    sub = synth.csr_rows(*tiny["db"], np.arange(300))
+    prob = {"E": tiny["E"], "db": sub, "queries": tiny["queries"]}
+    E, db, qs = upload(prob)
+    n, q, k = 300, 10, 4
+    hmax = (longest(sub), longest(tiny["queries"]))
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(E.shape[0], 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ev = torch.zeros(q, dtype=torch.int64)
+    print("wmd_topk on the device", flush=True)
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
+    torch.cuda.synchronize()
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    print("evaluations per query:", ev.numpy().tolist(), flush=True)
+    # the oracle evaluates the first three queries with the same procedure (its LP solves take ~30 ms each)
+    R = oracle.rwmd_table(prob["E"], sub, tiny["queries"])
+    three = synth.csr_rows(*tiny["queries"], np.arange(3))
+    oi, od, need = oracle.wmd_topk_pruned(prob["E"], sub, three, k, R[:, :3])
+    for j in range(3):
+        assert_close(gd[j], od[j], what=f"pruned top-k distances of query {j}")
+        if np.min(np.diff(od[j])) > 1e-4 * od[j][-1]:
+            assert np.array_equal(gi[j], oi[j])
+        assert ev[j] >= need[j] - 1
+    # for the other queries: the reported rows carry the reported distances
+    for j in range(3, q):
+        ref = oracle.wmd_pairs(prob["E"], sub, tiny["queries"], gi[j], np.full(k, j))
+        assert_close(gd[j], ref, what="reported distances are WMDs of the reported rows")
+        assert np.all(np.diff(gd[j]) >= 0)
