@@ -211,8 +211,8 @@ typedef struct {
        words * m flops); the two table passes are timed here, bytes = table rows streamed + outputs. */
     double table_fwd_ms;  int64_t table_fwd_launches;  double table_fwd_bytes;
     double table_rev_ms;  int64_t table_rev_launches;  double table_rev_bytes;
-    /* lcrwmd_wmd_pairs / lcrwmd_wmd_topk: the transport solver and the kernel that writes its cost matrices */
-    double emd_ms;  int64_t emd_launches;  double emd_pairs;  double emd_cost_ms;
+    /* lcrwmd_wmd_pairs / lcrwmd_wmd_topk: the transport solver (it also forms its cost matrices) */
+    double emd_ms;  int64_t emd_launches;  double emd_pairs;
 } lcrwmd_profile;
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
@@ -236,6 +236,8 @@ lcrwmd_status lcrwmd_wcd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwm
  * Workspace of lcrwmd_wmd_pairs for `pairs_in_flight` transport problems at a time, and the part of
  * lcrwmd_wmd_topk's workspace that holds them: per problem max_h_db * max_h_q * 12 bytes (fp32 costs,
  * fp64 flows), where max_h_* are the largest stored-entry counts of a database / query histogram.
+ * pairs_in_flight <= 0 asks for as many as the device keeps resident at once (one wavefront each);
+ * more than that is never used.
  */
 lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db, int64_t max_h_q,
                                                int64_t pairs_in_flight, size_t* out_bytes);
@@ -253,7 +255,7 @@ lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db
  * successive shortest paths; flags[t] = 1 where it ran out of its augmentation budget
  * (8 (h1 + h2) + 64 paths), in which case out[t] is the cost of a partial flow - none has been
  * seen to; the call then also returns LCRWMD_ENOCONVERGE when flags is NULL.
- * The problems are processed as many at a time as the workspace holds (at least one must fit).
+ * As many wavefronts as the workspace has room for (at least one) take the problems off a queue.
  * Synchronises the stream when it has to fetch row pointers, when validating, and (flags NULL) at
  * the end to read the failure count.  Histograms of more than about 5,000 words in total per pair
  * are LCRWMD_EUNSUPPORTED (per-word solver state is kept in LDS).

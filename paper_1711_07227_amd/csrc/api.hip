@@ -509,7 +509,6 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
         else if (r.kind == 3) { out->table_fwd_ms += ms; out->table_fwd_launches += 1; out->table_fwd_bytes += r.work; }
         else if (r.kind == 4) { out->table_rev_ms += ms; out->table_rev_launches += 1; out->table_rev_bytes += r.work; }
         else if (r.kind == 5) { out->emd_ms += ms; out->emd_launches += 1; out->emd_pairs += r.work; }
-        else if (r.kind == 6) { out->emd_cost_ms += ms; }
         else { out->phase2_ms += ms; out->phase2_launches += 1; out->phase2_bytes += r.work; out->phase2_gather_bytes += r.work2; }
     }
     ctx->prof.clear();
@@ -744,7 +743,8 @@ lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db
 {
     if (!ctx) return LCRWMD_EINVAL;
     if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
-    if (max_h_db <= 0 || max_h_q <= 0 || pairs_in_flight <= 0) return fail(ctx, LCRWMD_EINVAL, "sizes must be positive");
+    if (max_h_db <= 0 || max_h_q <= 0) return fail(ctx, LCRWMD_EINVAL, "sizes must be positive");
+    if (pairs_in_flight <= 0) pairs_in_flight = emd_preferred_slots(ctx->num_cu, max_h_db, max_h_q);
     *out_bytes = emd_pair_bytes(max_h_db, max_h_q) * (size_t)pairs_in_flight + 1024;
     return LCRWMD_OK;
 }
@@ -761,27 +761,21 @@ int64_t longest_row(const int64_t* rp, int64_t rows)
     return mx;
 }
 
-constexpr int64_t kEmdChunk = 65536;      // transport problems per launch at most
-
-// WMD of `count` listed pairs into out, as many at a time as `slabs` holds.
+// WMD of `count` listed pairs into out; the wavefronts that solve them share `slabs`.  counters: [0] failures
+// (accumulated), [2] the work queue's position.
 lcrwmd_status run_wmd_list(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_csr* DB, const lcrwmd_emb* E,
                            const int32_t* pair_db, const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max,
-                           void* slabs, size_t slab_bytes, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s)
+                           void* slabs, size_t slab_bytes, float* out, int32_t* flags, int32_t* counters, hipStream_t s)
 {
-    int64_t cap = (int64_t)(slab_bytes / emd_pair_bytes(h1max, h2max));
-    if (cap > kEmdChunk) cap = kEmdChunk;
-    if (cap < 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem (%zu bytes)",
-                             emd_pair_bytes(h1max, h2max));
-    for (int64_t t0 = 0; t0 < count; t0 += cap) {
-        const int64_t c = count - t0 < cap ? count - t0 : cap;
-        {
-            ProfScope ps(ctx, s, 6, (double)c);
-            HIP_TRY(launch_pair_costs(*E, *DB, *Q, pair_db + t0, pair_q + t0, c, h1max, h2max, slabs, s));
-        }
-        ProfScope ps(ctx, s, 5, (double)c);
-        HIP_TRY(launch_emd(*DB, *Q, pair_db + t0, pair_q + t0, c, h1max, h2max, slabs, out + t0, flags ? flags + t0 : nullptr,
-                           fail_count, s));
-    }
+    if (count <= 0) return LCRWMD_OK;
+    if (count > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "more than 2^31 pairs in one list");
+    int64_t slots = (int64_t)(slab_bytes / emd_pair_bytes(h1max, h2max));
+    const int64_t pref = emd_preferred_slots(ctx->num_cu, h1max, h2max);
+    if (slots > pref) slots = pref;
+    if (slots < 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem (%zu bytes)",
+                               emd_pair_bytes(h1max, h2max));
+    ProfScope ps(ctx, s, 5, (double)count);
+    HIP_TRY(launch_emd(*E, *DB, *Q, pair_db, pair_q, count, h1max, h2max, slabs, slots, counters + 2, out, flags, counters, s));
     return LCRWMD_OK;
 }
 
@@ -811,7 +805,7 @@ lcrwmd_status lcrwmd_wmd_pairs(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     Bump b(ws, ws_bytes);
     int32_t* counters = b.take_n<int32_t>(64);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
-    HIP_TRY(launch_fill_i32(counters, 2, 0, s));
+    HIP_TRY(launch_fill_i32(counters, 4, 0, s));
     if (ctx->opt.validate) {
         HIP_TRY(launch_check_pairs(pair_db, pair_q, npairs, database->rows, queries->rows, counters + 1, s));
         int32_t bad = 0;
@@ -842,9 +836,9 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
     ST_TRY(lcrwmd_workspace_bytes(ctx, v, m, n, nnz_db, q, nnz_q, emb_dtype, k, &base));
     int64_t qb = q < 2048 ? q : 2048;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
-    // per-query arrays, lists for a quarter of all pairs of a batch, 8,192 transport problems in flight
+    // per-query arrays, lists for a quarter of all pairs of a batch, one transport problem per resident wavefront
     const size_t lists = (size_t)qb * (size_t)k * 24 + (size_t)qb * 32 + (size_t)n * (size_t)qb / 4 * 12;
-    const size_t slabs = emd_pair_bytes(max_h_db, max_h_q) * 8192;
+    const size_t slabs = emd_pair_bytes(max_h_db, max_h_q) * (size_t)emd_preferred_slots(ctx->num_cu, max_h_db, max_h_q);
     *out_bytes = base + lists + slabs + 16384;
     return LCRWMD_OK;
 }
@@ -923,7 +917,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, rest, rest_bytes, s));
         HIP_TRY(launch_topk(tile, n, nq, ldt, k, R0, R0d, tk, tkb, s));
         // WMD to those; their largest value is the cut-off
-        HIP_TRY(launch_fill_i32(counters, 1, 0, s));
+        HIP_TRY(launch_fill_i32(counters, 4, 0, s));
         HIP_TRY(launch_first_pairs(R0, nq, k, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
         ST_TRY(run_wmd_list(ctx, queries, database, E, p0_db, p0_q, nq * k, h1max, h2max, rest, rest_bytes, wmd0, nullptr,
                             counters, s));
@@ -935,7 +929,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         if (evaluated)
             for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k + hoff[j + 1] - hoff[j];
         // Lists hold 12 bytes per survivor; they share `rest` with the transport problems in flight.
-        size_t slab_part = pair_bytes * 8192;
+        size_t slab_part = pair_bytes * (size_t)emd_preferred_slots(ctx->num_cu, h1max, h2max);
         if (slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
         if (slab_part < pair_bytes) slab_part = pair_bytes;
         slab_part = slab_part / 256 * 256;

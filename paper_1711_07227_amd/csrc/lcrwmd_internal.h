@@ -12,7 +12,7 @@
 
 struct lcrwmd_prof_rec {
     hipEvent_t start, stop;
-    int kind;              // 1: first-phase kernel, 2: second-phase kernel, 3/4: table passes, 5: transport solver, 6: its costs
+    int kind;              // 1: first-phase kernel, 2: second-phase kernel, 3/4: table passes, 5: transport solver
     double work, work2;
 };
 
@@ -160,11 +160,10 @@ hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k,
 // wmd.hip: transport problems (one wavefront each), centroid distances, pruning lists
 size_t emd_pair_bytes(int64_t h1max, int64_t h2max);
 bool emd_supported(int64_t h1max, int64_t h2max);
-hipError_t launch_pair_costs(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
-                             const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, hipStream_t s);
-hipError_t launch_emd(const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db, const int32_t* pair_q,
-                      int64_t count, int64_t h1max, int64_t h2max, void* slabs, float* out, int32_t* flags,
-                      int32_t* fail_count, hipStream_t s);
+int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max);
+hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
+                      const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, int64_t slots,
+                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s);
 hipError_t launch_check_pairs(const int32_t* pair_db, const int32_t* pair_q, int64_t npairs, int64_t n, int64_t q,
                               int32_t* status, hipStream_t s);
 hipError_t launch_centroids(const lcrwmd_emb& E, const lcrwmd_csr& X, float* C, int64_t ldc, hipStream_t s);

@@ -32,6 +32,11 @@ __device__ inline void wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// A value that is the same in every lane, moved to a scalar register.  The solver's control flow depends only on
+// such values; saying so keeps its branches scalar, so that every cross-lane operation runs with all lanes active
+// (left to itself the compiler treats them as divergent and may route lanes through a loop header separately).
+__device__ inline int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
 __device__ inline double wave_sum(double x)
 {
 #pragma unroll
@@ -40,60 +45,61 @@ __device__ inline double wave_sum(double x)
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// C = T1 o T2 for every pair of a chunk (Sec. III): c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||,
+// C = T1 o T2 of one pair (Sec. III), by one wavefront: c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||
 // as the square root of the sum of squared differences (no norm expansion: equal words give exactly 0).
-// One workgroup per pair, 32 x 32 output tiles, the embedding dimension staged through LDS 32 values at a time.
+// 32 x 32 output tiles, 4 x 4 outputs per lane, the embedding dimension staged through LDS 32 values at a time.
+// `tiles` is kCostLds bytes of this wavefront's LDS.
 // ---------------------------------------------------------------------------------------------------------------
 constexpr int kCT = 32;
+constexpr int kCostLds = (2 * kCT * (kCT + 1) + 2 * kCT) * 4;
 
-__global__ __launch_bounds__(256) void k_pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
-                                                    const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
-                                                    const int64_t* __restrict__ q_rp, const int32_t* __restrict__ q_col,
-                                                    const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q,
-                                                    float* __restrict__ slabs_c, int64_t slab_elems)
+__device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m, const int32_t* __restrict__ wa_g,
+                           int h1, const int32_t* __restrict__ wb_g, int h2, float* c, float* tiles, int lane)
 {
-    __shared__ float A[kCT][kCT + 1], B[kCT][kCT + 1];
-    __shared__ int32_t wa[kCT], wb[kCT];
-    const int tid = threadIdx.x;
-    const int64_t t = blockIdx.x;
-    const int32_t i = pair_db[t], j = pair_q[t];
-    const int64_t a0 = db_rp[i], b0 = q_rp[j];
-    const int h1 = (int)(db_rp[i + 1] - a0), h2 = (int)(q_rp[j + 1] - b0);
-    float* c = slabs_c + t * slab_elems;
-    const int tx = tid & 15, ty = tid >> 4;       // 16 x 16 threads, 2 x 2 outputs each
-    const int lr = tid >> 5, lc = tid & 31;       // loader: rows lr + 8 e, column lc
+    float (*A)[kCT + 1] = reinterpret_cast<float (*)[kCT + 1]>(tiles);
+    float (*B)[kCT + 1] = reinterpret_cast<float (*)[kCT + 1]>(tiles + kCT * (kCT + 1));
+    int32_t* wa = reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCT + 1));
+    int32_t* wb = wa + kCT;
+    const int tx = lane & 7, ty = lane >> 3;      // 8 x 8 lanes; rows ty + 8 a, columns tx + 8 b
+    const int lr = lane >> 5, lc = lane & 31;     // loader: rows lr + 2 e, column lc
     for (int p0 = 0; p0 < h1; p0 += kCT)
         for (int u0 = 0; u0 < h2; u0 += kCT) {
-            if (tid < kCT) wa[tid] = p0 + tid < h1 ? db_col[a0 + p0 + tid] : -1;
-            else if (tid < 2 * kCT) wb[tid - kCT] = u0 + tid - kCT < h2 ? q_col[b0 + u0 + tid - kCT] : -1;
-            float acc00 = 0.f, acc01 = 0.f, acc10 = 0.f, acc11 = 0.f;
+            if (lane < kCT) wa[lane] = p0 + lane < h1 ? wa_g[p0 + lane] : -1;
+            else wb[lane - kCT] = u0 + lane - kCT < h2 ? wb_g[u0 + lane - kCT] : -1;
+            float acc[4][4] = {};
             for (int k0 = 0; k0 < m; k0 += kCT) {
-                __syncthreads();                   // word ids written; the previous slice has been consumed
+                wave_sync();                       // word ids written; the previous slice has been consumed
                 const int kk = k0 + lc;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int r = lr + 8 * e;
+                for (int e = 0; e < 16; ++e) {
+                    const int r = lr + 2 * e;
                     const int32_t w1 = wa[r], w2 = wb[r];
                     A[r][lc] = (w1 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w1 * ld + kk) : 0.f;
                     B[r][lc] = (w2 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w2 * ld + kk) : 0.f;
                 }
-                __syncthreads();
-#pragma unroll 8
+                wave_sync();
+#pragma unroll 4
                 for (int k = 0; k < kCT; ++k) {
-                    const float x0 = A[ty][k], x1 = A[ty + 16][k], y0 = B[tx][k], y1 = B[tx + 16][k];
-                    float d;
-                    d = x0 - y0; acc00 = fmaf(d, d, acc00);
-                    d = x0 - y1; acc01 = fmaf(d, d, acc01);
-                    d = x1 - y0; acc10 = fmaf(d, d, acc10);
-                    d = x1 - y1; acc11 = fmaf(d, d, acc11);
+                    float x[4], y[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { x[e] = A[ty + 8 * e][k]; y[e] = B[tx + 8 * e][k]; }
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const float d = x[a] - y[b];
+                            acc[a][b] = fmaf(d, d, acc[a][b]);
+                        }
                 }
             }
-            const int p = p0 + ty, u = u0 + tx;
-            if (p < h1 && u < h2) c[(int64_t)p * h2 + u] = sqrtf(acc00);
-            if (p < h1 && u + 16 < h2) c[(int64_t)p * h2 + u + 16] = sqrtf(acc01);
-            if (p + 16 < h1 && u < h2) c[(int64_t)(p + 16) * h2 + u] = sqrtf(acc10);
-            if (p + 16 < h1 && u + 16 < h2) c[(int64_t)(p + 16) * h2 + u + 16] = sqrtf(acc11);
-            __syncthreads();                       // wa / wb are rewritten by the next tile
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int p = p0 + ty + 8 * a, u = u0 + tx + 8 * b;
+                    if (p < h1 && u < h2) c[(int64_t)p * h2 + u] = sqrtf(acc[a][b]);
+                }
+            wave_sync();                           // wa / wb are rewritten by the next tile
         }
 }
 
@@ -106,17 +112,24 @@ __global__ __launch_bounds__(256) void k_pair_costs(const void* __restrict__ E, 
 // finds the nearest sink with unmet demand: forward edges exist between every source and every sink, a backward
 // edge from sink u to source p exists where y[p,u] > 0 and has reduced cost zero, so a source enters the search at
 // the distance of the sink that reaches it.  Mass min(supply left, demand left, smallest flow on a backward edge
-// of the path) is moved, the potentials are shifted by the search distances, and the objective grows by mass x path
-// cost.  Lane l owns sinks and sources l, l + 64, ...; their per-node state sits in LDS, the flow matrix
-// (transposed: one row per sink) and the costs in the pair's slab in device memory.
+// of the path) is moved and the objective grows by mass x path cost.  If that filled the sink and emptied no
+// backward edge, the search goes on from where it stands (the sink now passes flow on like any full sink);
+// otherwise it ends, the potentials are shifted by the search distances, and the next search starts.
+// Lane l owns sinks and sources l, l + 64, ...; their per-node state sits in LDS, the flow matrix (transposed: one
+// row per sink) and the costs in the wavefront's slab in device memory.
 // Histogram weights are divided by their fp64 sums first, so both sides carry mass 1.
+//
+// The grid is a set of wavefronts that take pairs off a shared counter until it passes `count`: every wavefront
+// ends because every loop below is bounded by the pair's dimensions or by the augmentation budget.
 // flags[t]: 0 solved; 1 the augmentation budget ran out (the result is then the cost of a partial flow).
 // ---------------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_emd(const int64_t* __restrict__ db_rp, const float* __restrict__ db_val,
-                                            const int64_t* __restrict__ q_rp, const float* __restrict__ q_val,
+__global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+                                            const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
+                                            const float* __restrict__ db_val, const int64_t* __restrict__ q_rp,
+                                            const int32_t* __restrict__ q_col, const float* __restrict__ q_val,
                                             const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q,
-                                            const float* __restrict__ slabs_c, int64_t slab_elems, double* slabs_f,
-                                            int32_t h1max, int32_t h2max, float* __restrict__ out,
+                                            int64_t count, int32_t* next_pair, float* slabs_c, int64_t slab_elems,
+                                            double* slabs_f, int32_t h1max, int32_t h2max, float* __restrict__ out,
                                             int32_t* __restrict__ flags, int32_t* fail_count)
 {
     extern __shared__ double lds_d[];
@@ -132,136 +145,153 @@ __global__ __launch_bounds__(64) void k_emd(const int64_t* __restrict__ db_rp, c
     int32_t* used = way + h2max;
 
     const int lane = threadIdx.x;
-    const int64_t t = blockIdx.x;
-    const int32_t i = pair_db[t], j = pair_q[t];
-    const int64_t a0 = db_rp[i], b0 = q_rp[j];
-    const int h1 = (int)(db_rp[i + 1] - a0), h2 = (int)(q_rp[j + 1] - b0);
-    const float* c = slabs_c + t * slab_elems;
-    double* f = slabs_f + t * slab_elems;          // f[u * h1 + p] = y[p, u]
+    float* c = slabs_c + (int64_t)blockIdx.x * slab_elems;
+    double* f = slabs_f + (int64_t)blockIdx.x * slab_elems;          // f[u * h1 + p] = y[p, u]
 
-    double sa = 0.0, sb = 0.0;
-    for (int p = lane; p < h1; p += 64) sa += (double)db_val[a0 + p];
-    for (int u = lane; u < h2; u += 64) sb += (double)q_val[b0 + u];
-    sa = wave_sum(sa);
-    sb = wave_sum(sb);
-    for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
-    for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
-    for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
-    wave_sync();
+    for (;;) {
+        wave_sync();                                                 // the previous pair's state has been read
+        int32_t got = 0;
+        if (lane == 0) got = atomicAdd(next_pair, 1);
+        const int32_t t = uni(got);
+        if (t >= count) break;
+        const int32_t i = pair_db[t], j = pair_q[t];
+        const int64_t a0 = db_rp[i], b0 = q_rp[j];
+        const int h1 = uni((int)(db_rp[i + 1] - a0)), h2 = uni((int)(q_rp[j + 1] - b0));
 
-    const int budget = 8 * (h1 + h2) + 64;         // augmentations; each empties a source, a sink or a flow entry
-    int naug = 0;
-    bool exhausted = false;
-    double total = 0.0;
+        pair_costs(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
 
-    for (int s = 0; s < h1 && !exhausted; ++s) {
-        while (sup[s] > kMassEps) {
-            if (naug >= budget) { exhausted = true; break; }
-            // ---- search from s ----
-            for (int u = lane; u < h2; u += 64) { dT[u] = kFar; used[u] = 0; way[u] = -1; }
-            for (int p = lane; p < h1; p += 64) vis[p] = 0;
-            wave_sync();
-            if (lane == (s & 63)) { vis[s] = 1; dS[s] = 0.0; par[s] = -1; }
-            {
-                const double ps = phiS[s];
-                const float* crow = c + (int64_t)s * h2;
-                for (int u = lane; u < h2; u += 64) {
-                    double rc = (double)crow[u] + ps - phiT[u];
-                    rc = rc > 0.0 ? rc : 0.0;
-                    dT[u] = rc;
-                    way[u] = s;
-                }
-            }
-            int target = -1;
-            double Dt = 0.0;
-            for (int it = 0; it < h2; ++it) {
-                double bv = kFar;
-                int bi = INT_MAX;
-                for (int u = lane; u < h2; u += 64)
-                    if (!used[u] && dT[u] < bv) { bv = dT[u]; bi = u; }
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) {
-                    const double ov = __shfl_xor(bv, o);
-                    const int oi = __shfl_xor(bi, o);
-                    if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                }
-                if (bi == INT_MAX || bv >= kFar) break;        // every reachable sink has been taken
-                const int u = bi;
-                if (lane == (u & 63)) used[u] = 1;
-                if (dem[u] > 0.0) { target = u; Dt = bv; break; }
-                // sources that send flow to u join the search at u's distance
-                const double* frow = f + (int64_t)u * h1;
-                for (int pb = 0; pb < h1; pb += 64) {
-                    const int p = pb + lane;
-                    const bool add = p < h1 && frow[p] > 0.0 && !vis[p];
-                    if (add) { vis[p] = 1; dS[p] = bv; par[p] = u; }
-                    unsigned long long mask = __ballot(add);
-                    while (mask) {
-                        const int pp = pb + __ffsll((long long)mask) - 1;
-                        mask &= mask - 1;
-                        const double ps = phiS[pp];
-                        const float* crow = c + (int64_t)pp * h2;
-                        for (int uu = lane; uu < h2; uu += 64)
-                            if (!used[uu]) {
-                                double rc = (double)crow[uu] + ps - phiT[uu];
-                                rc = rc > 0.0 ? rc : 0.0;
-                                const double nd = bv + rc;
-                                if (nd < dT[uu]) { dT[uu] = nd; way[uu] = pp; }
-                            }
+        double sa = 0.0, sb = 0.0;
+        for (int p = lane; p < h1; p += 64) sa += (double)db_val[a0 + p];
+        for (int u = lane; u < h2; u += 64) sb += (double)q_val[b0 + u];
+        sa = wave_sum(sa);
+        sb = wave_sum(sb);
+        for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
+        for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
+        for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
+        wave_sync();
+
+        const int budget = 8 * (h1 + h2) + 64;     // augmentations; each empties a source, a sink or a flow entry
+        int naug = 0;
+        bool exhausted = false;
+        double total = 0.0;
+
+        for (int s = 0; s < h1 && !exhausted; ++s) {
+            while (uni(sup[s] > kMassEps)) {
+                if (naug >= budget) { exhausted = true; break; }
+                // ---- search from s ----
+                for (int u = lane; u < h2; u += 64) used[u] = 0;
+                for (int p = lane; p < h1; p += 64) vis[p] = 0;
+                wave_sync();
+                if (lane == (s & 63)) { vis[s] = 1; dS[s] = 0.0; par[s] = -1; }
+                {
+                    const double ps = phiS[s];
+                    const float* crow = c + (int64_t)s * h2;
+                    for (int u = lane; u < h2; u += 64) {
+                        double rc = (double)crow[u] + ps - phiT[u];
+                        dT[u] = rc > 0.0 ? rc : 0.0;
+                        way[u] = s;
                     }
                 }
-            }
-            wave_sync();
-            if (target < 0) {                                   // only rounding residue is left on this side
-                if (lane == (s & 63)) sup[s] = 0.0;
+                bool reached = false;
+                double Dt = 0.0;
+                for (int it = 0; it < h2; ++it) {
+                    double bv = kFar;
+                    int bi = INT_MAX;
+                    for (int u = lane; u < h2; u += 64)
+                        if (!used[u] && dT[u] < bv) { bv = dT[u]; bi = u; }
+#pragma unroll
+                    for (int o = 32; o > 0; o >>= 1) {
+                        const double ov = __shfl_xor(bv, o);
+                        const int oi = __shfl_xor(bi, o);
+                        if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                    }
+                    const int u = uni(bi);
+                    if (u == INT_MAX) break;                       // every sink has been taken
+                    if (lane == (u & 63)) used[u] = 1;
+                    if (uni(dem[u] > 0.0)) {
+                        // ---- a sink with unmet demand at distance bv: walk the path back to s for the amount ----
+                        reached = true;
+                        Dt = bv;
+                        wave_sync();                                 // vis / dS / par of sources added since the last sync
+                        double delta = sup[s] < dem[u] ? sup[s] : dem[u];
+                        {
+                            int p = uni(way[u]);
+                            for (int g = 0; g < h1; ++g) {
+                                const int up = uni(par[p]);
+                                if (up < 0) break;
+                                const double fl = f[(int64_t)up * h1 + p];
+                                delta = fl < delta ? fl : delta;
+                                p = uni(way[up]);
+                            }
+                        }
+                        total += delta * (bv - phiS[s] + phiT[u]);   // potentials are those of the search's start
+                        wave_sync();                                 // reads of the old flows are done
+                        int cut = 0;
+                        if (lane == 0) {                             // move the mass
+                            int uu = u, p = way[uu];
+                            for (int g = 0; g <= h1; ++g) {
+                                f[(int64_t)uu * h1 + p] += delta;
+                                const int up = par[p];
+                                if (up < 0) break;
+                                const double nf = f[(int64_t)up * h1 + p] - delta;
+                                if (nf > kMassEps) f[(int64_t)up * h1 + p] = nf;
+                                else { f[(int64_t)up * h1 + p] = 0.0; cut = 1; }
+                                uu = up;
+                                p = way[uu];
+                            }
+                            double r = sup[s] - delta;
+                            sup[s] = r > kMassEps ? r : 0.0;
+                            r = dem[u] - delta;
+                            dem[u] = r > kMassEps ? r : 0.0;
+                        }
+                        cut = uni(cut);
+                        wave_sync();
+                        ++naug;
+                        // go on only if the sink is full now, s has mass left and no backward edge emptied
+                        if (cut || naug >= budget || uni(sup[s] <= kMassEps || dem[u] > 0.0)) break;
+                    }
+                    // sources that send flow to u join the search at u's distance
+                    const double* frow = f + (int64_t)u * h1;
+                    for (int pb = 0; pb < h1; pb += 64) {
+                        const int p = pb + lane;
+                        const bool add = p < h1 && frow[p] > 0.0 && !vis[p];
+                        if (add) { vis[p] = 1; dS[p] = bv; par[p] = u; }
+                        unsigned long long mask = __ballot(add);
+                        while (mask) {
+                            const int pp = pb + __ffsll((long long)mask) - 1;
+                            mask &= mask - 1;
+                            const double ps = phiS[pp];
+                            const float* crow = c + (int64_t)pp * h2;
+                            for (int uu = lane; uu < h2; uu += 64)
+                                if (!used[uu]) {
+                                    double rc = (double)crow[uu] + ps - phiT[uu];
+                                    rc = rc > 0.0 ? rc : 0.0;
+                                    const double nd = bv + rc;
+                                    if (nd < dT[uu]) { dT[uu] = nd; way[uu] = pp; }
+                                }
+                        }
+                    }
+                }
                 wave_sync();
-                break;
-            }
-            // ---- amount: walk the path from the target back to s ----
-            double delta = sup[s] < dem[target] ? sup[s] : dem[target];
-            {
-                int p = way[target];
-                for (int g = 0; g < h1; ++g) {
-                    const int up = par[p];
-                    if (up < 0) break;
-                    const double fl = f[(int64_t)up * h1 + p];
-                    delta = fl < delta ? fl : delta;
-                    p = way[up];
+                if (!reached) {                                     // only rounding residue is left on this side
+                    if (lane == (s & 63)) sup[s] = 0.0;
+                    wave_sync();
+                    break;
                 }
+                // ---- potentials: nodes the search settled move by their distance minus the last target's ----
+                // (a search that went on past its last target may have settled nodes farther away: those stay)
+                for (int p = lane; p < h1; p += 64)
+                    if (vis[p] && dS[p] < Dt) phiS[p] += dS[p] - Dt;
+                for (int u = lane; u < h2; u += 64)
+                    if (used[u] && dT[u] < Dt) phiT[u] += dT[u] - Dt;
+                wave_sync();
             }
-            const double path_cost = Dt - phiS[s] + phiT[target];
-            total += delta * path_cost;
-            wave_sync();                                         // reads of the old state are done
-            // ---- move the mass ----
-            if (lane == 0) {
-                int u = target, p = way[u];
-                for (int g = 0; g <= h1; ++g) {
-                    f[(int64_t)u * h1 + p] += delta;
-                    const int up = par[p];
-                    if (up < 0) break;
-                    const double nf = f[(int64_t)up * h1 + p] - delta;
-                    f[(int64_t)up * h1 + p] = nf > kMassEps ? nf : 0.0;
-                    u = up;
-                    p = way[u];
-                }
-                double r = sup[s] - delta;
-                sup[s] = r > kMassEps ? r : 0.0;
-                r = dem[target] - delta;
-                dem[target] = r > kMassEps ? r : 0.0;
-            }
-            // ---- potentials: nodes the search settled move by their distance minus the target's ----
-            for (int p = lane; p < h1; p += 64)
-                if (vis[p]) phiS[p] += dS[p] - Dt;
-            for (int u = lane; u < h2; u += 64)
-                if (used[u]) phiT[u] += dT[u] - Dt;
-            wave_sync();
-            ++naug;
         }
-    }
-    if (lane == 0) {
-        out[t] = (float)total;
-        if (flags) flags[t] = exhausted ? 1 : 0;
-        if (exhausted && fail_count) atomicAdd(fail_count, 1);
+        if (lane == 0) {
+            out[t] = (float)total;
+            if (flags) flags[t] = exhausted ? 1 : 0;
+            if (exhausted && fail_count) atomicAdd(fail_count, 1);
+        }
     }
 }
 
@@ -468,42 +498,46 @@ static size_t emd_slab_elems(int64_t h1max, int64_t h2max) { return (size_t)h1ma
 
 size_t emd_pair_bytes(int64_t h1max, int64_t h2max) { return emd_slab_elems(h1max, h2max) * 12; }   // fp32 costs, fp64 flows
 
-static size_t emd_lds_bytes(int64_t h1max, int64_t h2max) { return (size_t)(h1max + h2max) * 32; }
+// per-word solver state, or the cost tiles when those are larger (the two are never live together)
+static size_t emd_lds_bytes(int64_t h1max, int64_t h2max)
+{
+    const size_t state = (size_t)(h1max + h2max) * 32;
+    return state > (size_t)kCostLds ? state : (size_t)kCostLds;
+}
 
 bool emd_supported(int64_t h1max, int64_t h2max) { return emd_lds_bytes(h1max, h2max) <= 159 * 1024; }
 
-// Slab layout for `count` problems in flight: count flow matrices (fp64), then count cost matrices (fp32).
-static float* cost_slabs(void* slabs, int64_t count, size_t elems)
+// Wavefronts that fit the device at once for histograms of this size.
+int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max)
 {
-    return reinterpret_cast<float*>(reinterpret_cast<double*>(slabs) + (size_t)count * elems);
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_emd, 64, emd_lds_bytes(h1max, h2max)) != hipSuccess || occ < 1)
+        occ = 1;
+    return (int64_t)num_cu * occ;
 }
 
-hipError_t launch_pair_costs(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
-                             const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, hipStream_t s)
+// WMD of `count` listed pairs.  `slabs` holds `slots` flow matrices (fp64) followed by `slots` cost matrices (fp32),
+// one of each per wavefront of the grid; next_pair is a device counter this call resets.
+hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
+                      const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, int64_t slots,
+                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
-    const size_t elems = emd_slab_elems(h1max, h2max);
-    k_pair_costs<<<dim3((unsigned)count), 256, 0, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx,
-                                                      Q.row_ptr, Q.col_idx, pair_db, pair_q, cost_slabs(slabs, count, elems),
-                                                      (int64_t)elems);
-    return hipGetLastError();
-}
-
-hipError_t launch_emd(const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db, const int32_t* pair_q,
-                      int64_t count, int64_t h1max, int64_t h2max, void* slabs, float* out, int32_t* flags,
-                      int32_t* fail_count, hipStream_t s)
-{
-    if (count <= 0) return hipSuccess;
+    if (slots > count) slots = count;
     const size_t elems = emd_slab_elems(h1max, h2max);
     const size_t lds = emd_lds_bytes(h1max, h2max);
+    hipError_t e;
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_emd), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_emd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_emd<<<dim3((unsigned)count), 64, lds, s>>>(DB.row_ptr, DB.val, Q.row_ptr, Q.val, pair_db, pair_q,
-                                                 cost_slabs(slabs, count, elems), (int64_t)elems,
-                                                 reinterpret_cast<double*>(slabs), (int32_t)h1max, (int32_t)h2max, out, flags,
+    e = launch_fill_i32(next_pair, 1, 0, s);
+    if (e != hipSuccess) return e;
+    double* slabs_f = reinterpret_cast<double*>(slabs);
+    float* slabs_c = reinterpret_cast<float*>(slabs_f + (size_t)slots * elems);
+    k_emd<<<dim3((unsigned)slots), 64, lds, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx, DB.val,
+                                                 Q.row_ptr, Q.col_idx, Q.val, pair_db, pair_q, count, next_pair, slabs_c,
+                                                 (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max, out, flags,
                                                  fail_count);
     return hipGetLastError();
 }
