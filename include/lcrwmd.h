@@ -257,8 +257,8 @@ lcrwmd_status lcrwmd_wmd_pairs_workspace_bytes(lcrwmd_ctx* ctx, int64_t max_h_db
  * seen to; the call then also returns LCRWMD_ENOCONVERGE when flags is NULL.
  * As many wavefronts as the workspace has room for (at least one) take the problems off a queue.
  * Synchronises the stream when it has to fetch row pointers, when validating, and (flags NULL) at
- * the end to read the failure count.  Histograms of more than about 5,000 words in total per pair
- * are LCRWMD_EUNSUPPORTED (per-word solver state is kept in LDS).
+ * the end to read the failure count.  Histograms of more than 2,048 words
+ * are LCRWMD_EUNSUPPORTED (per-word solver state is kept in LDS and registers).
  */
 lcrwmd_status lcrwmd_wmd_pairs(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
                                const lcrwmd_emb* E, const int32_t* pair_db, const int32_t* pair_q,

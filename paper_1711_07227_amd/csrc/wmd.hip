@@ -37,6 +37,31 @@ __device__ inline void wave_sync()
 // (left to itself the compiler treats them as divergent and may route lanes through a loop header separately).
 __device__ inline int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Minimum of x over the wavefront, the same value in every lane.  Data-parallel-primitive moves inside rows of 16
+// lanes (shifts by 1, 2, 4, 8: lane 15 of a row ends up with the row's minimum), then row 0 -> row 1 and row 2 -> row 3,
+// then rows 0-1 -> rows 2-3; lane 63 holds the result.  A lane without a source keeps its own value.
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_min_step(double x)
+{
+    const int lo = __double2loint(x), hi = __double2hiint(x);
+    const int olo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xf, false);
+    const int ohi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xf, false);
+    const double o = __hiloint2double(ohi, olo);
+    return o < x ? o : x;
+}
+
+__device__ inline double wave_min(double x)
+{
+    x = dpp_min_step<0x111, 0xf>(x);      // row_shr:1
+    x = dpp_min_step<0x112, 0xf>(x);      // row_shr:2
+    x = dpp_min_step<0x114, 0xf>(x);      // row_shr:4
+    x = dpp_min_step<0x118, 0xf>(x);      // row_shr:8
+    x = dpp_min_step<0x142, 0xa>(x);      // row_bcast:15 into rows 1 and 3
+    x = dpp_min_step<0x143, 0xc>(x);      // row_bcast:31 into rows 2 and 3
+    const int lo = __builtin_amdgcn_readlane(__double2loint(x), 63), hi = __builtin_amdgcn_readlane(__double2hiint(x), 63);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ inline double wave_sum(double x)
 {
 #pragma unroll
@@ -47,39 +72,40 @@ __device__ inline double wave_sum(double x)
 // ---------------------------------------------------------------------------------------------------------------
 // C = T1 o T2 of one pair (Sec. III), by one wavefront: c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||
 // as the square root of the sum of squared differences (no norm expansion: equal words give exactly 0).
-// 32 x 32 output tiles, 4 x 4 outputs per lane, the embedding dimension staged through LDS 32 values at a time.
+// 32 x 32 output tiles, 4 x 4 outputs per lane, the embedding dimension staged through LDS 16 values at a time.
 // `tiles` is kCostLds bytes of this wavefront's LDS.
 // ---------------------------------------------------------------------------------------------------------------
-constexpr int kCT = 32;
-constexpr int kCostLds = (2 * kCT * (kCT + 1) + 2 * kCT) * 4;
+constexpr int kCT = 32;      // tile edge
+constexpr int kCK = 16;      // embedding values per slice
+constexpr int kCostLds = (2 * kCT * (kCK + 1) + 2 * kCT) * 4;
 
 __device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m, const int32_t* __restrict__ wa_g,
                            int h1, const int32_t* __restrict__ wb_g, int h2, float* c, float* tiles, int lane)
 {
-    float (*A)[kCT + 1] = reinterpret_cast<float (*)[kCT + 1]>(tiles);
-    float (*B)[kCT + 1] = reinterpret_cast<float (*)[kCT + 1]>(tiles + kCT * (kCT + 1));
-    int32_t* wa = reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCT + 1));
+    float (*A)[kCK + 1] = reinterpret_cast<float (*)[kCK + 1]>(tiles);
+    float (*B)[kCK + 1] = reinterpret_cast<float (*)[kCK + 1]>(tiles + kCT * (kCK + 1));
+    int32_t* wa = reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCK + 1));
     int32_t* wb = wa + kCT;
     const int tx = lane & 7, ty = lane >> 3;      // 8 x 8 lanes; rows ty + 8 a, columns tx + 8 b
-    const int lr = lane >> 5, lc = lane & 31;     // loader: rows lr + 2 e, column lc
+    const int lr = lane >> 4, lc = lane & 15;     // loader: rows lr + 4 e, column lc
     for (int p0 = 0; p0 < h1; p0 += kCT)
         for (int u0 = 0; u0 < h2; u0 += kCT) {
             if (lane < kCT) wa[lane] = p0 + lane < h1 ? wa_g[p0 + lane] : -1;
             else wb[lane - kCT] = u0 + lane - kCT < h2 ? wb_g[u0 + lane - kCT] : -1;
             float acc[4][4] = {};
-            for (int k0 = 0; k0 < m; k0 += kCT) {
+            for (int k0 = 0; k0 < m; k0 += kCK) {
                 wave_sync();                       // word ids written; the previous slice has been consumed
                 const int kk = k0 + lc;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int r = lr + 2 * e;
+                for (int e = 0; e < 8; ++e) {
+                    const int r = lr + 4 * e;
                     const int32_t w1 = wa[r], w2 = wb[r];
                     A[r][lc] = (w1 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w1 * ld + kk) : 0.f;
                     B[r][lc] = (w2 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w2 * ld + kk) : 0.f;
                 }
                 wave_sync();
 #pragma unroll 4
-                for (int k = 0; k < kCT; ++k) {
+                for (int k = 0; k < kCK; ++k) {
                     float x[4], y[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { x[e] = A[ty + 8 * e][k]; y[e] = B[tx + 8 * e][k]; }
@@ -116,20 +142,23 @@ __device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, in
 // backward edge, the search goes on from where it stands (the sink now passes flow on like any full sink);
 // otherwise it ends, the potentials are shifted by the search distances, and the next search starts.
 // Lane l owns sinks and sources l, l + 64, ...; their per-node state sits in LDS, the flow matrix (transposed: one
-// row per sink) and the costs in the wavefront's slab in device memory.
+// row per sink) and the costs in the wavefront's slab in device memory.  Which entries of the flow matrix are
+// positive is also kept as one bit each in LDS when that fits (bm_words > 0 words per sink), so that a search reads
+// device memory only for rows of the cost matrix.
 // Histogram weights are divided by their fp64 sums first, so both sides carry mass 1.
 //
 // The grid is a set of wavefronts that take pairs off a shared counter until it passes `count`: every wavefront
 // ends because every loop below is bounded by the pair's dimensions or by the augmentation budget.
 // flags[t]: 0 solved; 1 the augmentation budget ran out (the result is then the cost of a partial flow).
 // ---------------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+__global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
                                             const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
                                             const float* __restrict__ db_val, const int64_t* __restrict__ q_rp,
                                             const int32_t* __restrict__ q_col, const float* __restrict__ q_val,
                                             const int32_t* __restrict__ pair_db, const int32_t* __restrict__ pair_q,
                                             int64_t count, int32_t* next_pair, float* slabs_c, int64_t slab_elems,
-                                            double* slabs_f, int32_t h1max, int32_t h2max, float* __restrict__ out,
+                                            double* slabs_f, int32_t h1max, int32_t h2max, int32_t bm_words,
+                                            float* __restrict__ out,
                                             int32_t* __restrict__ flags, int32_t* fail_count)
 {
     extern __shared__ double lds_d[];
@@ -140,9 +169,8 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
     double* dT = phiT + h2max;
     double* dem = dT + h2max;
     int32_t* par = reinterpret_cast<int32_t*>(dem + h2max);
-    int32_t* vis = par + h1max;
-    int32_t* way = vis + h1max;
-    int32_t* used = way + h2max;
+    int32_t* way = par + h1max;
+    uint32_t* bm = reinterpret_cast<uint32_t*>(way + h2max);        // [h2max][bm_words], bit p of row u: y[p, u] > 0
 
     const int lane = threadIdx.x;
     float* c = slabs_c + (int64_t)blockIdx.x * slab_elems;
@@ -168,6 +196,7 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
         for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
         for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
         for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
+        for (int e = lane; e < h2 * bm_words; e += 64) bm[e] = 0u;
         wave_sync();
 
         const int budget = 8 * (h1 + h2) + 64;     // augmentations; each empties a source, a sink or a flow entry
@@ -179,10 +208,10 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
             while (uni(sup[s] > kMassEps)) {
                 if (naug >= budget) { exhausted = true; break; }
                 // ---- search from s ----
-                for (int u = lane; u < h2; u += 64) used[u] = 0;
-                for (int p = lane; p < h1; p += 64) vis[p] = 0;
+                // bit r of a lane's masks: its sink / source lane + 64 r has been settled by this search
+                uint32_t used = 0, vis = 0;
                 wave_sync();
-                if (lane == (s & 63)) { vis[s] = 1; dS[s] = 0.0; par[s] = -1; }
+                if (lane == (s & 63)) { vis = 1u << (s >> 6); dS[s] = 0.0; par[s] = -1; }
                 {
                     const double ps = phiS[s];
                     const float* crow = c + (int64_t)s * h2;
@@ -197,22 +226,20 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
                 for (int it = 0; it < h2; ++it) {
                     double bv = kFar;
                     int bi = INT_MAX;
-                    for (int u = lane; u < h2; u += 64)
-                        if (!used[u] && dT[u] < bv) { bv = dT[u]; bi = u; }
-#pragma unroll
-                    for (int o = 32; o > 0; o >>= 1) {
-                        const double ov = __shfl_xor(bv, o);
-                        const int oi = __shfl_xor(bi, o);
-                        if (ov < bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                    }
-                    const int u = uni(bi);
-                    if (u == INT_MAX) break;                       // every sink has been taken
-                    if (lane == (u & 63)) used[u] = 1;
+                    for (int u = lane, r = 0; u < h2; u += 64, ++r)
+                        if (!((used >> r) & 1) && dT[u] < bv) { bv = dT[u]; bi = u; }
+                    // the nearest over all lanes; of equally near sinks the one in the lowest lane
+                    const double nearest = wave_min(bv);
+                    const unsigned long long holders = __ballot(bi != INT_MAX && bv == nearest);
+                    if (holders == 0ull) break;                    // every sink has been taken
+                    const int u = __builtin_amdgcn_readlane(bi, __ffsll((long long)holders) - 1);
+                    bv = nearest;
+                    if (lane == (u & 63)) used |= 1u << (u >> 6);
                     if (uni(dem[u] > 0.0)) {
                         // ---- a sink with unmet demand at distance bv: walk the path back to s for the amount ----
                         reached = true;
                         Dt = bv;
-                        wave_sync();                                 // vis / dS / par of sources added since the last sync
+                        wave_sync();                                 // dS / par of sources added since the last sync
                         double delta = sup[s] < dem[u] ? sup[s] : dem[u];
                         {
                             int p = uni(way[u]);
@@ -231,11 +258,16 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
                             int uu = u, p = way[uu];
                             for (int g = 0; g <= h1; ++g) {
                                 f[(int64_t)uu * h1 + p] += delta;
+                                if (bm_words) bm[uu * bm_words + (p >> 5)] |= 1u << (p & 31);
                                 const int up = par[p];
                                 if (up < 0) break;
                                 const double nf = f[(int64_t)up * h1 + p] - delta;
                                 if (nf > kMassEps) f[(int64_t)up * h1 + p] = nf;
-                                else { f[(int64_t)up * h1 + p] = 0.0; cut = 1; }
+                                else {
+                                    f[(int64_t)up * h1 + p] = 0.0;
+                                    if (bm_words) bm[up * bm_words + (p >> 5)] &= ~(1u << (p & 31));
+                                    cut = 1;
+                                }
                                 uu = up;
                                 p = way[uu];
                             }
@@ -254,16 +286,17 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
                     const double* frow = f + (int64_t)u * h1;
                     for (int pb = 0; pb < h1; pb += 64) {
                         const int p = pb + lane;
-                        const bool add = p < h1 && frow[p] > 0.0 && !vis[p];
-                        if (add) { vis[p] = 1; dS[p] = bv; par[p] = u; }
+                        bool add = p < h1 && !((vis >> (pb >> 6)) & 1);
+                        if (add) add = bm_words ? ((bm[u * bm_words + (p >> 5)] >> (p & 31)) & 1u) != 0u : frow[p] > 0.0;
+                        if (add) { vis |= 1u << (pb >> 6); dS[p] = bv; par[p] = u; }
                         unsigned long long mask = __ballot(add);
                         while (mask) {
                             const int pp = pb + __ffsll((long long)mask) - 1;
                             mask &= mask - 1;
                             const double ps = phiS[pp];
                             const float* crow = c + (int64_t)pp * h2;
-                            for (int uu = lane; uu < h2; uu += 64)
-                                if (!used[uu]) {
+                            for (int uu = lane, r = 0; uu < h2; uu += 64, ++r)
+                                if (!((used >> r) & 1)) {
                                     double rc = (double)crow[uu] + ps - phiT[uu];
                                     rc = rc > 0.0 ? rc : 0.0;
                                     const double nd = bv + rc;
@@ -280,10 +313,10 @@ __global__ __launch_bounds__(64) void k_emd(const void* __restrict__ E, int dtyp
                 }
                 // ---- potentials: nodes the search settled move by their distance minus the last target's ----
                 // (a search that went on past its last target may have settled nodes farther away: those stay)
-                for (int p = lane; p < h1; p += 64)
-                    if (vis[p] && dS[p] < Dt) phiS[p] += dS[p] - Dt;
-                for (int u = lane; u < h2; u += 64)
-                    if (used[u] && dT[u] < Dt) phiT[u] += dT[u] - Dt;
+                for (int p = lane, r = 0; p < h1; p += 64, ++r)
+                    if (((vis >> r) & 1) && dS[p] < Dt) phiS[p] += dS[p] - Dt;
+                for (int u = lane, r = 0; u < h2; u += 64, ++r)
+                    if (((used >> r) & 1) && dT[u] < Dt) phiT[u] += dT[u] - Dt;
                 wave_sync();
             }
         }
@@ -498,14 +531,25 @@ static size_t emd_slab_elems(int64_t h1max, int64_t h2max) { return (size_t)h1ma
 
 size_t emd_pair_bytes(int64_t h1max, int64_t h2max) { return emd_slab_elems(h1max, h2max) * 12; }   // fp32 costs, fp64 flows
 
+// Words per sink of the map of positive flows, or 0 when the map would take more than 16 KiB of LDS.
+static int32_t emd_bitmap_words(int64_t h1max, int64_t h2max)
+{
+    const int64_t w = (h1max + 31) / 32;
+    return w * h2max * 4 <= 16 * 1024 ? (int32_t)w : 0;
+}
+
 // per-word solver state, or the cost tiles when those are larger (the two are never live together)
 static size_t emd_lds_bytes(int64_t h1max, int64_t h2max)
 {
-    const size_t state = (size_t)(h1max + h2max) * 32;
+    const size_t state = (size_t)(h1max + h2max) * 28 + (size_t)emd_bitmap_words(h1max, h2max) * (size_t)h2max * 4;
     return state > (size_t)kCostLds ? state : (size_t)kCostLds;
 }
 
-bool emd_supported(int64_t h1max, int64_t h2max) { return emd_lds_bytes(h1max, h2max) <= 159 * 1024; }
+// the settled-node masks hold 32 nodes per lane; the per-word state must fit one workgroup's LDS
+bool emd_supported(int64_t h1max, int64_t h2max)
+{
+    return h1max <= 2048 && h2max <= 2048 && emd_lds_bytes(h1max, h2max) <= 159 * 1024;
+}
 
 // Wavefronts that fit the device at once for histograms of this size.
 int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max)
@@ -537,8 +581,8 @@ hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_cs
     float* slabs_c = reinterpret_cast<float*>(slabs_f + (size_t)slots * elems);
     k_emd<<<dim3((unsigned)slots), 64, lds, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx, DB.val,
                                                  Q.row_ptr, Q.col_idx, Q.val, pair_db, pair_q, count, next_pair, slabs_c,
-                                                 (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max, out, flags,
-                                                 fail_count);
+                                                 (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max,
+                                                 emd_bitmap_words(h1max, h2max), out, flags, fail_count);
     return hipGetLastError();
 }
 

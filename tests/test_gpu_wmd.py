@@ -123,6 +123,16 @@ def test_wmd_pairs_medium_sized_documents(ctx):
     assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="WMD of 50-150 word documents")
 
 
+def test_wmd_pairs_long_documents(ctx):
+    """About 400 words a side: beyond the size up to which the solver keeps its map of positive flows in LDS."""
+    p = {"E": synth.embeddings(3000, 300, 1), "db": synth.corpus(2, 3000, 380, 420, 1.0, 2),
+         "queries": synth.corpus(1, 3000, 380, 420, 1.0, 3)}
+    E, db, qs = upload(p)
+    got, flags = run_wmd_pairs(ctx, E, db, qs, [0, 1], [0, 0], (longest(p["db"]), longest(p["queries"])), flags=True)
+    assert np.all(flags == 0)
+    assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], [0, 1], [0, 0]), what="WMD of 400-word documents")
+
+
 def test_wmd_argument_checks(ctx, tiny):
     E, db, qs = upload(tiny)
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
