@@ -879,7 +879,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
     for (;;) {
         const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode) +
                                  fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
-        const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 64 + 4096;   // first k lists, >= 64 problems in flight
+        const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 2 + 8192;    // first k lists, a problem in flight
         if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query batch");
         qb = (qb + 1) / 2;
@@ -932,8 +932,8 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         size_t slab_part = pair_bytes * (size_t)emd_preferred_slots(ctx->num_cu, h1max, h2max);
         if (slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
         if (slab_part < pair_bytes) slab_part = pair_bytes;
-        slab_part = slab_part / 256 * 256;
-        if (slab_part < pair_bytes || slab_part + 4096 > rest_bytes)
+        slab_part = (slab_part + 255) / 256 * 256;
+        if (slab_part + 4096 > rest_bytes)
             return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem");
         const int64_t list_cap = (int64_t)((rest_bytes - slab_part - 2048) / 12);
         for (int64_t ja = 0; ja < nq;) {

@@ -223,6 +223,44 @@ def test_wmd_topk_pruned_equals_exhaustive(ctx):
     assert torch.equal(R2, R_idx) and torch.equal(D2, R_dist)
 
 
+def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
+    """Shrinking the workspace makes the library walk the queries in smaller batches and the survivor lists in ranges;
+    the result and the evaluation counts must not change.  Below some size the call must refuse, not misbehave."""
+    p = problem(v=600, m=300, n=8000, q=40, h_lo=20, h_hi=40, seed=23, s=1.0)
+    E, db, qs = upload(p)
+    n, q, k = 8000, 40, 16
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    full = ctx.wmd_topk_workspace_bytes(600, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax)
+
+    def run(nbytes):
+        ws = binding.alloc_workspace(nbytes)
+        R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+        R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+        ev = torch.zeros(q, dtype=torch.int64)
+        ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
+        torch.cuda.synchronize()
+        return R_idx.cpu(), R_dist.cpu(), ev.clone()
+
+    ref = run(full)
+    ok_sizes, nbytes = [], full
+    while nbytes > 1024:
+        nbytes = nbytes * 3 // 4
+        try:
+            got = run(nbytes)
+        except binding.LcrwmdError as e:
+            assert e.status == binding.EWORKSPACE
+            break
+        ok_sizes.append(nbytes)
+        assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]) and torch.equal(got[2], ref[2]), nbytes
+    assert len(ok_sizes) >= 3
+    # the lists (12 bytes per survivor) get at most half of the workspace: at the smallest size they cannot have fitted at once
+    assert (int(ref[2].sum()) - q * k) * 12 > ok_sizes[-1] // 2, (int(ref[2].sum()), ok_sizes)
+    # spot check of the reference itself against the oracle
+    gi, gd = ref[0].numpy(), ref[1].numpy()
+    for j in range(2):
+        assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
+
+
 def test_wmd_topk_tiny_configuration(ctx, tiny):
     """Tiny configuration (300 of its 1,000 documents x 10 queries, 20-80 words): the oracle follows the same pruning procedure."""
     sub = synth.csr_rows(*tiny["db"], np.arange(300))
