@@ -427,3 +427,30 @@ def test_medium_workload_at_full_size_sampled_pairs(ctx):
     cols = np.array([3, q - 1])
     ref_cols = oracle.rwmd_table(p["E"], p["db"], synth.csr_rows(*p["queries"], cols))
     assert_close(D[:, torch.from_numpy(cols).cuda()].cpu().numpy(), ref_cols, what="medium full columns")
+
+
+def test_calls_on_a_side_stream_give_the_same_results(ctx, tiny):
+    """Everything is enqueued on the caller's stream: a side stream (default priority) must give identical results,
+    with its inputs produced on that stream right before the call."""
+    E, db, qs = upload(tiny)
+    base = run_rwmd(ctx, E, db, qs)
+    side = torch.cuda.Stream()
+    n, q, k = db.rows, qs.rows, 4
+    with torch.cuda.stream(side):
+        E2 = E * 1.0                                   # produced on the side stream, consumed by the library there
+        ws = binding.alloc_workspace(ctx.workspace_bytes(E.shape[0], 300, n, db.nnz, q, qs.nnz))
+        D = torch.full((n, q), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.rwmd(qs, db, E2, D, ws)
+        R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+        R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+        hmax = (int(np.max(np.diff(tiny["db"][0]))), int(np.max(np.diff(tiny["queries"][0]))))
+        ws2 = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(E.shape[0], 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+        ctx.wmd_topk(qs, db, E2, k, R_idx, R_dist, ws2)
+    side.synchronize()
+    assert np.array_equal(D.cpu().numpy(), base)
+    ws3 = binding.alloc_workspace(ws2.numel())
+    R_idx0 = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist0 = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wmd_topk(qs, db, E, k, R_idx0, R_dist0, ws3)
+    torch.cuda.synchronize()
+    assert torch.equal(R_idx0, R_idx) and torch.equal(R_dist0, R_dist)
