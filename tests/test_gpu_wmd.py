@@ -185,7 +185,7 @@ def check_topk(gi, gd, W):
         assert_close(W[gi[j], j], gd[j], what="reported rows carry the reported distances")
         assert len(set(gi[j].tolist())) == k
         gaps = np.diff(W[order[:k + 1], j])
-        if np.min(gaps) > 1e-4 * W[order[k], j]:
+        if np.min(gaps) > 1e-4 * W[order[k - 1], j]:
             assert np.array_equal(gi[j], order[:k])
 
 
@@ -259,6 +259,44 @@ def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
     gi, gd = ref[0].numpy(), ref[1].numpy()
     for j in range(2):
         assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
+
+
+def test_wmd_topk_degenerate_shapes(ctx):
+    """k = n (nothing left to prune), one document against one query, no queries, no pairs."""
+    p = problem(v=100, m=300, n=5, q=3, h_lo=1, h_hi=9, seed=31)
+    E, db, qs = upload(p)
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(100, 300, 5, db.nnz, 3, qs.nnz, binding.F32, 5, *hmax))
+    R_idx = torch.full((3, 5), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((3, 5), float("nan"), dtype=torch.float32, device="cuda")
+    ev = torch.zeros(3, dtype=torch.int64)
+    ctx.wmd_topk(qs, db, E, 5, R_idx, R_dist, ws, ev)
+    torch.cuda.synchronize()
+    assert ev.tolist() == [5, 5, 5]
+    pi, pj = np.divmod(np.arange(15), 3)
+    W = oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj).reshape(5, 3)
+    check_topk(R_idx.cpu().numpy(), R_dist.cpu().numpy(), W)
+    one_db = binding.Csr.from_numpy(synth.csr_rows(*p["db"], np.arange(1)), 100)
+    one_q = binding.Csr.from_numpy(synth.csr_rows(*p["queries"], np.arange(1)), 100)
+    R_idx = torch.full((1, 1), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((1, 1), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wmd_topk(one_q, one_db, E, 1, R_idx, R_dist, ws)
+    torch.cuda.synchronize()
+    assert int(R_idx[0, 0]) == 0
+    assert_close(R_dist.cpu().numpy()[0], W[:1, 0], what="one document, one query")
+    # no queries / no pairs: nothing is launched, nothing is written
+    none = binding.Csr(torch.zeros(1, dtype=torch.int64, device="cuda"), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                       torch.zeros(0, dtype=torch.float32, device="cuda"), 100, torch.zeros(1, dtype=torch.int64))
+    ctx.wmd_topk(none, db, E, 1, R_idx, R_dist, ws)
+    out = torch.full((1,), 7.0, dtype=torch.float32, device="cuda")
+    empty = torch.zeros(0, dtype=torch.int32, device="cuda")
+    ctx.wmd_pairs(qs, db, E, empty, empty, out, ws)
+    torch.cuda.synchronize()
+    assert float(out[0]) == 7.0
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_topk(qs, db, E, 6, torch.zeros((3, 6), dtype=torch.int32, device="cuda"),
+                     torch.zeros((3, 6), dtype=torch.float32, device="cuda"), ws)
+    assert e.value.status == binding.EINVAL                      # k > n
 
 
 def test_wmd_topk_tiny_configuration(ctx, tiny):
