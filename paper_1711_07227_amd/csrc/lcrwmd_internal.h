@@ -30,10 +30,13 @@ namespace lcrwmd {
 // ---------------------------------------------------------------------------------------------
 // Padded token list of a batch of histograms (the stacked T matrix of Sec. IV, many-to-many
 // form, kept as word ids instead of gathered vectors).  Every histogram ("segment") is padded to
-// a multiple of 8 tokens by repeating its last word, which leaves every minimum unchanged and
-// makes each group of 8 consecutive tokens belong to exactly one segment.
+// a multiple of `group` tokens by repeating its last word, which leaves every minimum unchanged and
+// makes each group of consecutive tokens belong to exactly one segment.  In the 32x32 MFMA
+// accumulator a lane holds runs of 4 consecutive rows, and a lane and its partner 32 lanes up hold
+// 8 consecutive rows between them: kernels work on groups of 8, or of 4 where the shorter padding pays.
 // ---------------------------------------------------------------------------------------------
-constexpr int kGroup = 8;          // tokens per group; the 32x32 MFMA accumulator holds 8-row groups
+constexpr int kGroup = 8;          // largest group size (bounds the padding)
+constexpr int kGroupMin = 4;       // smallest group size (bounds the number of groups)
 constexpr int kTileTokens = 128;   // token rows per tile of the first-phase kernel
 constexpr int kTileVocab = 128;    // vocabulary columns per workgroup of the first-phase kernel
 
@@ -44,11 +47,12 @@ struct TokenPlan {
     int64_t tok_alloc;     // allocated padded tokens (bound rounded up to a tile, plus one tile)
     int32_t chunk_tokens;  // target padded tokens per chunk (multiple of kTileTokens)
     int32_t nchunks;       // upper bound on chunks
+    int32_t group;         // tokens per group: 4 or 8
     // device arrays (carved from the workspace)
     int32_t* pofs;         // [nseg + 1] padded token offset of each segment
     int32_t* tok_ids;      // [tok_alloc] word id per padded token (0 beyond the end)
     float* tok_hn;         // [tok_alloc] -0.5 * |E[word]|^2 per padded token
-    int32_t* grp_seg;      // [tok_alloc / 8] segment of each group, -1 beyond the end
+    int32_t* grp_seg;      // [tok_alloc / group] segment of each group, -1 beyond the end
     int32_t* chunk_seg;    // [nchunks + 1] first segment of each chunk
 };
 
@@ -72,7 +76,7 @@ struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
 // padded_exact: the exact padded token count when the caller knows the row lengths (else -1: the bound is used,
 // and the last chunks may turn out empty)
 bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles,
-                      int64_t padded_exact = -1);
+                      int64_t padded_exact = -1, int group = kGroup);
 
 // Operand description of one first-phase launch.
 struct Phase1Args {
@@ -120,6 +124,7 @@ bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s);
 hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
+int phase1_group_x3();             // group size the split-bf16 kernel expects of its token plan
 // split-bf16 operand copy: 640 bf16 per row (304 hi values, 304 lo values, zeros)
 size_t pack_x3_bytes(int64_t v);
 int32_t x3_pitch();

@@ -425,6 +425,7 @@ hipError_t launch_phase1_f32(const Phase1Args& a, const TokenPlan& tp, hipStream
 {
     if (a.nvoc <= 0 || tp.nseg <= 0) return hipSuccess;
     if (tiles_f32_supported(a)) return launch_phase1_tiles_f32(a, tp, s);   // 16-byte aligned rows, m <= 300
+    if (tp.group != kGroup) return hipErrorInvalidValue;                  // these kernels take groups of 8 rows
     P1Dev d;
     d.E = (const float*)a.E;
     d.ld = a.ld;

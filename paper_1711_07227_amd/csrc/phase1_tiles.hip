@@ -510,7 +510,11 @@ struct PP {
     static constexpr int NBUF = MODE == kBF16 ? 4 : 2;
     static constexpr int PD = NBUF - 1;
     static constexpr int OCT_BYTES = (ROWS / 8) * 1024, TILE_BYTES = NOCT * OCT_BYTES;
-    static constexpr int NG = ROWS / 8;
+    // Rows per group = the padding of a histogram's token list.  Groups of 4 cost sixteen epilogue steps per tile
+    // instead of eight; measured on Medium that pays for the split-bf16 arithmetic (-3 %) and costs the other two
+    // (fp32 +1.3 %, and the bf16 epilogue no longer fits in the other group's K loop), so only the split form uses it.
+    static constexpr int G = MODE == kX3 ? 4 : 8;
+    static constexpr int NG = ROWS / G;
     static constexpr int WG_COLS = 2 * 4 * NCT * 32;           // vocabulary words per workgroup
     static constexpr int COPY_EVERY = NITER / NOCT >= 1 ? NITER / NOCT : 1;
 };
@@ -532,7 +536,7 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     using C = PP<MODE>;
     constexpr bool BF16 = MODE == kBF16, X3 = MODE == kX3, F32 = MODE == kF32;
     constexpr int ROWS = C::ROWS, NRT = C::NRT, NCT = C::NCT, NS = C::NS, NITER = C::NITER, NF = C::NF, NOCT = C::NOCT;
-    constexpr int NBUF = C::NBUF, PD = C::PD, OCT_BYTES = C::OCT_BYTES, TILE_BYTES = C::TILE_BYTES, NG = C::NG;
+    constexpr int NBUF = C::NBUF, PD = C::PD, OCT_BYTES = C::OCT_BYTES, TILE_BYTES = C::TILE_BYTES, NG = C::NG, G = C::G;
     constexpr int WG_COLS = C::WG_COLS;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -663,7 +667,7 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     struct Grp { int32_t v[NG]; };
     auto load_gs = [&](int tb) {
         Grp r;
-        const int32_t* g = grp_seg + (tb >> 3);
+        const int32_t* g = grp_seg + tb / G;
 #pragma unroll
         for (int k = 0; k < NG; ++k) r.v[k] = g[k];
         return r;
@@ -689,10 +693,14 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     pp_barrier();
     if (grp == 1) pp_barrier();                // the second group starts half a period later
 
-    // The epilogue of a tile: histogram maxima of its 8 groups, the stores of the histograms that end in it, the
-    // source offsets of the copies two K loops ahead and the scalar table loads for the epilogue after this one.
+    // The epilogue of a tile: histogram maxima of its groups, the stores of the histograms that end in it, the source
+    // offsets of the copies two K loops ahead and the scalar table loads for the epilogue after this one.
+    // Rows 8 j .. 8 j + 3 of a 32-row tile sit in accumulator registers 4 j .. 4 j + 3 of the lower lane half, rows
+    // 8 j + 4 .. 8 j + 7 in the same registers of the upper half.  A group of 8 rows is those registers in both halves;
+    // groups of 4 are walked in row order and only the half that owns a group adds it to its running maximum (the
+    // store combines the two halves either way).
     auto epilogue = [&](int tb) {
-        int ng = (t1 - tb) >> 3;
+        int ng = (t1 - tb) / G;
         if (ng > NG) ng = NG;
         const Grp sgsv = grp_next;
         const Ids ids = ids_next;
@@ -709,13 +717,14 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
             const bool live = g < ng;                      // groups past the end of the chunk are someone else's
             const int sg = live ? sgs[g] : cur;
             const bool is_new = sg != cur;
-            const int rt = g >> 2, r0 = (g & 3) * 4;
+            const int rt = G == 4 ? g >> 3 : g >> 2, r0 = G == 4 ? ((g & 7) >> 1) * 4 : (g & 3) * 4;
+            const bool mine = G == 8 || (g & 1) == half;
             if (is_new && cur >= 0) flush();
             cur = sg;
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
                 const float mg = fmaxf(fmaxf(acc[rt][ct][r0], acc[rt][ct][r0 + 1]), fmaxf(acc[rt][ct][r0 + 2], acc[rt][ct][r0 + 3]));
-                run[ct] = fmaxf(live ? mg : -INFINITY, is_new ? -INFINITY : run[ct]);
+                run[ct] = fmaxf((live && mine) ? mg : -INFINITY, is_new ? -INFINITY : run[ct]);
             }
         }
     };
@@ -869,6 +878,8 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
 
 // fp32 rows are read in place: 300 values (75 whole 16-byte pieces; the 76th piece of the layout re-reads the 75th)
 // in 16-byte aligned rows.  Other shapes take the register-staged kernels of phase1_f32.hip.
+int phase1_group_x3() { return PP<kX3>::G; }
+
 bool tiles_f32_supported(const Phase1Args& a)
 {
     return a.m == 300 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0;
@@ -901,6 +912,7 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
+    if (tp.group != PP<kF32>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     return launch_pingpong<kF32>(d, a.num_cu, s);
 }
 
@@ -911,6 +923,7 @@ hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipS
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<kX3>::NOCT * 8;
     d.nzero_from = 0;
+    if (tp.group != PP<kX3>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     return launch_pingpong<kX3>(d, a.num_cu, s);
 }
 
@@ -921,6 +934,7 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
     d.pitch_b = a.ld * 2;
     d.nreal = Layout<kBF16>::NOCT * 8;
     d.nzero_from = 0;
+    if (tp.group != PP<kBF16>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     return launch_pingpong<kBF16>(d, num_cu, s);
 }
 

@@ -91,9 +91,9 @@ __global__ void k_remap_cols(const int32_t* __restrict__ col_idx, int64_t nnz, c
     for (; i < nnz; i += stride) out[i] = map[col_idx[i]];
 }
 
-// Single workgroup: pofs[s] = sum_{r<s} roundup8(len_r); pofs[nseg] = padded total.
+// Single workgroup: pofs[s] = sum_{r<s} len_r rounded up to the group size; pofs[nseg] = padded total.
 __global__ __launch_bounds__(kScanThreads) void k_seg_offsets(const int64_t* __restrict__ rp, int64_t nseg,
-                                                              int32_t* __restrict__ pofs)
+                                                              int32_t* __restrict__ pofs, int group)
 {
     __shared__ int32_t wave_sums[kScanThreads / 64 + 1];
     int32_t carry = 0;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kScanThreads) void k_seg_offsets(const int64_t* __r
         if (s < nseg) {
             int64_t l = rp[s + 1] - rp[s];
             if (l < 0) l = 0;
-            len = (int32_t)((l + (kGroup - 1)) & ~(int64_t)(kGroup - 1));
+            len = (int32_t)((l + (group - 1)) & ~(int64_t)(group - 1));
         }
         int32_t total;
         int32_t pos = carry + block_exclusive_scan(len, wave_sums, total);
@@ -124,19 +124,19 @@ __device__ inline int32_t last_le(const int32_t* pofs, int32_t nseg, int32_t x)
     return lo;
 }
 
-// One thread per group of 8 padded tokens.
+// One thread per group of padded tokens.
 __global__ void k_fill_tokens(const int64_t* __restrict__ rp, const int32_t* __restrict__ col_idx, int32_t nseg,
                               const int32_t* __restrict__ pofs, const float* __restrict__ normE,
                               int32_t* __restrict__ tok_ids, float* __restrict__ tok_hn,
-                              int32_t* __restrict__ grp_seg, int64_t ngroups_alloc)
+                              int32_t* __restrict__ grp_seg, int64_t ngroups_alloc, int group)
 {
     int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= ngroups_alloc) return;
     const int32_t total = pofs[nseg];
-    const int64_t start = g * kGroup;
+    const int64_t start = g * group;
     if (start >= total) {
         grp_seg[g] = -1;
-        for (int t = 0; t < kGroup; ++t) { tok_ids[start + t] = 0; tok_hn[start + t] = 0.f; }
+        for (int t = 0; t < group; ++t) { tok_ids[start + t] = 0; tok_hn[start + t] = 0.f; }
         return;
     }
     const int32_t seg = last_le(pofs, nseg, (int32_t)start);   // equal offsets: the last one is the non-empty one
@@ -144,7 +144,7 @@ __global__ void k_fill_tokens(const int64_t* __restrict__ rp, const int32_t* __r
     const int64_t len = rp[seg + 1] - base;
     const int64_t pos0 = start - pofs[seg];
     grp_seg[g] = seg;
-    for (int t = 0; t < kGroup; ++t) {
+    for (int t = 0; t < group; ++t) {
         int64_t pos = pos0 + t;
         if (pos > len - 1) pos = len - 1;                       // pad by repeating the last word
         int32_t id = col_idx[base + pos];
@@ -258,9 +258,11 @@ size_t token_plan_bytes(int64_t nseg, int64_t nnz_batch)
     return b.used + 256;
 }
 
-bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles, int64_t padded_exact)
+bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles, int64_t padded_exact,
+                      int group)
 {
     tp.nseg = nseg;
+    tp.group = group;
     tp.tok_bound = nnz_batch + (kGroup - 1) * nseg;
     tp.tok_alloc = ((tp.tok_bound + kTileTokens - 1) / kTileTokens + 1) * kTileTokens;
     // Aim at a few thousand workgroups (vocabulary tiles x chunks) so that 256 CUs stay busy and the
@@ -281,7 +283,7 @@ bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, i
     tp.pofs = b.take_n<int32_t>((size_t)nseg + 1);
     tp.tok_ids = b.take_n<int32_t>((size_t)tp.tok_alloc);
     tp.tok_hn = b.take_n<float>((size_t)tp.tok_alloc);
-    tp.grp_seg = b.take_n<int32_t>((size_t)(tp.tok_alloc / kGroup));
+    tp.grp_seg = b.take_n<int32_t>((size_t)(tp.tok_alloc / kGroupMin));       // sized for either group size
     tp.chunk_seg = b.take_n<int32_t>((size_t)chunks_alloc);
     return b.ok;
 }
@@ -289,10 +291,10 @@ bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, i
 hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, const int32_t* col_idx,
                              const float* normE, hipStream_t s)
 {
-    k_seg_offsets<<<1, kScanThreads, 0, s>>>(row_ptr_batch, tp.nseg, tp.pofs);
-    int64_t ngroups = tp.tok_alloc / kGroup;
+    k_seg_offsets<<<1, kScanThreads, 0, s>>>(row_ptr_batch, tp.nseg, tp.pofs, tp.group);
+    int64_t ngroups = tp.tok_alloc / tp.group;
     k_fill_tokens<<<grid_for(ngroups, 256), 256, 0, s>>>(row_ptr_batch, col_idx, (int32_t)tp.nseg, tp.pofs, normE,
-                                                         tp.tok_ids, tp.tok_hn, tp.grp_seg, ngroups);
+                                                         tp.tok_ids, tp.tok_hn, tp.grp_seg, ngroups, tp.group);
     k_chunk_bounds<<<grid_for(tp.nchunks + 1, 256), 256, 0, s>>>(tp.pofs, (int32_t)tp.nseg, tp.chunk_tokens,
                                                                  tp.nchunks, tp.chunk_seg);
     return hipGetLastError();
