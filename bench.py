@@ -94,8 +94,8 @@ def main():
     ap.add_argument("--permute-vocab", action="store_true",
                     help="stress variant: renumber the vocabulary at random, so that word id is no longer frequency rank")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-dedup-variant", action="store_true",
-                    help="do not time the de-duplicated form after the default one (keeps a profile to the timed kernels)")
+    ap.add_argument("--no-dedup-variant", action="store_true", dest="no_dedup_variant",
+                    help="do not time the de-duplicated and split-bf16 forms after the default one (keeps a profile to the timed kernels)")
     ap.add_argument("--no-wmd", action="store_true",
                     help="skip the exact-WMD leg (top-k WMD with the RWMD cut-off on a slice of the same workload)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -207,6 +207,23 @@ def main():
         finally:
             ctx.set_options(compute=compute, dedup=0)
 
+    # The split-bf16 arithmetic on the same job (fp32-grade results on the bf16 matrix units), timed next to the default.
+    x3 = None
+    if args.compute == "f32" and not args.dedup and not args.no_dedup_variant and not k and not cfg.queries_from_db and m <= 300:
+        ctx.set_options(compute=binding.BF16X3, dedup=0)
+        D3 = torch.empty((n, q), dtype=torch.float32, device="cuda")
+        ctx.rwmd(qs, db, E, D3, ws)
+        torch.cuda.synchronize()
+        tv = time.perf_counter()
+        for _ in range(args.steps):
+            ctx.rwmd(qs, db, E, D3, ws)
+        torch.cuda.synchronize()
+        tv = (time.perf_counter() - tv) / args.steps
+        x3 = {"form": "compute = bf16x3 (hi*hi + hi*lo + lo*hi on the bf16 matrix units, fp32 accumulation)",
+              "ms_per_step": 1e3 * tv, "pairs_per_s": n * q / tv, "max_abs_diff_vs_default": float((D3 - D).abs().max())}
+        del D3
+        ctx.set_options(compute=compute, dedup=0)
+
     # Exact WMD behind the bound (reported, never `value`): the k nearest by WMD with the RWMD cut-off, on the first
     # 5,000 database rows and 32 queries of the same workload.
     wmd = None
@@ -284,6 +301,7 @@ def main():
                    "avg_launch_ms": p2_ms, "share_of_step": prof["phase2_ms"] / (1e3 * sec)},
         "cpu_baseline": cpu,
         "dedup_variant": variant,
+        "bf16x3_variant": x3,
         "wmd_topk": wmd,
         "time_split_ms_per_step": {"phase1": prof["phase1_ms"] / args.steps, "phase2": prof["phase2_ms"] / args.steps,
                                    "table_passes": (prof["table_fwd_ms"] + prof["table_rev_ms"]) / args.steps,
