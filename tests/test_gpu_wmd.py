@@ -133,6 +133,28 @@ def test_wmd_pairs_long_documents(ctx):
     assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], [0, 1], [0, 0]), what="WMD of 400-word documents")
 
 
+def test_wmd_largest_supported_documents(ctx):
+    """2,048 words a side is the limit: closed forms at the limit, LCRWMD_EUNSUPPORTED one word beyond it."""
+    v = 6000
+    E = synth.embeddings(v, 300, 4)
+    big = synth.corpus(1, v, 2048, 2048, 0.6, 5)
+    one = (np.array([0, 1], np.int64), np.array([11], np.int32), np.array([1.0], np.float32))
+    Eg, db, qs = upload({"E": E, "db": big, "queries": one})
+    got = run_wmd_pairs(ctx, Eg, db, qs, [0], [0], (2048, 1))
+    ptr, col, val = big
+    w = val.astype(np.float64) / val.astype(np.float64).sum()
+    ref = np.sum(w * np.linalg.norm(E[col].astype(np.float64) - E[11].astype(np.float64), axis=1))
+    assert_close(got, np.array([ref]), what="2,048 words against one word")
+    Eg, db, qs = upload({"E": E, "db": big, "queries": big})
+    got, flags = run_wmd_pairs(ctx, Eg, db, qs, [0], [0], (2048, 2048), in_flight=1, flags=True)
+    assert got[0] == 0.0 and flags[0] == 0                                   # against itself
+    too_big = synth.corpus(1, v, 2049, 2049, 0.6, 6)
+    Eg, db, qs = upload({"E": E, "db": too_big, "queries": one})
+    with pytest.raises(binding.LcrwmdError) as e:
+        run_wmd_pairs(ctx, Eg, db, qs, [0], [0], (2049, 1))
+    assert e.value.status == binding.EUNSUPPORTED
+
+
 def test_wmd_argument_checks(ctx, tiny):
     E, db, qs = upload(tiny)
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
