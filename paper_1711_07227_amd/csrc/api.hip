@@ -264,6 +264,18 @@ int64_t padded_tokens(const int64_t* rp, int64_t a, int64_t b, int group)
 // to 8.
 int plan_group(const EmbPrep& ep) { return ep.mode == 2 ? phase1_group_x3() : kGroup; }
 
+// Chunk length limit of the token plan: short where the kernel that walks runs of chunks will run (bf16 and split
+// bf16 always; fp32 where its operand shape allows), long for the other fp32 kernels.
+int plan_chunk_tiles(const EmbPrep& ep, int32_t m)
+{
+    if (ep.mode != 0) return kShortChunkTiles;
+    Phase1Args a;
+    a.E = ep.data;
+    a.ld = ep.ld;
+    a.m = m;
+    return tiles_f32_supported(a) ? kShortChunkTiles : kLongChunkTiles;
+}
+
 int64_t max_tokens_per_batch(const int64_t* rp, int64_t rows, int64_t batch)
 {
     int64_t mx = 0;
@@ -374,7 +386,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     }
 
     // ---- forward: cost of moving database docs onto the queries, D1 = X1 * Z ----
-    const int grp = plan_group(ep);
+    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep, m);
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     for (;;) {
@@ -388,7 +400,8 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1, grp), grp);
+        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1, grp), grp,
+                         chunk_tiles);
         const int64_t ldz = round_up(j1 - j0, 4);
         float* Z = bb.take_n<float>((size_t)ve * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
@@ -411,7 +424,8 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         const int64_t i1 = i0 + nb < n ? i0 + nb : n;
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], plan_tiles(nvt_r, ep.bf16), padded_tokens(rdb, i0, i1, grp), grp);
+        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], plan_tiles(nvt_r, ep.bf16), padded_tokens(rdb, i0, i1, grp), grp,
+                         chunk_tiles);
         const int64_t ldz = round_up(i1 - i0, 4);
         float* Z = bb.take_n<float>((size_t)vq * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");
@@ -602,7 +616,7 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     ST_TRY(prepare_emb(ctx, E, b, ep, s));
     TokenPlan tp;
     carve_token_plan(b, tp, queries->rows, queries->nnz, plan_tiles((E->v + kTileVocab - 1) / kTileVocab, ep.bf16), -1,
-                     plan_group(ep));
+                     plan_group(ep), plan_chunk_tiles(ep, (int32_t)E->m));
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
                            emb_prep_bytes(E->v, (int32_t)E->m, ep.mode) + token_plan_bytes(queries->rows, queries->nnz));
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,

@@ -75,8 +75,12 @@ struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
 
 // padded_exact: the exact padded token count when the caller knows the row lengths (else -1: the bound is used,
 // and the last chunks may turn out empty)
+// max_chunk_tiles: upper limit on a chunk's length in tiles of kTileTokens.  Kernels whose workgroups own one chunk
+// and reload the vocabulary operand for it want long chunks (64); the kernel that walks runs of chunks without
+// reloading balances its load in units of chunks and wants short ones (kShortChunkTiles).
+constexpr int kLongChunkTiles = 64, kShortChunkTiles = 8;
 bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles,
-                      int64_t padded_exact = -1, int group = kGroup);
+                      int64_t padded_exact = -1, int group = kGroup, int max_chunk_tiles = kLongChunkTiles);
 
 // Operand description of one first-phase launch.
 struct Phase1Args {

@@ -259,7 +259,7 @@ size_t token_plan_bytes(int64_t nseg, int64_t nnz_batch)
 }
 
 bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles, int64_t padded_exact,
-                      int group)
+                      int group, int max_chunk_tiles)
 {
     tp.nseg = nseg;
     tp.group = group;
@@ -272,7 +272,7 @@ bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, i
     int64_t ct = (tp.tok_bound + want_chunks - 1) / want_chunks;
     ct = ((ct + kTileTokens - 1) / kTileTokens) * kTileTokens;
     if (ct < 4 * kTileTokens) ct = 4 * kTileTokens;
-    if (ct > 64 * kTileTokens) ct = 64 * kTileTokens;
+    if (ct > max_chunk_tiles * kTileTokens) ct = (int64_t)max_chunk_tiles * kTileTokens;
     tp.chunk_tokens = (int32_t)ct;
     const int64_t tok_for_chunks = padded_exact >= 0 ? padded_exact : tp.tok_bound;
     tp.nchunks = (int32_t)((tok_for_chunks + ct - 1) / ct);
