@@ -78,7 +78,10 @@ struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
 // max_chunk_tiles: upper limit on a chunk's length in tiles of kTileTokens.  Kernels whose workgroups own one chunk
 // and reload the vocabulary operand for it want long chunks (64); the kernel that walks runs of chunks without
 // reloading balances its load in units of chunks and wants short ones (kShortChunkTiles).
-constexpr int kLongChunkTiles = 64, kShortChunkTiles = 8;
+#ifndef LCRWMD_SHORT_CHUNK_TILES
+#define LCRWMD_SHORT_CHUNK_TILES 8      // build-time knob for load-balance experiments
+#endif
+constexpr int kLongChunkTiles = 64, kShortChunkTiles = LCRWMD_SHORT_CHUNK_TILES;
 bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles,
                       int64_t padded_exact = -1, int group = kGroup, int max_chunk_tiles = kLongChunkTiles);
 
