@@ -62,6 +62,10 @@ struct ProfScope {
 };
 
 constexpr int64_t kMaxTokens = (int64_t)1 << 30;   // padded tokens per launch (int32 offsets)
+#ifndef LCRWMD_DB_BATCH
+#define LCRWMD_DB_BATCH 16384          // build-time knob: database rows per pass of the swapped direction
+#endif
+constexpr int64_t kDbBatch = LCRWMD_DB_BATCH;
 
 lcrwmd_status check_csr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, bool need_val)
 {
@@ -411,7 +415,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     }
 
     // ---- swapped: cost of moving the queries onto database docs, D = max(D1, (X2 * Z')^T) ----
-    int64_t nb = n < 16384 ? n : 16384;
+    int64_t nb = n < kDbBatch ? n : kDbBatch;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
     for (;;) {
         int64_t tok = max_tokens_per_batch(rdb, n, nb);
@@ -567,7 +571,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     if (k > 0 && qb > 2048) qb = 2048;
-    int64_t nb = n < 16384 ? n : 16384;
+    int64_t nb = n < kDbBatch ? n : kDbBatch;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
     const int64_t vq = v < nnz_q ? v : nnz_q;
     size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16);
