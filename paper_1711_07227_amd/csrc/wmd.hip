@@ -150,8 +150,13 @@ __device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, in
 // The grid is a set of wavefronts that take pairs off a shared counter until it passes `count`: every wavefront
 // ends because every loop below is bounded by the pair's dimensions or by the augmentation budget.
 // flags[t]: 0 solved; 1 the augmentation budget ran out (the result is then the cost of a partial flow).
+//
+// NPL > 0 (histograms of the query side of at most 64 NPL words): the potentials and the tentative distances of a
+// lane's sinks live in registers, so that settling a node touches LDS only to record a predecessor; NPL == 0: any
+// size, that state in LDS.
 // ---------------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+template <int NPL>
+__global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
                                             const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
                                             const float* __restrict__ db_val, const int64_t* __restrict__ q_rp,
                                             const int32_t* __restrict__ q_col, const float* __restrict__ q_val,
@@ -172,9 +177,12 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
     int32_t* way = par + h1max;
     uint32_t* bm = reinterpret_cast<uint32_t*>(way + h2max);        // [h2max][bm_words], bit p of row u: y[p, u] > 0
 
+    constexpr bool REG = NPL > 0;
+    constexpr int NR = REG ? NPL : 1;
     const int lane = threadIdx.x;
     float* c = slabs_c + (int64_t)blockIdx.x * slab_elems;
     double* f = slabs_f + (int64_t)blockIdx.x * slab_elems;          // f[u * h1 + p] = y[p, u]
+    double pT[NR], dTr[NR];                                          // REG: potential / distance of sink lane + 64 k
 
     for (;;) {
         wave_sync();                                                 // the previous pair's state has been read
@@ -195,6 +203,8 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
         sb = wave_sum(sb);
         for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
         for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
+#pragma unroll
+        for (int k = 0; k < NR; ++k) pT[k] = 0.0;
         for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
         for (int e = lane; e < h2 * bm_words; e += 64) bm[e] = 0u;
         wave_sync();
@@ -215,10 +225,23 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
                 {
                     const double ps = phiS[s];
                     const float* crow = c + (int64_t)s * h2;
-                    for (int u = lane; u < h2; u += 64) {
-                        double rc = (double)crow[u] + ps - phiT[u];
-                        dT[u] = rc > 0.0 ? rc : 0.0;
-                        way[u] = s;
+                    if constexpr (REG) {
+#pragma unroll
+                        for (int k = 0; k < NR; ++k) {
+                            const int u = lane + 64 * k;
+                            dTr[k] = kFar;
+                            if (u < h2) {
+                                const double rc = (double)crow[u] + ps - pT[k];
+                                dTr[k] = rc > 0.0 ? rc : 0.0;
+                                way[u] = s;
+                            }
+                        }
+                    } else {
+                        for (int u = lane; u < h2; u += 64) {
+                            double rc = (double)crow[u] + ps - phiT[u];
+                            dT[u] = rc > 0.0 ? rc : 0.0;
+                            way[u] = s;
+                        }
                     }
                 }
                 bool reached = false;
@@ -226,8 +249,14 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
                 for (int it = 0; it < h2; ++it) {
                     double bv = kFar;
                     int bi = INT_MAX;
-                    for (int u = lane, r = 0; u < h2; u += 64, ++r)
-                        if (!((used >> r) & 1) && dT[u] < bv) { bv = dT[u]; bi = u; }
+                    if constexpr (REG) {
+#pragma unroll
+                        for (int k = 0; k < NR; ++k)                // sinks past the end carry kFar
+                            if (!((used >> k) & 1) && dTr[k] < bv) { bv = dTr[k]; bi = lane + 64 * k; }
+                    } else {
+                        for (int u = lane, r = 0; u < h2; u += 64, ++r)
+                            if (!((used >> r) & 1) && dT[u] < bv) { bv = dT[u]; bi = u; }
+                    }
                     // the nearest over all lanes; of equally near sinks the one in the lowest lane
                     const double nearest = wave_min(bv);
                     const unsigned long long holders = __ballot(bi != INT_MAX && bv == nearest);
@@ -295,13 +324,26 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
                             mask &= mask - 1;
                             const double ps = phiS[pp];
                             const float* crow = c + (int64_t)pp * h2;
-                            for (int uu = lane, r = 0; uu < h2; uu += 64, ++r)
-                                if (!((used >> r) & 1)) {
-                                    double rc = (double)crow[uu] + ps - phiT[uu];
-                                    rc = rc > 0.0 ? rc : 0.0;
-                                    const double nd = bv + rc;
-                                    if (nd < dT[uu]) { dT[uu] = nd; way[uu] = pp; }
+                            if constexpr (REG) {
+#pragma unroll
+                                for (int k = 0; k < NR; ++k) {
+                                    const int uu = lane + 64 * k;
+                                    if (uu < h2 && !((used >> k) & 1)) {
+                                        double rc = (double)crow[uu] + ps - pT[k];
+                                        rc = rc > 0.0 ? rc : 0.0;
+                                        const double nd = bv + rc;
+                                        if (nd < dTr[k]) { dTr[k] = nd; way[uu] = pp; }
+                                    }
                                 }
+                            } else {
+                                for (int uu = lane, r = 0; uu < h2; uu += 64, ++r)
+                                    if (!((used >> r) & 1)) {
+                                        double rc = (double)crow[uu] + ps - phiT[uu];
+                                        rc = rc > 0.0 ? rc : 0.0;
+                                        const double nd = bv + rc;
+                                        if (nd < dT[uu]) { dT[uu] = nd; way[uu] = pp; }
+                                    }
+                            }
                         }
                     }
                 }
@@ -315,8 +357,17 @@ __global__ __launch_bounds__(64, 8) void k_emd(const void* __restrict__ E, int d
                 // (a search that went on past its last target may have settled nodes farther away: those stay)
                 for (int p = lane, r = 0; p < h1; p += 64, ++r)
                     if (((vis >> r) & 1) && dS[p] < Dt) phiS[p] += dS[p] - Dt;
-                for (int u = lane, r = 0; u < h2; u += 64, ++r)
-                    if (((used >> r) & 1) && dT[u] < Dt) phiT[u] += dT[u] - Dt;
+                if constexpr (REG) {
+#pragma unroll
+                    for (int k = 0; k < NR; ++k)
+                        if (((used >> k) & 1) && dTr[k] < Dt) {
+                            pT[k] += dTr[k] - Dt;
+                            phiT[lane + 64 * k] = pT[k];             // the copy other lanes read for a path's cost
+                        }
+                } else {
+                    for (int u = lane, r = 0; u < h2; u += 64, ++r)
+                        if (((used >> r) & 1) && dT[u] < Dt) phiT[u] += dT[u] - Dt;
+                }
                 wave_sync();
             }
         }
@@ -552,11 +603,28 @@ bool emd_supported(int64_t h1max, int64_t h2max)
 }
 
 // Wavefronts that fit the device at once for histograms of this size.
+// Sinks per lane whose state the kernel variant keeps in registers, by the longest query-side histogram: up to 128
+// words 2, up to 256 words 4, beyond that 0 (state in LDS).
+static int emd_reg_sinks(int64_t h2max) { return h2max <= 128 ? 2 : h2max <= 256 ? 4 : 0; }
+
+typedef void (*EmdKernel)(const void*, int, int64_t, int32_t, const int64_t*, const int32_t*, const float*, const int64_t*,
+                          const int32_t*, const float*, const int32_t*, const int32_t*, int64_t, int32_t*, float*, int64_t,
+                          double*, int32_t, int32_t, int32_t, float*, int32_t*, int32_t*);
+
+static EmdKernel emd_kernel(int64_t h2max)
+{
+    switch (emd_reg_sinks(h2max)) {
+    case 2: return k_emd<2>;
+    case 4: return k_emd<4>;
+    default: return k_emd<0>;
+    }
+}
+
 int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max)
 {
     int occ = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_emd, 64, emd_lds_bytes(h1max, h2max)) != hipSuccess || occ < 1)
-        occ = 1;
+    const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, emd_kernel(h2max), 64, emd_lds_bytes(h1max, h2max));
+    if (e != hipSuccess || occ < 1) occ = 1;
     return (int64_t)num_cu * occ;
 }
 
@@ -571,18 +639,20 @@ hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_cs
     const size_t elems = emd_slab_elems(h1max, h2max);
     const size_t lds = emd_lds_bytes(h1max, h2max);
     hipError_t e;
+    const EmdKernel kernel = emd_kernel(h2max);
     if (lds > 64 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_emd), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     e = launch_fill_i32(next_pair, 1, 0, s);
     if (e != hipSuccess) return e;
     double* slabs_f = reinterpret_cast<double*>(slabs);
     float* slabs_c = reinterpret_cast<float*>(slabs_f + (size_t)slots * elems);
-    k_emd<<<dim3((unsigned)slots), 64, lds, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx, DB.val,
-                                                 Q.row_ptr, Q.col_idx, Q.val, pair_db, pair_q, count, next_pair, slabs_c,
-                                                 (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max,
-                                                 emd_bitmap_words(h1max, h2max), out, flags, fail_count);
+    const int32_t bmw = emd_bitmap_words(h1max, h2max);
+    kernel<<<dim3((unsigned)slots), 64, lds, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx, DB.val,
+                                                  Q.row_ptr, Q.col_idx, Q.val, pair_db, pair_q, count, next_pair, slabs_c,
+                                                  (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max, bmw, out, flags,
+                                                  fail_count);
     return hipGetLastError();
 }
 
