@@ -205,7 +205,9 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
         for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
 #pragma unroll
         for (int k = 0; k < NR; ++k) pT[k] = 0.0;
-        for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
+        // with the map of positive flows an entry of f is read only after it has been written: no need to clear f
+        if (!bm_words)
+            for (int64_t e = lane; e < (int64_t)h1 * h2; e += 64) f[e] = 0.0;
         for (int e = lane; e < h2 * bm_words; e += 64) bm[e] = 0u;
         wave_sync();
 
@@ -286,8 +288,13 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
                         if (lane == 0) {                             // move the mass
                             int uu = u, p = way[uu];
                             for (int g = 0; g <= h1; ++g) {
-                                f[(int64_t)uu * h1 + p] += delta;
-                                if (bm_words) bm[uu * bm_words + (p >> 5)] |= 1u << (p & 31);
+                                if (bm_words) {
+                                    const uint32_t w = bm[uu * bm_words + (p >> 5)], bit = 1u << (p & 31);
+                                    f[(int64_t)uu * h1 + p] = (w & bit) ? f[(int64_t)uu * h1 + p] + delta : delta;
+                                    bm[uu * bm_words + (p >> 5)] = w | bit;
+                                } else {
+                                    f[(int64_t)uu * h1 + p] += delta;
+                                }
                                 const int up = par[p];
                                 if (up < 0) break;
                                 const double nf = f[(int64_t)up * h1 + p] - delta;
