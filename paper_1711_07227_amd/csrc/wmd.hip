@@ -3,9 +3,9 @@
 // using RWMD", "Word Centroid Distance").
 //
 // The transport problems are small (tens to hundreds of words a side) and there are many of them, so each is given
-// to one wavefront: successive shortest paths with node potentials on the dense bipartite graph, costs in fp32 as
-// produced by the cost kernel, everything the solver itself computes (potentials, path lengths, flows, the
-// objective) in fp64.  Every loop is bounded by the problem's dimensions, so every wavefront ends.
+// to one wavefront, which forms the pair's cost matrix (fp32) and then runs successive shortest paths with node
+// potentials on the dense bipartite graph; everything the solver itself computes (potentials, path lengths, flows,
+// the objective) is fp64.  Every loop is bounded by the problem's dimensions, so every wavefront ends.
 #include <float.h>
 #include <limits.h>
 
