@@ -454,3 +454,15 @@ def test_calls_on_a_side_stream_give_the_same_results(ctx, tiny):
     ctx.wmd_topk(qs, db, E, k, R_idx0, R_dist0, ws3)
     torch.cuda.synchronize()
     assert torch.equal(R_idx0, R_idx) and torch.equal(R_dist0, R_dist)
+
+
+@pytest.mark.parametrize("compute", [binding.F32, binding.BF16X3])
+def test_histograms_longer_than_a_chunk(ctx, compute):
+    """Documents of 1,500-3,000 words are longer than the 1,024-token chunks the first phase balances its load with:
+    a chunk then holds one whole histogram, and some chunks are empty."""
+    ctx.set_options(compute=compute)
+    v = 6000
+    p = {"E": synth.embeddings(v, 300, 3), "db": synth.corpus(24, v, 1500, 3000, 0.8, 4),
+         "queries": synth.corpus(3, v, 1100, 2100, 0.8, 5)}
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    assert_close(run_rwmd(ctx, *upload(p)), ref, what="very long documents")
