@@ -98,8 +98,8 @@ typedef struct {
                                        and both passes take their minima from it.  Same result as the
                                        default up to fp32 summation order.  The table lives in the
                                        workspace (4 bytes x distinct database words x distinct query
-                                       words); when it does not fit, or for fp32 E with m != 300, the call
-                                       silently runs the default form.  0 (default): distances are
+                                       words); when it does not fit, or for fp32 E with m < 208 or m > 300,
+                                       the call silently runs the default form.  0 (default): distances are
                                        recomputed per stored entry, as the paper's two phases do.      */
 } lcrwmd_options;
 

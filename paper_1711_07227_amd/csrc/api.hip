@@ -126,20 +126,42 @@ lcrwmd_status validate_on_device(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const cha
 struct EmbPrep {
     const void* data;
     int64_t ld;
+    int32_t m;     // embedding dimension the first-phase kernels are told (300 for the padded fp32 copy)
     float* normE;
     bool bf16;     // mode 1
     int mode;      // see prec_mode
 };
 
-size_t emb_prep_bytes(int64_t v, int32_t m, int mode)
+// fp32 E that the tile kernel cannot read in place (a pitch or base that is not 16-byte aligned, or 200 < m < 300):
+// a zero-padded copy with the shape that kernel takes (300 columns, 304 floats per row) is cheaper than the general
+// kernels, which reach 50-58 % of peak: measured crossover near m = 190.
+constexpr int32_t kPadM = 300, kPadPitch = 304, kPadFromM = 208;
+
+bool wants_padded_copy(const lcrwmd_emb* E)
 {
-    return (size_t)v * 4 + 256 + (mode == 1 ? pack_bf16_bytes(v, m) + 256 : mode == 2 ? pack_x3_bytes(v) + 256 : 0);
+    if (E->dtype != LCRWMD_F32 || E->m > kPadM || E->m < kPadFromM) return false;
+    Phase1Args a;
+    a.E = E->data;
+    a.ld = E->ld;
+    a.m = (int32_t)E->m;
+    return !tiles_f32_supported(a);
+}
+
+// padded: room for the zero-padded fp32 copy (wants_padded_copy; the public size query, which does not know E's
+// address, counts it for every width that may need it)
+size_t emb_prep_bytes(int64_t v, int32_t m, int mode, bool padded)
+{
+    return (size_t)v * 4 + 256 +
+           (mode == 1 ? pack_bf16_bytes(v, m) + 256
+            : mode == 2 ? pack_x3_bytes(v) + 256
+            : padded ? (size_t)v * kPadPitch * 4 + 256 : 0);
 }
 
 lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep& ep, hipStream_t s)
 {
     ep.mode = prec_mode(ctx, E);
     ep.bf16 = ep.mode == 1;
+    ep.m = (int32_t)E->m;
     ep.normE = b.take_n<float>((size_t)E->v);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the word norms");
     if (ep.mode == 2) {
@@ -159,6 +181,18 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
         ep.data = packed;
         ep.ld = bf16_pitch((int32_t)E->m);
     } else {
+        if (wants_padded_copy(E)) {
+            Bump saved = b;
+            float* packed = b.take_n<float>((size_t)E->v * kPadPitch);
+            if (b.ok) {
+                HIP_TRY(launch_pack_f32((const float*)E->data, E->v, (int32_t)E->m, E->ld, kPadPitch, packed, ep.normE, s));
+                ep.data = packed;
+                ep.ld = kPadPitch;
+                ep.m = kPadM;
+                return LCRWMD_OK;
+            }
+            b = saved;                  // no room for the copy: the general kernels read E in place
+        }
         HIP_TRY(launch_row_norms_f32((const float*)E->data, E->v, (int32_t)E->m, E->ld, ep.normE, s));
         ep.data = E->data;
         ep.ld = E->ld;
@@ -176,7 +210,7 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     Phase1Args a;
     a.E = ep.data;
     a.ld = ep.ld;
-    a.m = m;
+    a.m = ep.m;                 // what the kernel multiplies; the flop count below uses the caller's m
     a.normE = ep.normE;
     a.voc_rows = voc_rows;
     a.nvoc = nvoc;
@@ -216,9 +250,9 @@ int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 int64_t plan_tiles(int64_t nvt, bool bf16) { return bf16 ? (nvt + 7) / 8 : nvt; }
 
 // Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
-size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int mode)
+size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int mode, bool padded)
 {
-    size_t b = emb_prep_bytes(v, m, mode);
+    size_t b = emb_prep_bytes(v, m, mode, padded);
     b += 4 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position maps of both sets
     b += (size_t)(v < nnz_q ? v : nnz_q) * 4 + 256;   // word list of the queries
     b += (size_t)nnz_q * 4 + 256;             // query columns renumbered to positions
@@ -270,13 +304,13 @@ int plan_group(const EmbPrep& ep) { return ep.mode == 2 ? phase1_group_x3() : kG
 
 // Chunk length limit of the token plan: short where the kernel that walks runs of chunks will run (bf16 and split
 // bf16 always; fp32 where its operand shape allows), long for the other fp32 kernels.
-int plan_chunk_tiles(const EmbPrep& ep, int32_t m)
+int plan_chunk_tiles(const EmbPrep& ep)
 {
     if (ep.mode != 0) return kShortChunkTiles;
     Phase1Args a;
     a.E = ep.data;
     a.ld = ep.ld;
-    a.m = m;
+    a.m = ep.m;
     return tiles_f32_supported(a) ? kShortChunkTiles : kLongChunkTiles;
 }
 
@@ -339,7 +373,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         Phase1Args a;
         a.E = ep.data;
         a.ld = ep.ld;
-        a.m = m;
+        a.m = ep.m;
         a.normE = ep.normE;
         a.z_by_position = 1;
         // columns of the table: the query words dealt out over the column strips (vc places, a few of them unused)
@@ -390,7 +424,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     }
 
     // ---- forward: cost of moving database docs onto the queries, D1 = X1 * Z ----
-    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep, m);
+    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep);
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     for (;;) {
@@ -574,7 +608,8 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     int64_t nb = n < kDbBatch ? n : kDbBatch;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
     const int64_t vq = v < nnz_q ? v : nnz_q;
-    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16);
+    const bool padded = bf16 == 0 && m <= kPadM && m >= kPadFromM;
+    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded);
     size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
     size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
     size_t total = fixed + (f > r ? f : r) + 4096;
@@ -588,7 +623,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     }
     if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
     // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
-    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
+    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
     *out_bytes = total > p1 ? total : p1;
     return LCRWMD_OK;
 }
@@ -620,9 +655,10 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     ST_TRY(prepare_emb(ctx, E, b, ep, s));
     TokenPlan tp;
     carve_token_plan(b, tp, queries->rows, queries->nnz, plan_tiles((E->v + kTileVocab - 1) / kTileVocab, ep.bf16), -1,
-                     plan_group(ep), plan_chunk_tiles(ep, (int32_t)E->m));
+                     plan_group(ep), plan_chunk_tiles(ep));
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
-                           emb_prep_bytes(E->v, (int32_t)E->m, ep.mode) + token_plan_bytes(queries->rows, queries->nnz));
+                           emb_prep_bytes(E->v, (int32_t)E->m, ep.mode, wants_padded_copy(E)) +
+                               token_plan_bytes(queries->rows, queries->nnz));
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,
                       queries->nnz, tp, Z, ldz, s);
 }
@@ -709,7 +745,8 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     const int bf16 = prec_mode(ctx, E);
     for (;;) {
         size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
-        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16) +
+        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16,
+                                                                               bf16 == 0 && wants_padded_copy(E)) +
                       fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
         if (need <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query tile of D");
@@ -901,7 +938,8 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         return (size_t)n * (size_t)round_up(b, 4) * 4 + topk_bytes(n, b, k) + (size_t)b * (size_t)k * 24 + (size_t)b * 32 + 8192;
     };
     for (;;) {
-        const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode) +
+        const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode,
+                                                     mode == 0 && wants_padded_copy(E)) +
                                  fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
         const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 2 + 8192;    // first k lists, a problem in flight
         if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;

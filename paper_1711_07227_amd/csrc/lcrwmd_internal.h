@@ -102,6 +102,9 @@ struct Phase1Args {
 // prep.hip
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s);
 hipError_t launch_row_norms_f32(const float* E, int64_t v, int32_t m, int64_t ld, float* normE, hipStream_t s);
+// copy of E with `pitch` >= m floats per row (zeros beyond column m) and the squared norms
+hipError_t launch_pack_f32(const float* E, int64_t v, int32_t m, int64_t ld, int32_t pitch, float* packed, float* normE,
+                           hipStream_t s);
 hipError_t launch_mark_words(const int32_t* col_idx, int64_t nnz, int32_t* flags, hipStream_t s);
 // list[pos] = w and map[w] = pos for flagged words (map[w] = -1 otherwise); *count = number flagged
 hipError_t launch_compact_words(const int32_t* flags, int64_t v, int32_t* list, int32_t* map, int32_t* count,

@@ -31,6 +31,25 @@ __global__ __launch_bounds__(256) void k_row_norms_f32(const float* __restrict__
     if (lane == 0) normE[w] = s;
 }
 
+// One wavefront per row: a copy of E with `pitch` floats per row, zeros beyond column m, and the squared norms.
+__global__ __launch_bounds__(256) void k_pack_f32(const float* __restrict__ E, int64_t v, int32_t m, int64_t ld,
+                                                  int32_t pitch, float* __restrict__ packed, float* __restrict__ normE)
+{
+    const int lane = threadIdx.x & 63;
+    int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= v) return;
+    const float* row = E + w * ld;
+    float* out = packed + w * pitch;
+    float s = 0.f;
+    for (int t = lane; t < pitch; t += 64) {
+        const float x = t < m ? row[t] : 0.f;
+        out[t] = x;
+        s = fmaf(x, x, s);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) normE[w] = s;
+}
+
 __global__ void k_mark_words(const int32_t* __restrict__ col_idx, int64_t nnz, int32_t* __restrict__ flags)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -226,6 +245,14 @@ hipError_t launch_row_norms_f32(const float* E, int64_t v, int32_t m, int64_t ld
 {
     if (v <= 0) return hipSuccess;
     k_row_norms_f32<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, v, m, ld, normE);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_f32(const float* E, int64_t v, int32_t m, int64_t ld, int32_t pitch, float* packed, float* normE,
+                           hipStream_t s)
+{
+    if (v <= 0) return hipSuccess;
+    k_pack_f32<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, v, m, ld, pitch, packed, normE);
     return hipGetLastError();
 }
 

@@ -460,9 +460,38 @@ def test_calls_on_a_side_stream_give_the_same_results(ctx, tiny):
 def test_histograms_longer_than_a_chunk(ctx, compute):
     """Documents of 1,500-3,000 words are longer than the 1,024-token chunks the first phase balances its load with:
     a chunk then holds one whole histogram, and some chunks are empty."""
-    ctx.set_options(compute=compute)
     v = 6000
     p = {"E": synth.embeddings(v, 300, 3), "db": synth.corpus(24, v, 1500, 3000, 0.8, 4),
          "queries": synth.corpus(3, v, 1100, 2100, 0.8, 5)}
     ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
-    assert_close(run_rwmd(ctx, *upload(p)), ref, what="very long documents")
+    ctx.set_options(compute=compute)
+    try:
+        got = run_rwmd(ctx, *upload(p))
+    finally:
+        ctx.set_options()                                    # the context is shared by the tests of this module
+    assert_close(got, ref, what="very long documents")
+
+
+@pytest.mark.parametrize("m,pitch,offset", [(300, 301, 0), (300, 304, 1), (256, 256, 0), (208, 211, 0), (299, 300, 0)])
+def test_fp32_shapes_served_by_the_padded_copy(ctx, m, pitch, offset):
+    """fp32 E that the tile kernel cannot read in place (odd pitch, unaligned base, 208 <= m < 300) goes through a
+    zero-padded copy; a workspace without room for the copy falls back to the general kernels.  Same results."""
+    ctx.set_options()
+    v = 1500
+    p = {"E": synth.embeddings(v, m, 11), "db": synth.corpus(400, v, 1, 60, 1.1, 12),
+         "queries": synth.corpus(9, v, 1, 60, 1.1, 13)}
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    flat = torch.zeros(v * pitch + 8, dtype=torch.float32, device="cuda")
+    view = flat[offset:offset + v * pitch].view(v, pitch)[:, :m]
+    view.copy_(torch.from_numpy(p["E"]).cuda())
+    db = binding.Csr.from_numpy(p["db"], v)
+    qs = binding.Csr.from_numpy(p["queries"], v)
+    full = ctx.workspace_bytes(v, m, db.rows, db.nnz, qs.rows, qs.nnz)
+    assert_close(run_rwmd(ctx, view, db, qs, ws_bytes=full), ref, what=f"m={m} pitch={pitch} offset={offset}")
+    # without the copy's share of the workspace the call still succeeds (general kernels) with the same result
+    assert_close(run_rwmd(ctx, view, db, qs, ws_bytes=full - v * 304 * 4), ref, what="no room for the copy")
+    # the stand-alone first phase takes the same route
+    Z = torch.full((v, 12), -1.0, dtype=torch.float32, device="cuda")
+    ctx.phase1_mindist(view, qs, Z, binding.alloc_workspace(full))
+    torch.cuda.synchronize()
+    assert_close(Z.cpu().numpy()[:, :9], oracle.phase1(p["E"], p["queries"]), what="Z through the padded copy")
