@@ -80,7 +80,9 @@ typedef struct {
                                        LCRWMD_F32 (default for fp32 E): fp32 MFMA.  LCRWMD_BF16: E is
                                        rounded to bf16 (round-to-nearest-even) unless already bf16,
                                        products accumulate in fp32.  bf16 E always computes in bf16.
-                                       The bf16 path needs m <= 300 (LCRWMD_EUNSUPPORTED otherwise).
+                                       The bf16 kernels take m <= 300; wider embeddings are computed in
+                                       fp32 on an fp32 copy of the bf16 values (same results, workspace
+                                       4 v m bytes more).
                                        LCRWMD_BF16X3 (fp32 E, m <= 300; otherwise it means
                                        LCRWMD_F32): every fp32 value x is split into hi = bf16(x) and
                                        lo = bf16(x - hi) and a product is taken as hi*hi + hi*lo + lo*hi

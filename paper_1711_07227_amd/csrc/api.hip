@@ -100,14 +100,19 @@ lcrwmd_status check_ws(lcrwmd_ctx* ctx, const void* ws, size_t ws_bytes)
 
 bool use_bf16(const lcrwmd_ctx* ctx, const lcrwmd_emb* E) { return E->dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16; }
 
-// Arithmetic of the first phase: 0 fp32, 1 bf16, 2 split bf16 (three products per fp32 product).  The split form
-// exists for fp32 E with m <= 300; anything else that asks for it computes in fp32.
+// Arithmetic of the first phase: 0 fp32, 1 bf16, 2 split bf16 (three products per fp32 product).  The bf16 kernels
+// take m <= 300.  Wider embeddings compute in fp32: the split form on E as it is, the bf16 form on an fp32 copy of the
+// values as bf16 numbers (products of bf16 values are exact in fp32, so the results are those the bf16 form defines).
 int prec_mode(const lcrwmd_ctx* ctx, const lcrwmd_emb* E)
 {
+    if (E->m > 300) return 0;
     if (use_bf16(ctx, E)) return 1;
-    if (ctx->opt.compute == LCRWMD_BF16X3 && E->m <= 300) return 2;
+    if (ctx->opt.compute == LCRWMD_BF16X3) return 2;
     return 0;
 }
+
+// bf16 was asked for (storage or compute option) but the embeddings are too wide for the bf16 kernels
+bool wants_widened_copy(const lcrwmd_ctx* ctx, const lcrwmd_emb* E) { return E->m > 300 && use_bf16(ctx, E); }
 
 lcrwmd_status validate_on_device(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, int32_t* dev_status,
                                  hipStream_t s)
@@ -149,12 +154,14 @@ bool wants_padded_copy(const lcrwmd_emb* E)
 
 // padded: room for the zero-padded fp32 copy (wants_padded_copy; the public size query, which does not know E's
 // address, counts it for every width that may need it)
-size_t emb_prep_bytes(int64_t v, int32_t m, int mode, bool padded)
+// widened: room for the fp32 copy of bf16-valued embeddings wider than the bf16 kernels take
+size_t emb_prep_bytes(int64_t v, int32_t m, int mode, bool padded, bool widened = false)
 {
     return (size_t)v * 4 + 256 +
            (mode == 1 ? pack_bf16_bytes(v, m) + 256
             : mode == 2 ? pack_x3_bytes(v) + 256
-            : padded ? (size_t)v * kPadPitch * 4 + 256 : 0);
+            : padded ? (size_t)v * kPadPitch * 4 + 256
+            : widened ? (size_t)v * (size_t)m * 4 + 256 : 0);
 }
 
 lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep& ep, hipStream_t s)
@@ -173,13 +180,18 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
         return LCRWMD_OK;
     }
     if (ep.bf16) {
-        if (!bf16_supported((int32_t)E->m))
-            return fail(ctx, LCRWMD_EUNSUPPORTED, "the bf16 path supports m <= 300 (got %lld)", (long long)E->m);
         void* packed = b.take(pack_bf16_bytes(E->v, (int32_t)E->m));
         if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the bf16 copy of E");
         HIP_TRY(launch_pack_bf16(E->data, E->dtype, E->v, (int32_t)E->m, E->ld, packed, ep.normE, s));
         ep.data = packed;
         ep.ld = bf16_pitch((int32_t)E->m);
+    } else if (wants_widened_copy(ctx, E)) {
+        float* wide = b.take_n<float>((size_t)E->v * (size_t)E->m);
+        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the fp32 copy of the wide embeddings");
+        HIP_TRY(launch_widen_bf16(E->data, E->dtype, E->v, (int32_t)E->m, E->ld, wide, s));
+        HIP_TRY(launch_row_norms_f32(wide, E->v, (int32_t)E->m, E->m, ep.normE, s));
+        ep.data = wide;
+        ep.ld = E->m;
     } else {
         if (wants_padded_copy(E)) {
             Bump saved = b;
@@ -250,9 +262,9 @@ int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 int64_t plan_tiles(int64_t nvt, bool bf16) { return bf16 ? (nvt + 7) / 8 : nvt; }
 
 // Fixed part of the workspace of lcrwmd_rwmd (everything but the per-batch region).
-size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int mode, bool padded)
+size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int mode, bool padded, bool widened = false)
 {
-    size_t b = emb_prep_bytes(v, m, mode, padded);
+    size_t b = emb_prep_bytes(v, m, mode, padded, widened);
     b += 4 * ((size_t)v * 4 + 256);           // flags, word list of the database, word -> position maps of both sets
     b += (size_t)(v < nnz_q ? v : nnz_q) * 4 + 256;   // word list of the queries
     b += (size_t)nnz_q * 4 + 256;             // query columns renumbered to positions
@@ -600,8 +612,9 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
     if (v <= 0 || m <= 0 || n < 0 || nnz_db < 0 || q < 0 || nnz_q < 0 || k < 0)
         return fail(ctx, LCRWMD_EINVAL, "negative size");
-    const int bf16 = (emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16) ? 1
-                     : (ctx->opt.compute == LCRWMD_BF16X3 && m <= 300) ? 2 : 0;     // see prec_mode
+    const bool asks_bf16 = emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16;
+    const int bf16 = m > 300 ? 0 : asks_bf16 ? 1 : ctx->opt.compute == LCRWMD_BF16X3 ? 2 : 0;     // see prec_mode
+    const bool widened = m > 300 && asks_bf16;
     int64_t qb = q;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     if (k > 0 && qb > 2048) qb = 2048;
@@ -609,7 +622,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
     const int64_t vq = v < nnz_q ? v : nnz_q;
     const bool padded = bf16 == 0 && m <= kPadM && m >= kPadFromM;
-    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded);
+    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded, widened);
     size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
     size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
     size_t total = fixed + (f > r ? f : r) + 4096;
@@ -623,7 +636,7 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     }
     if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
     // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
-    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
+    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded, widened) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
     *out_bytes = total > p1 ? total : p1;
     return LCRWMD_OK;
 }
@@ -657,7 +670,7 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     carve_token_plan(b, tp, queries->rows, queries->nnz, plan_tiles((E->v + kTileVocab - 1) / kTileVocab, ep.bf16), -1,
                      plan_group(ep), plan_chunk_tiles(ep));
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
-                           emb_prep_bytes(E->v, (int32_t)E->m, ep.mode, wants_padded_copy(E)) +
+                           emb_prep_bytes(E->v, (int32_t)E->m, ep.mode, wants_padded_copy(E), wants_widened_copy(ctx, E)) +
                                token_plan_bytes(queries->rows, queries->nnz));
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,
                       queries->nnz, tp, Z, ldz, s);
@@ -746,7 +759,7 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     for (;;) {
         size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
         size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16,
-                                                                               bf16 == 0 && wants_padded_copy(E)) +
+                                                                               bf16 == 0 && wants_padded_copy(E), wants_widened_copy(ctx, E)) +
                       fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
         if (need <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query tile of D");
@@ -939,7 +952,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
     };
     for (;;) {
         const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode,
-                                                     mode == 0 && wants_padded_copy(E)) +
+                                                     mode == 0 && wants_padded_copy(E), wants_widened_copy(ctx, E)) +
                                  fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
         const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 2 + 8192;    // first k lists, a problem in flight
         if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;

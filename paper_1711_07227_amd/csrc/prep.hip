@@ -50,6 +50,24 @@ __global__ __launch_bounds__(256) void k_pack_f32(const float* __restrict__ E, i
     if (lane == 0) normE[w] = s;
 }
 
+// fp32 copy (pitch m) of bf16-valued embeddings: bf16 storage widened, or fp32 storage rounded to bf16 (nearest even).
+__global__ void k_widen_bf16(const void* __restrict__ E, int is_bf16, int64_t v, int32_t m, int64_t ld, float* __restrict__ out)
+{
+    const int64_t total = v * m;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t w = e / m;
+        const int32_t t = (int32_t)(e - w * m);
+        uint32_t bits;
+        if (is_bf16) {
+            bits = (uint32_t)reinterpret_cast<const uint16_t*>(E)[w * ld + t] << 16;
+        } else {
+            const uint32_t u = __float_as_uint(reinterpret_cast<const float*>(E)[w * ld + t]);
+            bits = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
+        }
+        out[e] = __uint_as_float(bits);
+    }
+}
+
 __global__ void k_mark_words(const int32_t* __restrict__ col_idx, int64_t nnz, int32_t* __restrict__ flags)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -253,6 +271,13 @@ hipError_t launch_pack_f32(const float* E, int64_t v, int32_t m, int64_t ld, int
 {
     if (v <= 0) return hipSuccess;
     k_pack_f32<<<(unsigned)((v + 3) / 4), 256, 0, s>>>(E, v, m, ld, pitch, packed, normE);
+    return hipGetLastError();
+}
+
+hipError_t launch_widen_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_t m, int64_t ld, float* out, hipStream_t s)
+{
+    if (v <= 0) return hipSuccess;
+    k_widen_bf16<<<grid_for(v * m, 256, 16384), 256, 0, s>>>(E, dtype == LCRWMD_BF16 ? 1 : 0, v, m, ld, out);
     return hipGetLastError();
 }
 

@@ -391,13 +391,24 @@ def test_rwmd_bf16_tiny_and_ragged(ctx, tiny):
         assert_close(got, ref_exact, rtol=2e-2, what="bf16 D vs oracle on fp32 E")
 
 
-def test_bf16_rejects_wide_embeddings(ctx):
-    E = torch.zeros((10, 400), dtype=torch.bfloat16, device="cuda")
-    qs = binding.Csr.from_numpy(synth.corpus(2, 10, 1, 3, 1.0, 1), 10)
-    Z = torch.zeros((10, 2), dtype=torch.float32, device="cuda")
-    with pytest.raises(binding.LcrwmdError) as e:
-        ctx.phase1_mindist(E, qs, Z, binding.alloc_workspace(1 << 20))
-    assert e.value.status == binding.EUNSUPPORTED
+def test_bf16_wide_embeddings_run_in_fp32_on_the_rounded_values(ctx):
+    """The bf16 kernels take m <= 300; wider embeddings in bf16 (storage or compute option) go through an fp32 copy of
+    the bf16 values: same definition of the result."""
+    v, m = 600, 400
+    p = problem(v, m, 120, 7, 1, 30, seed=41)
+    Er = synth.bf16_bits_to_f32(synth.to_bf16_bits(p["E"]))
+    ref = oracle.rwmd_table(Er, p["db"], p["queries"])
+    db = binding.Csr.from_numpy(p["db"], v)
+    qs = binding.Csr.from_numpy(p["queries"], v)
+    Eb = torch.from_numpy(Er).cuda().to(torch.bfloat16)
+    got = run_rwmd(ctx, Eb, db, qs, emb_dtype=binding.BF16)
+    assert_close(got, ref, what="bf16 storage, m = 400")
+    ctx.set_options(compute=binding.BF16)
+    try:
+        got = run_rwmd(ctx, torch.from_numpy(p["E"]).cuda(), db, qs)
+    finally:
+        ctx.set_options()
+    assert_close(got, ref, what="fp32 storage with the bf16 compute option, m = 400")
 
 
 # ------------------------------------------------------------------------------------------- full-size workload
