@@ -177,6 +177,43 @@ def test_wmd_argument_checks(ctx, tiny):
     assert e.value.status == binding.EUNSUPPORTED
 
 
+def test_wcd_and_wmd_error_codes(ctx, tiny):
+    E, db, qs = upload(tiny)
+    n, q = db.rows, qs.rows
+    D = torch.empty((n, q), dtype=torch.float32, device="cuda")
+    ws = binding.alloc_workspace(1 << 24)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wcd(qs, db, E, D, None)
+    assert e.value.status == binding.EWORKSPACE
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wcd(qs, db, E, D, ws[:1024])                        # no room for the centroids
+    assert e.value.status == binding.EWORKSPACE
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wcd(qs, db, E, torch.empty((n, 4), dtype=torch.float32, device="cuda"), ws)      # ldd < q
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wcd(qs, db, E[:50], D, ws)                          # histogram columns != v
+    assert e.value.status == binding.EINVAL
+    R_idx = torch.zeros((q, 3), dtype=torch.int32, device="cuda")
+    R_dist = torch.zeros((q, 3), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_topk(qs, db, E, 0, R_idx, R_dist, ws)
+    assert e.value.status == binding.EINVAL
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_topk(qs, db, E, 65, torch.zeros((q, 65), dtype=torch.int32, device="cuda"),
+                     torch.zeros((q, 65), dtype=torch.float32, device="cuda"), ws)
+    assert e.value.status == binding.EUNSUPPORTED
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.wmd_topk(qs, db, E, 3, R_idx, R_dist, ws[:65536])
+    assert e.value.status == binding.EWORKSPACE
+    with pytest.raises(binding.LcrwmdError):
+        ctx.wmd_pairs_workspace_bytes(0, 5, 1)
+    # a context that has seen errors keeps working
+    ctx.wcd(qs, db, E, D, binding.alloc_workspace((n + q) * 300 * 4 + 1024))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(D).all())
+
+
 def test_wcd_against_oracle(ctx, tiny):
     E, db, qs = upload(tiny)
     ws = binding.alloc_workspace((db.rows + qs.rows) * 300 * 4 + 1024)
