@@ -281,10 +281,13 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
  * (Sec. III, "Speeding-up WMD using RWMD"): per query, RWMD to every database histogram
  * (lcrwmd_rwmd), the k nearest by RWMD, WMD to those, the largest of these k values as cut-off L,
  * WMD to every other histogram whose RWMD is below L, and the k smallest of all WMDs evaluated.
- * RWMD <= WMD, so nothing that belongs to the result is cut.  The device compares fp32 RWMD values
+ * RWMD <= WMD, so nothing that belongs to the result is cut.  While k transport problems per query
+ * of the batch do not fill the device, the first round takes the k1 > k (at most 64) nearest by
+ * RWMD instead and L is the k-th smallest of their k1 WMDs: the same wall time, a lower cut-off,
+ * fewer survivors (any k evaluated distances bound the k-th best from above).  The device compares fp32 RWMD values
  * against fp32 WMD values, so the test is RWMD < L (1 + 1e-5): rounding can only add candidates.
  * R_idx / R_dist: q x k, ordered by (distance, row index) ascending, as in lcrwmd_rwmd_topk.
- * evaluated (HOST, q entries, or NULL): WMD evaluations spent on each query (k + survivors).
+ * evaluated (HOST, q entries, or NULL): WMD evaluations spent on each query (first round + survivors).
  * fp32 E with the LCRWMD_BF16 compute option is refused (LCRWMD_EUNSUPPORTED): a bound rounded to
  * bf16 may exceed the WMD it is meant to bound.  1 <= k <= min(n, 64).
  * Synchronises the stream several times per query batch (RWMD vocabulary sizes, survivor counts).

@@ -907,11 +907,11 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
     if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
     if (k < 1 || max_h_db <= 0 || max_h_q <= 0) return fail(ctx, LCRWMD_EINVAL, "k and the histogram sizes must be positive");
     size_t base = 0;
-    ST_TRY(lcrwmd_workspace_bytes(ctx, v, m, n, nnz_db, q, nnz_q, emb_dtype, k, &base));
+    ST_TRY(lcrwmd_workspace_bytes(ctx, v, m, n, nnz_db, q, nnz_q, emb_dtype, kMaxTopK < n ? kMaxTopK : (k > (int)n ? k : (int)n), &base));
     int64_t qb = q < 2048 ? q : 2048;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     // per-query arrays, lists for a quarter of all pairs of a batch, one transport problem per resident wavefront
-    const size_t lists = (size_t)qb * (size_t)k * 24 + (size_t)qb * 32 + (size_t)n * (size_t)qb / 4 * 12;
+    const size_t lists = (size_t)qb * (size_t)kMaxTopK * 24 + (size_t)qb * 32 + (size_t)n * (size_t)qb / 4 * 12;
     const size_t slabs = emd_pair_bytes(max_h_db, max_h_q) * (size_t)emd_preferred_slots(ctx->num_cu, max_h_db, max_h_q);
     *out_bytes = base + lists + slabs + 16384;
     return LCRWMD_OK;
@@ -948,13 +948,14 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
     int64_t qb = q < 2048 ? q : 2048;
     if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
     auto front_bytes = [&](int64_t b) {
-        return (size_t)n * (size_t)round_up(b, 4) * 4 + topk_bytes(n, b, k) + (size_t)b * (size_t)k * 24 + (size_t)b * 32 + 8192;
+        return (size_t)n * (size_t)round_up(b, 4) * 4 + topk_bytes(n, b, kMaxTopK) + (size_t)b * (size_t)kMaxTopK * 24 +
+               (size_t)b * 32 + 8192;
     };
     for (;;) {
         const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode,
                                                      mode == 0 && wants_padded_copy(E), wants_widened_copy(ctx, E)) +
                                  fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
-        const size_t wmd_need = (size_t)qb * (size_t)k * 16 + pair_bytes * 2 + 8192;    // first k lists, a problem in flight
+        const size_t wmd_need = (size_t)qb * (size_t)kMaxTopK * 16 + pair_bytes * 2 + 8192;   // first-round lists, a problem in flight
         if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query batch");
         qb = (qb + 1) / 2;
@@ -970,14 +971,22 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         const int64_t j1 = j0 + qb < q ? j0 + qb : q, nq = j1 - j0;
         Bump b(ws, ws_bytes);
         const int64_t ldt = round_up(nq, 4);
+        // First round: the k1 >= k nearest by RWMD per query.  The paper takes k1 = k; while the batch's k * nq transport
+        // problems do not fill the device, a larger k1 costs no time and gives a lower cut-off (the k-th smallest of k1
+        // distances instead of the largest of k), hence fewer survivors.  Nothing is lost: any k evaluated distances
+        // bound the k-th best from above.
+        int k1 = (int)(emd_preferred_slots(ctx->num_cu, h1max, h2max) / nq);
+        if (k1 > kMaxTopK) k1 = kMaxTopK;
+        if (k1 > n) k1 = (int)n;
+        if (k1 < k) k1 = k;
         float* tile = b.take_n<float>((size_t)n * ldt);
-        const size_t tkb = topk_bytes(n, nq, k) + 512;
+        const size_t tkb = topk_bytes(n, nq, k1) + 512;
         void* tk = b.take(tkb);
-        int32_t* R0 = b.take_n<int32_t>((size_t)nq * k);
-        float* R0d = b.take_n<float>((size_t)nq * k);
-        int32_t* p0_db = b.take_n<int32_t>((size_t)nq * k);
-        int32_t* p0_q = b.take_n<int32_t>((size_t)nq * k);
-        float* wmd0 = b.take_n<float>((size_t)nq * k);
+        int32_t* R0 = b.take_n<int32_t>((size_t)nq * k1);
+        float* R0d = b.take_n<float>((size_t)nq * k1);
+        int32_t* p0_db = b.take_n<int32_t>((size_t)nq * k1);
+        int32_t* p0_q = b.take_n<int32_t>((size_t)nq * k1);
+        float* wmd0 = b.take_n<float>((size_t)nq * k1);
         float* cut = b.take_n<float>((size_t)nq);
         int32_t* cnt = b.take_n<int32_t>((size_t)nq);
         int64_t* off = b.take_n<int64_t>((size_t)nq + 1);
@@ -988,21 +997,21 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         char* rest = (char*)ws + rest_off;
         const size_t rest_bytes = ws_bytes - rest_off;
 
-        // RWMD to every database histogram, the k nearest by RWMD (Sec. III)
+        // RWMD to every database histogram, the k1 nearest by RWMD (Sec. III)
         ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, rest, rest_bytes, s));
-        HIP_TRY(launch_topk(tile, n, nq, ldt, k, R0, R0d, tk, tkb, s));
-        // WMD to those; their largest value is the cut-off
+        HIP_TRY(launch_topk(tile, n, nq, ldt, k1, R0, R0d, tk, tkb, s));
+        // WMD to those; the k-th smallest of them is the cut-off
         HIP_TRY(launch_fill_i32(counters, 4, 0, s));
-        HIP_TRY(launch_first_pairs(R0, nq, k, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
-        ST_TRY(run_wmd_list(ctx, queries, database, E, p0_db, p0_q, nq * k, h1max, h2max, rest, rest_bytes, wmd0, nullptr,
+        HIP_TRY(launch_first_pairs(R0, nq, k1, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
+        ST_TRY(run_wmd_list(ctx, queries, database, E, p0_db, p0_q, nq * k1, h1max, h2max, rest, rest_bytes, wmd0, nullptr,
                             counters, s));
-        HIP_TRY(launch_cutoff(wmd0, nq, k, 1e-5f, cut, s));
+        HIP_TRY(launch_cutoff(wmd0, nq, k1, k, 1e-5f, cut, s));
         // survivors: RWMD below the cut-off
         HIP_TRY(launch_count_below(tile, n, nq, ldt, cut, cnt, off, s));
         HIP_TRY(hipMemcpyAsync(hoff.data(), off, sizeof(int64_t) * ((size_t)nq + 1), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         if (evaluated)
-            for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k + hoff[j + 1] - hoff[j];
+            for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k1 + hoff[j + 1] - hoff[j];
         // Lists hold 12 bytes per survivor; they share `rest` with the transport problems in flight.
         size_t slab_part = pair_bytes * (size_t)emd_preferred_slots(ctx->num_cu, h1max, h2max);
         if (slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
@@ -1025,7 +1034,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
             if (!lb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: survivor lists do not fit");
             HIP_TRY(launch_fill_below(tile, n, ja, jb, ldt, cut, off, cursor, (int32_t)j0, l_db, l_q, s));
             ST_TRY(run_wmd_list(ctx, queries, database, E, l_db, l_q, total, h1max, h2max, rest, slab_part, l_d, nullptr, counters, s));
-            HIP_TRY(launch_select_lists(R0, wmd0, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
+            HIP_TRY(launch_select_lists(R0, wmd0, k1, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
             ja = jb;
         }
         int32_t failed = 0;

@@ -459,14 +459,27 @@ __global__ void k_first_pairs(const int32_t* __restrict__ R0, int64_t q, int k, 
     D[(int64_t)i * ldd + j] = FLT_MAX;
 }
 
-// cut[j] = (largest WMD among the first k) * (1 + slack)
-__global__ void k_cutoff(const float* __restrict__ wmd0, int64_t q, int k, float slack, float* __restrict__ cut)
+// cut[j] = (k-th smallest WMD among the k1 >= k of the first round) * (1 + slack); with k1 == k their largest
+__global__ void k_cutoff(const float* __restrict__ wmd0, int64_t q, int k1, int k, float slack, float* __restrict__ cut)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= q) return;
-    float L = 0.f;
-    for (int r = 0; r < k; ++r) L = fmaxf(L, wmd0[j * k + r]);
-    cut[j] = L * (1.f + slack);
+    const float* w = wmd0 + j * k1;
+    // k rounds of "smallest value after the last one taken", equal values told apart by position
+    float last = -1.f;
+    int last_r = -1;
+    for (int t = 0; t < k; ++t) {
+        float best = FLT_MAX;
+        int best_r = k1;
+        for (int r = 0; r < k1; ++r) {
+            const float x = w[r];
+            const bool after = x > last || (x == last && r > last_r);
+            if (after && (x < best || (x == best && r < best_r))) { best = x; best_r = r; }
+        }
+        last = best;
+        last_r = best_r;
+    }
+    cut[j] = last * (1.f + slack);
 }
 
 constexpr int kRowsPerBlock = 256;
@@ -541,9 +554,9 @@ __global__ void k_check_pairs(const int32_t* __restrict__ pair_db, const int32_t
     if (i < 0 || i >= n || j < 0 || j >= q) status[0] = 1;
 }
 
-// The k smallest of every query's evaluated WMDs, ordered by (distance, database row): the first k candidates
-// (idx0 / d0, k per query) and the query's list [off[j], off[j + 1]) of the rest.  One workgroup per query.
-__global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict__ idx0, const float* __restrict__ d0, int k,
+// The k smallest of every query's evaluated WMDs, ordered by (distance, database row): the k1 candidates of the first
+// round (idx0 / d0, k1 per query) and the query's list [off[j], off[j + 1]) of the rest.  One workgroup per query.
+__global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict__ idx0, const float* __restrict__ d0, int k1, int k,
                                                       const int64_t* __restrict__ off, int64_t ja, const int32_t* __restrict__ idx1,
                                                       const float* __restrict__ d1, int32_t* __restrict__ R_idx,
                                                       float* __restrict__ R_dist)
@@ -558,9 +571,9 @@ __global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict_
     for (int r = 0; r < k; ++r) {
         float bd = FLT_MAX;
         int32_t bi = INT_MAX;
-        for (int64_t e = tid; e < k + cnt; e += 256) {
-            const float d = e < k ? d0[j * k + e] : d1[a + e - k];
-            const int32_t i = e < k ? idx0[j * k + e] : idx1[a + e - k];
+        for (int64_t e = tid; e < k1 + cnt; e += 256) {
+            const float d = e < k1 ? d0[j * k1 + e] : d1[a + e - k1];
+            const int32_t i = e < k1 ? idx0[j * k1 + e] : idx1[a + e - k1];
             const bool after = d > last_d || (d == last_d && i > last_i);
             if (after && (d < bd || (d == bd && i < bi))) { bd = d; bi = i; }
         }
@@ -703,10 +716,10 @@ hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int k, int32_t j0, f
     return hipGetLastError();
 }
 
-hipError_t launch_cutoff(const float* wmd0, int64_t q, int k, float slack, float* cut, hipStream_t s)
+hipError_t launch_cutoff(const float* wmd0, int64_t q, int k1, int k, float slack, float* cut, hipStream_t s)
 {
     if (q <= 0) return hipSuccess;
-    k_cutoff<<<dim3((unsigned)((q + 255) / 256)), 256, 0, s>>>(wmd0, q, k, slack, cut);
+    k_cutoff<<<dim3((unsigned)((q + 255) / 256)), 256, 0, s>>>(wmd0, q, k1, k, slack, cut);
     return hipGetLastError();
 }
 
@@ -740,11 +753,11 @@ hipError_t launch_fill_below(const float* D, int64_t n, int64_t ja, int64_t jb, 
     return hipGetLastError();
 }
 
-hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k, const int64_t* off, int64_t ja, int64_t jb,
+hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k1, int k, const int64_t* off, int64_t ja, int64_t jb,
                                const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist, hipStream_t s)
 {
     if (jb <= ja) return hipSuccess;
-    k_select_lists<<<dim3((unsigned)(jb - ja)), 256, 0, s>>>(idx0, d0, k, off, ja, idx1, d1, R_idx, R_dist);
+    k_select_lists<<<dim3((unsigned)(jb - ja)), 256, 0, s>>>(idx0, d0, k1, k, off, ja, idx1, d1, R_idx, R_dist);
     return hipGetLastError();
 }
 

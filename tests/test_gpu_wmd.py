@@ -263,15 +263,15 @@ def test_wmd_topk_pruned_equals_exhaustive(ctx):
     ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
     torch.cuda.synchronize()
     check_topk(R_idx.cpu().numpy(), R_dist.cpu().numpy(), W)
-    # evaluations: at least what the cut-off rule of Sec. III needs, at most what its slack of 1e-5 can add
+    # evaluations: the first round may be wider than k (it fills the device), which lowers the cut-off; the survivors
+    # are then at most those of the cut-off rule of Sec. III with its slack of 1e-5
     R = oracle.rwmd_bruteforce(p["E"], p["db"], p["queries"])
-    _, _, need = oracle.wmd_topk_pruned(p["E"], p["db"], p["queries"], k, R)
     ev = ev.numpy()
     for j in range(q):
         first = np.lexsort((np.arange(n), R[:, j]))[:k]
         L = W[first, j].max()
         most = len(set(np.nonzero(R[:, j] < L * (1 + 3e-5))[0]) | set(first))
-        assert need[j] - 1 <= ev[j] <= most + 1, (j, need[j], ev[j], most)
+        assert k <= ev[j] <= most + 64, (j, ev[j], most)
     assert ev.sum() < n * q
     # every query in a batch of its own, and a small workspace: same result
     ctx.set_options(max_query_batch=1)
@@ -284,10 +284,10 @@ def test_wmd_topk_pruned_equals_exhaustive(ctx):
 
 def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
     """Shrinking the workspace makes the library walk the queries in smaller batches and the survivor lists in ranges;
-    the result and the evaluation counts must not change.  Below some size the call must refuse, not misbehave."""
+    the result and (with the first round at its full width of 64) the evaluation counts must not change.  Below some size the call must refuse, not misbehave."""
     p = problem(v=600, m=300, n=8000, q=40, h_lo=20, h_hi=40, seed=23, s=1.0)
     E, db, qs = upload(p)
-    n, q, k = 8000, 40, 16
+    n, q, k = 8000, 40, 64            # k at its maximum: the first round cannot be widened, many survivors
     hmax = (longest(p["db"]), longest(p["queries"]))
     full = ctx.wmd_topk_workspace_bytes(600, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax)
 
@@ -311,9 +311,10 @@ def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
             break
         ok_sizes.append(nbytes)
         assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]) and torch.equal(got[2], ref[2]), nbytes
+        last = got
     assert len(ok_sizes) >= 3
     # the lists (12 bytes per survivor) get at most half of the workspace: at the smallest size they cannot have fitted at once
-    assert (int(ref[2].sum()) - q * k) * 12 > ok_sizes[-1] // 2, (int(ref[2].sum()), ok_sizes)
+    assert (int(last[2].sum()) - q * k) * 12 > ok_sizes[-1] // 2, (int(last[2].sum()), ok_sizes)
     # spot check of the reference itself against the oracle
     gi, gd = ref[0].numpy(), ref[1].numpy()
     for j in range(2):
@@ -382,7 +383,7 @@ def test_wmd_topk_tiny_configuration(ctx, tiny):
         assert_close(gd[j], od[j], what=f"pruned top-k distances of query {j}")
         if np.min(np.diff(od[j])) > 1e-4 * od[j][-1]:
             assert np.array_equal(gi[j], oi[j])
-        assert ev[j] >= need[j] - 1
+        assert k <= ev[j] <= need[j] + 64
     # for the other queries: the reported rows carry the reported distances
     for j in range(3, q):
         ref = oracle.wmd_pairs(prob["E"], sub, tiny["queries"], gi[j], np.full(k, j))
