@@ -60,6 +60,7 @@ def wmd_leg(ctx, binding, synth, prob, E, v, m, n_w, q_w, k_w, with_oracle):
     evaluated = int(ev.sum())
     out = {"workload": f"first {n_w} database rows x first {q_w} queries, k = {k_w}", "ms": 1e3 * t,
            "wmd_evaluated": evaluated, "evaluated_fraction": evaluated / (n_w * q_w),
+           "abandoned_above_cutoff": int(pr["emd_abandoned"]),
            "solver_ms": pr["emd_ms"], "rwmd_first_phase_ms": pr["phase1_ms"],
            "solver_pairs_per_s": pr["emd_pairs"] / max(pr["emd_ms"], 1e-9) * 1e3,
            "equivalent_exhaustive_pairs_per_s": n_w * q_w / t}

@@ -215,6 +215,8 @@ typedef struct {
     double table_rev_ms;  int64_t table_rev_launches;  double table_rev_bytes;
     /* lcrwmd_wmd_pairs / lcrwmd_wmd_topk: the transport solver (it also forms its cost matrices) */
     double emd_ms;  int64_t emd_launches;  double emd_pairs;
+    /* lcrwmd_wmd_topk: survivors whose solve stopped early because a lower bound passed the cut-off */
+    double emd_abandoned;
 } lcrwmd_profile;
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
@@ -284,10 +286,13 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
  * RWMD <= WMD, so nothing that belongs to the result is cut.  While k transport problems per query
  * of the batch do not fill the device, the first round takes the k1 > k (at most 64) nearest by
  * RWMD instead and L is the k-th smallest of their k1 WMDs: the same wall time, a lower cut-off,
- * fewer survivors (any k evaluated distances bound the k-th best from above).  The device compares fp32 RWMD values
+ * fewer survivors (any k evaluated distances bound the k-th best from above).  A survivor's solve
+ * stops as soon as a lower bound on its distance (the value of the solver's dual variables, which
+ * starts at the one-sided RWMD and ends at the WMD) exceeds L: it cannot be among the k nearest.  The device compares fp32 RWMD values
  * against fp32 WMD values, so the test is RWMD < L (1 + 1e-5): rounding can only add candidates.
  * R_idx / R_dist: q x k, ordered by (distance, row index) ascending, as in lcrwmd_rwmd_topk.
- * evaluated (HOST, q entries, or NULL): WMD evaluations spent on each query (first round + survivors).
+ * evaluated (HOST, q entries, or NULL): WMD evaluations started for each query (first round +
+ * survivors, including those that stopped early).
  * fp32 E with the LCRWMD_BF16 compute option is refused (LCRWMD_EUNSUPPORTED): a bound rounded to
  * bf16 may exceed the WMD it is meant to bound.  1 <= k <= min(n, 64).
  * Synchronises the stream several times per query batch (RWMD vocabulary sizes, survivor counts).

@@ -556,6 +556,7 @@ lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx)
     if (!ctx) return LCRWMD_EINVAL;
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     ctx->prof.clear();
+    ctx->prof_abandoned = 0.0;
     ctx->profiling = true;
     return LCRWMD_OK;
 }
@@ -581,6 +582,7 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
         else { out->phase2_ms += ms; out->phase2_launches += 1; out->phase2_bytes += r.work; out->phase2_gather_bytes += r.work2; }
     }
     ctx->prof.clear();
+    out->emd_abandoned = ctx->prof_abandoned;
     return LCRWMD_OK;
 }
 
@@ -836,10 +838,13 @@ int64_t longest_row(const int64_t* rp, int64_t rows)
 }
 
 // WMD of `count` listed pairs into out; the wavefronts that solve them share `slabs`.  counters: [0] failures
-// (accumulated), [2] the work queue's position.
+// (accumulated), [2] the work queue's position, [3] pairs abandoned above their limit (accumulated).
+// limit (or nullptr): pair (i, j) may be abandoned, its output set to FLT_MAX, once its distance is known to exceed
+// limit[j - limit_j0].
 lcrwmd_status run_wmd_list(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_csr* DB, const lcrwmd_emb* E,
                            const int32_t* pair_db, const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max,
-                           void* slabs, size_t slab_bytes, float* out, int32_t* flags, int32_t* counters, hipStream_t s)
+                           void* slabs, size_t slab_bytes, float* out, int32_t* flags, int32_t* counters, hipStream_t s,
+                           const float* limit = nullptr, int32_t limit_j0 = 0)
 {
     if (count <= 0) return LCRWMD_OK;
     if (count > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "more than 2^31 pairs in one list");
@@ -849,7 +854,8 @@ lcrwmd_status run_wmd_list(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const lcrwmd_cs
     if (slots < 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one transport problem (%zu bytes)",
                                emd_pair_bytes(h1max, h2max));
     ProfScope ps(ctx, s, 5, (double)count);
-    HIP_TRY(launch_emd(*E, *DB, *Q, pair_db, pair_q, count, h1max, h2max, slabs, slots, counters + 2, out, flags, counters, s));
+    HIP_TRY(launch_emd(*E, *DB, *Q, pair_db, pair_q, count, h1max, h2max, slabs, slots, counters + 2, out, flags, counters,
+                       limit, limit_j0, counters + 3, s));
     return LCRWMD_OK;
 }
 
@@ -1033,14 +1039,17 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
             float* l_d = lb.take_n<float>((size_t)total + 1);
             if (!lb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: survivor lists do not fit");
             HIP_TRY(launch_fill_below(tile, n, ja, jb, ldt, cut, off, cursor, (int32_t)j0, l_db, l_q, s));
-            ST_TRY(run_wmd_list(ctx, queries, database, E, l_db, l_q, total, h1max, h2max, rest, slab_part, l_d, nullptr, counters, s));
+            // a survivor is dropped as soon as the solver's lower bound on its distance passes the cut-off
+            ST_TRY(run_wmd_list(ctx, queries, database, E, l_db, l_q, total, h1max, h2max, rest, slab_part, l_d, nullptr, counters, s,
+                                cut, (int32_t)j0));
             HIP_TRY(launch_select_lists(R0, wmd0, k1, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
             ja = jb;
         }
-        int32_t failed = 0;
-        HIP_TRY(hipMemcpyAsync(&failed, counters, sizeof(failed), hipMemcpyDeviceToHost, s));
+        int32_t hc[4] = {0, 0, 0, 0};
+        HIP_TRY(hipMemcpyAsync(hc, counters, sizeof(hc), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
-        failed_total += failed;
+        failed_total += hc[0];
+        if (ctx->profiling) ctx->prof_abandoned += (double)hc[3];
     }
     if (failed_total)
         return fail(ctx, LCRWMD_ENOCONVERGE, "%d transport problems ran out of their augmentation budget", failed_total);

@@ -22,6 +22,7 @@ struct lcrwmd_ctx {
     lcrwmd_options opt;
     char err[512];
     bool profiling;
+    double prof_abandoned = 0.0;      // lcrwmd_wmd_topk: survivors whose solve stopped above the cut-off, while profiling
     std::vector<lcrwmd_prof_rec> prof;
 };
 
@@ -180,7 +181,8 @@ bool emd_supported(int64_t h1max, int64_t h2max);
 int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max);
 hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
                       const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, int64_t slots,
-                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s);
+                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, const float* limit,
+                      int32_t limit_j0, int32_t* give_up_count, hipStream_t s);
 hipError_t launch_check_pairs(const int32_t* pair_db, const int32_t* pair_q, int64_t npairs, int64_t n, int64_t q,
                               int32_t* status, hipStream_t s);
 hipError_t launch_centroids(const lcrwmd_emb& E, const lcrwmd_csr& X, float* C, int64_t ldc, hipStream_t s);

@@ -151,6 +151,14 @@ __device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, in
 // ends because every loop below is bounded by the pair's dimensions or by the augmentation budget.
 // flags[t]: 0 solved; 1 the augmentation budget ran out (the result is then the cost of a partial flow).
 //
+// Giving up above a limit (limit != nullptr: pair t only matters if its distance is at most limit[j - limit_j0]).
+// Between searches the potentials are a feasible point of the dual programme whose value is the cost of the flow so
+// far plus, for every source with supply left, that supply times its dual variable: the negated potential of the
+// source being served, and for a source not yet served any r with r <= c[p, u] - phiT[u] for all u, in particular
+// r_p = min_u c[p, u] because the potentials of sinks only ever fall.  The value of a dual point bounds the optimum
+// from below, so once  total + sup[s] max(r_s, -phiS[s]) + sum_{p > s} x1[p] r_p  exceeds the limit the pair is
+// abandoned: out[t] = FLT_MAX, one more in give_up_count.  (At the start the bound is the one-sided RWMD.)
+//
 // NPL > 0 (histograms of the query side of at most 64 NPL words): the potentials and the tentative distances of a
 // lane's sinks live in registers, so that settling a node touches LDS only to record a predecessor; NPL == 0: any
 // size, that state in LDS.
@@ -164,7 +172,8 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
                                             int64_t count, int32_t* next_pair, float* slabs_c, int64_t slab_elems,
                                             double* slabs_f, int32_t h1max, int32_t h2max, int32_t bm_words,
                                             float* __restrict__ out,
-                                            int32_t* __restrict__ flags, int32_t* fail_count)
+                                            int32_t* __restrict__ flags, int32_t* fail_count,
+                                            const float* __restrict__ limit, int32_t limit_j0, int32_t* give_up_count)
 {
     extern __shared__ double lds_d[];
     double* phiS = lds_d;
@@ -213,10 +222,33 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
 
         const int budget = 8 * (h1 + h2) + 64;     // augmentations; each empties a source, a sink or a flow entry
         int naug = 0;
-        bool exhausted = false;
+        bool exhausted = false, abandoned = false;
         double total = 0.0;
 
-        for (int s = 0; s < h1 && !exhausted; ++s) {
+        // what the sources not yet served must at least pay: sum of x1[p] min_u c[p, u]
+        const bool bounded = limit != nullptr;
+        const double lim = bounded ? (double)limit[j - limit_j0] : 0.0;
+        double tail = 0.0;
+        if (bounded) {
+            for (int p = lane; p < h1; p += 64) {
+                const float* row = c + (int64_t)p * h2;
+                float r = FLT_MAX;
+                for (int u = 0; u < h2; ++u) r = fminf(r, row[u]);
+                tail += sup[p] * (double)r;
+            }
+            tail = wave_sum(tail);
+        }
+
+        for (int s = 0; s < h1 && !exhausted && !abandoned; ++s) {
+            double r_s = 0.0, paid = 0.0;           // bounded: min_u c[s, u]; sum of this source's search distances
+            if (bounded) {
+                const float* row = c + (int64_t)s * h2;
+                float r = FLT_MAX;
+                for (int u = lane; u < h2; u += 64) r = fminf(r, row[u]);
+                r_s = wave_min((double)r);
+                tail -= sup[s] * r_s;
+                tail = tail > 0.0 ? tail : 0.0;
+            }
             while (uni(sup[s] > kMassEps)) {
                 if (naug >= budget) { exhausted = true; break; }
                 // ---- search from s ----
@@ -376,12 +408,18 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
                         if (((used >> r) & 1) && dT[u] < Dt) phiT[u] += dT[u] - Dt;
                 }
                 wave_sync();
+                if (bounded) {
+                    paid += Dt;                                    // -phiS[s]
+                    const double bound = total + sup[s] * (paid > r_s ? paid : r_s) + tail;
+                    if (uni(bound * (1.0 - 1e-9) > lim)) { abandoned = true; break; }
+                }
             }
         }
         if (lane == 0) {
-            out[t] = (float)total;
+            out[t] = abandoned ? FLT_MAX : (float)total;
             if (flags) flags[t] = exhausted ? 1 : 0;
             if (exhausted && fail_count) atomicAdd(fail_count, 1);
+            if (abandoned && give_up_count) atomicAdd(give_up_count, 1);
         }
     }
 }
@@ -629,7 +667,7 @@ static int emd_reg_sinks(int64_t h2max) { return h2max <= 128 ? 2 : h2max <= 256
 
 typedef void (*EmdKernel)(const void*, int, int64_t, int32_t, const int64_t*, const int32_t*, const float*, const int64_t*,
                           const int32_t*, const float*, const int32_t*, const int32_t*, int64_t, int32_t*, float*, int64_t,
-                          double*, int32_t, int32_t, int32_t, float*, int32_t*, int32_t*);
+                          double*, int32_t, int32_t, int32_t, float*, int32_t*, int32_t*, const float*, int32_t, int32_t*);
 
 static EmdKernel emd_kernel(int64_t h2max)
 {
@@ -652,7 +690,8 @@ int64_t emd_preferred_slots(int num_cu, int64_t h1max, int64_t h2max)
 // one of each per wavefront of the grid; next_pair is a device counter this call resets.
 hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_csr& Q, const int32_t* pair_db,
                       const int32_t* pair_q, int64_t count, int64_t h1max, int64_t h2max, void* slabs, int64_t slots,
-                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, hipStream_t s)
+                      int32_t* next_pair, float* out, int32_t* flags, int32_t* fail_count, const float* limit,
+                      int32_t limit_j0, int32_t* give_up_count, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
     if (slots > count) slots = count;
@@ -672,7 +711,7 @@ hipError_t launch_emd(const lcrwmd_emb& E, const lcrwmd_csr& DB, const lcrwmd_cs
     kernel<<<dim3((unsigned)slots), 64, lds, s>>>(E.data, (int)E.dtype, E.ld, (int32_t)E.m, DB.row_ptr, DB.col_idx, DB.val,
                                                   Q.row_ptr, Q.col_idx, Q.val, pair_db, pair_q, count, next_pair, slabs_c,
                                                   (int64_t)elems, slabs_f, (int32_t)h1max, (int32_t)h2max, bmw, out, flags,
-                                                  fail_count);
+                                                  fail_count, limit, limit_j0, give_up_count);
     return hipGetLastError();
 }
 

@@ -282,6 +282,33 @@ def test_wmd_topk_pruned_equals_exhaustive(ctx):
     assert torch.equal(R2, R_idx) and torch.equal(D2, R_dist)
 
 
+def test_wmd_topk_abandons_survivors_without_losing_a_neighbour(ctx):
+    """Survivors are dropped as soon as the solver's lower bound on their distance passes the cut-off.  On a problem
+    where that happens hundreds of times, the k nearest must still be those of the exhaustive matrix (every pair
+    solved to the end by lcrwmd_wmd_pairs, itself checked against the oracle on the rows returned)."""
+    p = problem(v=3000, m=300, n=2500, q=12, h_lo=8, h_hi=40, seed=41)
+    E, db, qs = upload(p)
+    n, q, k = 2500, 12, 7
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    pi, pj = np.divmod(np.arange(n * q), q)
+    W = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=4096).reshape(n, q).astype(np.float64)
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(3000, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ev = torch.zeros(q, dtype=torch.int64)
+    ctx.profile_begin()
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
+    pr = ctx.profile_end()
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    assert pr["emd_pairs"] == int(ev.sum())                                        # every pair counted was handed to the solver
+    assert 100 < pr["emd_abandoned"] < int(ev.sum()) - q * k                       # abandoned: some, never a kept one
+    for j in range(q):
+        order = np.lexsort((np.arange(n), W[:, j]))[:k]
+        assert np.array_equal(gd[j], W[order, j].astype(np.float32))               # same solver, same pairs: bit-equal
+        assert np.array_equal(gi[j], order)
+        assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
+
+
 def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
     """Shrinking the workspace makes the library walk the queries in smaller batches and the survivor lists in ranges;
     the result and (with the first round at its full width of 64) the evaluation counts must not change.  Below some size the call must refuse, not misbehave."""
