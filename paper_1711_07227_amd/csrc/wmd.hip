@@ -70,63 +70,158 @@ __device__ inline double wave_sum(double x)
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// C = T1 o T2 of one pair (Sec. III), by one wavefront: c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||
-// as the square root of the sum of squared differences (no norm expansion: equal words give exactly 0).
-// 32 x 32 output tiles, 4 x 4 outputs per lane, the embedding dimension staged through LDS 16 values at a time.
+// C = T1 o T2 of one pair (Sec. III), by one wavefront: c[p * h2 + u] = || E[word p of X1[i]] - E[word u of X2[j]] ||.
+//
+// 32 x 32 output tiles, the embedding dimension staged through LDS 16 values at a time.  A tile is first evaluated on
+// the matrix cores as |a|^2 + |b|^2 - 2 a.b (v_mfma_f32_32x32x2_f32, fp32 throughout; the norms are summed from the
+// very operand values the products use).  That form loses digits where two different words lie close together, so a
+// tile holding any entry with d^2 < kCloseFrac (|a|^2 + |b|^2) is evaluated again from coordinate differences, and
+// equal word ids give exactly 0 either way.  What is kept from the expansion therefore has a relative error of the
+// order of the fp32 dot product's own (m roundings, about 1e-6) divided by 2 kCloseFrac.
 // `tiles` is kCostLds bytes of this wavefront's LDS.
 // ---------------------------------------------------------------------------------------------------------------
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
 constexpr int kCT = 32;      // tile edge
 constexpr int kCK = 16;      // embedding values per slice
-constexpr int kCostLds = (2 * kCT * (kCK + 1) + 2 * kCT) * 4;
+constexpr int kCostLds = (2 * kCT * (kCK + 1) + 4 * kCT) * 4;
+constexpr float kCloseFrac = 0.25f;
 
-__device__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m, const int32_t* __restrict__ wa_g,
-                           int h1, const int32_t* __restrict__ wb_g, int h2, float* c, float* tiles, int lane)
+__device__ inline float as_float(float x) { return x; }
+__device__ inline float as_float(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }      // bf16 bits
+
+struct CostTile {
+    float (*A)[kCK + 1];
+    float (*B)[kCK + 1];
+    int32_t* wa;
+    int32_t* wb;
+    float* nA;
+    __device__ explicit CostTile(float* tiles)
+        : A(reinterpret_cast<float (*)[kCK + 1]>(tiles)), B(reinterpret_cast<float (*)[kCK + 1]>(tiles + kCT * (kCK + 1))),
+          wa(reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCK + 1))), wb(wa + kCT),
+          nA(tiles + 2 * kCT * (kCK + 1) + 2 * kCT)
+    {
+    }
+    // word ids of the tile's rows and columns; past the end of a histogram its last word again (never stored)
+    __device__ void set_words(const int32_t* __restrict__ wa_g, int p0, int h1, const int32_t* __restrict__ wb_g, int u0, int h2,
+                              int lane) const
+    {
+        if (lane < kCT) wa[lane] = wa_g[p0 + lane < h1 ? p0 + lane : h1 - 1];
+        else wb[lane - kCT] = wb_g[u0 + lane - kCT < h2 ? u0 + lane - kCT : h2 - 1];
+    }
+    // slice k0 of the 32 + 32 embedding rows of the tile into A and B (zeros past m): all sixteen loads of a lane are
+    // issued before the first is used
+    template <typename TE>
+    __device__ void stage_as(const TE* __restrict__ E, int64_t ld, int32_t m, int k0, int lane) const
+    {
+        const int lr = lane >> 4, lc = lane & 15;     // rows lr + 4 e, column lc
+        const bool kin = k0 + lc < m;
+        const int kk = kin ? k0 + lc : m - 1;
+        TE va[8], vb[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            va[e] = E[(int64_t)wa[lr + 4 * e] * ld + kk];
+            vb[e] = E[(int64_t)wb[lr + 4 * e] * ld + kk];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            A[lr + 4 * e][lc] = kin ? as_float(va[e]) : 0.f;
+            B[lr + 4 * e][lc] = kin ? as_float(vb[e]) : 0.f;
+        }
+    }
+    __device__ void stage(const void* __restrict__ E, int dtype, int64_t ld, int32_t m, int k0, int lane) const
+    {
+        if (dtype == LCRWMD_BF16) stage_as(reinterpret_cast<const uint16_t*>(E), ld, m, k0, lane);
+        else stage_as(reinterpret_cast<const float*>(E), ld, m, k0, lane);
+    }
+};
+
+// one tile from coordinate differences (no norm expansion): 4 x 4 outputs per lane, rows ty + 8 a, columns tx + 8 b
+__device__ __forceinline__ void cost_tile_exact(const CostTile& T, const void* __restrict__ E, int dtype, int64_t ld, int32_t m, int p0, int h1,
+                                int u0, int h2, float* c, int lane)
 {
-    float (*A)[kCK + 1] = reinterpret_cast<float (*)[kCK + 1]>(tiles);
-    float (*B)[kCK + 1] = reinterpret_cast<float (*)[kCK + 1]>(tiles + kCT * (kCK + 1));
-    int32_t* wa = reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCK + 1));
-    int32_t* wb = wa + kCT;
-    const int tx = lane & 7, ty = lane >> 3;      // 8 x 8 lanes; rows ty + 8 a, columns tx + 8 b
-    const int lr = lane >> 4, lc = lane & 15;     // loader: rows lr + 4 e, column lc
-    for (int p0 = 0; p0 < h1; p0 += kCT)
-        for (int u0 = 0; u0 < h2; u0 += kCT) {
-            if (lane < kCT) wa[lane] = p0 + lane < h1 ? wa_g[p0 + lane] : -1;
-            else wb[lane - kCT] = u0 + lane - kCT < h2 ? wb_g[u0 + lane - kCT] : -1;
-            float acc[4][4] = {};
-            for (int k0 = 0; k0 < m; k0 += kCK) {
-                wave_sync();                       // word ids written; the previous slice has been consumed
-                const int kk = k0 + lc;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int r = lr + 4 * e;
-                    const int32_t w1 = wa[r], w2 = wb[r];
-                    A[r][lc] = (w1 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w1 * ld + kk) : 0.f;
-                    B[r][lc] = (w2 >= 0 && kk < m) ? emb_val(E, dtype, (int64_t)w2 * ld + kk) : 0.f;
-                }
-                wave_sync();
+    const int tx = lane & 7, ty = lane >> 3;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < m; k0 += kCK) {
+        wave_sync();                               // the previous slice has been consumed
+        T.stage(E, dtype, ld, m, k0, lane);
+        wave_sync();
 #pragma unroll 4
-                for (int k = 0; k < kCK; ++k) {
-                    float x[4], y[4];
+        for (int k = 0; k < kCK; ++k) {
+            float x[4], y[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { x[e] = A[ty + 8 * e][k]; y[e] = B[tx + 8 * e][k]; }
-#pragma unroll
-                    for (int a = 0; a < 4; ++a)
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) {
-                            const float d = x[a] - y[b];
-                            acc[a][b] = fmaf(d, d, acc[a][b]);
-                        }
-                }
-            }
+            for (int e = 0; e < 4; ++e) { x[e] = T.A[ty + 8 * e][k]; y[e] = T.B[tx + 8 * e][k]; }
 #pragma unroll
             for (int a = 0; a < 4; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const int p = p0 + ty + 8 * a, u = u0 + tx + 8 * b;
-                    if (p < h1 && u < h2) c[(int64_t)p * h2 + u] = sqrtf(acc[a][b]);
+                    const float d = x[a] - y[b];
+                    acc[a][b] = fmaf(d, d, acc[a][b]);
                 }
-            wave_sync();                           // wa / wb are rewritten by the next tile
         }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int p = p0 + ty + 8 * a, u = u0 + tx + 8 * b;
+            if (p < h1 && u < h2) c[(int64_t)p * h2 + u] = sqrtf(acc[a][b]);
+        }
+}
+
+__device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+                                           const int32_t* __restrict__ wa_g, int h1, const int32_t* __restrict__ wb_g, int h2,
+                                           float* c, float* tiles, int lane)
+{
+    const CostTile T(tiles);
+    const int l31 = lane & 31, half = lane >> 5;
+    for (int p0 = 0; p0 < h1; p0 += kCT)
+        for (int u0 = 0; u0 < h2; u0 += kCT) {
+            wave_sync();                           // the previous tile's ids and norms have been read
+            T.set_words(wa_g, p0, h1, wb_g, u0, h2, lane);
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            float na = 0.f, nb = 0.f;
+            for (int k0 = 0; k0 < m; k0 += kCK) {
+                wave_sync();                       // word ids written; the previous slice has been consumed
+                T.stage(E, dtype, ld, m, k0, lane);
+                wave_sync();
+#pragma unroll
+                for (int i = 0; i < kCK / 2; ++i) {
+                    const float a = T.A[l31][2 * i + half], b = T.B[l31][2 * i + half];
+                    na = fmaf(a, a, na);
+                    nb = fmaf(b, b, nb);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+                }
+            }
+            na += __shfl_xor(na, 32);              // both halves of the embedding dimension
+            nb += __shfl_xor(nb, 32);
+            if (half == 0) T.nA[l31] = na;
+            wave_sync();
+            // accumulator register v of a lane: row 8 (v / 4) + 4 half + v % 4 of the tile, column l31
+            const int32_t wcol = T.wb[l31];
+            const bool col_in = u0 + l31 < h2;
+            bool close = false;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 8 * (v >> 2) + 4 * half + (v & 3);
+                const float s = T.nA[i] + nb;
+                close |= col_in && p0 + i < h1 && T.wa[i] != wcol && s - 2.f * acc[v] < kCloseFrac * s;
+            }
+            if (uni(__any(close) ? 1 : 0)) {
+                cost_tile_exact(T, E, dtype, ld, m, p0, h1, u0, h2, c, lane);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int i = 8 * (v >> 2) + 4 * half + (v & 3);
+                    if (col_in && p0 + i < h1)
+                        c[(int64_t)(p0 + i) * h2 + u0 + l31] =
+                            T.wa[i] == wcol ? 0.f : sqrtf(fmaxf(T.nA[i] + nb - 2.f * acc[v], 0.f));
+                }
+            }
+        }
+    wave_sync();                                   // the tile buffers become the solver's state
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -203,13 +298,13 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
         const int64_t a0 = db_rp[i], b0 = q_rp[j];
         const int h1 = uni((int)(db_rp[i + 1] - a0)), h2 = uni((int)(q_rp[j + 1] - b0));
 
-        pair_costs(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
-
         double sa = 0.0, sb = 0.0;
         for (int p = lane; p < h1; p += 64) sa += (double)db_val[a0 + p];
         for (int u = lane; u < h2; u += 64) sb += (double)q_val[b0 + u];
         sa = wave_sum(sa);
         sb = wave_sum(sb);
+
+        pair_costs(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
         for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
         for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
 #pragma unroll

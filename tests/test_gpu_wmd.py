@@ -123,6 +123,27 @@ def test_wmd_pairs_medium_sized_documents(ctx):
     assert_close(got, oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj), what="WMD of 50-150 word documents")
 
 
+@pytest.mark.parametrize("spread", [1e-3, 0.05, 0.6])
+def test_wmd_pairs_with_words_that_lie_close_together(ctx, spread):
+    """Clusters of near-identical embeddings: the distance between two words of a cluster is a small difference of
+    large numbers in the norm expansion the matrix cores evaluate, so those tiles must come from coordinate
+    differences.  spread = 0.6 puts part of the pairs on either side of the switch."""
+    rng = np.random.default_rng(9)
+    v, m = 600, 300
+    centres = rng.standard_normal((12, m))
+    E = (centres[np.arange(v) // 50] * 3.0 + spread * rng.standard_normal((v, m))).astype(np.float32)   # word w: cluster w // 50
+    for vocab, what in ((v, "documents over all clusters"), (50, "documents inside one cluster")):
+        p = {"E": E, "db": synth.corpus(14, vocab, 20, 45, 1.0, 10), "queries": synth.corpus(3, vocab, 20, 45, 1.0, 11)}
+        Eg, db, qs = upload(p)
+        pi, pj = np.divmod(np.arange(14 * 3), 3)
+        got, flags = run_wmd_pairs(ctx, Eg, db, qs, pi, pj, (longest(p["db"]), longest(p["queries"])), flags=True)
+        assert np.all(flags == 0)
+        ref = oracle.wmd_pairs(p["E"], p["db"], p["queries"], pi, pj)
+        assert_close(got, ref, what=f"WMD with clustered embeddings, spread {spread}, {what}")
+        if vocab == 50:
+            assert ref.max() < 2.0 * spread * np.sqrt(2 * m)      # these distances are differences inside a cluster
+
+
 def test_wmd_pairs_long_documents(ctx):
     """About 400 words a side: beyond the size up to which the solver keeps its map of positive flows in LDS."""
     p = {"E": synth.embeddings(3000, 300, 1), "db": synth.corpus(2, 3000, 380, 420, 1.0, 2),
