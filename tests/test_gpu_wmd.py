@@ -330,6 +330,32 @@ def test_wmd_topk_abandons_survivors_without_losing_a_neighbour(ctx):
         assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
 
 
+def test_wmd_topk_with_queries_longer_than_the_register_variants_hold(ctx):
+    """Queries of 260-300 words take the solver variant that keeps the sinks' state in LDS; survivors are abandoned
+    there by the same rule.  Reference: every pair solved to the end on the device, the rows returned re-solved by
+    the oracle."""
+    p = {"E": synth.embeddings(3000, 300, 1), "db": synth.corpus(400, 3000, 200, 300, 1.0, 2),
+         "queries": synth.corpus(2, 3000, 260, 300, 1.0, 3)}
+    E, db, qs = upload(p)
+    n, q, k = 400, 2, 3
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    assert hmax[1] > 256
+    pi, pj = np.divmod(np.arange(n * q), q)
+    W = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=512).reshape(n, q).astype(np.float64)
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(3000, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.profile_begin()
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws)
+    pr = ctx.profile_end()
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    assert pr["emd_abandoned"] > 0
+    for j in range(q):
+        order = np.lexsort((np.arange(n), W[:, j]))[:k]
+        assert np.array_equal(gi[j], order) and np.array_equal(gd[j], W[order, j].astype(np.float32))
+    assert_close(gd[0], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[0], np.zeros(k, np.int64)), what="top-k WMD values")
+
+
 def test_wmd_topk_with_the_smallest_workspace_that_works(ctx):
     """Shrinking the workspace makes the library walk the queries in smaller batches and the survivor lists in ranges;
     the result and (with the first round at its full width of 64) the evaluation counts must not change.  Below some size the call must refuse, not misbehave."""
