@@ -226,11 +226,11 @@ def main():
         ctx.set_options(compute=compute, dedup=0)
 
     # Exact WMD behind the bound (reported, never `value`): the k nearest by WMD with the RWMD cut-off, on the first
-    # 5,000 database rows and 32 queries of the same workload.
+    # 20,000 database rows and 64 queries of the same workload.
     wmd = None
     # (documents of up to 200 words: a transport problem's cost grows with the cube of its size, and so does the oracle's)
-    if not args.no_wmd and not k and not cfg.queries_from_db and not bf16_in and n >= 5000 and q >= 32 and cfg.h_hi <= 200:
-        wmd = wmd_leg(ctx, binding, synth, prob, E, v, m, 5000, 32, 16, not args.no_cpu_baseline)
+    if not args.no_wmd and not k and not cfg.queries_from_db and not bf16_in and n >= 20000 and q >= 64 and cfg.h_hi <= 200:
+        wmd = wmd_leg(ctx, binding, synth, prob, E, v, m, 20000, 64, 16, not args.no_cpu_baseline)
 
     # sampled check of the timed result against the oracle's per-pair brute force
     cpu = None
