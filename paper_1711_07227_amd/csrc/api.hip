@@ -87,7 +87,8 @@ lcrwmd_status check_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E)
     if (!E->data) return fail(ctx, LCRWMD_EINVAL, "E.data is NULL");
     if (E->ld < E->m) return fail(ctx, LCRWMD_EINVAL, "E.ld < E.m");
     if (E->dtype != LCRWMD_F32 && E->dtype != LCRWMD_BF16) return fail(ctx, LCRWMD_EINVAL, "unknown E.dtype");
-    if (E->v > 0x7fffffffLL || E->m > 65536) return fail(ctx, LCRWMD_EUNSUPPORTED, "E is too large (v < 2^31, m <= 65536)");
+    if (E->v > 0x7fffffffLL || E->m > 65536 || E->ld > 0x7fffffffLL)
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "E is too large (v < 2^31, m <= 65536, ld < 2^31)");
     return LCRWMD_OK;
 }
 
@@ -1019,8 +1020,11 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         if (evaluated)
             for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k1 + hoff[j + 1] - hoff[j];
         // Lists hold 12 bytes per survivor; they share `rest` with the transport problems in flight.
+        // The transport problems get all the room they can use when the batch's lists fit beside it in one piece,
+        // half of the rest otherwise.
         size_t slab_part = pair_bytes * (size_t)emd_preferred_slots(ctx->num_cu, h1max, h2max);
-        if (slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
+        const size_t lists_all = (size_t)hoff[nq] * 12 + 8192;
+        if (slab_part + lists_all > rest_bytes && slab_part > rest_bytes / 2) slab_part = rest_bytes / 2;
         if (slab_part < pair_bytes) slab_part = pair_bytes;
         slab_part = (slab_part + 255) / 256 * 256;
         if (slab_part + 4096 > rest_bytes)

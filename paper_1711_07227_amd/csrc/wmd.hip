@@ -9,6 +9,8 @@
 #include <float.h>
 #include <limits.h>
 
+#include <type_traits>
+
 #include "lcrwmd_internal.h"
 
 namespace lcrwmd {
@@ -62,6 +64,25 @@ __device__ inline double wave_min(double x)
     return __hiloint2double(hi, lo);
 }
 
+// the same for a float, one instruction per step
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_min_step(float x)
+{
+    const int o = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+    return fminf(x, __int_as_float(o));
+}
+
+__device__ inline float wave_min(float x)
+{
+    x = dpp_min_step<0x111, 0xf>(x);
+    x = dpp_min_step<0x112, 0xf>(x);
+    x = dpp_min_step<0x114, 0xf>(x);
+    x = dpp_min_step<0x118, 0xf>(x);
+    x = dpp_min_step<0x142, 0xa>(x);
+    x = dpp_min_step<0x143, 0xc>(x);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
 __device__ inline double wave_sum(double x)
 {
 #pragma unroll
@@ -78,28 +99,56 @@ __device__ inline double wave_sum(double x)
 // tile holding any entry with d^2 < kCloseFrac (|a|^2 + |b|^2) is evaluated again from coordinate differences, and
 // equal word ids give exactly 0 either way.  What is kept from the expansion therefore has a relative error of the
 // order of the fp32 dot product's own (m roundings, about 1e-6) divided by 2 kCloseFrac.
-// `tiles` is kCostLds bytes of this wavefront's LDS.
+// `tiles` is cost_lds_bytes(slice width) bytes of this wavefront's LDS.
 // ---------------------------------------------------------------------------------------------------------------
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kCT = 32;      // tile edge
-constexpr int kCK = 16;      // embedding values per slice
-constexpr int kCostLds = (2 * kCT * (kCK + 1) + 4 * kCT) * 4;
 constexpr float kCloseFrac = 0.25f;
+// LDS of the tile buffers for slices of CK embedding values: two 32-row operand tiles, word ids, norms
+constexpr int cost_lds_bytes(int CK) { return (2 * kCT * (CK + 1) + 4 * kCT) * 4; }
+
+// What a lane gathers of one slice (CK embedding values of the tile's 32 + 32 rows), and how.
+//   VEC: CK / 4 lanes per row, each one group of four values as one 16-byte (fp32) or 8-byte (bf16) load, so that a
+//        row's share of the slice is one contiguous request of 4 CK bytes (a whole 128-byte line for CK = 32); needs
+//        the rows to start on such boundaries (base address and pitch), which the caller checks.
+//   else: CK lanes per row, one element per load.
+template <typename TE>
+struct Vec4;
+template <>
+struct Vec4<float> { typedef float4 type; };
+template <>
+struct Vec4<uint16_t> { typedef uint2 type; };
+
+template <typename TE, bool VEC, int CK>
+struct Gather;
+template <typename TE, int CK>
+struct Gather<TE, true, CK> { typename Vec4<TE>::type a[CK / 8], b[CK / 8]; };
+template <typename TE, int CK>
+struct Gather<TE, false, CK> { TE a[CK / 2], b[CK / 2]; };
 
 __device__ inline float as_float(float x) { return x; }
 __device__ inline float as_float(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }      // bf16 bits
+__device__ inline void unpack4(const float4& v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+__device__ inline void unpack4(const uint2& v, float (&f)[4])
+{
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xffff0000u);
+}
 
+template <int CK>
 struct CostTile {
-    float (*A)[kCK + 1];
-    float (*B)[kCK + 1];
+    float (*A)[CK + 1];
+    float (*B)[CK + 1];
     int32_t* wa;
     int32_t* wb;
     float* nA;
     __device__ explicit CostTile(float* tiles)
-        : A(reinterpret_cast<float (*)[kCK + 1]>(tiles)), B(reinterpret_cast<float (*)[kCK + 1]>(tiles + kCT * (kCK + 1))),
-          wa(reinterpret_cast<int32_t*>(tiles + 2 * kCT * (kCK + 1))), wb(wa + kCT),
-          nA(tiles + 2 * kCT * (kCK + 1) + 2 * kCT)
+        : A(reinterpret_cast<float (*)[CK + 1]>(tiles)), B(reinterpret_cast<float (*)[CK + 1]>(tiles + kCT * (CK + 1))),
+          wa(reinterpret_cast<int32_t*>(tiles + 2 * kCT * (CK + 1))), wb(wa + kCT),
+          nA(tiles + 2 * kCT * (CK + 1) + 2 * kCT)
     {
     }
     // word ids of the tile's rows and columns; past the end of a histogram its last word again (never stored)
@@ -109,45 +158,84 @@ struct CostTile {
         if (lane < kCT) wa[lane] = wa_g[p0 + lane < h1 ? p0 + lane : h1 - 1];
         else wb[lane - kCT] = wb_g[u0 + lane - kCT < h2 ? u0 + lane - kCT : h2 - 1];
     }
-    // slice k0 of the 32 + 32 embedding rows of the tile into A and B (zeros past m): all sixteen loads of a lane are
-    // issued before the first is used
+    // Slice k0: `fetch` requests a lane's share (all loads in flight together), `put` writes it to A and B with zeros
+    // past m.  Word ids and pitches are below 2^31: one 32 x 32 -> 64 bit multiply per row.
     template <typename TE>
-    __device__ void stage_as(const TE* __restrict__ E, int64_t ld, int32_t m, int k0, int lane) const
+    __device__ void fetch(const TE* __restrict__ E, int64_t ld, int32_t m, int k0, int lane, Gather<TE, false, CK>& g) const
     {
-        const int lr = lane >> 4, lc = lane & 15;     // rows lr + 4 e, column lc
-        const bool kin = k0 + lc < m;
-        const int kk = kin ? k0 + lc : m - 1;
-        TE va[8], vb[8];
+        constexpr int RP = 64 / CK;                   // rows per pass
+        const int lr = lane / CK, lc = lane % CK;
+        const uint32_t kk = k0 + lc < m ? k0 + lc : m - 1;
+        const uint32_t pitch = (uint32_t)ld;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            va[e] = E[(int64_t)wa[lr + 4 * e] * ld + kk];
-            vb[e] = E[(int64_t)wb[lr + 4 * e] * ld + kk];
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            A[lr + 4 * e][lc] = kin ? as_float(va[e]) : 0.f;
-            B[lr + 4 * e][lc] = kin ? as_float(vb[e]) : 0.f;
+        for (int e = 0; e < CK / 2; ++e) {
+            g.a[e] = E[(uint64_t)(uint32_t)wa[lr + RP * e] * pitch + kk];
+            g.b[e] = E[(uint64_t)(uint32_t)wb[lr + RP * e] * pitch + kk];
         }
     }
-    __device__ void stage(const void* __restrict__ E, int dtype, int64_t ld, int32_t m, int k0, int lane) const
+    template <typename TE>
+    __device__ void put(int32_t m, int k0, int lane, const Gather<TE, false, CK>& g) const
     {
-        if (dtype == LCRWMD_BF16) stage_as(reinterpret_cast<const uint16_t*>(E), ld, m, k0, lane);
-        else stage_as(reinterpret_cast<const float*>(E), ld, m, k0, lane);
+        constexpr int RP = 64 / CK;
+        const int lr = lane / CK, lc = lane % CK;
+        const bool kin = k0 + lc < m;
+#pragma unroll
+        for (int e = 0; e < CK / 2; ++e) {
+            A[lr + RP * e][lc] = kin ? as_float(g.a[e]) : 0.f;
+            B[lr + RP * e][lc] = kin ? as_float(g.b[e]) : 0.f;
+        }
+    }
+    // the pitch is a multiple of 4 here, so a group of four values that starts below m ends inside the row's pitch
+    template <typename TE>
+    __device__ void fetch(const TE* __restrict__ E, int64_t ld, int32_t m, int k0, int lane, Gather<TE, true, CK>& g) const
+    {
+        constexpr int LR = CK / 4, RP = 64 / LR;      // lanes per row, rows per pass
+        const int lr = lane / LR;
+        const int k4 = k0 + 4 * (lane % LR);
+        const uint32_t kk = k4 < m ? k4 : 0;
+        const uint32_t pitch = (uint32_t)ld;
+        typedef typename Vec4<TE>::type V;
+#pragma unroll
+        for (int e = 0; e < CK / 8; ++e) {
+            g.a[e] = *reinterpret_cast<const V*>(E + ((uint64_t)(uint32_t)wa[lr + RP * e] * pitch + kk));
+            g.b[e] = *reinterpret_cast<const V*>(E + ((uint64_t)(uint32_t)wb[lr + RP * e] * pitch + kk));
+        }
+    }
+    template <typename TE>
+    __device__ void put(int32_t m, int k0, int lane, const Gather<TE, true, CK>& g) const
+    {
+        constexpr int LR = CK / 4, RP = 64 / LR;
+        const int lr = lane / LR, lc = 4 * (lane % LR);
+#pragma unroll
+        for (int e = 0; e < CK / 8; ++e) {
+            float fa[4], fb[4];
+            unpack4(g.a[e], fa);
+            unpack4(g.b[e], fb);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bool kin = k0 + lc + t < m;
+                A[lr + RP * e][lc + t] = kin ? fa[t] : 0.f;
+                B[lr + RP * e][lc + t] = kin ? fb[t] : 0.f;
+            }
+        }
     }
 };
 
 // one tile from coordinate differences (no norm expansion): 4 x 4 outputs per lane, rows ty + 8 a, columns tx + 8 b
-__device__ __forceinline__ void cost_tile_exact(const CostTile& T, const void* __restrict__ E, int dtype, int64_t ld, int32_t m, int p0, int h1,
-                                int u0, int h2, float* c, int lane)
+template <typename TE, bool VEC, int CK>
+__device__ __forceinline__ void cost_tile_exact(const CostTile<CK>& T, const TE* __restrict__ E, int64_t ld, int32_t m, int p0,
+                                                int h1, int u0, int h2, float* c, int lane)
 {
     const int tx = lane & 7, ty = lane >> 3;
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < m; k0 += kCK) {
+    Gather<TE, VEC, CK> g;
+    for (int k0 = 0; k0 < m; k0 += CK) {
+        T.fetch(E, ld, m, k0, lane, g);
         wave_sync();                               // the previous slice has been consumed
-        T.stage(E, dtype, ld, m, k0, lane);
+        T.put(m, k0, lane, g);
         wave_sync();
 #pragma unroll 4
-        for (int k = 0; k < kCK; ++k) {
+        for (int k = 0; k < CK; ++k) {
             float x[4], y[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) { x[e] = T.A[ty + 8 * e][k]; y[e] = T.B[tx + 8 * e][k]; }
@@ -169,26 +257,30 @@ __device__ __forceinline__ void cost_tile_exact(const CostTile& T, const void* _
         }
 }
 
-__device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
-                                           const int32_t* __restrict__ wa_g, int h1, const int32_t* __restrict__ wb_g, int h2,
-                                           float* c, float* tiles, int lane)
+template <typename TE, bool VEC, int CK>
+__device__ __forceinline__ void pair_costs_as(const TE* __restrict__ E, int64_t ld, int32_t m, const int32_t* __restrict__ wa_g,
+                                              int h1, const int32_t* __restrict__ wb_g, int h2, float* c, float* tiles, int lane)
 {
-    const CostTile T(tiles);
+    const CostTile<CK> T(tiles);
     const int l31 = lane & 31, half = lane >> 5;
+    Gather<TE, VEC, CK> g;
     for (int p0 = 0; p0 < h1; p0 += kCT)
         for (int u0 = 0; u0 < h2; u0 += kCT) {
             wave_sync();                           // the previous tile's ids and norms have been read
             T.set_words(wa_g, p0, h1, wb_g, u0, h2, lane);
+            wave_sync();
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
             float na = 0.f, nb = 0.f;
-            for (int k0 = 0; k0 < m; k0 += kCK) {
-                wave_sync();                       // word ids written; the previous slice has been consumed
-                T.stage(E, dtype, ld, m, k0, lane);
+            T.fetch(E, ld, m, 0, lane, g);
+            for (int k0 = 0; k0 < m; k0 += CK) {
+                wave_sync();                       // the previous slice has been consumed
+                T.put(m, k0, lane, g);
                 wave_sync();
+                if (k0 + CK < m) T.fetch(E, ld, m, k0 + CK, lane, g);             // in flight behind this slice's products
 #pragma unroll
-                for (int i = 0; i < kCK / 2; ++i) {
+                for (int i = 0; i < CK / 2; ++i) {
                     const float a = T.A[l31][2 * i + half], b = T.B[l31][2 * i + half];
                     na = fmaf(a, a, na);
                     nb = fmaf(b, b, nb);
@@ -210,7 +302,7 @@ __device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype
                 close |= col_in && p0 + i < h1 && T.wa[i] != wcol && s - 2.f * acc[v] < kCloseFrac * s;
             }
             if (uni(__any(close) ? 1 : 0)) {
-                cost_tile_exact(T, E, dtype, ld, m, p0, h1, u0, h2, c, lane);
+                cost_tile_exact<TE, VEC, CK>(T, E, ld, m, p0, h1, u0, h2, c, lane);
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -222,6 +314,26 @@ __device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype
             }
         }
     wave_sync();                                   // the tile buffers become the solver's state
+}
+
+// CKV: slice width of the vectorised gathers (`tiles` holds cost_lds_bytes(CKV) bytes)
+template <int CKV>
+__device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+                                           const int32_t* __restrict__ wa_g, int h1, const int32_t* __restrict__ wb_g, int h2,
+                                           float* c, float* tiles, int lane)
+{
+    // groups of four values per load where every row starts on a group's boundary
+    const bool bf = dtype == LCRWMD_BF16;
+    const bool vec = (ld & 3) == 0 && (reinterpret_cast<uintptr_t>(E) & (bf ? 7 : 15)) == 0;
+    if (bf) {
+        const uint16_t* Eb = reinterpret_cast<const uint16_t*>(E);
+        if (vec) pair_costs_as<uint16_t, true, CKV>(Eb, ld, m, wa_g, h1, wb_g, h2, c, tiles, lane);
+        else pair_costs_as<uint16_t, false, 16>(Eb, ld, m, wa_g, h1, wb_g, h2, c, tiles, lane);
+    } else {
+        const float* Ef = reinterpret_cast<const float*>(E);
+        if (vec) pair_costs_as<float, true, CKV>(Ef, ld, m, wa_g, h1, wb_g, h2, c, tiles, lane);
+        else pair_costs_as<float, false, 16>(Ef, ld, m, wa_g, h1, wb_g, h2, c, tiles, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -258,8 +370,12 @@ __device__ __forceinline__ void pair_costs(const void* __restrict__ E, int dtype
 // lane's sinks live in registers, so that settling a node touches LDS only to record a predecessor; NPL == 0: any
 // size, that state in LDS.
 // ---------------------------------------------------------------------------------------------------------------
+// slices of the cost tiles: 16 values in every variant (32, whole 128-byte lines per row, measured 4 % slower on
+// 100-word histograms and would take more LDS than the per-word state of small problems)
+constexpr int emd_slice(int) { return 16; }
+
 template <int NPL>
-__global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
+__global__ __launch_bounds__(64, NPL == 2 ? 6 : 4) void k_emd(const void* __restrict__ E, int dtype, int64_t ld, int32_t m,
                                             const int64_t* __restrict__ db_rp, const int32_t* __restrict__ db_col,
                                             const float* __restrict__ db_val, const int64_t* __restrict__ q_rp,
                                             const int32_t* __restrict__ q_col, const float* __restrict__ q_val,
@@ -304,7 +420,7 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
         sa = wave_sum(sa);
         sb = wave_sum(sb);
 
-        pair_costs(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
+        pair_costs<emd_slice(NPL)>(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
         for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
         for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
 #pragma unroll
@@ -325,11 +441,12 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
         const double lim = bounded ? (double)limit[j - limit_j0] : 0.0;
         double tail = 0.0;
         if (bounded) {
-            for (int p = lane; p < h1; p += 64) {
+            for (int p = 0; p < h1; ++p) {                       // rows read whole, lanes over the sinks
                 const float* row = c + (int64_t)p * h2;
                 float r = FLT_MAX;
-                for (int u = 0; u < h2; ++u) r = fminf(r, row[u]);
-                tail += sup[p] * (double)r;
+                for (int u = lane; u < h2; u += 64) r = fminf(r, row[u]);
+                r = wave_min(r);
+                if (lane == (p & 63)) tail += sup[p] * (double)r;
             }
             tail = wave_sum(tail);
         }
@@ -340,7 +457,7 @@ __global__ __launch_bounds__(64, NPL ? 6 : 8) void k_emd(const void* __restrict_
                 const float* row = c + (int64_t)s * h2;
                 float r = FLT_MAX;
                 for (int u = lane; u < h2; u += 64) r = fminf(r, row[u]);
-                r_s = wave_min((double)r);
+                r_s = (double)wave_min(r);
                 tail -= sup[s] * r_s;
                 tail = tail > 0.0 ? tail : 0.0;
             }
@@ -742,11 +859,16 @@ static int32_t emd_bitmap_words(int64_t h1max, int64_t h2max)
     return w * h2max * 4 <= 16 * 1024 ? (int32_t)w : 0;
 }
 
+// Sinks per lane whose state the kernel variant keeps in registers, by the longest query-side histogram: up to 128
+// words 2, up to 256 words 4, beyond that 0 (state in LDS).
+static int emd_reg_sinks(int64_t h2max) { return h2max <= 128 ? 2 : h2max <= 256 ? 4 : 0; }
+
 // per-word solver state, or the cost tiles when those are larger (the two are never live together)
 static size_t emd_lds_bytes(int64_t h1max, int64_t h2max)
 {
     const size_t state = (size_t)(h1max + h2max) * 28 + (size_t)emd_bitmap_words(h1max, h2max) * (size_t)h2max * 4;
-    return state > (size_t)kCostLds ? state : (size_t)kCostLds;
+    const size_t tiles = (size_t)cost_lds_bytes(emd_slice(emd_reg_sinks(h2max)));
+    return state > tiles ? state : tiles;
 }
 
 // the settled-node masks hold 32 nodes per lane; the per-word state must fit one workgroup's LDS
@@ -756,9 +878,6 @@ bool emd_supported(int64_t h1max, int64_t h2max)
 }
 
 // Wavefronts that fit the device at once for histograms of this size.
-// Sinks per lane whose state the kernel variant keeps in registers, by the longest query-side histogram: up to 128
-// words 2, up to 256 words 4, beyond that 0 (state in LDS).
-static int emd_reg_sinks(int64_t h2max) { return h2max <= 128 ? 2 : h2max <= 256 ? 4 : 0; }
 
 typedef void (*EmdKernel)(const void*, int, int64_t, int32_t, const int64_t*, const int32_t*, const float*, const int64_t*,
                           const int32_t*, const float*, const int32_t*, const int32_t*, int64_t, int32_t*, float*, int64_t,
