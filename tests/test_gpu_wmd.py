@@ -113,6 +113,28 @@ def test_wmd_on_a_line_and_other_embedding_widths(ctx):
     assert_close(run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax), oracle.wmd_pairs(Er, p["db"], p["queries"], pi, pj), what="bf16 storage")
 
 
+@pytest.mark.parametrize("m,pitch,offset,dtype", [(300, 300, 0, "bf16"), (298, 300, 0, "f32"), (298, 304, 0, "bf16"),
+                                                  (300, 300, 1, "f32"), (300, 301, 0, "bf16"), (70, 72, 0, "f32")])
+def test_wmd_pairs_embedding_layouts(ctx, m, pitch, offset, dtype):
+    """Rows that start on 16-byte (bf16: 8-byte) boundaries are gathered four values per load, others one value per
+    load; m need not be a multiple of four or of the slice, and the columns between m and the pitch hold other data."""
+    rng = np.random.default_rng(21)
+    v = 500
+    E = synth.embeddings(v, m, 3)
+    if dtype == "bf16":
+        E = synth.bf16_bits_to_f32(synth.to_bf16_bits(E))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    flat = torch.full((v * pitch + 8,), 7.0, dtype=tdt, device="cuda")           # 7s wherever no embedding value sits
+    Eg = flat[offset:offset + v * pitch].view(v, pitch)[:, :m]
+    Eg.copy_(torch.from_numpy(E).cuda().to(tdt))
+    p = {"E": E, "db": synth.corpus(9, v, 10, 60, 1.0, 22), "queries": synth.corpus(4, v, 10, 60, 1.0, 23)}
+    db = binding.Csr.from_numpy(p["db"], v)
+    qs = binding.Csr.from_numpy(p["queries"], v)
+    pi, pj = np.divmod(np.arange(36), 4)
+    got = run_wmd_pairs(ctx, Eg, db, qs, pi, pj, (longest(p["db"]), longest(p["queries"])))
+    assert_close(got, oracle.wmd_pairs(E, p["db"], p["queries"], pi, pj), what=f"m = {m}, pitch {pitch}, offset {offset}, {dtype}")
+
+
 def test_wmd_pairs_medium_sized_documents(ctx):
     """Documents of the Medium configuration's lengths (50-150 words): the sizes the benchmark solves."""
     p = synth.make(synth.CONFIGS["medium"], n=40, q=4, v=20000)
