@@ -45,6 +45,8 @@ def wmd_leg(ctx, binding, synth, prob, E, v, m, n_w, q_w, k_w, with_oracle):
     sub_q = synth.csr_rows(*prob["queries"], np.arange(q_w))
     db, qs = binding.Csr.from_numpy(sub_db, v), binding.Csr.from_numpy(sub_q, v)
     hmax = (int(np.max(np.diff(sub_db[0]))), int(np.max(np.diff(sub_q[0]))))
+    saved = ctx.get_options()
+    ctx.set_options(**{**saved, "dedup": 1})      # the bounds come from the de-duplicated form here (same values, a tenth of the time)
     ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(v, m, n_w, db.nnz, q_w, qs.nnz, binding.F32, k_w, *hmax))
     R_idx = torch.empty((q_w, k_w), dtype=torch.int32, device="cuda")
     R_dist = torch.empty((q_w, k_w), dtype=torch.float32, device="cuda")
@@ -57,8 +59,9 @@ def wmd_leg(ctx, binding, synth, prob, E, v, m, n_w, q_w, k_w, with_oracle):
     torch.cuda.synchronize()
     t = time.perf_counter() - t
     pr = ctx.profile_end()
+    ctx.set_options(**saved)
     evaluated = int(ev.sum())
-    out = {"workload": f"first {n_w} database rows x first {q_w} queries, k = {k_w}", "ms": 1e3 * t,
+    out = {"workload": f"first {n_w} database rows x first {q_w} queries, k = {k_w}", "rwmd_form": "dedup", "ms": 1e3 * t,
            "wmd_evaluated": evaluated, "evaluated_fraction": evaluated / (n_w * q_w),
            "abandoned_above_cutoff": int(pr["emd_abandoned"]),
            "solver_ms": pr["emd_ms"], "rwmd_first_phase_ms": pr["phase1_ms"],
