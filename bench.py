@@ -308,7 +308,10 @@ def main():
         "dedup_variant": variant,
         "bf16x3_variant": x3,
         "wmd_topk": wmd,
-        "time_split_ms_per_step": {"phase1": prof["phase1_ms"] / args.steps, "phase2": prof["phase2_ms"] / args.steps,
+        "time_split_ms_per_step": {"phase1": prof["phase1_ms"] / args.steps,
+                                   "phase1_forward": (prof["phase1_ms"] - prof["phase1_swapped_ms"]) / args.steps,
+                                   "phase1_swapped": prof["phase1_swapped_ms"] / args.steps,
+                                   "phase2": prof["phase2_ms"] / args.steps,
                                    "table_passes": (prof["table_fwd_ms"] + prof["table_rev_ms"]) / args.steps,
                                    "rest": ms_per_step - (prof["phase1_ms"] + prof["phase2_ms"] + prof["table_fwd_ms"] +
                                                           prof["table_rev_ms"]) / args.steps},

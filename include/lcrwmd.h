@@ -217,6 +217,8 @@ typedef struct {
     double emd_ms;  int64_t emd_launches;  double emd_pairs;
     /* lcrwmd_wmd_topk: survivors whose solve stopped early because a lower bound passed the cut-off */
     double emd_abandoned;
+    /* the part of phase1_ms / phase1_flops spent in the pass with the two sets swapped (Sec. IV) */
+    double phase1_swapped_ms;  double phase1_swapped_flops;
 } lcrwmd_profile;
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);

@@ -54,7 +54,8 @@ class ProfileStruct(ctypes.Structure):
                 ("table_fwd_ms", ctypes.c_double), ("table_fwd_launches", ctypes.c_int64), ("table_fwd_bytes", ctypes.c_double),
                 ("table_rev_ms", ctypes.c_double), ("table_rev_launches", ctypes.c_int64), ("table_rev_bytes", ctypes.c_double),
                 ("emd_ms", ctypes.c_double), ("emd_launches", ctypes.c_int64), ("emd_pairs", ctypes.c_double),
-                ("emd_abandoned", ctypes.c_double)]
+                ("emd_abandoned", ctypes.c_double),
+                ("phase1_swapped_ms", ctypes.c_double), ("phase1_swapped_flops", ctypes.c_double)]
 
 
 class LcrwmdError(RuntimeError):

@@ -217,7 +217,7 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
 lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const int32_t* voc_rows, int64_t nvoc,
                          int z_by_position, const int32_t* zero_map, const int64_t* rp_batch,
                          const int32_t* col_idx, int64_t tokens, const TokenPlan& tp, float* Z, int64_t ldz,
-                         hipStream_t s)
+                         hipStream_t s, bool swapped = false)
 {
     HIP_TRY(launch_token_plan(tp, rp_batch, col_idx, ep.normE, s));
     Phase1Args a;
@@ -232,7 +232,7 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     a.ldz = ldz;
     a.num_cu = ctx->num_cu;
     {
-        ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m);
+        ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m, swapped ? 1.0 : 0.0);
         if (ep.mode == 2) HIP_TRY(launch_phase1_tiles_x3(a, tp, s));
         else if (ep.bf16) HIP_TRY(launch_phase1_bf16(a, tp, s));
         else HIP_TRY(launch_phase1_f32(a, tp, s));
@@ -481,7 +481,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         float* Z = bb.take_n<float>((size_t)vq * ldz);
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");
         ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
-                          DB->col_idx, rdb[i1] - rdb[i0], tp, Z, ldz, s));
+                          DB->col_idx, rdb[i1] - rdb[i0], tp, Z, ldz, s, /*swapped=*/true));
         // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
         ST_TRY(run_spmm(ctx, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, nnz_q, vq, Z, ldz, i1 - i0, D + i0 * ldd, ldd, 2, s));
     }
@@ -576,7 +576,12 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out)
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
         if (e != hipSuccess) continue;
-        if (r.kind == 1) { out->phase1_ms += ms; out->phase1_launches += 1; out->phase1_flops += r.work; }
+        if (r.kind == 1) {
+            out->phase1_ms += ms;
+            out->phase1_launches += 1;
+            out->phase1_flops += r.work;
+            if (r.work2 > 0.0) { out->phase1_swapped_ms += ms; out->phase1_swapped_flops += r.work; }
+        }
         else if (r.kind == 3) { out->table_fwd_ms += ms; out->table_fwd_launches += 1; out->table_fwd_bytes += r.work; }
         else if (r.kind == 4) { out->table_rev_ms += ms; out->table_rev_launches += 1; out->table_rev_bytes += r.work; }
         else if (r.kind == 5) { out->emd_ms += ms; out->emd_launches += 1; out->emd_pairs += r.work; }

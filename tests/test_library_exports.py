@@ -28,7 +28,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(binding.CsrStruct) == 56
     assert ctypes.sizeof(binding.EmbStruct) == 40
     assert ctypes.sizeof(binding.OptionsStruct) == 32
-    assert ctypes.sizeof(binding.ProfileStruct) == 136
+    assert ctypes.sizeof(binding.ProfileStruct) == 152
 
 
 def test_no_oracle_in_product_path():
