@@ -38,6 +38,16 @@ def recorded_traffic(workload, compute):
     return None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def wmd_leg(ctx, binding, synth, prob, E, v, m, n_w, q_w, k_w, with_oracle):
     """Top-k exact WMD with the RWMD cut-off on the first n_w database rows x q_w queries; solver rate; oracle rate."""
     import torch
@@ -258,7 +268,8 @@ def main():
         oracle.rwmd_table(prob["E"], prob["db"], sub)
         tc = time.perf_counter() - tc
         cpu = {"value": n * qn / tc, "unit": "pairs/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"per-query table oracle (fp64), all {n} database docs x first {qn} queries, {tc:.1f} s"}
+               "sample": f"per-query table oracle (fp64), all {n} database docs x first {qn} queries, {tc:.1f} s",
+               "cpu": cpu_model()}
 
     p1_roof = {"bound": "mfma", "kernel": f"phase1_{args.compute}", "achieved": achieved_tflops, "peak": peak,
                "unit": "TFLOP/s", "frac": achieved_tflops / peak,
