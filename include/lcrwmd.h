@@ -290,7 +290,9 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
  * RWMD instead and L is the k-th smallest of their k1 WMDs: the same wall time, a lower cut-off,
  * fewer survivors (any k evaluated distances bound the k-th best from above).  A survivor's solve
  * stops as soon as a lower bound on its distance (the value of the solver's dual variables, which
- * starts at the one-sided RWMD and ends at the WMD) exceeds L: it cannot be among the k nearest.  The device compares fp32 RWMD values
+ * starts at the one-sided RWMD and ends at the WMD) exceeds L: it cannot be among the k nearest.
+ * Where k1 < 64, the next nearest by RWMD up to 64 per query are evaluated against that L in the
+ * same way before the survivors are listed, and L becomes the k-th smallest of all 64.  The device compares fp32 RWMD values
  * against fp32 WMD values, so the test is RWMD < L (1 + 1e-5): rounding can only add candidates.
  * R_idx / R_dist: q x k, ordered by (distance, row index) ascending, as in lcrwmd_rwmd_topk.
  * evaluated (HOST, q entries, or NULL): WMD evaluations started for each query (first round +

@@ -983,22 +983,30 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         const int64_t j1 = j0 + qb < q ? j0 + qb : q, nq = j1 - j0;
         Bump b(ws, ws_bytes);
         const int64_t ldt = round_up(nq, 4);
-        // First round: the k1 >= k nearest by RWMD per query.  The paper takes k1 = k; while the batch's k * nq transport
-        // problems do not fill the device, a larger k1 costs no time and gives a lower cut-off (the k-th smallest of k1
-        // distances instead of the largest of k), hence fewer survivors.  Nothing is lost: any k evaluated distances
-        // bound the k-th best from above.
+        // First round: the k1 >= k nearest by RWMD per query, solved to the end.  The paper takes k1 = k; while the
+        // batch's k * nq transport problems do not fill the device, a larger k1 costs no time and gives a lower cut-off
+        // (the k-th smallest of k1 distances instead of the largest of k), hence fewer survivors.  Nothing is lost: any
+        // k evaluated distances bound the k-th best from above.
+        // Second round, when the first one already fills the device with k per query: the next nearest up to 64 per
+        // query against that cut-off (abandoned as soon as they pass it, like survivors, so they cost little), after
+        // which the cut-off is the k-th smallest of all evaluated so far.  (With fewer queries the wider first round
+        // does the same without a launch of its own, which would be bound by the latency of its few full solves.)
+        const int kmax = n < kMaxTopK ? (int)n : kMaxTopK;
         int k1 = (int)(emd_preferred_slots(ctx->num_cu, h1max, h2max) / nq);
-        if (k1 > kMaxTopK) k1 = kMaxTopK;
-        if (k1 > n) k1 = (int)n;
+        if (k1 > kmax) k1 = kmax;
+        const bool full_device = k1 <= k;
         if (k1 < k) k1 = k;
+        const int kx = full_device ? kmax : k1;                  // candidates taken off the top of the bounds
+        const int k2 = kx - k1;
         float* tile = b.take_n<float>((size_t)n * ldt);
-        const size_t tkb = topk_bytes(n, nq, k1) + 512;
+        const size_t tkb = topk_bytes(n, nq, kx) + 512;
         void* tk = b.take(tkb);
-        int32_t* R0 = b.take_n<int32_t>((size_t)nq * k1);
-        float* R0d = b.take_n<float>((size_t)nq * k1);
-        int32_t* p0_db = b.take_n<int32_t>((size_t)nq * k1);
-        int32_t* p0_q = b.take_n<int32_t>((size_t)nq * k1);
-        float* wmd0 = b.take_n<float>((size_t)nq * k1);
+        int32_t* R0 = b.take_n<int32_t>((size_t)nq * kx);
+        float* R0d = b.take_n<float>((size_t)nq * kx);
+        int32_t* p0_db = b.take_n<int32_t>((size_t)nq * kx);
+        int32_t* p0_q = b.take_n<int32_t>((size_t)nq * kx);
+        float* wmd0 = b.take_n<float>((size_t)nq * kx);
+        float* wmd1 = wmd0 + (size_t)nq * k1;                    // second round: k2 per query
         float* cut = b.take_n<float>((size_t)nq);
         int32_t* cnt = b.take_n<int32_t>((size_t)nq);
         int64_t* off = b.take_n<int64_t>((size_t)nq + 1);
@@ -1009,21 +1017,29 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         char* rest = (char*)ws + rest_off;
         const size_t rest_bytes = ws_bytes - rest_off;
 
-        // RWMD to every database histogram, the k1 nearest by RWMD (Sec. III)
+        // RWMD to every database histogram, the kx nearest by RWMD (Sec. III)
         ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, rest, rest_bytes, s));
-        HIP_TRY(launch_topk(tile, n, nq, ldt, k1, R0, R0d, tk, tkb, s));
-        // WMD to those; the k-th smallest of them is the cut-off
+        HIP_TRY(launch_topk(tile, n, nq, ldt, kx, R0, R0d, tk, tkb, s));
+        // WMD to the first k1 of those; the k-th smallest of them is the cut-off
         HIP_TRY(launch_fill_i32(counters, 4, 0, s));
-        HIP_TRY(launch_first_pairs(R0, nq, k1, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
+        HIP_TRY(launch_first_pairs(R0, nq, kx, 0, k1, (int32_t)j0, tile, ldt, p0_db, p0_q, s));
         ST_TRY(run_wmd_list(ctx, queries, database, E, p0_db, p0_q, nq * k1, h1max, h2max, rest, rest_bytes, wmd0, nullptr,
                             counters, s));
-        HIP_TRY(launch_cutoff(wmd0, nq, k1, k, 1e-5f, cut, s));
+        HIP_TRY(launch_cutoff(wmd0, k1, wmd1, 0, nq, k, 1e-5f, cut, s));
+        if (k2 > 0) {
+            int32_t* p1_db = p0_db + (size_t)nq * k1;
+            int32_t* p1_q = p0_q + (size_t)nq * k1;
+            HIP_TRY(launch_first_pairs(R0, nq, kx, k1, kx, (int32_t)j0, tile, ldt, p1_db, p1_q, s));
+            ST_TRY(run_wmd_list(ctx, queries, database, E, p1_db, p1_q, nq * k2, h1max, h2max, rest, rest_bytes, wmd1, nullptr,
+                                counters, s, cut, (int32_t)j0));
+            HIP_TRY(launch_cutoff(wmd0, k1, wmd1, k2, nq, k, 1e-5f, cut, s));
+        }
         // survivors: RWMD below the cut-off
         HIP_TRY(launch_count_below(tile, n, nq, ldt, cut, cnt, off, s));
         HIP_TRY(hipMemcpyAsync(hoff.data(), off, sizeof(int64_t) * ((size_t)nq + 1), hipMemcpyDeviceToHost, s));
         HIP_TRY(hipStreamSynchronize(s));
         if (evaluated)
-            for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = k1 + hoff[j + 1] - hoff[j];
+            for (int64_t j = 0; j < nq; ++j) evaluated[j0 + j] = kx + hoff[j + 1] - hoff[j];
         // Lists hold 12 bytes per survivor; they share `rest` with the transport problems in flight.
         // The transport problems get all the room they can use when the batch's lists fit beside it in one piece,
         // half of the rest otherwise.
@@ -1051,7 +1067,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
             // a survivor is dropped as soon as the solver's lower bound on its distance passes the cut-off
             ST_TRY(run_wmd_list(ctx, queries, database, E, l_db, l_q, total, h1max, h2max, rest, slab_part, l_d, nullptr, counters, s,
                                 cut, (int32_t)j0));
-            HIP_TRY(launch_select_lists(R0, wmd0, k1, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
+            HIP_TRY(launch_select_lists(R0, wmd0, k1, wmd1, k2, k, off, ja, jb, l_db, l_d, R_idx + j0 * k, R_dist + j0 * k, s));
             ja = jb;
         }
         int32_t hc[4] = {0, 0, 0, 0};

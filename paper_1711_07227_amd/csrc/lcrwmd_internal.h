@@ -188,15 +188,17 @@ hipError_t launch_check_pairs(const int32_t* pair_db, const int32_t* pair_q, int
 hipError_t launch_centroids(const lcrwmd_emb& E, const lcrwmd_csr& X, float* C, int64_t ldc, hipStream_t s);
 hipError_t launch_centroid_dist(const float* C1, int64_t n, const float* C2, int64_t q, int64_t ldc, int32_t m, float* D,
                                 int64_t ldd, hipStream_t s);
-hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int k, int32_t j0, float* D, int64_t ldd, int32_t* pair_db,
-                              int32_t* pair_q, hipStream_t s);
-hipError_t launch_cutoff(const float* wmd0, int64_t q, int k1, int k, float slack, float* cut, hipStream_t s);
+hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int stride, int lo, int hi, int32_t j0, float* D, int64_t ldd,
+                              int32_t* pair_db, int32_t* pair_q, hipStream_t s);
+hipError_t launch_cutoff(const float* wa, int ka, const float* wb, int kb, int64_t q, int k, float slack, float* cut,
+                         hipStream_t s);
 hipError_t launch_count_below(const float* D, int64_t n, int64_t q, int64_t ldd, const float* cut, int32_t* cnt,
                               int64_t* off, hipStream_t s);
 hipError_t launch_fill_below(const float* D, int64_t n, int64_t ja, int64_t jb, int64_t ldd, const float* cut,
                              const int64_t* off, int64_t* cursor, int32_t j0, int32_t* pair_db, int32_t* pair_q,
                              hipStream_t s);
-hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k1, int k, const int64_t* off, int64_t ja, int64_t jb,
-                               const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist, hipStream_t s);
+hipError_t launch_select_lists(const int32_t* idx0, const float* da, int ka, const float* db, int kb, int k, const int64_t* off,
+                               int64_t ja, int64_t jb, const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist,
+                               hipStream_t s);
 
 }  // namespace lcrwmd

@@ -696,25 +696,29 @@ __global__ __launch_bounds__(256) void k_centroid_dist(const float* __restrict__
 // ---------------------------------------------------------------------------------------------------------------
 // Pruning (Sec. III, "Speeding-up WMD using RWMD").  D is the n x q tile of RWMD bounds, R0 the k nearest by RWMD.
 // ---------------------------------------------------------------------------------------------------------------
-// pair lists of the first k candidates of every query, and those entries of D masked so that they are not chosen again
-__global__ void k_first_pairs(const int32_t* __restrict__ R0, int64_t q, int k, int32_t j0, float* __restrict__ D,
-                              int64_t ldd, int32_t* __restrict__ pair_db, int32_t* __restrict__ pair_q)
+// pair lists of candidates lo .. hi - 1 of every query (R0 holds `stride` of them per query, nearest first), and those
+// entries of D masked so that they are not chosen again
+__global__ void k_first_pairs(const int32_t* __restrict__ R0, int64_t q, int stride, int lo, int hi, int32_t j0,
+                              float* __restrict__ D, int64_t ldd, int32_t* __restrict__ pair_db, int32_t* __restrict__ pair_q)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= q * k) return;
-    const int64_t j = e / k;
-    const int32_t i = R0[e];
+    const int w = hi - lo;
+    if (e >= q * w) return;
+    const int64_t j = e / w;
+    const int32_t i = R0[j * stride + lo + (int)(e - j * w)];
     pair_db[e] = i;
     pair_q[e] = j0 + (int32_t)j;
     D[(int64_t)i * ldd + j] = FLT_MAX;
 }
 
-// cut[j] = (k-th smallest WMD among the k1 >= k of the first round) * (1 + slack); with k1 == k their largest
-__global__ void k_cutoff(const float* __restrict__ wmd0, int64_t q, int k1, int k, float slack, float* __restrict__ cut)
+// cut[j] = (k-th smallest WMD among the ka + kb >= k evaluated so far: ka per query in wa, kb in wb) * (1 + slack);
+// with ka == k and kb == 0 their largest.  At least k of them are finite (abandoned ones hold FLT_MAX).
+__global__ void k_cutoff(const float* __restrict__ wa, int ka, const float* __restrict__ wb, int kb, int64_t q, int k,
+                         float slack, float* __restrict__ cut)
 {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= q) return;
-    const float* w = wmd0 + j * k1;
+    const int k1 = ka + kb;
     // k rounds of "smallest value after the last one taken", equal values told apart by position
     float last = -1.f;
     int last_r = -1;
@@ -722,7 +726,7 @@ __global__ void k_cutoff(const float* __restrict__ wmd0, int64_t q, int k1, int 
         float best = FLT_MAX;
         int best_r = k1;
         for (int r = 0; r < k1; ++r) {
-            const float x = w[r];
+            const float x = r < ka ? wa[j * ka + r] : wb[j * kb + r - ka];
             const bool after = x > last || (x == last && r > last_r);
             if (after && (x < best || (x == best && r < best_r))) { best = x; best_r = r; }
         }
@@ -804,9 +808,11 @@ __global__ void k_check_pairs(const int32_t* __restrict__ pair_db, const int32_t
     if (i < 0 || i >= n || j < 0 || j >= q) status[0] = 1;
 }
 
-// The k smallest of every query's evaluated WMDs, ordered by (distance, database row): the k1 candidates of the first
-// round (idx0 / d0, k1 per query) and the query's list [off[j], off[j + 1]) of the rest.  One workgroup per query.
-__global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict__ idx0, const float* __restrict__ d0, int k1, int k,
+// The k smallest of every query's evaluated WMDs, ordered by (distance, database row): the ka + kb candidates of the
+// first rounds (rows idx0, ka + kb per query; distances da, ka per query, then db, kb per query) and the query's list
+// [off[j], off[j + 1]) of the rest.  One workgroup per query.
+__global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict__ idx0, const float* __restrict__ da, int ka,
+                                                      const float* __restrict__ db, int kb, int k,
                                                       const int64_t* __restrict__ off, int64_t ja, const int32_t* __restrict__ idx1,
                                                       const float* __restrict__ d1, int32_t* __restrict__ R_idx,
                                                       float* __restrict__ R_dist)
@@ -816,13 +822,14 @@ __global__ __launch_bounds__(256) void k_select_lists(const int32_t* __restrict_
     const int tid = threadIdx.x;
     const int64_t j = ja + blockIdx.x;
     const int64_t a = off[j] - off[ja], cnt = off[j + 1] - off[j];      // idx1 / d1 start at the range's first query
+    const int k1 = ka + kb;
     float last_d = -1.f;                 // distances are >= 0, so (-1, -1) precedes every item
     int32_t last_i = -1;
     for (int r = 0; r < k; ++r) {
         float bd = FLT_MAX;
         int32_t bi = INT_MAX;
         for (int64_t e = tid; e < k1 + cnt; e += 256) {
-            const float d = e < k1 ? d0[j * k1 + e] : d1[a + e - k1];
+            const float d = e < ka ? da[j * ka + e] : e < k1 ? db[j * kb + e - ka] : d1[a + e - k1];
             const int32_t i = e < k1 ? idx0[j * k1 + e] : idx1[a + e - k1];
             const bool after = d > last_d || (d == last_d && i > last_i);
             if (after && (d < bd || (d == bd && i < bi))) { bd = d; bi = i; }
@@ -960,19 +967,20 @@ hipError_t launch_centroid_dist(const float* C1, int64_t n, const float* C2, int
     return hipSuccess;
 }
 
-hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int k, int32_t j0, float* D, int64_t ldd, int32_t* pair_db,
-                              int32_t* pair_q, hipStream_t s)
+hipError_t launch_first_pairs(const int32_t* R0, int64_t q, int stride, int lo, int hi, int32_t j0, float* D, int64_t ldd,
+                              int32_t* pair_db, int32_t* pair_q, hipStream_t s)
 {
-    const int64_t total = q * k;
+    const int64_t total = q * (hi - lo);
     if (total <= 0) return hipSuccess;
-    k_first_pairs<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>(R0, q, k, j0, D, ldd, pair_db, pair_q);
+    k_first_pairs<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>(R0, q, stride, lo, hi, j0, D, ldd, pair_db, pair_q);
     return hipGetLastError();
 }
 
-hipError_t launch_cutoff(const float* wmd0, int64_t q, int k1, int k, float slack, float* cut, hipStream_t s)
+hipError_t launch_cutoff(const float* wa, int ka, const float* wb, int kb, int64_t q, int k, float slack, float* cut,
+                         hipStream_t s)
 {
     if (q <= 0) return hipSuccess;
-    k_cutoff<<<dim3((unsigned)((q + 255) / 256)), 256, 0, s>>>(wmd0, q, k1, k, slack, cut);
+    k_cutoff<<<dim3((unsigned)((q + 255) / 256)), 256, 0, s>>>(wa, ka, wb, kb, q, k, slack, cut);
     return hipGetLastError();
 }
 
@@ -1006,11 +1014,12 @@ hipError_t launch_fill_below(const float* D, int64_t n, int64_t ja, int64_t jb, 
     return hipGetLastError();
 }
 
-hipError_t launch_select_lists(const int32_t* idx0, const float* d0, int k1, int k, const int64_t* off, int64_t ja, int64_t jb,
-                               const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist, hipStream_t s)
+hipError_t launch_select_lists(const int32_t* idx0, const float* da, int ka, const float* db, int kb, int k, const int64_t* off,
+                               int64_t ja, int64_t jb, const int32_t* idx1, const float* d1, int32_t* R_idx, float* R_dist,
+                               hipStream_t s)
 {
     if (jb <= ja) return hipSuccess;
-    k_select_lists<<<dim3((unsigned)(jb - ja)), 256, 0, s>>>(idx0, d0, k1, k, off, ja, idx1, d1, R_idx, R_dist);
+    k_select_lists<<<dim3((unsigned)(jb - ja)), 256, 0, s>>>(idx0, da, ka, db, kb, k, off, ja, idx1, d1, R_idx, R_dist);
     return hipGetLastError();
 }
 

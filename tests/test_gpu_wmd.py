@@ -352,6 +352,30 @@ def test_wmd_topk_abandons_survivors_without_losing_a_neighbour(ctx):
         assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
 
 
+def test_wmd_topk_with_more_queries_than_the_first_round_can_widen_for(ctx):
+    """With hundreds of queries in a batch the first round is k per query (the device is full), the second round
+    takes the next nearest up to 64 against the first cut-off.  Same result as the exhaustive matrix."""
+    p = problem(v=2000, m=300, n=900, q=500, h_lo=3, h_hi=16, seed=51)
+    E, db, qs = upload(p)
+    n, q, k = 900, 500, 16
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    pi, pj = np.divmod(np.arange(n * q), q)
+    W = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=8192).reshape(n, q).astype(np.float64)
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(2000, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ev = torch.zeros(q, dtype=torch.int64)
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws, ev)
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    assert int(ev.min()) >= 64 and int(ev.sum()) < n * q
+    for j in range(q):
+        order = np.lexsort((np.arange(n), W[:, j]))[:k]
+        assert np.array_equal(gd[j], W[order, j].astype(np.float32)), j
+        assert np.array_equal(gi[j], order), j
+    for j in (0, 499):
+        assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
+
+
 def test_wmd_topk_with_queries_longer_than_the_register_variants_hold(ctx):
     """Queries of 260-300 words take the solver variant that keeps the sinks' state in LDS; survivors are abandoned
     there by the same rule.  Reference: every pair solved to the end on the device, the rows returned re-solved by
