@@ -224,9 +224,10 @@ lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
 
 /* ---------------------------------------------------------------------------------------------
- * Exact WMD behind the RWMD bound (Sec. II, Sec. III).  These calls take fp32 or bf16 E of any m;
- * cost matrices are evaluated from differences of the stored values in fp32, the transport
- * problems are solved in fp64, results are returned as fp32.
+ * Exact WMD behind the RWMD bound (Sec. II, Sec. III).  These calls take fp32 or bf16 E of any m and
+ * pitch.  Cost matrices are fp32: |a|^2 + |b|^2 - 2 a.b on the matrix cores where the two words lie
+ * apart (d^2 >= (|a|^2 + |b|^2) / 4), sums of squared coordinate differences where they lie close,
+ * exactly 0 for equal word ids.  The transport problems are solved in fp64, results returned as fp32.
  * ------------------------------------------------------------------------------------------- */
 
 /*
@@ -291,9 +292,10 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
  * fewer survivors (any k evaluated distances bound the k-th best from above).  A survivor's solve
  * stops as soon as a lower bound on its distance (the value of the solver's dual variables, which
  * starts at the one-sided RWMD and ends at the WMD) exceeds L: it cannot be among the k nearest.
- * Where k1 < 64, the next nearest by RWMD up to 64 per query are evaluated against that L in the
- * same way before the survivors are listed, and L becomes the k-th smallest of all 64.  The device compares fp32 RWMD values
- * against fp32 WMD values, so the test is RWMD < L (1 + 1e-5): rounding can only add candidates.
+ * Where k per query does fill the device, the next nearest by RWMD up to 64 per query are evaluated
+ * against that L in the same way before the survivors are listed, and L becomes the k-th smallest of
+ * all 64.  The device compares fp32 RWMD values against fp32 WMD values, so the test is
+ * RWMD < L (1 + 1e-5): rounding can only add candidates.
  * R_idx / R_dist: q x k, ordered by (distance, row index) ascending, as in lcrwmd_rwmd_topk.
  * evaluated (HOST, q entries, or NULL): WMD evaluations started for each query (first round +
  * survivors, including those that stopped early).
