@@ -115,7 +115,7 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
-    ap.add_argument("--cpu-queries", type=int, default=24, help="queries in the CPU oracle's timed sample")
+    ap.add_argument("--cpu-queries", type=int, default=48, help="queries in the CPU oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
