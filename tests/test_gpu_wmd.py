@@ -374,6 +374,15 @@ def test_wmd_topk_with_more_queries_than_the_first_round_can_widen_for(ctx):
         assert np.array_equal(gi[j], order), j
     for j in (0, 499):
         assert_close(gd[j], oracle.wmd_pairs(p["E"], p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values")
+    # the same queries in batches of 190 (one first round each, wider): same result
+    try:
+        ctx.set_options(max_query_batch=190)
+        R2 = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+        D2 = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.wmd_topk(qs, db, E, k, R2, D2, ws)
+        assert torch.equal(R2, R_idx) and torch.equal(D2, R_dist)
+    finally:
+        ctx.set_options()
 
 
 def test_wmd_topk_with_queries_longer_than_the_register_variants_hold(ctx):
