@@ -385,6 +385,28 @@ def test_wmd_topk_with_more_queries_than_the_first_round_can_widen_for(ctx):
         ctx.set_options()
 
 
+def test_wmd_topk_with_bf16_embeddings(ctx):
+    """Embeddings stored as bf16: bounds and transport costs are both taken from the stored values, so the bound stays
+    a bound and the search returns the k nearest of the exhaustive matrix; values against the oracle on those values."""
+    p = problem(v=1500, m=300, n=700, q=9, h_lo=5, h_hi=30, seed=61)
+    Er = synth.bf16_bits_to_f32(synth.to_bf16_bits(p["E"]))
+    E, db, qs = upload({"E": Er, "db": p["db"], "queries": p["queries"]}, dtype=torch.bfloat16)
+    n, q, k = 700, 9, 6
+    hmax = (longest(p["db"]), longest(p["queries"]))
+    pi, pj = np.divmod(np.arange(n * q), q)
+    W = run_wmd_pairs(ctx, E, db, qs, pi, pj, hmax, in_flight=4096).reshape(n, q).astype(np.float64)
+    ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(1500, 300, n, db.nnz, q, qs.nnz, binding.BF16, k, *hmax))
+    R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws)
+    gi, gd = R_idx.cpu().numpy(), R_dist.cpu().numpy()
+    for j in range(q):
+        order = np.lexsort((np.arange(n), W[:, j]))[:k]
+        assert np.array_equal(gi[j], order) and np.array_equal(gd[j], W[order, j].astype(np.float32))
+    for j in (0, 8):
+        assert_close(gd[j], oracle.wmd_pairs(Er, p["db"], p["queries"], gi[j], np.full(k, j)), what="top-k WMD values, bf16 storage")
+
+
 def test_wmd_topk_with_queries_longer_than_the_register_variants_hold(ctx):
     """Queries of 260-300 words take the solver variant that keeps the sinks' state in LDS; survivors are abandoned
     there by the same rule.  Reference: every pair solved to the end on the device, the rows returned re-solved by
