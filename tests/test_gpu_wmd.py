@@ -385,6 +385,33 @@ def test_wmd_topk_with_more_queries_than_the_first_round_can_widen_for(ctx):
         ctx.set_options()
 
 
+@pytest.mark.parametrize("options", [{"dedup": 1}, {"compute": binding.BF16X3}, {"dedup": 1, "compute": binding.BF16X3}])
+def test_wmd_topk_does_not_depend_on_the_form_of_the_bounds(ctx, options):
+    """The de-duplicated form and the split-bf16 arithmetic give the same bounds up to fp32 rounding; the k nearest by
+    WMD and their distances must come out bit-identical to the default form's."""
+    p = problem(v=3000, m=300, n=1500, q=12, h_lo=8, h_hi=40, seed=71)
+    E, db, qs = upload(p)
+    n, q, k = 1500, 12, 7
+    hmax = (longest(p["db"]), longest(p["queries"]))
+
+    def run():
+        ws = binding.alloc_workspace(ctx.wmd_topk_workspace_bytes(3000, 300, n, db.nnz, q, qs.nnz, binding.F32, k, *hmax))
+        R_idx = torch.full((q, k), -1, dtype=torch.int32, device="cuda")
+        R_dist = torch.full((q, k), float("nan"), dtype=torch.float32, device="cuda")
+        ctx.wmd_topk(qs, db, E, k, R_idx, R_dist, ws)
+        return R_idx.cpu(), R_dist.cpu()
+
+    ref = run()
+    try:
+        ctx.set_options(**options)
+        got = run()
+    finally:
+        ctx.set_options()
+    assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1])
+    assert_close(ref[1][0].numpy(), oracle.wmd_pairs(p["E"], p["db"], p["queries"], ref[0][0].numpy(), np.zeros(k, np.int64)),
+                 what="top-k WMD values")
+
+
 def test_wmd_topk_with_bf16_embeddings(ctx):
     """Embeddings stored as bf16: bounds and transport costs are both taken from the stored values, so the bound stays
     a bound and the search returns the k nearest of the exhaustive matrix; values against the oracle on those values."""
