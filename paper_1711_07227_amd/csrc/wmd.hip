@@ -390,14 +390,15 @@ __global__ __launch_bounds__(64, NPL == 2 ? 6 : 4) void k_emd(const void* __rest
     double* phiS = lds_d;
     double* dS = phiS + h1max;
     double* sup = dS + h1max;
+    // the register variants keep the sinks' potentials and tentative distances out of LDS altogether
+    constexpr bool REG = NPL > 0;
     double* phiT = sup + h1max;
-    double* dT = phiT + h2max;
-    double* dem = dT + h2max;
+    double* dT = phiT + (REG ? 0 : h2max);
+    double* dem = REG ? sup + h1max : dT + h2max;
     int32_t* par = reinterpret_cast<int32_t*>(dem + h2max);
     int32_t* way = par + h1max;
     uint32_t* bm = reinterpret_cast<uint32_t*>(way + h2max);        // [h2max][bm_words], bit p of row u: y[p, u] > 0
 
-    constexpr bool REG = NPL > 0;
     constexpr int NR = REG ? NPL : 1;
     const int lane = threadIdx.x;
     float* c = slabs_c + (int64_t)blockIdx.x * slab_elems;
@@ -422,7 +423,10 @@ __global__ __launch_bounds__(64, NPL == 2 ? 6 : 4) void k_emd(const void* __rest
 
         pair_costs<emd_slice(NPL)>(E, dtype, ld, m, db_col + a0, h1, q_col + b0, h2, c, reinterpret_cast<float*>(lds_d), lane);
         for (int p = lane; p < h1; p += 64) { phiS[p] = 0.0; sup[p] = (double)db_val[a0 + p] / sa; }
-        for (int u = lane; u < h2; u += 64) { phiT[u] = 0.0; dem[u] = (double)q_val[b0 + u] / sb; }
+        for (int u = lane; u < h2; u += 64) {
+            if constexpr (!REG) phiT[u] = 0.0;
+            dem[u] = (double)q_val[b0 + u] / sb;
+        }
 #pragma unroll
         for (int k = 0; k < NR; ++k) pT[k] = 0.0;
         // with the map of positive flows an entry of f is read only after it has been written: no need to clear f
@@ -526,7 +530,18 @@ __global__ __launch_bounds__(64, NPL == 2 ? 6 : 4) void k_emd(const void* __rest
                                 p = uni(way[up]);
                             }
                         }
-                        total += delta * (bv - phiS[s] + phiT[u]);   // potentials are those of the search's start
+                        // potentials are those of the search's start; REG: sink u's sits in register u / 64 of lane u % 64
+                        double phiT_u;
+                        if constexpr (REG) {
+                            double mine = pT[0];
+#pragma unroll
+                            for (int k = 1; k < NR; ++k) mine = (u >> 6) == k ? pT[k] : mine;
+                            phiT_u = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(mine), u & 63),
+                                                      __builtin_amdgcn_readlane(__double2loint(mine), u & 63));
+                        } else {
+                            phiT_u = phiT[u];
+                        }
+                        total += delta * (bv - phiS[s] + phiT_u);
                         wave_sync();                                 // reads of the old flows are done
                         int cut = 0;
                         if (lane == 0) {                             // move the mass
@@ -611,10 +626,7 @@ __global__ __launch_bounds__(64, NPL == 2 ? 6 : 4) void k_emd(const void* __rest
                 if constexpr (REG) {
 #pragma unroll
                     for (int k = 0; k < NR; ++k)
-                        if (((used >> k) & 1) && dTr[k] < Dt) {
-                            pT[k] += dTr[k] - Dt;
-                            phiT[lane + 64 * k] = pT[k];             // the copy other lanes read for a path's cost
-                        }
+                        if (((used >> k) & 1) && dTr[k] < Dt) pT[k] += dTr[k] - Dt;
                 } else {
                     for (int u = lane, r = 0; u < h2; u += 64, ++r)
                         if (((used >> r) & 1) && dT[u] < Dt) phiT[u] += dT[u] - Dt;
@@ -873,7 +885,10 @@ static int emd_reg_sinks(int64_t h2max) { return h2max <= 128 ? 2 : h2max <= 256
 // per-word solver state, or the cost tiles when those are larger (the two are never live together)
 static size_t emd_lds_bytes(int64_t h1max, int64_t h2max)
 {
-    const size_t state = (size_t)(h1max + h2max) * 28 + (size_t)emd_bitmap_words(h1max, h2max) * (size_t)h2max * 4;
+    // per source 28 bytes (potential, distance, supply, predecessor); per sink 28 (potential, distance, demand, way),
+    // 12 in the register variants (demand, way)
+    const size_t per_sink = emd_reg_sinks(h2max) ? 12 : 28;
+    const size_t state = (size_t)h1max * 28 + (size_t)h2max * per_sink + (size_t)emd_bitmap_words(h1max, h2max) * (size_t)h2max * 4;
     const size_t tiles = (size_t)cost_lds_bytes(emd_slice(emd_reg_sinks(h2max)));
     return state > tiles ? state : tiles;
 }
