@@ -62,10 +62,7 @@ struct ProfScope {
 };
 
 constexpr int64_t kMaxTokens = (int64_t)1 << 30;   // padded tokens per launch (int32 offsets)
-#ifndef LCRWMD_DB_BATCH
-#define LCRWMD_DB_BATCH 16384          // build-time knob: database rows per pass of the swapped direction
-#endif
-constexpr int64_t kDbBatch = LCRWMD_DB_BATCH;
+constexpr int64_t kDbBatch = 16384;                // database rows per pass of the swapped direction (option max_db_batch lowers it)
 
 lcrwmd_status check_csr(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const char* name, bool need_val)
 {
@@ -132,10 +129,16 @@ lcrwmd_status validate_on_device(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const cha
 struct EmbPrep {
     const void* data;
     int64_t ld;
+    int64_t rows;  // rows of `data`
     int32_t m;     // embedding dimension the first-phase kernels are told (300 for the padded fp32 copy)
     float* normE;
     bool bf16;     // mode 1
     int mode;      // see prec_mode
+    // the same values for the pass that redoes close word pairs from coordinate differences (launch_redo_close)
+    const void* xdata;
+    int64_t xld;
+    int32_t xm;
+    bool xbf16;
 };
 
 // fp32 E that the tile kernel cannot read in place (a pitch or base that is not 16-byte aligned, or 200 < m < 300):
@@ -149,8 +152,9 @@ bool wants_padded_copy(const lcrwmd_emb* E)
     Phase1Args a;
     a.E = E->data;
     a.ld = E->ld;
+    a.erows = E->v;
     a.m = (int32_t)E->m;
-    return !tiles_f32_supported(a);
+    return !tiles_f32_supported(a) && tiles_rows_addressable(E->v, (int64_t)kPadPitch * 4);
 }
 
 // padded: room for the zero-padded fp32 copy (wants_padded_copy; the public size query, which does not know E's
@@ -170,6 +174,9 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
     ep.mode = prec_mode(ctx, E);
     ep.bf16 = ep.mode == 1;
     ep.m = (int32_t)E->m;
+    ep.rows = E->v;
+    if (ep.mode != 0 && !tiles_rows_addressable(E->v, ep.mode == 1 ? bf16_pitch((int32_t)E->m) * 2 : x3_pitch() * 2))
+        return fail(ctx, LCRWMD_EUNSUPPORTED, "E has too many rows for the bf16 kernels' packed copy (64 GiB limit)");
     ep.normE = b.take_n<float>((size_t)E->v);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the word norms");
     if (ep.mode == 2) {
@@ -178,6 +185,10 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
         HIP_TRY(launch_pack_x3((const float*)E->data, E->v, (int32_t)E->m, E->ld, packed, ep.normE, s));
         ep.data = packed;
         ep.ld = x3_pitch();
+        ep.xdata = E->data;             // hi + lo stands for the fp32 value
+        ep.xld = E->ld;
+        ep.xm = (int32_t)E->m;
+        ep.xbf16 = false;
         return LCRWMD_OK;
     }
     if (ep.bf16) {
@@ -202,6 +213,10 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
                 ep.data = packed;
                 ep.ld = kPadPitch;
                 ep.m = kPadM;
+                ep.xdata = packed;
+                ep.xld = kPadPitch;
+                ep.xm = (int32_t)E->m;
+                ep.xbf16 = false;
                 return LCRWMD_OK;
             }
             b = saved;                  // no room for the copy: the general kernels read E in place
@@ -210,6 +225,10 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
         ep.data = E->data;
         ep.ld = E->ld;
     }
+    ep.xdata = ep.data;                 // fp32 rows, or the packed bf16 rows (values first)
+    ep.xld = ep.ld;
+    ep.xm = (int32_t)E->m;
+    ep.xbf16 = ep.bf16;
     return LCRWMD_OK;
 }
 
@@ -223,6 +242,7 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     Phase1Args a;
     a.E = ep.data;
     a.ld = ep.ld;
+    a.erows = ep.rows;
     a.m = ep.m;                 // what the kernel multiplies; the flop count below uses the caller's m
     a.normE = ep.normE;
     a.voc_rows = voc_rows;
@@ -240,6 +260,8 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     // a word that occurs in the histogram is at distance exactly 0 from it; the norm expansion
     // only gets there up to cancellation error
     HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
+    // ... and loses relative accuracy where two different words lie close together: those entries are redone
+    HIP_TRY(launch_redo_close(ep.xdata, ep.xbf16, ep.xld, ep.xm, ep.normE, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, s));
     return LCRWMD_OK;
 }
 
@@ -323,6 +345,7 @@ int plan_chunk_tiles(const EmbPrep& ep)
     Phase1Args a;
     a.E = ep.data;
     a.ld = ep.ld;
+    a.erows = ep.rows;
     a.m = ep.m;
     return tiles_f32_supported(a) ? kShortChunkTiles : kLongChunkTiles;
 }
@@ -386,6 +409,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         Phase1Args a;
         a.E = ep.data;
         a.ld = ep.ld;
+        a.erows = ep.rows;
         a.m = ep.m;
         a.normE = ep.normE;
         a.z_by_position = 1;
@@ -421,6 +445,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
                 HIP_TRY(launch_distance_table(a, ep.mode, tok_ids, tok_hn, ve, s));
             }
             HIP_TRY(launch_table_zero_same(col_word, vc, map_db, W, ldw, s));
+            HIP_TRY(launch_table_redo_close(ep.xdata, ep.xbf16, ep.xld, ep.xm, ep.normE, list_db, ve, col_word, vc, W, ldw, s));
             HIP_TRY(launch_table_buckets(Q->row_ptr + jq0, qcol - qoff, Q->val, q, vc, bcnt, boffs, bcur, bpos, bval, s));
             {   // forward: every table row once, Z once
                 ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);

@@ -79,10 +79,7 @@ struct Bump {   // carves 256-byte aligned pieces from the caller's workspace
 // max_chunk_tiles: upper limit on a chunk's length in tiles of kTileTokens.  Kernels whose workgroups own one chunk
 // and reload the vocabulary operand for it want long chunks (64); the kernel that walks runs of chunks without
 // reloading balances its load in units of chunks and wants short ones (kShortChunkTiles).
-#ifndef LCRWMD_SHORT_CHUNK_TILES
-#define LCRWMD_SHORT_CHUNK_TILES 8      // build-time knob for load-balance experiments
-#endif
-constexpr int kLongChunkTiles = 64, kShortChunkTiles = LCRWMD_SHORT_CHUNK_TILES;
+constexpr int kLongChunkTiles = 64, kShortChunkTiles = 8;
 bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, int64_t nvoc_tiles,
                       int64_t padded_exact = -1, int group = kGroup, int max_chunk_tiles = kLongChunkTiles);
 
@@ -90,6 +87,8 @@ bool carve_token_plan(Bump& b, TokenPlan& tp, int64_t nseg, int64_t nnz_batch, i
 struct Phase1Args {
     const void* E;            // fp32: caller's E.  bf16: packed copy made by pack_bf16
     int64_t ld;               // row pitch of E in elements
+    int64_t erows = -1;       // rows of the matrix E points at (all of them, not only those this pass touches); the tile
+                              // kernels address rows with 32-bit offsets and need to know that they suffice
     int32_t m;                // embedding dimension
     const float* normE;       // [v] squared norms by word id
     const int32_t* voc_rows;  // word ids that form the vocabulary of this pass, or nullptr = 0..nvoc-1
@@ -118,6 +117,12 @@ hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, 
 // Z[row(word) * ldz + seg] = 0 for every stored (seg, word) of the batch; row() through map when given
 hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg,
                                const int32_t* map, float* Z, int64_t ldz, hipStream_t s);
+// Entries of Z (rows by position in voc_rows, or by word id when voc_rows is null) whose square is below a quarter of
+// the word's squared norm are recomputed from coordinate differences over the histogram's words.  E: fp32 rows, or
+// bf16 rows when `bf16`, pitch ld elements.  Runs after launch_zero_matches.
+hipError_t launch_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, const float* normE, const int32_t* voc_rows,
+                             int64_t nvoc, const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg, float* Z,
+                             int64_t ldz, hipStream_t s);
 // status[0] = 0 ok, 2 bad csr, 3 empty doc (values of lcrwmd_status)
 hipError_t launch_validate_csr(const lcrwmd_csr& X, int32_t* status, hipStream_t s);
 
@@ -133,6 +138,7 @@ hipError_t launch_pack_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_
 hipError_t launch_phase1_bf16(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 
 // phase1_tiles.hip: the direct-to-LDS tile kernel for both precisions
+bool tiles_rows_addressable(int64_t rows, int64_t pitch_bytes);
 bool tiles_f32_supported(const Phase1Args& a);
 hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s);
@@ -152,6 +158,10 @@ hipError_t launch_table_tokens(const int32_t* list_db, int64_t ve, const float* 
                                int64_t count, hipStream_t s);
 hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32_t* map_db, float* W, int64_t ldw,
                                   hipStream_t s);
+// table entries of two different words that lie close (w^2 < |row word|^2 / 4) recomputed from coordinate differences
+hipError_t launch_table_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, const float* normE,
+                                   const int32_t* list_db, int64_t ve, const int32_t* col_word, int64_t vc, float* W,
+                                   int64_t ldw, hipStream_t s);
 void table_strips(int64_t vq, int32_t* ws, int32_t* nstrip);
 size_t table_bucket_bytes(int64_t vq, int64_t q, int64_t nnz_q);
 hipError_t launch_table_spread(const int32_t* list_q, int64_t vq, const int32_t* pos_in, int64_t nnz, int32_t* col_word,

@@ -317,10 +317,8 @@ __global__ __launch_bounds__(256, 1) void k_phase1_f32_regb(P1Dev p)
         for (int i = 0; i < SLOTS; ++i) w[i] = p.tok_ids[tb + lrow + 16 * i];
     };
     auto prefetch = [&](int kc) {
-#ifndef DBG_NO_PREFETCH
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) pa[i] = load4<VEC>(p.E + (int64_t)aword[i] * p.ld, kc * KC + lk, p.m);
-#endif
     };
 
     f32x16 acc[4];
@@ -376,12 +374,8 @@ __global__ __launch_bounds__(256, 1) void k_phase1_f32_regb(P1Dev p)
 #pragma unroll
                     for (int rt = 0; rt < 4; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rt].y, b.y, acc[rt], 0, 0, 0);
                 }
-#ifndef DBG_NO_STAGE
                 if (!last || more) stage(As[buf ^ 1]);
-#endif
-#ifndef DBG_NO_BARRIER
                 __syncthreads();
-#endif
                 buf ^= 1;
             }
         }
@@ -392,14 +386,6 @@ __global__ __launch_bounds__(256, 1) void k_phase1_f32_regb(P1Dev p)
         }
         int ng = (t1 - tb) >> 3;
         if (ng > 16) ng = 16;
-#ifdef DBG_NO_EPILOGUE
-        cur = s0;
-#pragma unroll
-        for (int rt = 0; rt < 4; ++rt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) run = fmaxf(run, acc[rt][r]);
-        ng = 0;
-#endif
 #pragma unroll
         for (int g = 0; g < 16; ++g) {
             if (g < ng) {

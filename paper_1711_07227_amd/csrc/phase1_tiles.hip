@@ -208,11 +208,12 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     // ---- copy jobs of this wavefront ----
     // job J -> octet J / NRT, row block (of 8 rows) wave + 4 (J % NRT); lane -> row lane / 8, slot lane % 8
     const int lane8 = lane >> 3;                                   // row within an 8-row block; also this lane's token group
+    // Source offsets are counted in 16-byte pieces: 32 bits then reach 64 GiB of operand rows (the host checks it).
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
-    const uint32_t offO = pieceO * 16;
+    const uint32_t offO = pieceO;
     // fp32: the last octet reaches past the end of the row (pieces 75..79): re-read the last real piece
     const int last_piece = (L::NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = (BF16 || X3) ? offO + (L::NOCT - 1) * 128 : (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16);
+    const uint32_t off_last = (BF16 || X3) ? offO + (L::NOCT - 1) * 8 : (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1);
 
     // Word ids of the two token rows this lane copies.  They are fetched when the previous tile's copy jobs have
     // all been issued (one pair of registers serves both) and are multiplied out to byte offsets job by job.
@@ -222,13 +223,13 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         wA = t[lane8];
         if (NRT == 2) wB = t[lane8 + 32];
     };
-    const uint32_t pitch32 = (uint32_t)p.pitch_b;     // the host guarantees rows * pitch < 2^32
+    const uint32_t pitch16 = (uint32_t)(p.pitch_b >> 4);     // the host guarantees rows * pitch16 < 2^32
     // copy job J (compile time) of this wavefront into buffer `lbase`
     auto copy_job = [&](auto j_c, unsigned char* lbase) {
         constexpr int J = decltype(j_c)::value;
         constexpr int oct = J / NRT, blk = J % NRT;
-        const uint32_t off = (uint32_t)(blk ? wB : wA) * pitch32 + (oct == L::NOCT - 1 ? off_last : offO + oct * 128);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + off),
+        const uint32_t off = (uint32_t)(blk ? wB : wA) * pitch16 + (oct == L::NOCT - 1 ? off_last : offO + oct * 8);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + ((uint64_t)off << 4)),
                                          (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + blk * 4 + wave) * 1024),
                                          16, 0, 0);
     };
@@ -282,23 +283,13 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     if (!BF16) load_hn(t0, hn);
     int buf = 0;                               // ring position of the tile being multiplied
 
-#ifdef DBG_TIMING
-    long long tacc[6] = {0, 0, 0, 0, 0, 0};
-    long long tprev = clock64();
-    const long long dbg_c0 = tprev, dbg_w0 = wall_clock64();
-#define DBG_T(k) { long long tn = clock64(); tacc[k] += tn - tprev; tprev = tn; }
-#else
-#define DBG_T(k)
-#endif
     for (int tb = t0; tb < t1; tb += ROWS) {
         // This wavefront's copies of the tile have landed.  Vector memory operations complete in issue order and the
         // copies of the PD - 1 later tiles were issued after this tile's: while those are all still to come, at most
         // (PD - 1) * NJOBS operations may remain outstanding; at the end of the chunk everything is waited for.
         if (PD > 1 && tb + (PD - 1) * ROWS < t1) __builtin_amdgcn_s_waitcnt(0x0f70 | ((PD - 1) * L::NJOBS));
         else __builtin_amdgcn_s_waitcnt(0x0f70);
-        DBG_T(0)
         __syncthreads();                        // ... and everyone's; everyone has left the buffer refilled next
-        DBG_T(1)
         const bool more = tb + ROWS < t1;
         const bool more_copy = tb + PD * ROWS < t1;
         const int buf_copy = buf == 0 ? NBUF - 1 : buf - 1;          // = (buf + PD) mod NBUF
@@ -307,7 +298,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         if (more) {
             if (!BF16) load_hn(tb + ROWS, hn_next);
         }
-        DBG_T(2)
 
         // Software pipeline over the K steps: the LDS reads of step s + LA are issued before the MFMAs of step s,
         // into a ring of LA + 1 fragment register sets (LA steps of MFMAs have to cover the LDS latency: a bf16 step
@@ -378,7 +368,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                             acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(
                                 a[rt][0][t], breg[s][ct][t], (s == 0 && t == 0) ? zero16 : acc[rt][ct], 0, 0, 0);
             }
-#ifndef DBG_NO_COPY
             // copy jobs of a later tile, spread over the iterations (X3: 20 jobs over 19 iterations, the last takes two)
             static_for<0, L::NJOBS>([&](auto j_c) {
                 constexpr int j = decltype(j_c)::value;
@@ -392,7 +381,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 // all copy jobs issued: fetch the ids for the next tile to copy
                 if (tb + (PD + 1) * ROWS < t1) load_words(tb + (PD + 1) * ROWS);
             }
-#endif
             __builtin_amdgcn_sched_barrier(0);
         });
         if constexpr (WGS_PER_CU > 1) __builtin_amdgcn_s_setprio(3);      // the epilogue's few instructions go first
@@ -405,7 +393,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                 for (int ct = 0; ct < NCT; ++ct)
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(half == 0 ? hn[rt] : 0.f, one, acc[rt][ct], 0, 0, 0);
         }
-        DBG_T(3)
 
         if constexpr (TABLE) {
             // every element is a result: register r of row tile rt is token row 32 rt + 8 (r / 4) + 4 half + r % 4
@@ -432,16 +419,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 #pragma unroll
         for (int g = 0; g < NG; ++g) sgs[g] = __builtin_amdgcn_readlane(gsv, 8 * g);
         if (more) gsv = load_gs(tb + ROWS);
-#ifdef DBG_NO_EPI
-        cur = s0;
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < NCT; ++ct)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) run[ct] = fmaxf(run[ct], acc[rt][ct][r]);
-        ng = 0;
-#endif
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             if (g < ng) {
@@ -467,17 +444,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
             for (int rt = 0; rt < NRT; ++rt) hn[rt] = hn_next[rt];
         }
         buf = buf == NBUF - 1 ? 0 : buf + 1;
-        DBG_T(4)
     }
     if (!TABLE) flush();
-#ifdef DBG_TIMING
-    if (blockIdx.x == 0 && tid == 0) {
-        for (int k = 0; k < 5; ++k) p.Z[k] = (float)tacc[k];
-        p.Z[5] = (float)((t1 - t0) / ROWS);
-        p.Z[6] = (float)(clock64() - dbg_c0);
-        p.Z[7] = (float)(wall_clock64() - dbg_w0);
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -559,12 +527,13 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     const unsigned char* Eb = p.Eb;
     const int lane8 = lane >> 3;
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
-    const uint32_t offO = (uint32_t)(pieceO * 16);
+    // Source offsets are counted in 16-byte pieces: 32 bits then reach 64 GiB of operand rows (the host checks it).
+    const uint32_t offO = (uint32_t)pieceO;
     // fp32 rows end inside the last octet (pieces 75..79 do not exist): those lanes re-read the last real piece,
     // which meets zeros on the vocabulary side
     const int last_piece = (NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = (uint32_t)((last_piece < p.nreal ? last_piece : p.nreal - 1) * 16) - offO;
-    const uint32_t pitch32 = (uint32_t)p.pitch_b;
+    const uint32_t off_last = (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1) - offO;
+    const uint32_t pitch16 = (uint32_t)(p.pitch_b >> 4);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t a_oct0 = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -618,19 +587,19 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
         for (int k = 0; k < 8; ++k) r.v[k] = t[k];
         return r;
     };
-    // byte offset of this lane's piece of its row, from the row block's 8 word ids
+    // offset (in 16-byte pieces) of this lane's piece of its row, from the row block's 8 word ids
     auto row_offset = [&](const Ids& ids) {
         // lane l < 8 takes id l, then every lane fetches the id of its row from lane (row within the block)
         int32_t spread = 0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) asm("v_writelane_b32 %0, %1, %2" : "+v"(spread) : "s"(ids.v[k]), "n"(k));
         const int32_t wA = __builtin_amdgcn_ds_bpermute(lane8 << 2, spread);
-        return (uint32_t)wA * pitch32 + offO;
+        return (uint32_t)wA * pitch16 + offO;
     };
     auto copy_octet = [&](auto o_c, uint32_t off, unsigned char* lbase) {
         constexpr int oct = decltype(o_c)::value;
-        const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 128));
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + o),
+        const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 8));
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + ((uint64_t)o << 4)),
                                          (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
                                          16, 0, 0);
     };
@@ -880,9 +849,12 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
 // in 16-byte aligned rows.  Other shapes take the register-staged kernels of phase1_f32.hip.
 int phase1_group_x3() { return PP<kX3>::G; }
 
+// The copies address operand rows with 32-bit offsets counted in 16-byte pieces.
+bool tiles_rows_addressable(int64_t rows, int64_t pitch_bytes) { return pitch_bytes % 16 == 0 && rows * (pitch_bytes / 16) < ((int64_t)1 << 32); }
+
 bool tiles_f32_supported(const Phase1Args& a)
 {
-    return a.m == 300 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0;
+    return a.m == 300 && a.ld % 4 == 0 && (((uintptr_t)a.E) & 15) == 0 && tiles_rows_addressable(a.erows, a.ld * 4);
 }
 
 // One workgroup of eight wavefronts per CU (it takes all of a CU's LDS), fewer when there is less work than that.
@@ -913,6 +885,7 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
     if (tp.group != PP<kF32>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
+    if (!tiles_f32_supported(a)) return hipErrorInvalidValue;
     return launch_pingpong<kF32>(d, a.num_cu, s);
 }
 
@@ -924,6 +897,7 @@ hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipS
     d.nreal = Layout<kX3>::NOCT * 8;
     d.nzero_from = 0;
     if (tp.group != PP<kX3>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
+    if (!tiles_rows_addressable(a.erows, d.pitch_b)) return hipErrorInvalidValue;
     return launch_pingpong<kX3>(d, a.num_cu, s);
 }
 
@@ -935,12 +909,16 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
     d.nreal = Layout<kBF16>::NOCT * 8;
     d.nzero_from = 0;
     if (tp.group != PP<kBF16>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
+    if (!tiles_rows_addressable(a.erows, d.pitch_b)) return hipErrorInvalidValue;
     return launch_pingpong<kBF16>(d, num_cu, s);
 }
 
 // Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
 // tok_ids / tok_hn: the token rows' word ids and -|.|^2/2 (fp32 path), readable up to roundup(ntok, 64) + 64 entries.
-bool distance_table_supported(const Phase1Args& a, int mode) { return mode != 0 || tiles_f32_supported(a); }
+bool distance_table_supported(const Phase1Args& a, int mode)
+{
+    return mode != 0 ? tiles_rows_addressable(a.erows, a.ld * 2) : tiles_f32_supported(a);
+}
 
 hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* tok_ids, const float* tok_hn,
                                  int64_t ntok, hipStream_t s)

@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ r
     if (strip >= strips) return;
     const int64_t j = strip * (64 * W) + (int64_t)lane * W;
     // row bounds are wave-uniform: keep them scalar so that the loop control and the row addresses of Z are scalar too
-    const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
-    const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
+    const int64_t a = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
+    const int64_t b = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
     float acc[W];
     row_times_strip<W>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
 
@@ -170,8 +170,8 @@ __global__ __launch_bounds__(256) void k_spmm_tmax_wide(const int64_t* __restric
         const int64_t r = r0 + rr;
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         if (r < rows) {
-            const int64_t a = __builtin_amdgcn_readfirstlane((int)rp[r]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r] >> 32)) << 32);
-            const int64_t b = __builtin_amdgcn_readfirstlane((int)rp[r + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r + 1] >> 32)) << 32);
+            const int64_t a = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[r]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r] >> 32)) << 32);
+            const int64_t b = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[r + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r + 1] >> 32)) << 32);
             row_times_strip<4>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
         }
 #pragma unroll

@@ -221,6 +221,80 @@ __global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict_
     }
 }
 
+// Where a word and a word of the histogram lie close together, the squared distance the contraction delivers,
+// |x|^2 + |y|^2 - 2 x.y, is a small difference of large numbers: its absolute error is a few 1e-6 (|x|^2 + |y|^2), so
+// the relative error of the distance passes 1e-4 once d^2 falls below a few percent of the squared norms - and the
+// minimum of the first phase picks exactly those entries.  This pass re-evaluates every entry of Z whose square is
+// below a quarter of the word's squared norm from coordinate differences, sum_t (x_t - y_t)^2, whose error is relative
+// to d^2 itself.  (An entry above that threshold came from a d^2 >= (|x|^2 + |y|^2) / 8 or so - two vectors whose
+// norms differ by more than a factor 1.5 are further apart than half the shorter one - where the expansion is good
+// to 1e-5.)  The minimum of the exact distances is taken over all words of the histogram: the expansion's ranking of
+// near neighbours is not trusted either.  Entries that are 0 because the word itself occurs in the histogram
+// (k_zero_matches ran before) are recognised by a binary search in the sorted row and left alone.
+//
+// One wavefront per row of Z and strip of columns: 64 entries are tested at a time (one coalesced load); the flagged
+// ones are then redone one after the other by the whole wavefront, lanes along the embedding dimension.  On embeddings
+// without close pairs this is one read of Z.
+constexpr int kRedoBlocks = 16;      // 64-column blocks per wavefront
+
+template <bool BF16>
+__device__ inline float emb_value(const void* E, int64_t idx)
+{
+    if (BF16) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(E)[idx] << 16);
+    return reinterpret_cast<const float*>(E)[idx];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, int64_t ld, int32_t m,
+                                                    const float* __restrict__ normE, const int32_t* __restrict__ voc_rows,
+                                                    int64_t nvoc, const int64_t* __restrict__ rp,
+                                                    const int32_t* __restrict__ ci, int64_t nseg, float* __restrict__ Z,
+                                                    int64_t ldz, int64_t strips)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t unit = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t pos = unit / strips;
+    if (pos >= nvoc) return;
+    const int64_t strip = unit - pos * strips;
+    const int32_t w = voc_rows ? voc_rows[pos] : (int32_t)pos;
+    const float limit = 0.25f * normE[w];
+    float* zrow = Z + pos * ldz;
+    for (int blk = 0; blk < kRedoBlocks; ++blk) {
+        const int64_t j = (strip * kRedoBlocks + blk) * 64 + lane;
+        if (j - lane >= nseg) break;
+        const float z = j < nseg ? zrow[j] : 1e30f;
+        bool redo = z * z < limit;
+        if (redo && z == 0.f) {
+            // the word itself in the histogram?  (rows are sorted)
+            int64_t lo = rp[j], hi = rp[j + 1];
+            while (lo < hi) {
+                const int64_t mid = lo + ((hi - lo) >> 1);
+                if (ci[mid] < w) lo = mid + 1; else hi = mid;
+            }
+            if (lo < rp[j + 1] && ci[lo] == w) redo = false;
+        }
+        uint64_t todo = __ballot(redo);
+        while (todo) {
+            const int l = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int64_t jj = j - lane + l;
+            const int64_t a = rp[jj], b = rp[jj + 1];
+            float best = 3.0e38f;
+            for (int64_t t = a; t < b; ++t) {
+                const int32_t c = ci[t];
+                float s = 0.f;
+                for (int32_t k = lane; k < m; k += 64) {
+                    const float d = emb_value<BF16>(E, (int64_t)w * ld + k) - emb_value<BF16>(E, (int64_t)c * ld + k);
+                    s = fmaf(d, d, s);
+                }
+                for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+                best = fminf(best, s);
+            }
+            if (lane == l) zrow[j] = sqrtf(best);
+        }
+    }
+}
+
 __global__ void k_validate_csr(const int64_t* __restrict__ rp, const int32_t* __restrict__ col_idx,
                                const float* __restrict__ val, int64_t rows, int64_t cols, int64_t nnz,
                                int32_t* __restrict__ status)
@@ -357,6 +431,19 @@ hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_
 {
     if (nseg <= 0) return hipSuccess;
     k_zero_matches<<<(unsigned)((nseg + 3) / 4), 256, 0, s>>>(row_ptr_batch, col_idx, nseg, map, Z, ldz);
+    return hipGetLastError();
+}
+
+hipError_t launch_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, const float* normE, const int32_t* voc_rows,
+                             int64_t nvoc, const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg, float* Z,
+                             int64_t ldz, hipStream_t s)
+{
+    if (nvoc <= 0 || nseg <= 0) return hipSuccess;
+    const int64_t strips = (nseg + 64 * kRedoBlocks - 1) / (64 * kRedoBlocks);
+    const int64_t grid = (nvoc * strips + 3) / 4;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (bf16) k_redo_close<true><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, strips);
+    else k_redo_close<false><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, strips);
     return hipGetLastError();
 }
 

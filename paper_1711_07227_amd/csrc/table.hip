@@ -10,12 +10,12 @@
 //                                                                         (k_table_rev: both steps fused, Z' stays in LDS)
 // The swapped pass is a stream of table rows: 4 * (stored database entries) * (query words) bytes, bandwidth bound.
 //
-// Strips.  The columns u are cut into strips of at most 768 (3 KiB per table row) and the queries' entries are
+// Strips.  The columns u are cut into strips of at most 512 (2 KiB per table row) and the queries' entries are
 // regrouped by strip once per call (k_bucket_*).  The swapped pass is launched strip by strip: while one strip is
 // being worked on, the strip of the frequent database words' rows stays in the L2s and the strip of the whole table
 // fits the Infinity Cache, so most of the stream never reaches HBM; per-strip partial sums accumulate in a buffer
 // D2 (always in strip order: the result does not depend on timing).  One wavefront owns one database row: its
-// minima live in a private 3 KiB of LDS and no workgroup barrier is needed.
+// minima live in a private 2 KiB of LDS and no workgroup barrier is needed.
 #include "lcrwmd_internal.h"
 
 namespace lcrwmd {
@@ -37,6 +37,54 @@ __global__ void k_table_zero_same(const int32_t* __restrict__ list_q, int32_t vq
     if (u >= vq) return;
     const int32_t p = map_db[list_q[u]];
     if (p >= 0) W[(int64_t)p * ldw + u] = 0.f;
+}
+
+// Entries of the table below half the row word's norm (w^2 < |x|^2 / 4) come from a squared distance that is a small
+// difference of large numbers in the norm expansion: they are recomputed from coordinate differences, whose error is
+// relative to the distance itself.  One wavefront per table row and strip of 1,024 columns; the flagged entries of
+// each 64 are redone one after the other, lanes along the embedding dimension.  Equal words (already exactly 0) are
+// left alone.  Without close word pairs this is one read of the table.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_table_redo_close(const void* __restrict__ E, int64_t ld, int32_t m,
+                                                          const float* __restrict__ normE,
+                                                          const int32_t* __restrict__ list_db, int64_t ve,
+                                                          const int32_t* __restrict__ col_word, int64_t vc,
+                                                          float* __restrict__ W, int64_t ldw, int64_t strips)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t unit = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t p = unit / strips;
+    if (p >= ve) return;
+    const int64_t strip = unit - p * strips;
+    const int32_t w = list_db[p];
+    const float limit = 0.25f * normE[w];
+    float* row = W + p * ldw;
+    for (int blk = 0; blk < 16; ++blk) {
+        const int64_t c = (strip * 16 + blk) * 64 + lane;
+        if (c - lane >= vc) break;
+        const float x = c < vc ? row[c] : 1e30f;
+        const int32_t cw = c < vc ? col_word[c] : w;
+        uint64_t todo = __ballot(x * x < limit && cw != w);
+        while (todo) {
+            const int l = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int32_t u = __builtin_amdgcn_readlane(cw, l);
+            float sum = 0.f;
+            for (int32_t k = lane; k < m; k += 64) {
+                float a, b;
+                if (BF16) {
+                    a = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(E)[(int64_t)w * ld + k] << 16);
+                    b = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(E)[(int64_t)u * ld + k] << 16);
+                } else {
+                    a = reinterpret_cast<const float*>(E)[(int64_t)w * ld + k];
+                    b = reinterpret_cast<const float*>(E)[(int64_t)u * ld + k];
+                }
+                sum = fmaf(a - b, a - b, sum);
+            }
+            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            if (lane == l) row[c] = sqrtf(sum);
+        }
+    }
 }
 
 // Columns of the table: query word number u (in increasing word id) goes to strip u mod nstrip, place u / nstrip.
@@ -382,6 +430,19 @@ hipError_t launch_table_zero_same(const int32_t* list_q, int64_t vq, const int32
 {
     if (vq <= 0) return hipSuccess;
     k_table_zero_same<<<(unsigned)((vq + 255) / 256), 256, 0, s>>>(list_q, (int32_t)vq, map_db, W, ldw);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, const float* normE,
+                                   const int32_t* list_db, int64_t ve, const int32_t* col_word, int64_t vc, float* W,
+                                   int64_t ldw, hipStream_t s)
+{
+    if (ve <= 0 || vc <= 0) return hipSuccess;
+    const int64_t strips = (vc + 1023) / 1024;
+    const int64_t grid = (ve * strips + 3) / 4;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (bf16) k_table_redo_close<true><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, list_db, ve, col_word, vc, W, ldw, strips);
+    else k_table_redo_close<false><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, list_db, ve, col_word, vc, W, ldw, strips);
     return hipGetLastError();
 }
 
