@@ -197,6 +197,20 @@ lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q,
                           int32_t* R_idx, float* R_dist, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * lcrwmd_topk for callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same results bit for
+ * bit.  The partial lists of the row splits live in a file-scope device array of 8 MiB that every GPU the library runs
+ * on holds until the process ends; its address on the context's device is looked up once, in lcrwmd_create.  The call
+ * allocates and frees nothing.  Problems whose partial lists (what lcrwmd_topk would take from its workspace:
+ * 8 q k bytes per row split, at most 64 splits) exceed the array return LCRWMD_EWORKSPACE and launch nothing.
+ * All calls on one GPU share that GPU's array, whatever their context or stream: calls that overlap in time on one GPU
+ * race; calls ordered on one stream do not.  Nothing in the array has to start at zero (every slot that is read is
+ * written by the same call first).  No host synchronisation.
+ */
+lcrwmd_status lcrwmd_topk_noalloc(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q, int64_t ldd, int k,
+                                  int32_t* R_idx, float* R_dist, void* hip_stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the method).  Between lcrwmd_profile_begin and
  * lcrwmd_profile_end every launch of the first-phase contraction kernel and of the second-phase
  * SpMM kernel made through this context is bracketed by HIP events on the stream it is launched

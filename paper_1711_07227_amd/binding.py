@@ -27,7 +27,7 @@ EXPORTS = (
     "lcrwmd_workspace_bytes", "lcrwmd_phase1_mindist", "lcrwmd_phase2_spmm", "lcrwmd_rwmd",
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
-    "lcrwmd_wmd_topk",
+    "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc",
 )
 
 
@@ -90,6 +90,7 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_topk.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+        lib.lcrwmd_topk_noalloc.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp]
         lib.lcrwmd_wcd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_wmd_pairs_workspace_bytes.argtypes = [vp, i64, i64, i64, P(sz)]
         lib.lcrwmd_wmd_pairs.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, vp, i64, vp, vp, vp, sz, vp]
@@ -245,6 +246,12 @@ class Context:
         p, nbytes = self._ws(ws)
         self._check(self._lib.lcrwmd_topk(self._h, D.data_ptr(), D.shape[0], D.shape[1], D.stride(0), k,
                                           R_idx.data_ptr(), R_dist.data_ptr(), p, nbytes, _stream()))
+
+    def topk_noalloc(self, D: torch.Tensor, k: int, R_idx: torch.Tensor, R_dist: torch.Tensor):
+        assert D.is_cuda and D.dtype == torch.float32 and D.stride(1) == 1
+        assert R_idx.dtype == torch.int32 and R_dist.dtype == torch.float32 and R_idx.is_contiguous() and R_dist.is_contiguous()
+        self._check(self._lib.lcrwmd_topk_noalloc(self._h, D.data_ptr(), D.shape[0], D.shape[1], D.stride(0), k,
+                                                  R_idx.data_ptr(), R_dist.data_ptr(), _stream()))
 
     def wcd(self, queries: Csr, database: Csr, E: torch.Tensor, D: torch.Tensor, ws: torch.Tensor):
         assert D.is_cuda and D.dtype == torch.float32 and D.stride(1) == 1

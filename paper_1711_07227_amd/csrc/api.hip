@@ -564,6 +564,8 @@ lcrwmd_status lcrwmd_create(lcrwmd_ctx** out, int device)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
     c->num_cu = prop.multiProcessorCount;
+    // this device's address of the scratch array behind lcrwmd_topk_noalloc (looked up with the device current)
+    if (hipSetDevice(device) != hipSuccess || topk_static_init(device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
     c->opt.validate = 0;
     c->opt.compute = LCRWMD_F32;
     *out = c;
@@ -765,6 +767,30 @@ lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q,
     if (ws && ((uintptr_t)ws & 255) != 0) return fail(ctx, LCRWMD_EWORKSPACE, "the workspace must be 256-byte aligned");
     HIP_TRY(hipSetDevice(ctx->device));
     HIP_TRY(launch_topk(D, n, q, ldd, k, R_idx, R_dist, ws, ws ? ws_bytes : 0, s));
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_topk_noalloc(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q, int64_t ldd, int k,
+                                  int32_t* R_idx, float* R_dist, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n < 0 || q < 0) return fail(ctx, LCRWMD_EINVAL, "negative size");
+    if (q == 0) return LCRWMD_OK;
+    if (!D || !R_idx || !R_dist) return fail(ctx, LCRWMD_EINVAL, "D, R_idx or R_dist is NULL");
+    if (ldd < q) return fail(ctx, LCRWMD_EINVAL, "ldd < q");
+    if (k < 1 || k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    if (n > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "n exceeds int32 row indices");
+    const size_t need = topk_bytes(n, q, k);
+    if (need > topk_static_bytes())
+        return fail(ctx, LCRWMD_EWORKSPACE, "the partial lists of this problem take %zu bytes, the built-in scratch holds %zu: "
+                    "use lcrwmd_topk with a workspace", need, topk_static_bytes());
+    void* scratch = topk_static_ptr(ctx->device);
+    if (!scratch) return fail(ctx, LCRWMD_EHIP, "the scratch array of device %d was not found at lcrwmd_create", ctx->device);
+    HIP_TRY(hipSetDevice(ctx->device));
+    // every slot of the partial lists that the merge reads is written by the launch before it: nothing to clear
+    HIP_TRY(launch_topk(D, n, q, ldd, k, R_idx, R_dist, scratch, need, s));
     return LCRWMD_OK;
 }
 

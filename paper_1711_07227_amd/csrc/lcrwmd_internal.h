@@ -184,6 +184,10 @@ constexpr int kMaxTopK = 64;
 size_t topk_bytes(int64_t n, int64_t q, int k);
 hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
                        void* ws, size_t ws_bytes, hipStream_t s);
+// the file-scope device array behind lcrwmd_topk_noalloc: its size, the per-device address look-up (device current)
+size_t topk_static_bytes();
+hipError_t topk_static_init(int device);
+void* topk_static_ptr(int device);
 
 // wmd.hip: transport problems (one wavefront each), centroid distances, pruning lists
 size_t emd_pair_bytes(int64_t h1max, int64_t h2max);

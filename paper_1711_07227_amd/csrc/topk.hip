@@ -134,7 +134,31 @@ __global__ __launch_bounds__(64) void k_topk_merge(const float* __restrict__ par
     }
 }
 
+// Scratch of the entry point that allocates nothing: the partial lists live in this array instead of a workspace.
+// Every device the library runs on holds its own copy at its own address; host code uses the address obtained by
+// topk_static_init, never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+
 }  // namespace
+
+size_t topk_static_bytes() { return kStaticScratchBytes; }
+
+// Called with `device` current (lcrwmd_create): looks up this device's copy of the array once.
+hipError_t topk_static_init(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = ptr;
+    return hipSuccess;
+}
+
+void* topk_static_ptr(int device) { return device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr; }
 
 size_t topk_bytes(int64_t n, int64_t q, int k)
 {
