@@ -93,16 +93,22 @@ typedef struct {
                                        X2 is divided into batches); 0 = chosen from the workspace     */
     int64_t max_db_batch;           /* same for the database rows handled per pass of the swapped
                                        direction; 0 = chosen from the workspace                      */
-    int dedup;                      /* 1: lcrwmd_rwmd / lcrwmd_rwmd_topk use the de-duplicated form: the
-                                       Euclidean distances between the distinct words of the database and
-                                       the distinct words of a query batch are computed once, as one
-                                       table (the operator of Sec. III on the two reduced vocabularies),
-                                       and both passes take their minima from it.  Same result as the
-                                       default up to fp32 summation order.  The table lives in the
-                                       workspace (4 bytes x distinct database words x distinct query
-                                       words); when it does not fit, or for fp32 E with m < 208 or m > 300,
-                                       the call silently runs the default form.  0 (default): distances are
-                                       recomputed per stored entry, as the paper's two phases do.      */
+    int dedup;                      /* 0 (default): the per-entry form - distances are recomputed per stored
+                                       entry, as the paper's two phases do.
+                                       1: the table form where it can run - the Euclidean distances between
+                                       the distinct words of the database and the distinct words of a range
+                                       of queries are computed once, as one table (the operator of Sec. III
+                                       on the two reduced vocabularies), and both directions take their
+                                       minima from it.  Same result up to fp32 summation order.  The table
+                                       lives in the workspace (4 bytes x distinct database words x distinct
+                                       query words); when it does not fit, or for fp32 E with m < 208 or
+                                       m > 300, the per-entry form runs instead.
+                                       2: the library picks, per range of queries, the form its cost model
+                                       expects to be faster (contraction flops of the per-entry form against
+                                       the table's build and its two bandwidth-bound passes; Sec. III-B
+                                       discusses this trade-off); more than 4,096 queries in one call always
+                                       take the per-entry form.
+                                       lcrwmd_forms_ran tells which form(s) the last call used.        */
 } lcrwmd_options;
 
 /* Create a context bound to HIP device `device`.  No device memory is allocated. */
@@ -111,6 +117,10 @@ void lcrwmd_destroy(lcrwmd_ctx* ctx);
 
 /* Text for the last non-OK status returned on this context (owned by the context; "" if none). */
 const char* lcrwmd_last_error(const lcrwmd_ctx* ctx);
+
+/* Forms used by the last lcrwmd_rwmd / lcrwmd_rwmd_topk / lcrwmd_rwmd_reduce call on this context: bit 0 set when a
+   range of queries ran the per-entry form, bit 1 when one ran the table form (see lcrwmd_options.dedup). */
+int lcrwmd_forms_ran(const lcrwmd_ctx* ctx);
 
 /* Copy the options in / out.  Defaults: validate 0, compute LCRWMD_F32, batches 0, dedup 0. */
 lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt);
@@ -166,8 +176,11 @@ lcrwmd_status lcrwmd_phase2_spmm(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const flo
  * D is n x q fp32 row-major (n = database->rows, q = queries->rows, ldd >= q).  Both directions
  * run the two phases, the second one with the sets swapped; words that do not occur in the
  * set that plays X1 are dropped from the vocabulary of that pass (Sec. IV, vocabulary
- * reduction), queries are processed in batches and so are the database rows of the swapped
- * pass.  Results do not depend on the batch sizes.
+ * reduction).  The first-phase minima of all queries are kept in the workspace (in ranges of
+ * queries when it is smaller than lcrwmd_workspace_bytes asks for, each range then repeating the
+ * swapped pass), and the database rows are handled in blocks: forward second phase, swapped
+ * first and second phase and the maximum, block by block.  Results do not depend on the
+ * batch sizes.
  * Synchronises the stream to read back the two vocabulary sizes, which decide grids and batch
  * sizes (and before that once more when it has to fetch the row pointers because no host
  * copies were given); everything else is asynchronous.
@@ -180,13 +193,26 @@ lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrw
  * Top-k on the same bound (Sec. III: the k smallest distances of a query and the positions of
  * the respective database histograms, stored in an n2 x k matrix R): for each query j,
  * R_idx[j * k + r] / R_dist[j * k + r], r < k, are the database rows with the r-th smallest
- * D[.][j] and those distances, ordered by (distance, row index) ascending.  D is formed one
- * query batch at a time inside the workspace and never returned.  1 <= k <= min(n, 64).
- * Same synchronisation as lcrwmd_rwmd, once per query batch.
+ * D[.][j] and those distances, ordered by (distance, row index) ascending.  D is never formed:
+ * the bound of one block of database rows (at most 16,384, option max_db_batch) lives in a tile
+ * of the workspace just long enough to receive both directions and to be merged into the running
+ * lists.  1 <= k <= min(n, 64).  Same synchronisation as lcrwmd_rwmd, once per range of queries.
  */
 lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
                                const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist,
                                void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * The bound reduced on the device, for jobs whose n x q matrix is too large to keep (Sec. IV, many-to-many
+ * LC-RWMD in batches; Sec. III, top-k): lcrwmd_rwmd_topk's lists (when k > 0; R_idx / R_dist may be NULL when
+ * k == 0) and / or, when col_sum is not NULL, the column sums
+ *     col_sum[j] = sum over all database rows i of D[i][j]         (device, q doubles, fp64 accumulation
+ *                                                                   of the fp32 distances in a fixed order)
+ * - a checksum of everything the call computed.  Blocks of database rows as in lcrwmd_rwmd_topk.
+ */
+lcrwmd_status lcrwmd_rwmd_reduce(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                                 const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist, double* col_sum,
+                                 void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Top-k of an existing distance matrix: D is n x q fp32 row-major (ldd >= q); outputs as in

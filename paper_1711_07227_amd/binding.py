@@ -27,7 +27,7 @@ EXPORTS = (
     "lcrwmd_workspace_bytes", "lcrwmd_phase1_mindist", "lcrwmd_phase2_spmm", "lcrwmd_rwmd",
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
-    "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc",
+    "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc", "lcrwmd_rwmd_reduce", "lcrwmd_forms_ran",
 )
 
 
@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_phase2_spmm.argtypes = [vp, P(CsrStruct), vp, i64, i64, vp, i64, i32, vp]
         lib.lcrwmd_rwmd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
+        lib.lcrwmd_rwmd_reduce.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
+        lib.lcrwmd_forms_ran.argtypes = [vp]
         lib.lcrwmd_topk.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_topk_noalloc.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp]
         lib.lcrwmd_wcd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
@@ -239,6 +241,22 @@ class Context:
         p, nbytes = self._ws(ws)
         self._check(self._lib.lcrwmd_rwmd_topk(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es), k,
                                                R_idx.data_ptr(), R_dist.data_ptr(), p, nbytes, _stream()))
+
+    def rwmd_reduce(self, queries: Csr, database: Csr, E: torch.Tensor, k: int, R_idx: torch.Tensor | None,
+                    R_dist: torch.Tensor | None, col_sum: torch.Tensor | None, ws: torch.Tensor):
+        if k > 0:
+            assert R_idx.dtype == torch.int32 and R_dist.dtype == torch.float32 and R_idx.is_contiguous() and R_dist.is_contiguous()
+        assert col_sum is None or (col_sum.is_cuda and col_sum.dtype == torch.float64 and col_sum.is_contiguous()
+                                   and col_sum.numel() >= queries.rows)
+        es, qs, ds = _emb_struct(E), queries.struct(), database.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_rwmd_reduce(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es), k,
+                                                 R_idx.data_ptr() if k > 0 else None, R_dist.data_ptr() if k > 0 else None,
+                                                 col_sum.data_ptr() if col_sum is not None else None, p, nbytes, _stream()))
+
+    def forms_ran(self) -> int:
+        """Bit 0: the per-entry form ran in the last bound call; bit 1: the table form."""
+        return int(self._lib.lcrwmd_forms_ran(self._h))
 
     def topk(self, D: torch.Tensor, k: int, R_idx: torch.Tensor, R_dist: torch.Tensor, ws: torch.Tensor | None = None):
         assert D.is_cuda and D.dtype == torch.float32 and D.stride(1) == 1

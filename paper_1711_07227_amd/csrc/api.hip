@@ -296,11 +296,6 @@ size_t rwmd_fixed_bytes(int64_t v, int32_t m, int64_t nnz_q, int64_t nnz_db, int
     return b;
 }
 
-size_t fwd_batch_bytes(int64_t v, int64_t qb, int64_t tokens)
-{
-    return token_plan_bytes(qb, tokens) + (size_t)v * (size_t)round_up(qb, 4) * 4 + 256;
-}
-
 size_t rev_batch_bytes(int64_t vq, int64_t nb, int64_t tokens)
 {
     return token_plan_bytes(nb, tokens) + (size_t)vq * (size_t)round_up(nb, 4) * 4 + 256;
@@ -360,15 +355,49 @@ int64_t max_tokens_per_batch(const int64_t* rp, int64_t rows, int64_t batch)
     return mx;
 }
 
-// The whole bound for the query rows [jq0, jq1) of Q against the database, into D (n x (jq1 - jq0), ldd).
-// rq / rdb are host copies of the two row_ptr arrays.
+// What becomes of the bound of a block of database rows once both directions are in it (the top-k of
+// lcrwmd_rwmd_reduce, its column sums): tile is (i1 - i0) x q with pitch ldt, row r of it is database row i0 + r.
+struct TileSink {
+    virtual lcrwmd_status consume(int64_t i0, int64_t i1, const float* tile, int64_t ldt, hipStream_t s) = 0;
+    virtual ~TileSink() {}
+};
+
+// Which of the two forms is expected to be faster.  Rates measured on one MI355X (kernel times of the five benchmark
+// workloads): first-phase contraction in algorithmic flop/s per arithmetic; table passes in table bytes/s, lane
+// iterations/s of the per-query loop of the swapped table pass and LDS look-ups/s of the forward table pass.
+bool table_form_is_faster(int mode, int32_t m, int64_t ve, int64_t vq, int64_t n, int64_t nnz_db, int64_t q, int64_t nnz_q)
+{
+    const double rate_p1 = mode == 1 ? 1.2e15 : mode == 2 ? 4.3e14 : 1.37e14;
+    const double rate_tab = mode == 1 ? 1.0e15 : mode == 2 ? 2.8e14 : 1.17e14;
+    int32_t wcols, nstrip;
+    table_strips(vq, &wcols, &nstrip);
+    const double per_entry = 2.0 * m * ((double)ve * (double)nnz_q + (double)vq * (double)nnz_db) / rate_p1;
+    const double table = 2.0 * m * (double)ve * (double)vq / rate_tab + 4.0 * (double)nnz_db * (double)vq / 1.2e13 +
+                         (double)n * (double)q * (double)nstrip / 2.8e11 + (double)ve * (double)nnz_q / 1.3e12 +
+                         4.0 * (double)ve * (double)vq / 4.0e12;
+    return table < per_entry;
+}
+
+// The whole bound for the query rows [jq0, jq1) of Q against the database: into D (n x (jq1 - jq0), ldd) when sink is
+// null, else block of database rows by block into a tile of the workspace that is handed to the sink and never
+// written anywhere else.  rq / rdb are host copies of the two row_ptr arrays.
+//
+// Order of work (Sec. IV, many-to-many form, both directions): vocabulary reduction of both sets; forward first phase
+// for all queries of the range (Z: one row per database word, one column per query; per-entry form: contraction +
+// minimum in batches of queries; table form: one word-pair table, minima looked up); then per block of database rows
+//   forward second phase   tile  = X1[block] * Z
+//   swapped first phase    Z'    = minima of the query words against the block's histograms (per-entry form)
+//   swapped second phase   tile  = max(tile, (X2 * Z')^T)        (table form: both steps from the table)
+// so a block's tile is produced, completed and consumed while it is cache resident.
+// Returns LCRWMD_EWORKSPACE with *shrink = true when the range's Z does not fit and a smaller range could.
 lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq, int64_t jq0, int64_t jq1,
                         const lcrwmd_csr* DB, const int64_t* rdb, const lcrwmd_emb* E, float* D, int64_t ldd,
-                        void* ws, size_t ws_bytes, hipStream_t s)
+                        TileSink* sink, void* ws, size_t ws_bytes, hipStream_t s, bool* shrink)
 {
     const int64_t v = E->v, n = DB->rows, q = jq1 - jq0;
     const int64_t qoff = rq[jq0], nnz_q = rq[jq1] - rq[jq0];
     const int32_t m = (int32_t)E->m;
+    if (shrink) *shrink = false;
     Bump b(ws, ws_bytes);
 
     int32_t* counters = b.take_n<int32_t>(64);
@@ -400,12 +429,24 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     HIP_TRY(hipStreamSynchronize(s));          // the vocabulary sizes decide grids and batch sizes
     const int64_t ve = hc[0], vq = hc[1];
 
+    // Z of the whole range: one row per database word
+    const int64_t ldz = round_up(q, 4);
+    float* Z = b.take_n<float>((size_t)ve * ldz);
     const size_t region_off = (b.used + 255) & ~(size_t)255;
-    if (region_off >= b.size) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small");
+    if (!b.ok || region_off >= b.size) {
+        if (shrink) *shrink = q > 1;
+        return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the first-phase minima of %lld queries", (long long)q);
+    }
     const size_t region = b.size - region_off;
+    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep);
+    int64_t nb_max = n < kDbBatch ? n : kDbBatch;
+    if (ctx->opt.max_db_batch > 0 && nb_max > ctx->opt.max_db_batch) nb_max = ctx->opt.max_db_batch;
+    const size_t tile_row = sink ? (size_t)ldz * 4 : 0;          // a block's tile lives in the workspace when there is a sink
 
-    // ---- de-duplicated form: one word-pair table for the batch, both passes read it ----
-    if (ctx->opt.dedup && ve > 0 && vq > 0 && q <= table_max_queries()) {
+    // ---- table form: one word-pair table for the range, both directions read it ----
+    bool table = false;
+    if (ctx->opt.dedup && ve > 0 && vq > 0 && q <= table_max_queries() &&
+        (ctx->opt.dedup == 1 || table_form_is_faster(ep.mode, m, ve, vq, n, DB->nnz, q, nnz_q))) {
         Phase1Args a;
         a.E = ep.data;
         a.ld = ep.ld;
@@ -417,11 +458,10 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         int32_t ws_cols, nstrip;
         table_strips(vq, &ws_cols, &nstrip);
         const int64_t vc = (int64_t)ws_cols * nstrip;
-        const int64_t ldw = vc, ldz = round_up(q, 4);                  // ws_cols is a multiple of 32: rows start on 128-byte lines
+        const int64_t ldw = vc;                                      // ws_cols is a multiple of 32: rows start on 128-byte lines
         const int64_t tok_count = round_up(ve, kTileTokens) + kTileTokens;
         Bump bb(b.base + region_off, region);
         float* W = bb.take_n<float>((size_t)ve * ldw);
-        float* Z = bb.take_n<float>((size_t)ve * ldz);
         int32_t* tok_ids = bb.take_n<int32_t>((size_t)tok_count);
         float* tok_hn = bb.take_n<float>((size_t)tok_count);
         const size_t nsq = (size_t)nstrip * (size_t)q + 1;
@@ -432,12 +472,25 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         float* bval = bb.take_n<float>((size_t)nnz_q);
         int32_t* col_word = bb.take_n<int32_t>((size_t)vc);
         int32_t* qcol = bb.take_n<int32_t>((size_t)nnz_q);
-        float* D2 = nstrip > 1 ? bb.take_n<float>((size_t)n * ldz) : nullptr;     // partial sums between strips
+        // per block of database rows: partial sums between the strips, and the tile when a sink takes it
+        // (without a sink all rows go in one block: a strip of the table is then streamed once per call, not once
+        // per block)
+        int64_t nb = sink ? nb_max : n;
+        const size_t per_row = (nstrip > 1 ? (size_t)ldz * 4 : 0) + tile_row;
+        if (per_row > 0 && bb.ok) {
+            const size_t room = bb.size - ((bb.used + 255) & ~(size_t)255);
+            const int64_t fit = (int64_t)((room > 1024 ? room - 1024 : 0) / per_row);
+            if (fit < nb) nb = fit;
+        }
         a.voc_rows = col_word;
         a.nvoc = vc;
         a.Z = W;
         a.ldz = ldw;
-        if (bb.ok && distance_table_supported(a, ep.mode)) {
+        if (bb.ok && nb >= 1 && distance_table_supported(a, ep.mode)) {
+            float* D2 = nstrip > 1 ? bb.take_n<float>((size_t)nb * ldz) : nullptr;
+            float* tile = sink ? bb.take_n<float>((size_t)nb * ldz) : nullptr;
+            table = true;
+            ctx->forms_ran |= 2;
             HIP_TRY(launch_table_spread(list_q, vq, qcol_pos, nnz_q, col_word, qcol, s));
             HIP_TRY(launch_table_tokens(list_db, ve, ep.normE, tok_ids, tok_hn, tok_count, s));
             {
@@ -451,64 +504,97 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
                 ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);
                 HIP_TRY(launch_table_fwd(W, ldw, ve, vc, boffs, bpos, q, Z, ldz, s));
             }
-            ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, q, D, ldd, 0, s));
-            {   // swapped: one table row per stored database entry, D read and written once
-                ProfScope ps(ctx, s, 4, 4.0 * (double)DB->nnz * (double)vq + 8.0 * (double)n * (double)q + 4.0 * (double)DB->nnz);
-                HIP_TRY(launch_table_rev(W, ldw, vc, DB->row_ptr, dbcol_pos, n, boffs, bpos, bval, q, D2, ldz, D, ldd, s));
+            for (int64_t i0 = 0; i0 < n; i0 += nb) {
+                const int64_t i1 = i0 + nb < n ? i0 + nb : n;
+                const int64_t nnz_b = rdb[i1] - rdb[i0];
+                float* Db = sink ? tile : D + i0 * ldd;
+                const int64_t ldb = sink ? ldz : ldd;
+                ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, i0 == 0 ? ve : 0, Z, ldz, q, Db, ldb, 0, s));
+                {   // swapped: one table row per stored database entry, the block read and written once
+                    ProfScope ps(ctx, s, 4, 4.0 * (double)nnz_b * (double)vq + 8.0 * (double)(i1 - i0) * (double)q + 4.0 * (double)nnz_b);
+                    HIP_TRY(launch_table_rev(W, ldw, vc, DB->row_ptr + i0, dbcol_pos, i1 - i0, boffs, bpos, bval, q, D2, ldz, Db, ldb, s));
+                }
+                if (sink) ST_TRY(sink->consume(i0, i1, Db, ldb, s));
             }
             return LCRWMD_OK;
         }
-        // the table does not fit the workspace (or the embedding shape has no table kernel): per-entry passes below
+        // the table does not fit the workspace (or the embedding shape has no table kernel): per-entry form below
+    }
+    (void)table;
+    ctx->forms_ran |= 1;
+
+    // ---- forward first phase: Z[p][j] = min over the words of query j of the distance to database word p ----
+    {
+        int64_t qb = q;
+        if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
+        for (;;) {
+            int64_t tok = max_tokens_per_batch(rq + jq0, q, qb);
+            if (tok + 7 * qb < kMaxTokens && token_plan_bytes(qb, tok) <= region) break;
+            if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one query (forward pass)");
+            qb = (qb + 1) / 2;
+        }
+        const int64_t nvt_f = (ve + kTileVocab - 1) / kTileVocab;
+        for (int64_t j0 = jq0; j0 < jq1; j0 += qb) {
+            const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
+            Bump bb(b.base + region_off, region);
+            TokenPlan tp;
+            carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1, grp), grp,
+                             chunk_tiles);
+            if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
+            ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/1, /*zero_map=*/map_db, Q->row_ptr + j0,
+                              Q->col_idx, rq[j1] - rq[j0], tp, Z + (j0 - jq0), ldz, s));
+        }
     }
 
-    // ---- forward: cost of moving database docs onto the queries, D1 = X1 * Z ----
-    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep);
-    int64_t qb = q;
-    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
-    for (;;) {
-        int64_t tok = max_tokens_per_batch(rq + jq0, q, qb);
-        if (tok + 7 * qb < kMaxTokens && fwd_batch_bytes(v, qb, tok) <= region) break;
-        if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one query (forward pass)");
-        qb = (qb + 1) / 2;
-    }
-    const int64_t nvt_f = (ve + kTileVocab - 1) / kTileVocab;
-    for (int64_t j0 = jq0; j0 < jq1; j0 += qb) {
-        const int64_t j1 = j0 + qb < jq1 ? j0 + qb : jq1;
-        Bump bb(b.base + region_off, region);
-        TokenPlan tp;
-        carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1, grp), grp,
-                         chunk_tiles);
-        const int64_t ldz = round_up(j1 - j0, 4);
-        float* Z = bb.take_n<float>((size_t)ve * ldz);
-        if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
-        ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/1, /*zero_map=*/map_db, Q->row_ptr + j0,
-                          Q->col_idx, rq[j1] - rq[j0], tp, Z, ldz, s));
-        ST_TRY(run_spmm(ctx, DB->row_ptr, dbcol_pos, DB->val, n, DB->nnz, ve, Z, ldz, j1 - j0, D + (j0 - jq0), ldd, 0, s));
-    }
-
-    // ---- swapped: cost of moving the queries onto database docs, D = max(D1, (X2 * Z')^T) ----
-    int64_t nb = n < kDbBatch ? n : kDbBatch;
-    if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
+    // ---- per block of database rows: forward second phase, swapped first and second phase, D = max(D1, D2^T) ----
+    int64_t nb = nb_max;
     for (;;) {
         int64_t tok = max_tokens_per_batch(rdb, n, nb);
-        if (tok + 7 * nb < kMaxTokens && rev_batch_bytes(vq, nb, tok) <= region) break;
-        if (nb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one database row (swapped pass)");
+        if (tok + 7 * nb < kMaxTokens && rev_batch_bytes(vq, nb, tok) + (size_t)nb * tile_row + 256 <= region) break;
+        if (nb == 1) {
+            if (shrink) *shrink = q > 1;
+            return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one database row (swapped pass)");
+        }
         nb = (nb + 1) / 2;
     }
     const int64_t nvt_r = (vq + kTileVocab - 1) / kTileVocab;
     for (int64_t i0 = 0; i0 < n; i0 += nb) {
         const int64_t i1 = i0 + nb < n ? i0 + nb : n;
+        const int64_t nnz_b = rdb[i1] - rdb[i0];
         Bump bb(b.base + region_off, region);
         TokenPlan tp;
-        carve_token_plan(bb, tp, i1 - i0, rdb[i1] - rdb[i0], plan_tiles(nvt_r, ep.bf16), padded_tokens(rdb, i0, i1, grp), grp,
-                         chunk_tiles);
-        const int64_t ldz = round_up(i1 - i0, 4);
-        float* Z = bb.take_n<float>((size_t)vq * ldz);
-        if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: swapped batch does not fit");
+        carve_token_plan(bb, tp, i1 - i0, nnz_b, plan_tiles(nvt_r, ep.bf16), padded_tokens(rdb, i0, i1, grp), grp, chunk_tiles);
+        const int64_t ldzr = round_up(i1 - i0, 4);
+        float* Zr = bb.take_n<float>((size_t)vq * ldzr);
+        float* tile = sink ? bb.take_n<float>((size_t)(i1 - i0) * ldz) : nullptr;
+        if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: block of database rows does not fit");
+        float* Db = sink ? tile : D + i0 * ldd;
+        const int64_t ldb = sink ? ldz : ldd;
+        ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, i0 == 0 ? ve : 0, Z, ldz, q, Db, ldb, 0, s));
         ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
-                          DB->col_idx, rdb[i1] - rdb[i0], tp, Z, ldz, s, /*swapped=*/true));
+                          DB->col_idx, nnz_b, tp, Zr, ldzr, s, /*swapped=*/true));
         // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
-        ST_TRY(run_spmm(ctx, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, nnz_q, vq, Z, ldz, i1 - i0, D + i0 * ldd, ldd, 2, s));
+        ST_TRY(run_spmm(ctx, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, nnz_q, vq, Zr, ldzr, i1 - i0, Db, ldb, 2, s));
+        if (sink) ST_TRY(sink->consume(i0, i1, Db, ldb, s));
+    }
+    return LCRWMD_OK;
+}
+
+// rwmd_core over all queries: the whole set at once when its first-phase minima fit the workspace (and the table
+// kernels' limit on queries per pass, when the table form may run), otherwise in ranges of queries.
+lcrwmd_status rwmd_ranges(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq, const lcrwmd_csr* DB, const int64_t* rdb,
+                          const lcrwmd_emb* E, float* D, int64_t ldd, int64_t qr, void* ws, size_t ws_bytes, hipStream_t s)
+{
+    const int64_t q = Q->rows;
+    if (qr > q) qr = q;
+    if (ctx->opt.dedup == 1 && qr > table_max_queries()) qr = table_max_queries();
+    for (int64_t j0 = 0; j0 < q;) {
+        const int64_t j1 = j0 + qr < q ? j0 + qr : q;
+        bool shrink = false;
+        lcrwmd_status st = rwmd_core(ctx, Q, rq, j0, j1, DB, rdb, E, D + j0, ldd, nullptr, ws, ws_bytes, s, &shrink);
+        if (st == LCRWMD_EWORKSPACE && shrink && qr > 1) { qr = (qr + 1) / 2; continue; }    // nothing of this range was written
+        if (st != LCRWMD_OK) return st;
+        j0 = j1;
     }
     return LCRWMD_OK;
 }
@@ -627,7 +713,7 @@ lcrwmd_status lcrwmd_set_options(lcrwmd_ctx* ctx, const lcrwmd_options* opt)
     if (!opt) return fail(ctx, LCRWMD_EINVAL, "options are NULL");
     if ((opt->validate != 0 && opt->validate != 1) ||
         (opt->compute != LCRWMD_F32 && opt->compute != LCRWMD_BF16 && opt->compute != LCRWMD_BF16X3) ||
-        opt->max_query_batch < 0 || opt->max_db_batch < 0 || (opt->dedup != 0 && opt->dedup != 1))
+        opt->max_query_batch < 0 || opt->max_db_batch < 0 || opt->dedup < 0 || opt->dedup > 2)
         return fail(ctx, LCRWMD_EINVAL, "option out of range");
     ctx->opt = *opt;
     return LCRWMD_OK;
@@ -650,26 +736,29 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     const bool asks_bf16 = emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16;
     const int bf16 = m > 300 ? 0 : asks_bf16 ? 1 : ctx->opt.compute == LCRWMD_BF16X3 ? 2 : 0;     // see prec_mode
     const bool widened = m > 300 && asks_bf16;
-    int64_t qb = q;
-    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
-    if (k > 0 && qb > 2048) qb = 2048;
+    int64_t qr = q > 0 ? q : 1;                                  // queries per range: all of them when they fit
+    if (ctx->opt.dedup == 1 && qr > table_max_queries()) qr = table_max_queries();
     int64_t nb = n < kDbBatch ? n : kDbBatch;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
-    const int64_t vq = v < nnz_q ? v : nnz_q;
+    if (nb < 1) nb = 1;
+    const int64_t vq = v < nnz_q ? v : nnz_q, ve_max = v < nnz_db ? v : nnz_db;
+    const int64_t ldz = round_up(qr, 4);
     const bool padded = bf16 == 0 && m <= kPadM && m >= kPadFromM;
-    size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded, widened);
-    size_t f = fwd_batch_bytes(v, qb > 0 ? qb : 1, nnz_q);
-    size_t r = rev_batch_bytes(vq, nb > 0 ? nb : 1, nnz_db);
-    size_t total = fixed + (f > r ? f : r) + 4096;
+    const size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded, widened);
+    const size_t zfull = (size_t)ve_max * (size_t)ldz * 4 + 256;                       // first-phase minima of a range
+    const size_t tile = (size_t)nb * (size_t)ldz * 4 + 256;                            // a block's tile (lcrwmd_rwmd_reduce)
+    const size_t f = token_plan_bytes(qr, nnz_q);
+    const size_t r = rev_batch_bytes(vq, nb, nnz_db) + tile;
+    size_t region = f > r ? f : r;
     if (ctx->opt.dedup) {
-        // room for the word-pair table and the forward Z at their upper bounds (distinct words <= stored entries)
-        const int64_t qt = qb < table_max_queries() ? qb : table_max_queries();
-        const int64_t ve_max = v < nnz_db ? v : nnz_db;
-        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + 32 * ((vq + 255) / 256) + round_up(qt, 4)) * 4 + (size_t)(ve_max + 256) * 8 +
-                         table_bucket_bytes(vq, qt, nnz_q) + (size_t)n * (size_t)round_up(qt, 4) * 4 + 8192;
-        if (t > (f > r ? f : r)) total = fixed + t + 4096;
+        // room for the word-pair table at its upper bound (distinct words <= stored entries)
+        const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + 32 * ((vq + 255) / 256)) * 4 + (size_t)(ve_max + 256) * 8 +
+                         table_bucket_bytes(vq, qr, nnz_q) + (size_t)n * (size_t)ldz * 4 + 2 * tile + 8192;
+        if (t > region) region = t;
     }
-    if (k > 0) total += (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, k) + 1024;
+    size_t total = fixed + zfull + region + 4096;
+    // lcrwmd_rwmd_reduce: the running lists, a block's list and its partial lists, the column sums' scratch
+    total += 6 * ((size_t)qr * (size_t)(k > 0 ? k : 1) * 4 + 256) + topk_bytes(nb, qr, k > 0 ? k : 1) + col_sums_bytes(qr) + 2048;
     // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
     size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded, widened) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
     *out_bytes = total > p1 ? total : p1;
@@ -740,16 +829,8 @@ lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrw
     HIP_TRY(hipSetDevice(ctx->device));
     HostPtr rq, rdb;
     ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
-    const int64_t qr = table_max_queries();
-    if (ctx->opt.dedup && queries->rows > qr) {
-        // the table kernels keep one value per query in LDS: hand them the queries in ranges
-        for (int64_t j0 = 0; j0 < queries->rows; j0 += qr) {
-            const int64_t j1 = j0 + qr < queries->rows ? j0 + qr : queries->rows;
-            ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, D + j0, ldd, ws, ws_bytes, s));
-        }
-        return LCRWMD_OK;
-    }
-    return rwmd_core(ctx, queries, rq.p, 0, queries->rows, database, rdb.p, E, D, ldd, ws, ws_bytes, s);
+    ctx->forms_ran = 0;
+    return rwmd_ranges(ctx, queries, rq.p, database, rdb.p, E, D, ldd, queries->rows, ws, ws_bytes, s);
 }
 
 lcrwmd_status lcrwmd_topk(lcrwmd_ctx* ctx, const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx,
@@ -794,50 +875,122 @@ lcrwmd_status lcrwmd_topk_noalloc(lcrwmd_ctx* ctx, const float* D, int64_t n, in
     return LCRWMD_OK;
 }
 
-lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
-                               const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist, void* ws, size_t ws_bytes,
-                               void* hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Sink of lcrwmd_rwmd_reduce: a running top-k per query (two lists that take turns) and running column sums.
+struct ReduceSink : TileSink {
+    lcrwmd_ctx* ctx = nullptr;
+    int k = 0;
+    int64_t q = 0;
+    float* run_d[2] = {nullptr, nullptr};
+    int32_t* run_i[2] = {nullptr, nullptr};
+    float* blk_d = nullptr;
+    int32_t* blk_i = nullptr;
+    void* tk = nullptr;
+    size_t tkb = 0;
+    double* sums = nullptr;      // the caller's, already offset to this range's first query
+    double* part = nullptr;
+    int cur = 0;
+    bool any = false;
+
+    lcrwmd_status consume(int64_t i0, int64_t i1, const float* tile, int64_t ldt, hipStream_t s) override
+    {
+        if (k > 0) {
+            HIP_TRY(launch_topk(tile, i1 - i0, q, ldt, k, blk_i, blk_d, tk, tkb, s));       // slots a short block cannot fill: FLT_MAX
+            HIP_TRY(launch_topk_merge2(run_d[cur], run_i[cur], any, blk_d, blk_i, i0, q, k, run_d[cur ^ 1], run_i[cur ^ 1], s));
+            cur ^= 1;
+        }
+        if (sums) HIP_TRY(launch_col_sums(tile, i1 - i0, q, ldt, part, !any, sums, s));
+        any = true;
+        return LCRWMD_OK;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+lcrwmd_status lcrwmd_rwmd_reduce(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                                 const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist, double* col_sum,
+                                 void* ws, size_t ws_bytes, void* hip_stream)
 {
     if (!ctx) return LCRWMD_EINVAL;
     hipStream_t s = (hipStream_t)hip_stream;
     ST_TRY(check_rwmd_args(ctx, queries, database, E));
     const int64_t n = database->rows, q = queries->rows;
+    if (k < 0) return fail(ctx, LCRWMD_EINVAL, "k < 0");
+    if (k == 0 && !col_sum) return fail(ctx, LCRWMD_EINVAL, "nothing asked for: k == 0 and col_sum is NULL");
     if (q == 0) return LCRWMD_OK;
-    if (!R_idx || !R_dist) return fail(ctx, LCRWMD_EINVAL, "R_idx or R_dist is NULL");
-    if (k < 1 || k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > 0 && (!R_idx || !R_dist)) return fail(ctx, LCRWMD_EINVAL, "R_idx or R_dist is NULL");
+    if (k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
     if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    if (n > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "n exceeds int32 row indices");
     ST_TRY(check_ws(ctx, ws, ws_bytes));
     HIP_TRY(hipSetDevice(ctx->device));
-
-    // Query batches: the n x qb tile of D lives at the front of the workspace, the rest serves the bound.
     HostPtr rq, rdb;
     ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
-    int64_t qb = q < 2048 ? q : 2048;
-    if (ctx->opt.max_query_batch > 0 && qb > ctx->opt.max_query_batch) qb = ctx->opt.max_query_batch;
-    const int bf16 = prec_mode(ctx, E);
-    for (;;) {
-        size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + 256;
-        size_t need = tile + topk_bytes(n, qb, k) + 512 + rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, bf16,
-                                                                               bf16 == 0 && wants_padded_copy(E), wants_widened_copy(ctx, E)) +
-                      fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
-        if (need <= ws_bytes) break;
-        if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query tile of D");
-        qb = (qb + 1) / 2;
-    }
-    for (int64_t j0 = 0; j0 < q; j0 += qb) {
-        const int64_t j1 = j0 + qb < q ? j0 + qb : q;
+    ctx->forms_ran = 0;
+    if (n == 0) return LCRWMD_OK;
+
+    // Ranges of queries: all of them when their first-phase minima fit the workspace, otherwise fewer at a time.
+    int64_t qr = q;
+    if (ctx->opt.dedup == 1 && qr > table_max_queries()) qr = table_max_queries();
+    int64_t nb = n < kDbBatch ? n : kDbBatch;
+    if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
+    for (int64_t j0 = 0; j0 < q;) {
+        const int64_t j1 = j0 + qr < q ? j0 + qr : q, nq = j1 - j0;
         Bump b(ws, ws_bytes);
-        const int64_t ldt = round_up(j1 - j0, 4);
-        float* tile = b.take_n<float>((size_t)n * ldt);
-        const size_t tkb = topk_bytes(n, j1 - j0, k) + 512;
-        void* tk = b.take(tkb);
-        if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: top-k tile does not fit");
-        const size_t off = (b.used + 255) & ~(size_t)255;
-        ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, (char*)ws + off, ws_bytes - off, s));
-        HIP_TRY(launch_topk(tile, n, j1 - j0, ldt, k, R_idx + j0 * k, R_dist + j0 * k, tk, tkb, s));
+        ReduceSink sink;
+        sink.ctx = ctx;
+        sink.k = k;
+        sink.q = nq;
+        if (k > 0) {
+            for (int t = 0; t < 2; ++t) {
+                sink.run_d[t] = b.take_n<float>((size_t)nq * k);
+                sink.run_i[t] = b.take_n<int32_t>((size_t)nq * k);
+            }
+            sink.blk_d = b.take_n<float>((size_t)nq * k);
+            sink.blk_i = b.take_n<int32_t>((size_t)nq * k);
+            sink.tkb = topk_bytes(nb, nq, k) + 512;
+            sink.tk = b.take(sink.tkb);
+        }
+        if (col_sum) {
+            sink.sums = col_sum + j0;
+            sink.part = (double*)b.take(col_sums_bytes(nq));
+        }
+        bool shrink = !b.ok;
+        lcrwmd_status st = LCRWMD_EWORKSPACE;
+        if (b.ok) {
+            const size_t off = (b.used + 255) & ~(size_t)255;
+            st = off < ws_bytes ? rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, nullptr, 0, &sink, (char*)ws + off,
+                                            ws_bytes - off, s, &shrink)
+                                : LCRWMD_EWORKSPACE;
+            if (off >= ws_bytes) shrink = true;
+        }
+        if (st == LCRWMD_EWORKSPACE && shrink && qr > 1) { qr = (qr + 1) / 2; continue; }     // nothing of this range was written
+        if (st == LCRWMD_EWORKSPACE && !b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the lists of one query");
+        if (st != LCRWMD_OK) return st;
+        if (k > 0) {
+            HIP_TRY(hipMemcpyAsync(R_dist + j0 * k, sink.run_d[sink.cur], sizeof(float) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+            HIP_TRY(hipMemcpyAsync(R_idx + j0 * k, sink.run_i[sink.cur], sizeof(int32_t) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+        }
+        j0 = j1;
     }
     return LCRWMD_OK;
 }
+
+lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                               const lcrwmd_emb* E, int k, int32_t* R_idx, float* R_dist, void* ws, size_t ws_bytes,
+                               void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (k < 1) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    return lcrwmd_rwmd_reduce(ctx, queries, database, E, k, R_idx, R_dist, nullptr, ws, ws_bytes, hip_stream);
+}
+
+int lcrwmd_forms_ran(const lcrwmd_ctx* ctx) { return ctx ? ctx->forms_ran : 0; }
 
 // ------------------------------------------------------------------------------------------------ exact WMD, WCD, pruning
 
@@ -976,7 +1129,9 @@ lcrwmd_status lcrwmd_wmd_topk_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_
     // per-query arrays, lists for a quarter of all pairs of a batch, one transport problem per resident wavefront
     const size_t lists = (size_t)qb * (size_t)kMaxTopK * 24 + (size_t)qb * 32 + (size_t)n * (size_t)qb / 4 * 12;
     const size_t slabs = emd_pair_bytes(max_h_db, max_h_q) * (size_t)emd_preferred_slots(ctx->num_cu, max_h_db, max_h_q);
-    *out_bytes = base + lists + slabs + 16384;
+    // the n x qb tile of bounds the pruning reads, and the scratch of the top-k over it
+    const size_t tile = (size_t)n * (size_t)round_up(qb, 4) * 4 + topk_bytes(n, qb, kMaxTopK) + 1024;
+    *out_bytes = base + tile + lists + slabs + 16384;
     return LCRWMD_OK;
 }
 
@@ -1015,9 +1170,11 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
                (size_t)b * 32 + 8192;
     };
     for (;;) {
+        const int64_t ve_max = E->v < database->nnz ? E->v : database->nnz, vq_max = E->v < queries->nnz ? E->v : queries->nnz;
         const size_t rwmd_need = rwmd_fixed_bytes(E->v, (int32_t)E->m, queries->nnz, database->nnz, mode,
                                                      mode == 0 && wants_padded_copy(E), wants_widened_copy(ctx, E)) +
-                                 fwd_batch_bytes(E->v, 1, max_tokens_per_batch(rq.p, q, 1)) + 4096;
+                                 (size_t)ve_max * (size_t)round_up(qb, 4) * 4 + token_plan_bytes(qb, max_tokens_per_batch(rq.p, q, qb)) +
+                                 rev_batch_bytes(vq_max, 1, max_tokens_per_batch(rdb.p, n, 1)) + 8192;
         const size_t wmd_need = (size_t)qb * (size_t)kMaxTopK * 16 + pair_bytes * 2 + 8192;   // first-round lists, a problem in flight
         if (front_bytes(qb) + (rwmd_need > wmd_need ? rwmd_need : wmd_need) <= ws_bytes) break;
         if (qb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for a one-query batch");
@@ -1069,7 +1226,7 @@ lcrwmd_status lcrwmd_wmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const 
         const size_t rest_bytes = ws_bytes - rest_off;
 
         // RWMD to every database histogram, the kx nearest by RWMD (Sec. III)
-        ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, rest, rest_bytes, s));
+        ST_TRY(rwmd_core(ctx, queries, rq.p, j0, j1, database, rdb.p, E, tile, ldt, nullptr, rest, rest_bytes, s, nullptr));
         HIP_TRY(launch_topk(tile, n, nq, ldt, kx, R0, R0d, tk, tkb, s));
         // WMD to the first k1 of those; the k-th smallest of them is the cut-off
         HIP_TRY(launch_fill_i32(counters, 4, 0, s));

@@ -22,6 +22,7 @@ struct lcrwmd_ctx {
     lcrwmd_options opt;
     char err[512];
     bool profiling;
+    int forms_ran = 0;                // bit 0: the per-entry form ran in the last bound call, bit 1: the table form
     double prof_abandoned = 0.0;      // lcrwmd_wmd_topk: survivors whose solve stopped above the cut-off, while profiling
     std::vector<lcrwmd_prof_rec> prof;
 };
@@ -184,6 +185,13 @@ constexpr int kMaxTopK = 64;
 size_t topk_bytes(int64_t n, int64_t q, int k);
 hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
                        void* ws, size_t ws_bytes, hipStream_t s);
+// out = the k smallest of list a (absolute row indices; ignored unless have_a) and list b (row indices relative to row0)
+hipError_t launch_topk_merge2(const float* a_d, const int32_t* a_i, bool have_a, const float* b_d, const int32_t* b_i,
+                              int64_t row0, int64_t q, int k, float* out_d, int32_t* out_i, hipStream_t s);
+// sums[j] (+)= sum over the rows of tile[r][j] in fp64 (first: sums start at 0); part: col_sums_bytes(q) of scratch
+size_t col_sums_bytes(int64_t q);
+hipError_t launch_col_sums(const float* tile, int64_t rows, int64_t q, int64_t ldt, double* part, bool first, double* sums,
+                           hipStream_t s);
 // the file-scope device array behind lcrwmd_topk_noalloc: its size, the per-device address look-up (device current)
 size_t topk_static_bytes();
 hipError_t topk_static_init(int device);

@@ -115,7 +115,7 @@ constexpr int kMaxRows = 64;
 // TABLE = true turns the kernel into the plain pairwise-distance operation C = T o E of Sec. III: no minimum, every
 // element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0)) is stored, row t (token) x column u (vocabulary position) with
 // pitch ldz.  Tokens are then simply the rows tok_ids[0 .. ntok) cut into chunks of chunk_tokens.
-template <int MODE, int NCT, int WGS_PER_CU, bool TABLE>
+template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
 __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 {
     using L = Layout<MODE>;
@@ -208,12 +208,14 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
     // ---- copy jobs of this wavefront ----
     // job J -> octet J / NRT, row block (of 8 rows) wave + 4 (J % NRT); lane -> row lane / 8, slot lane % 8
     const int lane8 = lane >> 3;                                   // row within an 8-row block; also this lane's token group
-    // Source offsets are counted in 16-byte pieces: 32 bits then reach 64 GiB of operand rows (the host checks it).
+    // Source offsets in units of U bytes: 16-byte pieces when the operand rows span 4 GiB or more (32 bits then reach
+    // 64 GiB; the host checks it), bytes otherwise.
+    constexpr uint32_t U = WIDE ? 16 : 1, PIECE = 16 / U;
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
-    const uint32_t offO = pieceO;
+    const uint32_t offO = pieceO * PIECE;
     // fp32: the last octet reaches past the end of the row (pieces 75..79): re-read the last real piece
     const int last_piece = (L::NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = (BF16 || X3) ? offO + (L::NOCT - 1) * 8 : (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1);
+    const uint32_t off_last = (BF16 || X3) ? offO + (L::NOCT - 1) * 8 * PIECE : (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1) * PIECE;
 
     // Word ids of the two token rows this lane copies.  They are fetched when the previous tile's copy jobs have
     // all been issued (one pair of registers serves both) and are multiplied out to byte offsets job by job.
@@ -223,13 +225,13 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         wA = t[lane8];
         if (NRT == 2) wB = t[lane8 + 32];
     };
-    const uint32_t pitch16 = (uint32_t)(p.pitch_b >> 4);     // the host guarantees rows * pitch16 < 2^32
+    const uint32_t pitchU = (uint32_t)(p.pitch_b / U);     // the host guarantees rows * pitchU < 2^32
     // copy job J (compile time) of this wavefront into buffer `lbase`
     auto copy_job = [&](auto j_c, unsigned char* lbase) {
         constexpr int J = decltype(j_c)::value;
         constexpr int oct = J / NRT, blk = J % NRT;
-        const uint32_t off = (uint32_t)(blk ? wB : wA) * pitch16 + (oct == L::NOCT - 1 ? off_last : offO + oct * 8);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + ((uint64_t)off << 4)),
+        const uint32_t off = (uint32_t)(blk ? wB : wA) * pitchU + (oct == L::NOCT - 1 ? off_last : offO + oct * 8 * PIECE);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(WIDE ? Eb + ((uint64_t)off << 4) : Eb + off),
                                          (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + blk * 4 + wave) * 1024),
                                          16, 0, 0);
     };
@@ -497,7 +499,10 @@ __device__ inline void pp_barrier() { __builtin_amdgcn_s_barrier(); }
 // The per-tile side tables (word ids of the rows to copy, histogram of every group of 8 rows) are read with uniform
 // addresses through restrict-qualified arguments, i.e. as scalar loads: they are then not part of the vector memory
 // queue whose order the copy waits rely on, and they cost no vector registers.
-template <int MODE>
+// WIDE: the operand rows span 4 GiB or more: copy offsets are then counted in 16-byte pieces (32 bits reach 64 GiB)
+// instead of bytes, at the price of a shift per copy instruction (measured: 9 % of the bf16 kernel's time, which is
+// why the byte form stays the default).
+template <int MODE, bool WIDE>
 __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t* __restrict__ tok_ids,
                                                             const int32_t* __restrict__ grp_seg)
 {
@@ -527,13 +532,14 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     const unsigned char* Eb = p.Eb;
     const int lane8 = lane >> 3;
     const int pieceO = (lane & 7) ^ ((wave & 1) * 4 + (lane >> 4));
-    // Source offsets are counted in 16-byte pieces: 32 bits then reach 64 GiB of operand rows (the host checks it).
-    const uint32_t offO = (uint32_t)pieceO;
+    // Source offsets in units of U bytes (the host checks that 32 bits suffice)
+    constexpr uint32_t U = WIDE ? 16 : 1, PIECE = 16 / U;
+    const uint32_t offO = (uint32_t)pieceO * PIECE;
     // fp32 rows end inside the last octet (pieces 75..79 do not exist): those lanes re-read the last real piece,
     // which meets zeros on the vocabulary side
     const int last_piece = (NOCT - 1) * 8 + pieceO;
-    const uint32_t off_last = (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1) - offO;
-    const uint32_t pitch16 = (uint32_t)(p.pitch_b >> 4);
+    const uint32_t off_last = (uint32_t)(last_piece < p.nreal ? last_piece : p.nreal - 1) * PIECE - offO;
+    const uint32_t pitchU = (uint32_t)(p.pitch_b / U);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const uint32_t a_oct0 = lds0 + (l31 >> 3) * 1024 + (l31 & 7) * 128 + ((half ^ ((l31 >> 1) & 7)) * 16);
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -587,19 +593,19 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
         for (int k = 0; k < 8; ++k) r.v[k] = t[k];
         return r;
     };
-    // offset (in 16-byte pieces) of this lane's piece of its row, from the row block's 8 word ids
+    // offset of this lane's piece of its row, from the row block's 8 word ids
     auto row_offset = [&](const Ids& ids) {
         // lane l < 8 takes id l, then every lane fetches the id of its row from lane (row within the block)
         int32_t spread = 0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) asm("v_writelane_b32 %0, %1, %2" : "+v"(spread) : "s"(ids.v[k]), "n"(k));
         const int32_t wA = __builtin_amdgcn_ds_bpermute(lane8 << 2, spread);
-        return (uint32_t)wA * pitch16 + offO;
+        return (uint32_t)wA * pitchU + offO;
     };
     auto copy_octet = [&](auto o_c, uint32_t off, unsigned char* lbase) {
         constexpr int oct = decltype(o_c)::value;
-        const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 8));
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Eb + ((uint64_t)o << 4)),
+        const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 8) * PIECE);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(WIDE ? Eb + ((uint64_t)o << 4) : Eb + o),
                                          (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
                                          16, 0, 0);
     };
@@ -804,8 +810,20 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     }   // runs of this workgroup
 }
 
+bool rows_within_4gib(int64_t rows, int64_t pitch_bytes) { return rows * pitch_bytes < ((int64_t)1 << 32); }
+
+template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
+hipError_t launch_tiles_w(P1T d, hipStream_t s);
+
 template <int MODE, int NCT, int WGS_PER_CU, bool TABLE>
-hipError_t launch_tiles(P1T d, hipStream_t s)
+hipError_t launch_tiles(P1T d, int64_t erows, hipStream_t s)
+{
+    return rows_within_4gib(erows, d.pitch_b) ? launch_tiles_w<MODE, NCT, WGS_PER_CU, TABLE, false>(d, s)
+                                              : launch_tiles_w<MODE, NCT, WGS_PER_CU, TABLE, true>(d, s);
+}
+
+template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
+hipError_t launch_tiles_w(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
     const int64_t grid = 8 * (int64_t)d.nvt * ((d.nchunks + 7) / 8);       // per XCD: nvt items in every 8 chunks
@@ -813,12 +831,12 @@ hipError_t launch_tiles(P1T d, hipStream_t s)
     const size_t smem = (size_t)Layout<MODE>::NBUF * (size_t)Layout<MODE>::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE><<<(unsigned)grid, 256, smem, s>>>(d);
+    k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE, WIDE><<<(unsigned)grid, 256, smem, s>>>(d);
     return hipGetLastError();
 }
 
@@ -849,7 +867,8 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
 // in 16-byte aligned rows.  Other shapes take the register-staged kernels of phase1_f32.hip.
 int phase1_group_x3() { return PP<kX3>::G; }
 
-// The copies address operand rows with 32-bit offsets counted in 16-byte pieces.
+// The copies address operand rows with 32-bit offsets: bytes while the rows span less than 4 GiB, 16-byte pieces
+// (a slower variant of the kernels) up to 64 GiB.
 bool tiles_rows_addressable(int64_t rows, int64_t pitch_bytes) { return pitch_bytes % 16 == 0 && rows * (pitch_bytes / 16) < ((int64_t)1 << 32); }
 
 bool tiles_f32_supported(const Phase1Args& a)
@@ -858,8 +877,17 @@ bool tiles_f32_supported(const Phase1Args& a)
 }
 
 // One workgroup of eight wavefronts per CU (it takes all of a CU's LDS), fewer when there is less work than that.
+template <int MODE, bool WIDE>
+hipError_t launch_pingpong_w(P1T d, int num_cu, hipStream_t s);
+
 template <int MODE>
-hipError_t launch_pingpong(P1T d, int num_cu, hipStream_t s)
+hipError_t launch_pingpong(P1T d, int64_t erows, int num_cu, hipStream_t s)
+{
+    return rows_within_4gib(erows, d.pitch_b) ? launch_pingpong_w<MODE, false>(d, num_cu, s) : launch_pingpong_w<MODE, true>(d, num_cu, s);
+}
+
+template <int MODE, bool WIDE>
+hipError_t launch_pingpong_w(P1T d, int num_cu, hipStream_t s)
 {
     using C = PP<MODE>;
     d.nvt = (int32_t)((d.nvoc + C::WG_COLS - 1) / C::WG_COLS);
@@ -869,12 +897,12 @@ hipError_t launch_pingpong(P1T d, int num_cu, hipStream_t s)
     const size_t smem = (size_t)C::NBUF * C::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_pingpong<MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_pingpong<MODE, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    k_phase1_pingpong<MODE><<<(unsigned)grid, 512, smem, s>>>(d, d.tok_ids, d.grp_seg);
+    k_phase1_pingpong<MODE, WIDE><<<(unsigned)grid, 512, smem, s>>>(d, d.tok_ids, d.grp_seg);
     return hipGetLastError();
 }
 
@@ -886,7 +914,7 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
     d.nzero_from = a.m;
     if (tp.group != PP<kF32>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     if (!tiles_f32_supported(a)) return hipErrorInvalidValue;
-    return launch_pingpong<kF32>(d, a.num_cu, s);
+    return launch_pingpong<kF32>(d, a.erows, a.num_cu, s);
 }
 
 // a.E is the split copy: 640 bf16 per row (304 hi, 304 lo, zeros); norms and -|T|^2/2 stay fp32 as in the fp32 path
@@ -898,7 +926,7 @@ hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipS
     d.nzero_from = 0;
     if (tp.group != PP<kX3>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     if (!tiles_rows_addressable(a.erows, d.pitch_b)) return hipErrorInvalidValue;
-    return launch_pingpong<kX3>(d, a.num_cu, s);
+    return launch_pingpong<kX3>(d, a.erows, a.num_cu, s);
 }
 
 // a.E is the packed bf16 copy: 320 values per row, the norm terms in columns 300..302
@@ -910,7 +938,7 @@ hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, in
     d.nzero_from = 0;
     if (tp.group != PP<kBF16>::G) return hipErrorInvalidValue;      // the token plan was padded for another kernel
     if (!tiles_rows_addressable(a.erows, d.pitch_b)) return hipErrorInvalidValue;
-    return launch_pingpong<kBF16>(d, num_cu, s);
+    return launch_pingpong<kBF16>(d, a.erows, num_cu, s);
 }
 
 // Pairwise distance table W[t][u] = || E[rows_t[t]] - E[voc_rows[u]] ||, t < ntok, u < a.nvoc, into a.Z with pitch a.ldz.
@@ -951,18 +979,18 @@ hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* t
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kBF16>::NOCT * 8;
         d.nzero_from = 0;
-        return launch_tiles<kBF16, 2, 2, true>(d, s);
+        return launch_tiles<kBF16, 2, 2, true>(d, a.erows, s);
     }
     if (mode == 2) {
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kX3>::NOCT * 8;
         d.nzero_from = 0;
-        return launch_tiles<kX3, 2, 1, true>(d, s);
+        return launch_tiles<kX3, 2, 1, true>(d, a.erows, s);
     }
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<kF32, 2, 1, true>(d, s);
+    return launch_tiles<kF32, 2, 1, true>(d, a.erows, s);
 }
 
 }  // namespace lcrwmd

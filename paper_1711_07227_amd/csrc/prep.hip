@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict_
 // One wavefront per row of Z and strip of columns: 64 entries are tested at a time (one coalesced load); the flagged
 // ones are then redone one after the other by the whole wavefront, lanes along the embedding dimension.  On embeddings
 // without close pairs this is one read of Z.
-constexpr int kRedoBlocks = 16;      // 64-column blocks per wavefront
+constexpr int kRedoCols = 1024;      // columns per wavefront: four 16-byte loads per lane, all in flight together
 
 template <bool BF16>
 __device__ inline float emb_value(const void* E, int64_t idx)
@@ -244,7 +244,8 @@ __device__ inline float emb_value(const void* E, int64_t idx)
     return reinterpret_cast<const float*>(E)[idx];
 }
 
-template <bool BF16>
+// VEC: rows of Z are 16-byte aligned (pitch a multiple of 4, base aligned): lanes read float4; otherwise scalars.
+template <bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, int64_t ld, int32_t m,
                                                     const float* __restrict__ normE, const int32_t* __restrict__ voc_rows,
                                                     int64_t nvoc, const int64_t* __restrict__ rp,
@@ -259,12 +260,42 @@ __global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, 
     const int32_t w = voc_rows ? voc_rows[pos] : (int32_t)pos;
     const float limit = 0.25f * normE[w];
     float* zrow = Z + pos * ldz;
-    for (int blk = 0; blk < kRedoBlocks; ++blk) {
-        const int64_t j = (strip * kRedoBlocks + blk) * 64 + lane;
-        if (j - lane >= nseg) break;
-        const float z = j < nseg ? zrow[j] : 1e30f;
-        bool redo = z * z < limit;
-        if (redo && z == 0.f) {
+    // element e of this lane: column j0 + 256 * (e / 4) + 4 * lane + e % 4 (VEC) or j0 + 64 * e + lane
+    const int64_t j0 = strip * kRedoCols;
+    float z[16];
+    if (VEC) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t j = j0 + 256 * b + 4 * lane;
+            float4 x = make_float4(1e30f, 1e30f, 1e30f, 1e30f);
+            if (j + 3 < nseg) x = *reinterpret_cast<const float4*>(zrow + j);
+            else {
+                if (j < nseg) x.x = zrow[j];
+                if (j + 1 < nseg) x.y = zrow[j + 1];
+                if (j + 2 < nseg) x.z = zrow[j + 2];
+            }
+            z[4 * b] = x.x; z[4 * b + 1] = x.y; z[4 * b + 2] = x.z; z[4 * b + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int64_t j = j0 + 64 * e + lane;
+            z[e] = j < nseg ? zrow[j] : 1e30f;
+        }
+    }
+    bool any = false;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) any |= z[e] * z[e] < limit;
+    if (!__any(any)) return;
+
+#pragma unroll 1
+    for (int e = 0; e < 16; ++e) {
+        const int64_t j = VEC ? j0 + 256 * (e >> 2) + 4 * lane + (e & 3) : j0 + 64 * e + lane;
+        float ze = z[0];
+#pragma unroll
+        for (int t = 1; t < 16; ++t) ze = e == t ? z[t] : ze;
+        bool redo = j < nseg && ze * ze < limit;
+        if (redo && ze == 0.f) {
             // the word itself in the histogram?  (rows are sorted)
             int64_t lo = rp[j], hi = rp[j + 1];
             while (lo < hi) {
@@ -277,7 +308,7 @@ __global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, 
         while (todo) {
             const int l = __builtin_ctzll(todo);
             todo &= todo - 1;
-            const int64_t jj = j - lane + l;
+            const int64_t jj = __builtin_amdgcn_readlane((int)(j - j0), l) + j0;
             const int64_t a = rp[jj], b = rp[jj + 1];
             float best = 3.0e38f;
             for (int64_t t = a; t < b; ++t) {
@@ -439,11 +470,14 @@ hipError_t launch_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, co
                              int64_t ldz, hipStream_t s)
 {
     if (nvoc <= 0 || nseg <= 0) return hipSuccess;
-    const int64_t strips = (nseg + 64 * kRedoBlocks - 1) / (64 * kRedoBlocks);
+    const int64_t strips = (nseg + kRedoCols - 1) / kRedoCols;
     const int64_t grid = (nvoc * strips + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (bf16) k_redo_close<true><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, strips);
-    else k_redo_close<false><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, strips);
+    const bool vec = (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0);
+#define REDO(B, V) k_redo_close<B, V><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, normE, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, strips)
+    if (bf16) { if (vec) REDO(true, true); else REDO(true, false); }
+    else { if (vec) REDO(false, true); else REDO(false, false); }
+#undef REDO
     return hipGetLastError();
 }
 

@@ -59,12 +59,30 @@ __global__ __launch_bounds__(256) void k_table_redo_close(const void* __restrict
     const int32_t w = list_db[p];
     const float limit = 0.25f * normE[w];
     float* row = W + p * ldw;
-    for (int blk = 0; blk < 16; ++blk) {
-        const int64_t c = (strip * 16 + blk) * 64 + lane;
-        if (c - lane >= vc) break;
-        const float x = c < vc ? row[c] : 1e30f;
+    // element e of this lane: column c0 + 256 * (e / 4) + 4 * lane + e % 4; table rows are 16-byte aligned and the
+    // number of columns is a multiple of 32, so a float4 is inside the row or wholly beyond it
+    const int64_t c0 = strip * 1024;
+    f32x4 x[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int64_t c = c0 + 256 * b + 4 * lane;
+        x[b] = c < vc ? *reinterpret_cast<const f32x4*>(row + c) : f32x4{1e30f, 1e30f, 1e30f, 1e30f};
+    }
+    bool any = false;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) any |= x[b][t] * x[b][t] < limit;
+    if (!__any(any)) return;
+
+#pragma unroll 1
+    for (int e = 0; e < 16; ++e) {
+        const int64_t c = c0 + 256 * (e >> 2) + 4 * lane + (e & 3);
+        float xe = x[0][0];
+#pragma unroll
+        for (int t = 1; t < 16; ++t) xe = e == t ? x[t >> 2][t & 3] : xe;
         const int32_t cw = c < vc ? col_word[c] : w;
-        uint64_t todo = __ballot(x * x < limit && cw != w);
+        uint64_t todo = __ballot(xe * xe < limit && cw != w);
         while (todo) {
             const int l = __builtin_ctzll(todo);
             todo &= todo - 1;

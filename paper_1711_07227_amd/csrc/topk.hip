@@ -134,6 +134,65 @@ __global__ __launch_bounds__(64) void k_topk_merge(const float* __restrict__ par
     }
 }
 
+// Running top-k over blocks of database rows: one thread per query merges the list so far (row indices absolute,
+// unfilled slots FLT_MAX / INT_MAX) with the list of a block (row indices relative to row0) into `out`.
+__global__ void k_topk_merge2(const float* __restrict__ a_d, const int32_t* __restrict__ a_i, int have_a,
+                              const float* __restrict__ b_d, const int32_t* __restrict__ b_i, int32_t row0, int64_t q,
+                              int k, float* __restrict__ out_d, int32_t* __restrict__ out_i)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= q) return;
+    const float* ad = a_d + j * k;
+    const int32_t* ai = a_i + j * k;
+    const float* bd = b_d + j * k;
+    const int32_t* bi = b_i + j * k;
+    int ha = 0, hb = 0;
+    for (int r = 0; r < k; ++r) {
+        float da = FLT_MAX, db = FLT_MAX;
+        int32_t ia = INT_MAX, ib = INT_MAX;
+        if (have_a && ha < k) { da = ad[ha]; ia = ai[ha]; }
+        if (hb < k) { db = bd[hb]; ib = bi[hb]; if (ib != INT_MAX) ib += row0; }
+        const bool take_a = before(da, ia, db, ib) || (da == db && ia == ib);
+        out_d[j * k + r] = take_a ? da : db;
+        out_i[j * k + r] = take_a ? ia : ib;
+        if (take_a) ++ha; else ++hb;
+    }
+}
+
+// Column sums of a block, in fp64: part[split][j] = sum over the rows of the split of tile[r][j] ...
+constexpr int kSumSplits = 64;
+__global__ __launch_bounds__(256) void k_col_sums_part(const float* __restrict__ tile, int64_t rows, int64_t q, int64_t ldt,
+                                                       double* __restrict__ part)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t j = (int64_t)blockIdx.x * 64 + lane;
+    const int split = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int64_t per = (rows + kSumSplits - 1) / kSumSplits;
+    const int64_t r0 = split * per, r1 = r0 + per < rows ? r0 + per : rows;
+    if (j >= q) return;
+    double acc = 0.0;
+    int64_t r = r0;
+    for (; r + 3 < r1; r += 4) {
+        const float x0 = tile[r * ldt + j], x1 = tile[(r + 1) * ldt + j], x2 = tile[(r + 2) * ldt + j], x3 = tile[(r + 3) * ldt + j];
+        acc += (double)x0;
+        acc += (double)x1;
+        acc += (double)x2;
+        acc += (double)x3;
+    }
+    for (; r < r1; ++r) acc += (double)tile[r * ldt + j];
+    part[(int64_t)split * q + j] = acc;
+}
+
+// ... and sums[j] (+)= the splits' sums in split order: the total does not depend on timing.
+__global__ void k_col_sums_add(const double* __restrict__ part, int64_t q, int first, double* __restrict__ sums)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= q) return;
+    double acc = first ? 0.0 : sums[j];
+    for (int s = 0; s < kSumSplits; ++s) acc += part[(int64_t)s * q + j];
+    sums[j] = acc;
+}
+
 // Scratch of the entry point that allocates nothing: the partial lists live in this array instead of a workspace.
 // Every device the library runs on holds its own copy at its own address; host code uses the address obtained by
 // topk_static_init, never the array's name.
@@ -159,6 +218,25 @@ hipError_t topk_static_init(int device)
 }
 
 void* topk_static_ptr(int device) { return device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr; }
+
+hipError_t launch_topk_merge2(const float* a_d, const int32_t* a_i, bool have_a, const float* b_d, const int32_t* b_i,
+                              int64_t row0, int64_t q, int k, float* out_d, int32_t* out_i, hipStream_t s)
+{
+    if (q <= 0) return hipSuccess;
+    k_topk_merge2<<<(unsigned)((q + 63) / 64), 64, 0, s>>>(a_d, a_i, have_a ? 1 : 0, b_d, b_i, (int32_t)row0, q, k, out_d, out_i);
+    return hipGetLastError();
+}
+
+size_t col_sums_bytes(int64_t q) { return (size_t)kSumSplits * (size_t)q * 8 + 256; }
+
+hipError_t launch_col_sums(const float* tile, int64_t rows, int64_t q, int64_t ldt, double* part, bool first, double* sums,
+                           hipStream_t s)
+{
+    if (q <= 0 || rows <= 0) return hipSuccess;
+    k_col_sums_part<<<dim3((unsigned)((q + 63) / 64), kSumSplits / 4), 256, 0, s>>>(tile, rows, q, ldt, part);
+    k_col_sums_add<<<(unsigned)((q + 255) / 256), 256, 0, s>>>(part, q, first ? 1 : 0, sums);
+    return hipGetLastError();
+}
 
 size_t topk_bytes(int64_t n, int64_t q, int k)
 {

@@ -1,0 +1,136 @@
+"""The bound reduced on the device (lcrwmd_rwmd_reduce / lcrwmd_rwmd_topk): running top-k and column sums over blocks
+of database rows, never forming D; and the automatic choice between the per-entry and the table form.  Everything is
+checked against the CPU oracle's full matrix: top-k by (distance, row) with ties, column sums in fp64."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1711_07227_amd import binding, synth
+from helpers import assert_close, run_rwmd, upload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def ctx():
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+def problem(v, m, n, q, h_lo, h_hi, seed, s=1.1):
+    return {"E": synth.embeddings(v, m, seed), "db": synth.corpus(n, v, h_lo, h_hi, s, seed + 1),
+            "queries": synth.corpus(q, v, h_lo, h_hi, s, seed + 2)}
+
+
+def reduce_on_device(ctx, p, k, sums=True, ws_bytes=None):
+    E, db, qs = upload(p)
+    n, q = db.rows, qs.rows
+    if ws_bytes is None:
+        ws_bytes = ctx.workspace_bytes(E.shape[0], E.shape[1], n, db.nnz, q, qs.nnz, binding.F32, k)
+    ws = binding.alloc_workspace(ws_bytes)
+    R_idx = torch.full((q, max(k, 1)), -5, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((q, max(k, 1)), -5.0, dtype=torch.float32, device="cuda")
+    col = torch.full((q,), -5.0, dtype=torch.float64, device="cuda") if sums else None
+    ctx.rwmd_reduce(qs, db, E, k, R_idx if k else None, R_dist if k else None, col, ws)
+    torch.cuda.synchronize()
+    return R_idx.cpu().numpy(), R_dist.cpu().numpy(), (col.cpu().numpy() if sums else None)
+
+
+def check_against_full_matrix(ctx, p, k, gi, gd, gs, what):
+    """Distances against the oracle; rows against the device's own D (same arithmetic, so exact, ties included)."""
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    if k:
+        _, rdist = oracle.topk(ref, k)
+        assert_close(gd, rdist, what=f"{what}: top-k distances")
+        D = run_rwmd(ctx, *upload(p))
+        order = np.lexsort((np.broadcast_to(np.arange(D.shape[0])[:, None], D.shape), D), axis=0)[:k].T
+        assert np.array_equal(gi, order.astype(np.int32)), f"{what}: rows"
+        assert np.array_equal(gd, np.take_along_axis(D.T, order, axis=1)), f"{what}: distances are those of the rows"
+    if gs is not None:
+        assert_close(gs, ref.sum(axis=0), rtol=1e-5, what=f"{what}: column sums")
+
+
+@pytest.mark.parametrize("dedup", [0, 1])
+@pytest.mark.parametrize("k", [1, 16, 64])
+def test_reduce_over_many_blocks_of_database_rows(ctx, dedup, k):
+    """Blocks of 100 rows (the last one of 47, shorter than k = 64), queries in two forward batches."""
+    print(f"reduce: dedup={dedup} k={k}", flush=True)
+    p = problem(v=3000, m=300, n=747, q=37, h_lo=1, h_hi=90, seed=21)
+    ctx.set_options(dedup=dedup, max_db_batch=100, max_query_batch=20)
+    gi, gd, gs = reduce_on_device(ctx, p, k)
+    assert ctx.forms_ran() == (2 if dedup else 1)
+    ctx.set_options(dedup=dedup)
+    check_against_full_matrix(ctx, p, k, gi, gd, gs, f"dedup={dedup} k={k}")
+
+
+def test_reduce_sums_only_and_topk_only(ctx, tiny):
+    ref = oracle.rwmd_table(tiny["E"], tiny["db"], tiny["queries"])
+    _, _, gs = reduce_on_device(ctx, tiny, 0)
+    assert_close(gs, ref.sum(axis=0), rtol=1e-5, what="sums only")
+    gi, gd, none = reduce_on_device(ctx, tiny, 5, sums=False)
+    assert none is None
+    ridx, rdist = oracle.topk(ref, 5)
+    assert_close(gd, rdist, what="top-k only")
+    assert np.array_equal(gi, ridx.astype(np.int32))          # this seed has no near ties among the first five
+    E, db, qs = upload(tiny)
+    ws = binding.alloc_workspace(1 << 20)
+    with pytest.raises(binding.LcrwmdError) as e:
+        ctx.rwmd_reduce(qs, db, E, 0, None, None, None, ws)
+    assert e.value.status == binding.EINVAL
+
+
+def test_reduce_with_ties_between_rows(ctx):
+    """Duplicated database rows give equal distances: the smaller row index must come first, also across blocks."""
+    base = problem(v=800, m=300, n=120, q=9, h_lo=2, h_hi=30, seed=5)
+    ptr, col, val = base["db"]
+    rows = np.concatenate([np.arange(120), np.arange(120)[::-1], np.arange(60)])      # every row two or three times
+    p = {"E": base["E"], "db": synth.csr_rows(ptr, col, val, rows), "queries": base["queries"]}
+    ctx.set_options(max_db_batch=64)
+    gi, gd, gs = reduce_on_device(ctx, p, 16)
+    ctx.set_options()
+    ref = oracle.rwmd_table(p["E"], p["db"], p["queries"])
+    ridx, rdist = oracle.topk(ref, 16)
+    assert_close(gd, rdist, what="ties: distances")
+    dup = rdist[:, 1:] == rdist[:, :-1]
+    assert dup.any()
+    assert np.array_equal(gi, ridx.astype(np.int32))
+
+
+def test_reduce_in_a_small_workspace_runs_in_ranges_of_queries(ctx):
+    p = problem(v=3000, m=300, n=500, q=64, h_lo=5, h_hi=60, seed=31)
+    full = ctx.workspace_bytes(3000, 300, 500, len(p["db"][1]), 64, len(p["queries"][1]), binding.F32, 8)
+    gi, gd, gs = reduce_on_device(ctx, p, 8)
+    # leave room for the fixed part, the minima of about ten queries and one small block
+    small = 3000 * 304 * 4 + 3000 * 40 + len(p["db"][1]) * 8 + 3000 * 16 * 4 + 600_000
+    assert small < full
+    gi2, gd2, gs2 = reduce_on_device(ctx, p, 8, ws_bytes=small)
+    assert np.array_equal(gi, gi2) and np.array_equal(gd, gd2)
+    assert_close(gs2, gs, rtol=1e-12, what="sums, ranges of queries")
+    E, db, qs = upload(p)
+    D = torch.empty((500, 64), dtype=torch.float32, device="cuda")
+    ctx.rwmd(qs, db, E, D, binding.alloc_workspace(small))
+    ctx.rwmd(qs, db, E, D2 := torch.empty_like(D), binding.alloc_workspace(full))
+    torch.cuda.synchronize()
+    assert torch.equal(D, D2)
+
+
+def test_automatic_choice_of_form(ctx):
+    """Long documents against few query words favour the table; many short queries against short documents in bf16
+    the per-entry form.  Either way the result is the oracle's."""
+    p = problem(v=20000, m=300, n=3000, q=40, h_lo=60, h_hi=120, seed=41)
+    ctx.set_options(dedup=2)
+    got = run_rwmd(ctx, *upload(p))
+    assert ctx.forms_ran() == 2
+    assert_close(got, oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="auto form: table")
+    gi, gd, gs = reduce_on_device(ctx, p, 4)
+    assert ctx.forms_ran() == 2
+    check_against_full_matrix(ctx, p, 4, gi, gd, gs, "auto form, reduced")
+
+    v = 20000
+    E = synth.embeddings(v, 300, 51, bf16_valued=True)
+    p = {"E": E, "db": synth.corpus(2000, v, 3, 6, 1.1, 52), "queries": synth.corpus(1500, v, 3, 6, 1.1, 53)}
+    got = run_rwmd(ctx, *upload(p, dtype=torch.bfloat16), emb_dtype=binding.BF16)
+    assert ctx.forms_ran() == 1
+    assert_close(got, oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="auto form: per entry")
