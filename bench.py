@@ -260,6 +260,38 @@ class Job:
             extra["column_sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(s - col.sum(axis=0)) / col.sum(axis=0)))
         return err, cpu, extra
 
+    def quadratic_leg(self, qn):
+        """The quadratic-complexity method (Sec. III / Sec. V) against the linear-complexity one on the first qn queries."""
+        torch, b = self.torch, self.binding
+        sub = b.Csr.from_numpy(self.synth.csr_rows(*self.prob["queries"], np.arange(qn)), self.v)
+        saved = self.ctx.get_options()
+        self.ctx.set_options(compute=saved["compute"], dedup=0)
+        Dq = torch.empty((self.n, qn), dtype=torch.float32, device="cuda")
+        Dl = torch.empty_like(Dq)
+        wq = b.alloc_workspace(self.ctx.rwmd_quadratic_workspace_bytes(self.v, self.m, self.n, self.db.nnz, qn, sub.nnz, self.emb_dtype))
+        wl = b.alloc_workspace(self.ctx.workspace_bytes(self.v, self.m, self.n, self.db.nnz, qn, sub.nnz, self.emb_dtype))
+        times = {}
+        for name, fn in (("linear", lambda: self.ctx.rwmd(sub, self.db, self.E, Dl, wl)),
+                         ("quadratic", lambda: self.ctx.rwmd_quadratic(sub, self.db, self.E, Dq, wq))):
+            torch.cuda.synchronize()
+            self.ctx.profile_begin()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            times[name] = time.perf_counter() - t
+            times[name + "_prof"] = self.ctx.profile_end()
+        self.ctx.set_options(**saved)
+        pq = times["quadratic_prof"]
+        progress(f"{self.cfg.name}: quadratic method on {qn} queries, {1e3 * times['quadratic']:.0f} ms against "
+                 f"{1e3 * times['linear']:.0f} ms")
+        return {"queries": qn, "quadratic_ms": 1e3 * times["quadratic"], "linear_complexity_ms": 1e3 * times["linear"],
+                "speedup_of_linear_complexity": times["quadratic"] / times["linear"],
+                "mean_histogram_size": self.db.nnz / self.n,
+                "quadratic_first_phase_TFLOPs": pq["phase1_flops"] / max(pq["phase1_ms"], 1e-9) / 1e9,
+                "quadratic_flops": pq["phase1_flops"], "linear_complexity_flops": times["linear_prof"]["phase1_flops"],
+                "note": "the quadratic method evaluates C = T1 o T2 twice (once per kind of minimum); both in the per-entry form",
+                "max_abs_diff": float((Dq - Dl).abs().max())}
+
     def workload_string(self):
         c = self.cfg
         return f"{c.name}: v={self.v} m={self.m} n={self.n} q={self.q} h={c.h_lo}-{c.h_hi} zipf={c.zipf_s}"
@@ -321,6 +353,8 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False):
             job.options(dedup=2)
             sec_a, prof_a = job.timed(max(1, steps), 1)
             out["auto_form"] = job.report(max(1, steps), sec_a, prof_a)
+            job.options()
+            out["quadratic_method"] = job.quadratic_leg(16)
         return out
     finally:
         job.close()
@@ -402,6 +436,10 @@ def main():
         job.D.copy_(D_ref)
         del D_ref
         job.options()
+        try:
+            variants["quadratic_method"] = job.quadratic_leg(min(job.q, 200))
+        except (RuntimeError, job.binding.LcrwmdError) as e:
+            variants["quadratic_method"] = {"skipped": str(e)[:200]}
 
     # Exact WMD behind the bound (reported, never `value`): the k nearest by WMD with the RWMD cut-off, on the first
     # 20,000 database rows and 64 queries of the same workload.

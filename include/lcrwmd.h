@@ -190,6 +190,23 @@ lcrwmd_status lcrwmd_rwmd(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrw
                           void* hip_stream);
 
 /*
+ * The same bound by the quadratic-complexity method the paper starts from (Sec. III "Solving the RWMD problem";
+ * Sec. V, first GPU mapping): for every pair, C = T1,i o T2,j, its row minima dotted with F1,i, its column minima
+ * dotted with F2,j, the larger of the two.  The T1,i of a block of database histograms are stacked into one matrix
+ * and multiplied with the stacked T2,j of all queries, as in Sec. V - but nothing is shared between histograms:
+ * a word is paired with a query (a database histogram) once per histogram it occurs in, 2 nnz(X1) nnz(X2) m flops
+ * per evaluation of all C.  C is evaluated twice, once per kind of minimum: the minima are taken inside the
+ * contraction along one dimension, and C itself (nnz(X1) x nnz(X2) values) is never stored.  Same D as lcrwmd_rwmd
+ * up to fp32 summation order; it exists as the comparison the paper draws (Sec. VI: LC-RWMD is faster by about the
+ * average histogram size).  Arithmetic follows the compute option.  Synchronises only to fetch row pointers.
+ */
+lcrwmd_status lcrwmd_rwmd_quadratic_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db,
+                                                    int64_t q, int64_t nnz_q, lcrwmd_dtype emb_dtype, size_t* out_bytes);
+lcrwmd_status lcrwmd_rwmd_quadratic(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                                    const lcrwmd_emb* E, float* D, int64_t ldd, void* ws, size_t ws_bytes,
+                                    void* hip_stream);
+
+/*
  * Top-k on the same bound (Sec. III: the k smallest distances of a query and the positions of
  * the respective database histograms, stored in an n2 x k matrix R): for each query j,
  * R_idx[j * k + r] / R_dist[j * k + r], r < k, are the database rows with the r-th smallest

@@ -28,6 +28,7 @@ EXPORTS = (
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
     "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc", "lcrwmd_rwmd_reduce", "lcrwmd_forms_ran",
+    "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes",
 )
 
 
@@ -91,6 +92,8 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_rwmd_reduce.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
         lib.lcrwmd_forms_ran.argtypes = [vp]
+        lib.lcrwmd_rwmd_quadratic.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
+        lib.lcrwmd_rwmd_quadratic_workspace_bytes.argtypes = [vp, i64, i64, i64, i64, i64, i64, i32, P(sz)]
         lib.lcrwmd_topk.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_topk_noalloc.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp]
         lib.lcrwmd_wcd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
@@ -253,6 +256,18 @@ class Context:
         self._check(self._lib.lcrwmd_rwmd_reduce(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es), k,
                                                  R_idx.data_ptr() if k > 0 else None, R_dist.data_ptr() if k > 0 else None,
                                                  col_sum.data_ptr() if col_sum is not None else None, p, nbytes, _stream()))
+
+    def rwmd_quadratic_workspace_bytes(self, v, m, n, nnz_db, q, nnz_q, emb_dtype=F32) -> int:
+        out = ctypes.c_size_t()
+        self._check(self._lib.lcrwmd_rwmd_quadratic_workspace_bytes(self._h, v, m, n, nnz_db, q, nnz_q, emb_dtype, ctypes.byref(out)))
+        return int(out.value)
+
+    def rwmd_quadratic(self, queries: Csr, database: Csr, E: torch.Tensor, D: torch.Tensor, ws: torch.Tensor):
+        assert D.is_cuda and D.dtype == torch.float32 and D.stride(1) == 1
+        es, qs, ds = _emb_struct(E), queries.struct(), database.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_rwmd_quadratic(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es),
+                                                    D.data_ptr(), D.stride(0), p, nbytes, _stream()))
 
     def forms_ran(self) -> int:
         """Bit 0: the per-entry form ran in the last bound call; bit 1: the table form."""

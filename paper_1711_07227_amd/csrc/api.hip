@@ -258,8 +258,9 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
         else HIP_TRY(launch_phase1_f32(a, tp, s));
     }
     // a word that occurs in the histogram is at distance exactly 0 from it; the norm expansion
-    // only gets there up to cancellation error
-    HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
+    // only gets there up to cancellation error.  (A vocabulary that lists words more than once - the stacked
+    // histograms of the quadratic method - has no word -> row map: the pass below finds those entries itself.)
+    if (!voc_rows || zero_map) HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
     // ... and loses relative accuracy where two different words lie close together: those entries are redone
     HIP_TRY(launch_redo_close(ep.xdata, ep.xbf16, ep.xld, ep.xm, ep.normE, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, s));
     return LCRWMD_OK;
@@ -991,6 +992,107 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
 }
 
 int lcrwmd_forms_ran(const lcrwmd_ctx* ctx) { return ctx ? ctx->forms_ran : 0; }
+
+// Quadratic-complexity RWMD (Sec. III "Solving the RWMD problem", Sec. V first GPU mapping): every database
+// histogram against every query through its own T matrices, nothing shared between histograms.
+namespace {
+size_t quadratic_block_bytes(int64_t nb, int64_t nnz_b, int64_t q, int64_t nnz_q)
+{
+    const size_t a = token_plan_bytes(q, nnz_q) + (size_t)nnz_b * (size_t)round_up(q, 4) * 4 + 512;      // row minima
+    const size_t b = token_plan_bytes(nb, nnz_b) + (size_t)nnz_q * (size_t)round_up(nb, 4) * 4 + 512;    // column minima
+    return a > b ? a : b;
+}
+}  // namespace
+
+lcrwmd_status lcrwmd_rwmd_quadratic_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db,
+                                                    int64_t q, int64_t nnz_q, lcrwmd_dtype emb_dtype, size_t* out_bytes)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    if (!out_bytes) return fail(ctx, LCRWMD_EINVAL, "out_bytes is NULL");
+    if (v <= 0 || m <= 0 || n < 0 || nnz_db < 0 || q < 0 || nnz_q < 0) return fail(ctx, LCRWMD_EINVAL, "negative size");
+    const bool asks_bf16 = emb_dtype == LCRWMD_BF16 || ctx->opt.compute == LCRWMD_BF16;
+    const int mode = m > 300 ? 0 : asks_bf16 ? 1 : ctx->opt.compute == LCRWMD_BF16X3 ? 2 : 0;
+    const bool padded = mode == 0 && m <= kPadM && m >= kPadFromM;
+    // blocks of database rows: about 2^20 stored entries each, never more rows than the swapped pass of lcrwmd_rwmd takes
+    int64_t nb = n < 4096 ? (n > 0 ? n : 1) : 4096;
+    const int64_t nnz_b = n > 0 ? (nnz_db / n + 1) * nb * 2 : 1;
+    *out_bytes = emb_prep_bytes(v, (int32_t)m, mode, padded, m > 300 && asks_bf16) + ((size_t)(nnz_b > nnz_q ? nnz_b : nnz_q) * 4 + 256) +
+                 quadratic_block_bytes(nb, nnz_b < nnz_db ? nnz_b : nnz_db, q > 0 ? q : 1, nnz_q) + 8192;
+    return LCRWMD_OK;
+}
+
+lcrwmd_status lcrwmd_rwmd_quadratic(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const lcrwmd_csr* database,
+                                    const lcrwmd_emb* E, float* D, int64_t ldd, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, queries, database, E));
+    const int64_t n = database->rows, q = queries->rows, nnz_q = queries->nnz;
+    if (q == 0 || n == 0) return LCRWMD_OK;
+    if (!D) return fail(ctx, LCRWMD_EINVAL, "D is NULL");
+    if (ldd < q) return fail(ctx, LCRWMD_EINVAL, "ldd < queries.rows");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HostPtr rq, rdb;
+    ST_TRY(fetch_rows_and_validate(ctx, queries, database, rq, rdb, ws, ws_bytes, s));
+    if (nnz_q + 7 * q >= kMaxTokens) return fail(ctx, LCRWMD_EUNSUPPORTED, "too many query words for one pass; split the queries");
+    const int32_t m = (int32_t)E->m;
+    Bump b(ws, ws_bytes);
+    EmbPrep ep;
+    ST_TRY(prepare_emb(ctx, E, b, ep, s));
+    const int grp = plan_group(ep), chunk_tiles = plan_chunk_tiles(ep);
+
+    // Blocks of database rows whose two matrices of minima fit the workspace.
+    const size_t fixed_off = (b.used + 255) & ~(size_t)255;
+    int64_t nb = n < 4096 ? n : 4096;
+    int64_t iota_len = 0;
+    for (;;) {
+        const int64_t tok = max_tokens_per_batch(rdb.p, n, nb);
+        iota_len = tok > nnz_q ? tok : nnz_q;
+        const size_t need = fixed_off + (size_t)iota_len * 4 + 512 + quadratic_block_bytes(nb, tok, q, nnz_q) + 1024;
+        if (tok + 7 * nb < kMaxTokens && need <= ws_bytes) break;
+        if (nb == 1) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for one database row against all queries");
+        nb = (nb + 1) / 2;
+    }
+    int32_t* iota = b.take_n<int32_t>((size_t)iota_len);          // column ids of a stacked T matrix's rows: 0, 1, 2, ...
+    if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: index array does not fit");
+    HIP_TRY(launch_iota_i32(iota, iota_len, s));
+    const size_t region_off = (b.used + 255) & ~(size_t)255;
+    const size_t region = ws_bytes - region_off;
+
+    for (int64_t i0 = 0; i0 < n; i0 += nb) {
+        const int64_t i1 = i0 + nb < n ? i0 + nb : n;
+        const int64_t t0 = rdb.p[i0], nnz_b = rdb.p[i1] - t0;
+        float* Db = D + i0 * ldd;
+        {   // C = T1 o T2,j for all j at once (Sec. III): row minima of every stacked database word against each query,
+            // then the dot products with the database weights: D12 = F1 . Z1
+            Bump bb((char*)ws + region_off, region);
+            TokenPlan tp;
+            carve_token_plan(bb, tp, q, nnz_q, plan_tiles((nnz_b + kTileVocab - 1) / kTileVocab, ep.bf16), padded_tokens(rq.p, 0, q, grp), grp,
+                             chunk_tiles);
+            const int64_t ldz = round_up(q, 4);
+            float* Z1 = bb.take_n<float>((size_t)nnz_b * ldz);
+            if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: row minima do not fit");
+            ST_TRY(run_phase1(ctx, ep, m, database->col_idx + t0, nnz_b, 1, nullptr, queries->row_ptr, queries->col_idx, nnz_q, tp, Z1,
+                              ldz, s));
+            // rows of the block in their stacked order: entry p of the block reads row p - t0 of Z1
+            ST_TRY(run_spmm(ctx, database->row_ptr + i0, iota - t0, database->val, i1 - i0, nnz_b, nnz_b, Z1, ldz, q, Db, ldd, 0, s));
+        }
+        {   // column minima: every query word against each database histogram of the block, D21 = F2 . Z2, and the maximum
+            Bump bb((char*)ws + region_off, region);
+            TokenPlan tp;
+            carve_token_plan(bb, tp, i1 - i0, nnz_b, plan_tiles((nnz_q + kTileVocab - 1) / kTileVocab, ep.bf16),
+                             padded_tokens(rdb.p, i0, i1, grp), grp, chunk_tiles);
+            const int64_t ldz = round_up(i1 - i0, 4);
+            float* Z2 = bb.take_n<float>((size_t)nnz_q * ldz);
+            if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: column minima do not fit");
+            ST_TRY(run_phase1(ctx, ep, m, queries->col_idx, nnz_q, 1, nullptr, database->row_ptr + i0, database->col_idx, nnz_b, tp, Z2,
+                              ldz, s, /*swapped=*/true));
+            ST_TRY(run_spmm(ctx, queries->row_ptr, iota, queries->val, q, nnz_q, nnz_q, Z2, ldz, i1 - i0, Db, ldd, 2, s));
+        }
+    }
+    return LCRWMD_OK;
+}
 
 // ------------------------------------------------------------------------------------------------ exact WMD, WCD, pruning
 

@@ -102,6 +102,7 @@ struct Phase1Args {
 
 // prep.hip
 hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s);
+hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s);      // p[i] = i
 hipError_t launch_row_norms_f32(const float* E, int64_t v, int32_t m, int64_t ld, float* normE, hipStream_t s);
 // fp32 copy (pitch m) of E's values as bf16 numbers: bf16 storage widened, fp32 storage rounded to nearest even
 hipError_t launch_widen_bf16(const void* E, lcrwmd_dtype dtype, int64_t v, int32_t m, int64_t ld, float* out, hipStream_t s);

@@ -68,6 +68,13 @@ __global__ void k_widen_bf16(const void* __restrict__ E, int is_bf16, int64_t v,
     }
 }
 
+__global__ void k_iota_i32(int32_t* p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = (int32_t)i;
+}
+
 __global__ void k_mark_words(const int32_t* __restrict__ col_idx, int64_t nnz, int32_t* __restrict__ flags)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -229,8 +236,8 @@ __global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict_
 // to d^2 itself.  (An entry above that threshold came from a d^2 >= (|x|^2 + |y|^2) / 8 or so - two vectors whose
 // norms differ by more than a factor 1.5 are further apart than half the shorter one - where the expansion is good
 // to 1e-5.)  The minimum of the exact distances is taken over all words of the histogram: the expansion's ranking of
-// near neighbours is not trusted either.  Entries that are 0 because the word itself occurs in the histogram
-// (k_zero_matches ran before) are recognised by a binary search in the sorted row and left alone.
+// near neighbours is not trusted either.  An entry whose word itself occurs in the histogram is recognised by a
+// binary search in the sorted row and set to exactly 0 (k_zero_matches, where it ran before, has done so already).
 //
 // One wavefront per row of Z and strip of columns: 64 entries are tested at a time (one coalesced load); the flagged
 // ones are then redone one after the other by the whole wavefront, lanes along the embedding dimension.  On embeddings
@@ -295,14 +302,17 @@ __global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, 
 #pragma unroll
         for (int t = 1; t < 16; ++t) ze = e == t ? z[t] : ze;
         bool redo = j < nseg && ze * ze < limit;
-        if (redo && ze == 0.f) {
-            // the word itself in the histogram?  (rows are sorted)
+        if (redo) {
+            // the word itself in the histogram?  (rows are sorted)  Then the distance is exactly 0.
             int64_t lo = rp[j], hi = rp[j + 1];
             while (lo < hi) {
                 const int64_t mid = lo + ((hi - lo) >> 1);
                 if (ci[mid] < w) lo = mid + 1; else hi = mid;
             }
-            if (lo < rp[j + 1] && ci[lo] == w) redo = false;
+            if (lo < rp[j + 1] && ci[lo] == w) {
+                if (ze != 0.f) zrow[j] = 0.f;
+                redo = false;
+            }
         }
         uint64_t todo = __ballot(redo);
         while (todo) {
@@ -361,6 +371,13 @@ hipError_t launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     k_fill_i32<<<grid_for(n, 256, 8192), 256, 0, s>>>(p, n, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_iota_i32(int32_t* p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    k_iota_i32<<<grid_for(n, 256, 8192), 256, 0, s>>>(p, n);
     return hipGetLastError();
 }
 
