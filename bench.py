@@ -384,6 +384,9 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="instead of a workload: bare MFMA loops (lcrwmd_probe_mfma) in fp32 and bf16, on zero and on random "
+                         "operands, from registers and with the A operand from LDS; prints their rates and shader clocks")
     ap.add_argument("--cpu-queries", type=int, default=48, help="queries in the CPU oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -393,6 +396,21 @@ def main():
     import torch
     torch.cuda.set_device(0)
     with_cpu = not args.no_cpu_baseline
+    if args.mfma_probe:
+        from paper_1711_07227_amd import binding
+        ctx = binding.Context(0)
+        rows = []
+        for dtype, name, peak in ((binding.BF16, "bf16", PEAK_BF16_MFMA_TFLOPS), (binding.F32, "f32", PEAK_F32_MFMA_TFLOPS)):
+            for random_data in (False, True):
+                for lds in (False, True):
+                    ctx.probe_mfma(dtype, random_data, lds, 0.2)                       # warm-up, also of the clock
+                    tf, mhz = ctx.probe_mfma(dtype, random_data, lds, 1.0)
+                    rows.append({"mfma": name, "operands": "random" if random_data else "zero",
+                                 "a_operand": "LDS, one 16-byte read per two MFMAs" if lds else "registers",
+                                 "TFLOPs": tf, "of_peak": tf / peak, "shader_MHz": mhz})
+                    progress(f"probe {name} {'random' if random_data else 'zero'} {'lds' if lds else 'reg'}: {tf:.1f} TFLOP/s at {mhz:.0f} MHz")
+        print(json.dumps({"mfma_probe": rows, "peaks_TFLOPs": {"bf16": PEAK_BF16_MFMA_TFLOPS, "f32": PEAK_F32_MFMA_TFLOPS}}))
+        return
     main_is_default = args.workload == "medium" and args.compute == "f32" and args.dedup == 0 and not args.reduce
 
     job = Job(args.workload, args.compute, args.permute_vocab, batches=args.steps + args.warmup)

@@ -280,6 +280,18 @@ typedef struct {
 lcrwmd_status lcrwmd_profile_begin(lcrwmd_ctx* ctx);
 lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
 
+/*
+ * Diagnostic for benchmarks (not part of the method): the rate the matrix cores sustain for the first phase's MFMA
+ * shape on this device - v_mfma_f32_32x32x16_bf16 (LCRWMD_BF16) or v_mfma_f32_32x32x2_f32 (LCRWMD_F32) - in a loop
+ * of nothing but MFMAs running for about `seconds` on every CU.  random_data: operands are random values of
+ * magnitude 0.5 .. 1 (1) or all zero (0): under sustained load on data that toggles, the part lowers its shader
+ * clock.  a_from_lds: the A operand is re-read from LDS once per two MFMAs, as the first-phase kernel does (1), or
+ * both operands stay in registers (0).  Outputs (HOST): achieved TFLOP/s and the average shader clock in MHz.
+ * Workspace: 1 MiB is enough.  Synchronises the stream.
+ */
+lcrwmd_status lcrwmd_probe_mfma(lcrwmd_ctx* ctx, lcrwmd_dtype dtype, int random_data, int a_from_lds, double seconds,
+                                void* ws, size_t ws_bytes, double* tflops, double* shader_mhz, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Exact WMD behind the RWMD bound (Sec. II, Sec. III).  These calls take fp32 or bf16 E of any m and
  * pitch.  Cost matrices are fp32: |a|^2 + |b|^2 - 2 a.b on the matrix cores where the two words lie

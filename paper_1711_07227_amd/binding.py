@@ -28,7 +28,7 @@ EXPORTS = (
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
     "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc", "lcrwmd_rwmd_reduce", "lcrwmd_forms_ran",
-    "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes",
+    "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes", "lcrwmd_probe_mfma",
 )
 
 
@@ -92,6 +92,7 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_rwmd_reduce.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
         lib.lcrwmd_forms_ran.argtypes = [vp]
+        lib.lcrwmd_probe_mfma.argtypes = [vp, i32, i32, i32, ctypes.c_double, vp, sz, P(ctypes.c_double), P(ctypes.c_double), vp]
         lib.lcrwmd_rwmd_quadratic.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_rwmd_quadratic_workspace_bytes.argtypes = [vp, i64, i64, i64, i64, i64, i64, i32, P(sz)]
         lib.lcrwmd_topk.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]
@@ -268,6 +269,14 @@ class Context:
         p, nbytes = self._ws(ws)
         self._check(self._lib.lcrwmd_rwmd_quadratic(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es),
                                                     D.data_ptr(), D.stride(0), p, nbytes, _stream()))
+
+    def probe_mfma(self, dtype: int, random_data: bool, a_from_lds: bool, seconds: float = 0.5):
+        """(TFLOP/s, shader MHz) of a bare MFMA loop; see lcrwmd_probe_mfma."""
+        ws = alloc_workspace(1 << 20)
+        tf, mhz = ctypes.c_double(), ctypes.c_double()
+        self._check(self._lib.lcrwmd_probe_mfma(self._h, dtype, int(random_data), int(a_from_lds), seconds, ws.data_ptr(),
+                                                ws.numel(), ctypes.byref(tf), ctypes.byref(mhz), _stream()))
+        return tf.value, mhz.value
 
     def forms_ran(self) -> int:
         """Bit 0: the per-entry form ran in the last bound call; bit 1: the table form."""

@@ -268,14 +268,16 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
 
 // Second-phase launch with its algorithmic traffic: CSR arrays, `zrows` rows of Z, and the output once
 // (twice when it is read back for a maximum).
+// zrows: rows of Z; z_counted: whether this launch is the one that counts Z's bytes (a Z shared by the launches of
+// several blocks of rows is algorithmically read once)
 lcrwmd_status run_spmm(lcrwmd_ctx* ctx, const int64_t* rp, const int32_t* ci, const float* xv, int64_t rows,
                        int64_t nnz, int64_t zrows, const float* Z, int64_t ldz, int64_t ncols, float* D, int64_t ldd,
-                       int combine, hipStream_t s)
+                       int combine, hipStream_t s, bool z_counted = true)
 {
-    const double bytes = 8.0 * (double)nnz + 8.0 * (double)(rows + 1) + 4.0 * (double)ncols * (double)zrows +
+    const double bytes = 8.0 * (double)nnz + 8.0 * (double)(rows + 1) + (z_counted ? 4.0 * (double)ncols * (double)zrows : 0.0) +
                          (combine ? 8.0 : 4.0) * (double)ncols * (double)rows;
     ProfScope ps(ctx, s, 2, bytes, 4.0 * (double)nnz * (double)ncols);
-    HIP_TRY(launch_spmm(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, combine, s));
+    HIP_TRY(launch_spmm(rp, ci, xv, rows, Z, ldz, zrows, ncols, D, ldd, combine, s));
     return LCRWMD_OK;
 }
 
@@ -510,7 +512,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
                 const int64_t nnz_b = rdb[i1] - rdb[i0];
                 float* Db = sink ? tile : D + i0 * ldd;
                 const int64_t ldb = sink ? ldz : ldd;
-                ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, i0 == 0 ? ve : 0, Z, ldz, q, Db, ldb, 0, s));
+                ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == 0));
                 {   // swapped: one table row per stored database entry, the block read and written once
                     ProfScope ps(ctx, s, 4, 4.0 * (double)nnz_b * (double)vq + 8.0 * (double)(i1 - i0) * (double)q + 4.0 * (double)nnz_b);
                     HIP_TRY(launch_table_rev(W, ldw, vc, DB->row_ptr + i0, dbcol_pos, i1 - i0, boffs, bpos, bval, q, D2, ldz, Db, ldb, s));
@@ -571,7 +573,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: block of database rows does not fit");
         float* Db = sink ? tile : D + i0 * ldd;
         const int64_t ldb = sink ? ldz : ldd;
-        ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, i0 == 0 ? ve : 0, Z, ldz, q, Db, ldb, 0, s));
+        ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == 0));
         ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
                           DB->col_idx, nnz_b, tp, Zr, ldzr, s, /*swapped=*/true));
         // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
@@ -899,7 +901,8 @@ struct ReduceSink : TileSink {
     lcrwmd_status consume(int64_t i0, int64_t i1, const float* tile, int64_t ldt, hipStream_t s) override
     {
         if (k > 0) {
-            HIP_TRY(launch_topk(tile, i1 - i0, q, ldt, k, blk_i, blk_d, tk, tkb, s));       // slots a short block cannot fill: FLT_MAX
+            // slots a block cannot fill read FLT_MAX; values that the k rows of the list so far already beat are skipped
+            HIP_TRY(launch_topk(tile, i1 - i0, q, ldt, k, blk_i, blk_d, tk, tkb, s, any ? run_d[cur] : nullptr));
             HIP_TRY(launch_topk_merge2(run_d[cur], run_i[cur], any, blk_d, blk_i, i0, q, k, run_d[cur ^ 1], run_i[cur ^ 1], s));
             cur ^= 1;
         }
@@ -992,6 +995,43 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
 }
 
 int lcrwmd_forms_ran(const lcrwmd_ctx* ctx) { return ctx ? ctx->forms_ran : 0; }
+
+lcrwmd_status lcrwmd_probe_mfma(lcrwmd_ctx* ctx, lcrwmd_dtype dtype, int random_data, int a_from_lds, double seconds,
+                                void* ws, size_t ws_bytes, double* tflops, double* shader_mhz, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (dtype != LCRWMD_F32 && dtype != LCRWMD_BF16) return fail(ctx, LCRWMD_EINVAL, "dtype must be LCRWMD_F32 or LCRWMD_BF16");
+    if (!tflops || !shader_mhz) return fail(ctx, LCRWMD_EINVAL, "an output pointer is NULL");
+    if (!(seconds > 0.0) || seconds > 10.0) return fail(ctx, LCRWMD_EINVAL, "seconds must be in (0, 10]");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    if (ws_bytes < probe_bytes(ctx->num_cu)) return fail(ctx, LCRWMD_EWORKSPACE, "the probe needs %zu bytes", probe_bytes(ctx->num_cu));
+    HIP_TRY(hipSetDevice(ctx->device));
+    // iterations for about `seconds` at the spec-sheet rate (32 MFMAs of 8 / 16 passes per iteration and wavefront, two
+    // workgroups of four wavefronts per CU share the four matrix pipes of a CU)
+    const double clocks_per_iter = 32.0 * (dtype == LCRWMD_BF16 ? 32 : 64) * 2;
+    int iters = (int)(seconds * 2.4e9 / clocks_per_iter);
+    if (iters < 1000) iters = 1000;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(ctx, LCRWMD_EHIP, "hipEventCreate failed"); }
+    double flops = 0.0;
+    long long* clk = nullptr;
+    long long h[2] = {0, 1};
+    float ms = 0.f;
+    hipError_t e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch_probe_mfma(dtype == LCRWMD_BF16, random_data != 0, a_from_lds != 0, iters, ctx->num_cu, ws, &flops, &clk, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(ctx, LCRWMD_EHIP, "probe failed: %s", hipGetErrorString(e));
+    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    *shader_mhz = (double)h[0] / (double)(h[1] > 0 ? h[1] : 1) * 100.0;      // the wall-clock counter ticks at 100 MHz
+    return LCRWMD_OK;
+}
 
 // Quadratic-complexity RWMD (Sec. III "Solving the RWMD problem", Sec. V first GPU mapping): every database
 // histogram against every query through its own T matrices, nothing shared between histograms.

@@ -177,15 +177,18 @@ hipError_t launch_table_rev(const float* W, int64_t ldw, int64_t vq, const int64
                             float* D2, int64_t ld2, float* D, int64_t ldd, hipStream_t s);
 
 // phase2.hip
+// zrows: rows of Z (every col_idx is below it)
 hipError_t launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t rows,
-                       const float* Z, int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine,
+                       const float* Z, int64_t ldz, int64_t zrows, int64_t ncols, float* D, int64_t ldd, int combine,
                        hipStream_t s);
 
 // topk.hip
 constexpr int kMaxTopK = 64;
 size_t topk_bytes(int64_t n, int64_t q, int k);
+// bound (optional): q x k sorted lists of distances that earlier rows already reach; values not below a list's last
+// entry are skipped (slots left unfilled read FLT_MAX / INT_MAX)
 hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
-                       void* ws, size_t ws_bytes, hipStream_t s);
+                       void* ws, size_t ws_bytes, hipStream_t s, const float* bound = nullptr);
 // out = the k smallest of list a (absolute row indices; ignored unless have_a) and list b (row indices relative to row0)
 hipError_t launch_topk_merge2(const float* a_d, const int32_t* a_i, bool have_a, const float* b_d, const int32_t* b_i,
                               int64_t row0, int64_t q, int k, float* out_d, int32_t* out_i, hipStream_t s);
@@ -197,6 +200,11 @@ hipError_t launch_col_sums(const float* tile, int64_t rows, int64_t q, int64_t l
 size_t topk_static_bytes();
 hipError_t topk_static_init(int device);
 void* topk_static_ptr(int device);
+
+// probe.hip: bare MFMA loops (diagnostic)
+size_t probe_bytes(int num_cu);
+hipError_t launch_probe_mfma(bool bf16, bool random, bool a_from_lds, int iters, int num_cu, void* ws, double* flops,
+                             long long** clk_dev, hipStream_t s);
 
 // wmd.hip: transport problems (one wavefront each), centroid distances, pruning lists
 size_t emd_pair_bytes(int64_t h1max, int64_t h2max);

@@ -192,8 +192,9 @@ __global__ __launch_bounds__(256) void k_spmm_tmax_wide(const int64_t* __restric
 }  // namespace
 
 hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, int64_t rows, const float* Z,
-                       int64_t ldz, int64_t ncols, float* D, int64_t ldd, int combine, hipStream_t s)
+                       int64_t ldz, int64_t zrows, int64_t ncols, float* D, int64_t ldd, int combine, hipStream_t s)
 {
+    (void)zrows;
     if (rows <= 0 || ncols <= 0) return hipSuccess;
     if (combine == 2 && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 128) {
         const int64_t row_tiles = (rows + WR - 1) / WR, col_tiles = (ncols + WC - 1) / WC;

@@ -39,10 +39,14 @@ TopkPlan plan_topk(int64_t n, int64_t q, int k, size_t ws_bytes)
 __device__ inline bool before(float d, int32_t i, float bd, int32_t bi) { return d < bd || (d == bd && i < bi); }
 
 // Partial top-k of rows [split * rows_per_split, ...) for 32 columns.
+// bound (or null): bound[j * k + k - 1] is a distance that k rows seen EARLIER (smaller row indices) already reach for
+// column j - the running list of lcrwmd_rwmd_reduce.  Only strictly smaller values can still enter the final list (an
+// equal one loses the tie on its row index), so everything else is skipped without touching the lists: after the
+// first blocks of a long database almost every value is.
 __global__ __launch_bounds__(256) void k_topk_partial(const float* __restrict__ D, int64_t n, int64_t q,
                                                       int64_t ldd, int k, int64_t rows_per_split,
-                                                      int64_t col_strips, float* __restrict__ out_d,
-                                                      int32_t* __restrict__ out_i)
+                                                      int64_t col_strips, const float* __restrict__ bound,
+                                                      float* __restrict__ out_d, int32_t* __restrict__ out_i)
 {
     extern __shared__ unsigned char smem[];
     float* kd = reinterpret_cast<float*>(smem);                          // [k][256]
@@ -59,23 +63,33 @@ __global__ __launch_bounds__(256) void k_topk_partial(const float* __restrict__ 
     if (r_end > n) r_end = n;
 
     int cnt = 0;
-    float worst = FLT_MAX;
-    if (j < q) {
-        for (int64_t i = r_begin + rg; i < r_end; i += LISTS) {
-            const float d = D[i * ldd + j];
-            int pos;
-            if (cnt < k) pos = cnt++;
-            else if (d < worst) pos = k - 1;
-            else continue;
-            while (pos > 0 && d < kd[(pos - 1) * 256 + tid]) {
-                kd[pos * 256 + tid] = kd[(pos - 1) * 256 + tid];
-                ki[pos * 256 + tid] = ki[(pos - 1) * 256 + tid];
-                --pos;
-            }
-            kd[pos * 256 + tid] = d;
-            ki[pos * 256 + tid] = (int32_t)i;
-            if (cnt == k) worst = kd[(k - 1) * 256 + tid];
+    const float outer = (bound && j < q) ? bound[j * k + k - 1] : FLT_MAX;
+    float worst = outer;               // values not below this cannot enter the list
+    auto offer = [&](float d, int64_t i) {
+        if (!(d < worst)) return;
+        int pos = cnt < k ? cnt++ : k - 1;
+        while (pos > 0 && d < kd[(pos - 1) * 256 + tid]) {
+            kd[pos * 256 + tid] = kd[(pos - 1) * 256 + tid];
+            ki[pos * 256 + tid] = ki[(pos - 1) * 256 + tid];
+            --pos;
         }
+        kd[pos * 256 + tid] = d;
+        ki[pos * 256 + tid] = (int32_t)i;
+        if (cnt == k) worst = fminf(outer, kd[(k - 1) * 256 + tid]);
+    };
+    if (j < q) {
+        // eight rows' values are requested before the first is looked at: a list rarely changes once it is full, so
+        // the loop is a stream of loads whose latency must overlap
+        constexpr int UN = 8;
+        int64_t i = r_begin + rg;
+        for (; i + (UN - 1) * LISTS < r_end; i += UN * LISTS) {
+            float d[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) d[u] = D[(i + u * LISTS) * ldd + j];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) offer(d[u], i + u * LISTS);
+        }
+        for (; i < r_end; i += LISTS) offer(D[i * ldd + j], i);
     }
     cnt_s[tid] = cnt;
     __syncthreads();
@@ -245,7 +259,7 @@ size_t topk_bytes(int64_t n, int64_t q, int k)
 }
 
 hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k, int32_t* R_idx, float* R_dist,
-                       void* ws, size_t ws_bytes, hipStream_t s)
+                       void* ws, size_t ws_bytes, hipStream_t s, const float* bound)
 {
     if (q <= 0) return hipSuccess;
     Bump b(ws, ws ? ws_bytes : 0);
@@ -265,7 +279,7 @@ hipError_t launch_topk(const float* D, int64_t n, int64_t q, int64_t ldd, int k,
     }
     const int64_t grid = p.col_strips * p.nsplit;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    k_topk_partial<<<(unsigned)grid, 256, smem, s>>>(D, n, q, ldd, k, p.rows_per_split, p.col_strips, pd, pi);
+    k_topk_partial<<<(unsigned)grid, 256, smem, s>>>(D, n, q, ldd, k, p.rows_per_split, p.col_strips, bound, pd, pi);
     if (p.nsplit > 1) {
         if (q > 0x7fffffffLL) return hipErrorInvalidValue;
         k_topk_merge<<<(unsigned)q, 64, 0, s>>>(pd, pi, q, k, p.nsplit, R_dist, R_idx);

@@ -68,6 +68,36 @@ def test_phase1_with_row_pitch_and_unnormalised_embeddings(ctx):
 
 
 # ------------------------------------------------------------------------------------------- phase 2
+@pytest.mark.parametrize("rows,v,ncols,ld_extra", [(3000, 5000, 1500, 0), (2100, 150, 2050, 2), (5000, 40000, 1024, 4)])
+def test_phase2_large_products(ctx, rows, v, ncols, ld_extra):
+    """Millions of outputs: many strips and row tiles, a Z with few rows, a ragged last strip with padding columns that
+    hold NaN, all three write-backs."""
+    print(f"phase2 large rows={rows} v={v} ncols={ncols}", flush=True)
+    rng = np.random.default_rng(rows)
+    X = synth.corpus(rows, v, 1, min(70, v), 1.1, 3)
+    Zh = rng.random((v, ncols)).astype(np.float32)
+    ref = oracle.phase2(X, Zh.astype(np.float64))
+    Xd = binding.Csr.from_numpy(X, v)
+    Z = torch.full((v, ncols + ld_extra), float("nan"), dtype=torch.float32, device="cuda")
+    Z[:, :ncols] = torch.from_numpy(Zh).cuda()
+    Zv = Z[:, :ncols]
+    D = torch.full((rows, ncols), -1.0, dtype=torch.float32, device="cuda")
+    ctx.phase2_spmm(Xd, Zv, ncols, D, combine=0)
+    torch.cuda.synchronize()
+    assert_close(D.cpu().numpy(), ref, rtol=1e-5, what="large X*Z")
+    prev = rng.random((rows, ncols)).astype(np.float32) * 0.3
+    D1 = torch.from_numpy(prev).cuda()
+    ctx.phase2_spmm(Xd, Zv, ncols, D1, combine=1)
+    torch.cuda.synchronize()
+    assert_close(D1.cpu().numpy(), np.maximum(prev.astype(np.float64), ref), rtol=1e-5, what="large max")
+    prevT = rng.random((ncols, rows)).astype(np.float32) * 0.3
+    D2 = torch.from_numpy(prevT).cuda()
+    ctx.phase2_spmm(Xd, Zv, ncols, D2, combine=2)
+    torch.cuda.synchronize()
+    assert_close(D2.cpu().numpy(), np.maximum(prevT.astype(np.float64), ref.T), rtol=1e-5, what="large transposed max")
+
+
+
 @pytest.mark.parametrize("rows,v,ncols", [(90, 400, 10), (333, 1000, 64), (200, 500, 517), (5, 50, 1)])
 def test_phase2_store_and_max(ctx, rows, v, ncols):
     print(f"phase2 rows={rows} v={v} ncols={ncols}", flush=True)
