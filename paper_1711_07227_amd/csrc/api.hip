@@ -233,10 +233,20 @@ lcrwmd_status prepare_emb(lcrwmd_ctx* ctx, const lcrwmd_emb* E, Bump& b, EmbPrep
 }
 
 // One first-phase pass over histograms [r0, r0 + nseg) of a CSR whose row_ptr is `rp` (device).
+// Room for the contraction kernel's map of close pairs, when the workspace has it (nullptr otherwise: the pass that
+// redoes close pairs then reads all of Z to find them).
+uint64_t* take_close_bits(Bump& b, int64_t nseg, int64_t nvoc)
+{
+    Bump saved = b;
+    void* p = b.take(close_bits_bytes(nseg, nvoc));
+    if (!b.ok) { b = saved; return nullptr; }
+    return (uint64_t*)p;
+}
+
 lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const int32_t* voc_rows, int64_t nvoc,
                          int z_by_position, const int32_t* zero_map, const int64_t* rp_batch,
                          const int32_t* col_idx, int64_t tokens, const TokenPlan& tp, float* Z, int64_t ldz,
-                         hipStream_t s, bool swapped = false)
+                         hipStream_t s, bool swapped = false, uint64_t* close_bits = nullptr)
 {
     HIP_TRY(launch_token_plan(tp, rp_batch, col_idx, ep.normE, s));
     Phase1Args a;
@@ -251,6 +261,9 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     a.Z = Z;
     a.ldz = ldz;
     a.num_cu = ctx->num_cu;
+    // only the tile kernels write the map of close pairs (all bf16 and split-bf16 launches; fp32 where its shape allows)
+    const bool mapped = close_bits && (ep.mode != 0 || tiles_f32_supported(a));
+    a.close_bits = mapped ? close_bits : nullptr;
     {
         ProfScope ps(ctx, s, 1, 2.0 * (double)nvoc * (double)tokens * (double)m, swapped ? 1.0 : 0.0);
         if (ep.mode == 2) HIP_TRY(launch_phase1_tiles_x3(a, tp, s));
@@ -262,7 +275,11 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     // histograms of the quadratic method - has no word -> row map: the pass below finds those entries itself.)
     if (!voc_rows || zero_map) HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
     // ... and loses relative accuracy where two different words lie close together: those entries are redone
-    HIP_TRY(launch_redo_close(ep.xdata, ep.xbf16, ep.xld, ep.xm, ep.normE, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, s));
+    if (mapped)
+        HIP_TRY(launch_redo_close_bits(ep.xdata, ep.xbf16, ep.xld, ep.xm, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, close_bits,
+                                       close_bits_pitch(ep.mode, nvoc), close_bits_slice(ep.mode), s));
+    else
+        HIP_TRY(launch_redo_close(ep.xdata, ep.xbf16, ep.xld, ep.xm, ep.normE, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, s));
     return LCRWMD_OK;
 }
 
@@ -544,8 +561,9 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
             carve_token_plan(bb, tp, j1 - j0, rq[j1] - rq[j0], plan_tiles(nvt_f, ep.bf16), padded_tokens(rq, j0, j1, grp), grp,
                              chunk_tiles);
             if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: forward batch does not fit");
+            uint64_t* bits = take_close_bits(bb, j1 - j0, ve);
             ST_TRY(run_phase1(ctx, ep, m, list_db, ve, /*z_by_position=*/1, /*zero_map=*/map_db, Q->row_ptr + j0,
-                              Q->col_idx, rq[j1] - rq[j0], tp, Z + (j0 - jq0), ldz, s));
+                              Q->col_idx, rq[j1] - rq[j0], tp, Z + (j0 - jq0), ldz, s, false, bits));
         }
     }
 
@@ -571,11 +589,12 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         float* Zr = bb.take_n<float>((size_t)vq * ldzr);
         float* tile = sink ? bb.take_n<float>((size_t)(i1 - i0) * ldz) : nullptr;
         if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: block of database rows does not fit");
+        uint64_t* bits = take_close_bits(bb, i1 - i0, vq);
         float* Db = sink ? tile : D + i0 * ldd;
         const int64_t ldb = sink ? ldz : ldd;
         ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == 0));
         ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
-                          DB->col_idx, nnz_b, tp, Zr, ldzr, s, /*swapped=*/true));
+                          DB->col_idx, nnz_b, tp, Zr, ldzr, s, /*swapped=*/true, bits));
         // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
         ST_TRY(run_spmm(ctx, Q->row_ptr + jq0, qcol_pos - qoff, Q->val, q, nnz_q, vq, Zr, ldzr, i1 - i0, Db, ldb, 2, s));
         if (sink) ST_TRY(sink->consume(i0, i1, Db, ldb, s));
@@ -750,8 +769,8 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     const size_t fixed = rwmd_fixed_bytes(v, (int32_t)m, nnz_q, nnz_db, bf16, padded, widened);
     const size_t zfull = (size_t)ve_max * (size_t)ldz * 4 + 256;                       // first-phase minima of a range
     const size_t tile = (size_t)nb * (size_t)ldz * 4 + 256;                            // a block's tile (lcrwmd_rwmd_reduce)
-    const size_t f = token_plan_bytes(qr, nnz_q);
-    const size_t r = rev_batch_bytes(vq, nb, nnz_db) + tile;
+    const size_t f = token_plan_bytes(qr, nnz_q) + close_bits_bytes(qr, ve_max);
+    const size_t r = rev_batch_bytes(vq, nb, nnz_db) + tile + close_bits_bytes(nb, vq);
     size_t region = f > r ? f : r;
     if (ctx->opt.dedup) {
         // room for the word-pair table at its upper bound (distinct words <= stored entries)
@@ -763,7 +782,8 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     // lcrwmd_rwmd_reduce: the running lists, a block's list and its partial lists, the column sums' scratch
     total += 6 * ((size_t)qr * (size_t)(k > 0 ? k : 1) * 4 + 256) + topk_bytes(nb, qr, k > 0 ? k : 1) + col_sums_bytes(qr) + 2048;
     // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
-    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded, widened) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) + 4096;
+    size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded, widened) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) +
+                close_bits_bytes(q > n ? q : n, v) + 4096;
     *out_bytes = total > p1 ? total : p1;
     return LCRWMD_OK;
 }
@@ -799,8 +819,9 @@ lcrwmd_status lcrwmd_phase1_mindist(lcrwmd_ctx* ctx, const lcrwmd_emb* E, const 
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small: need about %zu bytes",
                            emb_prep_bytes(E->v, (int32_t)E->m, ep.mode, wants_padded_copy(E), wants_widened_copy(ctx, E)) +
                                token_plan_bytes(queries->rows, queries->nnz));
+    uint64_t* bits = take_close_bits(b, queries->rows, E->v);
     return run_phase1(ctx, ep, (int32_t)E->m, nullptr, E->v, 0, nullptr, queries->row_ptr, queries->col_idx,
-                      queries->nnz, tp, Z, ldz, s);
+                      queries->nnz, tp, Z, ldz, s, false, bits);
 }
 
 lcrwmd_status lcrwmd_phase2_spmm(lcrwmd_ctx* ctx, const lcrwmd_csr* X, const float* Z, int64_t ldz, int64_t ncols,
@@ -1038,8 +1059,8 @@ lcrwmd_status lcrwmd_probe_mfma(lcrwmd_ctx* ctx, lcrwmd_dtype dtype, int random_
 namespace {
 size_t quadratic_block_bytes(int64_t nb, int64_t nnz_b, int64_t q, int64_t nnz_q)
 {
-    const size_t a = token_plan_bytes(q, nnz_q) + (size_t)nnz_b * (size_t)round_up(q, 4) * 4 + 512;      // row minima
-    const size_t b = token_plan_bytes(nb, nnz_b) + (size_t)nnz_q * (size_t)round_up(nb, 4) * 4 + 512;    // column minima
+    const size_t a = token_plan_bytes(q, nnz_q) + (size_t)nnz_b * (size_t)round_up(q, 4) * 4 + close_bits_bytes(q, nnz_b) + 512;      // row minima
+    const size_t b = token_plan_bytes(nb, nnz_b) + (size_t)nnz_q * (size_t)round_up(nb, 4) * 4 + close_bits_bytes(nb, nnz_q) + 512;  // column minima
     return a > b ? a : b;
 }
 }  // namespace
@@ -1113,8 +1134,9 @@ lcrwmd_status lcrwmd_rwmd_quadratic(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, 
             const int64_t ldz = round_up(q, 4);
             float* Z1 = bb.take_n<float>((size_t)nnz_b * ldz);
             if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: row minima do not fit");
+            uint64_t* bits = take_close_bits(bb, q, nnz_b);
             ST_TRY(run_phase1(ctx, ep, m, database->col_idx + t0, nnz_b, 1, nullptr, queries->row_ptr, queries->col_idx, nnz_q, tp, Z1,
-                              ldz, s));
+                              ldz, s, false, bits));
             // rows of the block in their stacked order: entry p of the block reads row p - t0 of Z1
             ST_TRY(run_spmm(ctx, database->row_ptr + i0, iota - t0, database->val, i1 - i0, nnz_b, nnz_b, Z1, ldz, q, Db, ldd, 0, s));
         }
@@ -1126,8 +1148,9 @@ lcrwmd_status lcrwmd_rwmd_quadratic(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, 
             const int64_t ldz = round_up(i1 - i0, 4);
             float* Z2 = bb.take_n<float>((size_t)nnz_q * ldz);
             if (!bb.ok) return fail(ctx, LCRWMD_EWORKSPACE, "internal: column minima do not fit");
+            uint64_t* bits = take_close_bits(bb, i1 - i0, nnz_q);
             ST_TRY(run_phase1(ctx, ep, m, queries->col_idx, nnz_q, 1, nullptr, database->row_ptr + i0, database->col_idx, nnz_b, tp, Z2,
-                              ldz, s, /*swapped=*/true));
+                              ldz, s, /*swapped=*/true, bits));
             ST_TRY(run_spmm(ctx, queries->row_ptr, iota, queries->val, q, nnz_q, nnz_q, Z2, ldz, i1 - i0, Db, ldd, 2, s));
         }
     }

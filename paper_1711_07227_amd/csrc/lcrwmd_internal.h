@@ -98,6 +98,8 @@ struct Phase1Args {
     float* Z;
     int64_t ldz;
     int32_t num_cu = 256;     // compute units of the device (the bf16 kernel launches one workgroup per CU)
+    uint64_t* close_bits = nullptr;   // optional: map of the entries that came out close (see close_bits_pitch); written
+                                      // by the tile kernels only - launch_phase1_* report whether it was
 };
 
 // prep.hip
@@ -125,6 +127,11 @@ hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_
 hipError_t launch_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, const float* normE, const int32_t* voc_rows,
                              int64_t nvoc, const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg, float* Z,
                              int64_t ldz, hipStream_t s);
+// The same from the contraction kernel's map of close pairs instead of a read of all of Z: bits[pitch * j + slice] has
+// bit l set when entry (vocabulary position slice * slice_words + l % slice_words, histogram j) needs the second look.
+hipError_t launch_redo_close_bits(const void* E, bool bf16, int64_t ld, int32_t m, const int32_t* voc_rows, int64_t nvoc,
+                                  const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg, float* Z, int64_t ldz,
+                                  const uint64_t* bits, int64_t pitch, int slice_words, hipStream_t s);
 // status[0] = 0 ok, 2 bad csr, 3 empty doc (values of lcrwmd_status)
 hipError_t launch_validate_csr(const lcrwmd_csr& X, int32_t* status, hipStream_t s);
 
@@ -146,6 +153,10 @@ hipError_t launch_phase1_tiles_f32(const Phase1Args& a, const TokenPlan& tp, hip
 hipError_t launch_phase1_tiles_bf16(const Phase1Args& a, const TokenPlan& tp, int num_cu, hipStream_t s);
 hipError_t launch_phase1_tiles_x3(const Phase1Args& a, const TokenPlan& tp, hipStream_t s);
 int phase1_group_x3();             // group size the split-bf16 kernel expects of its token plan
+// Map of close pairs (Phase1Args::close_bits): vocabulary positions per 64-bit word, words per histogram; bytes for a batch
+int close_bits_slice(int mode);
+int64_t close_bits_pitch(int mode, int64_t nvoc);
+inline size_t close_bits_bytes(int64_t nseg, int64_t nvoc) { return (size_t)nseg * (size_t)((nvoc + 255) / 256 * 8) * 8 + 256; }
 // split-bf16 operand copy: 640 bf16 per row (304 hi values, 304 lo values, zeros)
 size_t pack_x3_bytes(int64_t v);
 int32_t x3_pitch();

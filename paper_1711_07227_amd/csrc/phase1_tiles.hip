@@ -84,6 +84,12 @@ struct P1T {
     const int32_t* chunk_seg;
     float* Z;
     int64_t ldz;
+    // Optional map of the entries that may need a second look (k_phase1_pingpong only): word close_pitch * j + slice
+    // holds, for histogram j and the 32 * NCT vocabulary positions of one wavefront (slice = that wavefront's number in
+    // vocabulary order), one bit per lane: set where the squared distance came out below a quarter of the word's squared
+    // norm - a pair of close or equal words, for which the norm expansion is not accurate.  Every word is written.
+    uint64_t* close_bits;
+    int64_t close_pitch;
 };
 
 // Arithmetic of the contraction.
@@ -633,10 +639,16 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     // Store the value of histogram `cur`.  One exchange hands the lower lanes both halves' maxima of column tile 0
     // and the upper lanes those of column tile 1, so one store serves 64 words (with a single column tile both
     // halves end up with the same value and store it to the same place).
+    uint64_t* const bits = p.close_bits ? p.close_bits + ((int64_t)vt * 8 + wave) : nullptr;      // this wavefront's slice
     auto flush = [&]() {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(run[0]), __float_as_uint(run[NCT - 1]), false, false);
         const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        zrow[cur] = __builtin_amdgcn_sqrtf(fmaxf(nEsel - 2.f * best, 0.f));
+        const float d2 = nEsel - 2.f * best;
+        zrow[cur] = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
+        if (bits) {
+            const uint64_t close = __ballot(4.f * d2 < nEsel);
+            if (lane == 0) bits[(int64_t)cur * p.close_pitch] = close;
+        }
     };
 
     struct Grp { int32_t v[NG]; };
@@ -858,6 +870,8 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
     d.chunk_seg = tp.chunk_seg;
     d.Z = a.Z;
     d.ldz = a.ldz;
+    d.close_bits = a.close_bits;
+    d.close_pitch = 0;
     return d;
 }
 
@@ -866,6 +880,15 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
 // fp32 rows are read in place: 300 values (75 whole 16-byte pieces; the 76th piece of the layout re-reads the 75th)
 // in 16-byte aligned rows.  Other shapes take the register-staged kernels of phase1_f32.hip.
 int phase1_group_x3() { return PP<kX3>::G; }
+
+// Shape of the map of close pairs the contraction kernel of a mode writes: vocabulary positions per 64-bit word (the
+// lower 32 bits count where it is 32) and words per histogram.
+int close_bits_slice(int mode) { return mode == 1 ? 64 : 32; }
+int64_t close_bits_pitch(int mode, int64_t nvoc)
+{
+    const int64_t wg = mode == 1 ? PP<kBF16>::WG_COLS : PP<kF32>::WG_COLS;
+    return (nvoc + wg - 1) / wg * 8;
+}
 
 // The copies address operand rows with 32-bit offsets: bytes while the rows span less than 4 GiB, 16-byte pieces
 // (a slower variant of the kernels) up to 64 GiB.
@@ -891,6 +914,7 @@ hipError_t launch_pingpong_w(P1T d, int num_cu, hipStream_t s)
 {
     using C = PP<MODE>;
     d.nvt = (int32_t)((d.nvoc + C::WG_COLS - 1) / C::WG_COLS);
+    d.close_pitch = (int64_t)d.nvt * 8;
     const int64_t total = (int64_t)d.nvt * d.nchunks;
     int64_t grid = num_cu > 8 ? num_cu / 8 * 8 : 8;
     while (grid > 8 && grid > total) grid -= 8;
@@ -975,6 +999,8 @@ hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* t
     d.chunk_seg = nullptr;
     d.Z = a.Z;
     d.ldz = a.ldz;
+    d.close_bits = nullptr;
+    d.close_pitch = 0;
     if (mode == 1) {
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kBF16>::NOCT * 8;

@@ -336,6 +336,66 @@ __global__ __launch_bounds__(256) void k_redo_close(const void* __restrict__ E, 
     }
 }
 
+// The second look driven by the contraction kernel's map of close pairs: one thread per 64-bit word of the map.  A
+// set bit is either the word itself in the histogram (binary search in the sorted row: the entry is exactly 0) or a
+// pair of different words that lie close: those are redone from coordinate differences by the whole wavefront, one
+// after the other, lanes along the embedding dimension.
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_redo_close_bits(const void* __restrict__ E, int64_t ld, int32_t m,
+                                                         const int32_t* __restrict__ voc_rows, int64_t nvoc,
+                                                         const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                                                         int64_t nseg, float* __restrict__ Z, int64_t ldz,
+                                                         const uint64_t* __restrict__ bits, int64_t pitch, int slice_words)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t j = t / pitch, slice = t - j * pitch;
+    uint64_t mine = j < nseg ? bits[t] : 0;
+    if (slice_words == 32) mine &= 0xffffffffull;                 // both lane halves hold the same 32 positions
+    if (!__any(mine != 0)) return;
+    while (__any(mine != 0)) {
+        // this lane's next candidate
+        int64_t pos = -1;
+        int32_t w = 0;
+        bool redo = false;
+        if (mine) {
+            const int bit = __builtin_ctzll(mine);
+            mine &= mine - 1;
+            pos = slice * slice_words + bit;
+            if (pos < nvoc) {
+                w = voc_rows ? voc_rows[pos] : (int32_t)pos;
+                int64_t lo = rp[j], hi = rp[j + 1];
+                while (lo < hi) {
+                    const int64_t mid = lo + ((hi - lo) >> 1);
+                    if (ci[mid] < w) lo = mid + 1; else hi = mid;
+                }
+                if (lo < rp[j + 1] && ci[lo] == w) Z[pos * ldz + j] = 0.f;
+                else redo = true;
+            }
+        }
+        uint64_t todo = __ballot(redo);
+        while (todo) {
+            const int l = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int32_t ww = __builtin_amdgcn_readlane(w, l);
+            const int64_t jj = __shfl(j, l);
+            const int64_t a = rp[jj], b = rp[jj + 1];
+            float best = 3.0e38f;
+            for (int64_t e = a; e < b; ++e) {
+                const int32_t c = ci[e];
+                float sum = 0.f;
+                for (int32_t k = lane; k < m; k += 64) {
+                    const float d = emb_value<BF16>(E, (int64_t)ww * ld + k) - emb_value<BF16>(E, (int64_t)c * ld + k);
+                    sum = fmaf(d, d, sum);
+                }
+                for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+                best = fminf(best, sum);
+            }
+            if (lane == l) Z[pos * ldz + j] = sqrtf(best);
+        }
+    }
+}
+
 __global__ void k_validate_csr(const int64_t* __restrict__ rp, const int32_t* __restrict__ col_idx,
                                const float* __restrict__ val, int64_t rows, int64_t cols, int64_t nnz,
                                int32_t* __restrict__ status)
@@ -495,6 +555,19 @@ hipError_t launch_redo_close(const void* E, bool bf16, int64_t ld, int32_t m, co
     if (bf16) { if (vec) REDO(true, true); else REDO(true, false); }
     else { if (vec) REDO(false, true); else REDO(false, false); }
 #undef REDO
+    return hipGetLastError();
+}
+
+hipError_t launch_redo_close_bits(const void* E, bool bf16, int64_t ld, int32_t m, const int32_t* voc_rows, int64_t nvoc,
+                                  const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg, float* Z, int64_t ldz,
+                                  const uint64_t* bits, int64_t pitch, int slice_words, hipStream_t s)
+{
+    if (nvoc <= 0 || nseg <= 0) return hipSuccess;
+    const int64_t words = nseg * pitch;
+    const int64_t grid = (words + 255) / 256;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (bf16) k_redo_close_bits<true><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, bits, pitch, slice_words);
+    else k_redo_close_bits<false><<<(unsigned)grid, 256, 0, s>>>(E, ld, m, voc_rows, nvoc, row_ptr_batch, col_idx, nseg, Z, ldz, bits, pitch, slice_words);
     return hipGetLastError();
 }
 
