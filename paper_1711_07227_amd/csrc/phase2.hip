@@ -12,47 +12,72 @@ namespace lcrwmd {
 
 namespace {
 
+// One batch of up to 64 stored entries of a row, one per lane: column and weight.  Lanes past the end repeat the
+// batch's first column with weight 0, so that a batch can be walked in full groups (a repeated row is a valid, finite
+// row of Z; it contributes nothing).
+struct EntryBatch {
+    int cv;
+    float xl;
+    int cnt;
+};
+
+__device__ inline EntryBatch load_entries(int64_t p0, int64_t b, const int32_t* __restrict__ ci, const float* __restrict__ xv, int lane)
+{
+    EntryBatch e;
+    e.cnt = (int)(b - p0 < 64 ? b - p0 : 64);
+    e.cv = 0;
+    e.xl = 0.f;
+    if (lane < e.cnt) { e.cv = ci[p0 + lane]; e.xl = xv[p0 + lane]; }
+    // Done here, with every lane active: the values are read across lanes later, also from inside branches that only
+    // part of the wavefront takes (a ragged last strip), and a lane must not read a register that was written while
+    // the lane it reads from was switched off.
+    const int c_first = __builtin_amdgcn_readfirstlane(e.cv);
+    if (lane >= e.cnt) e.cv = c_first;
+    return e;
+}
+
+// acc[t] += sum over the entries of the batch of weight * Z[column][j + t], t < W (full strips: vector gathers).
+// UN row segments of Z are requested before the first is used; the gathers of a group are independent of one another.
+template <int W, int UN>
+__device__ inline void batch_times_strip(const EntryBatch& e, const float* __restrict__ zj, int64_t ldz, float* acc)
+{
+    typedef float vecw __attribute__((ext_vector_type(W)));
+    const int cntu = (e.cnt + UN - 1) / UN * UN;          // cnt <= 64 and UN divides 64
+    for (int u = 0; u < cntu; u += UN) {
+        vecw z[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k)
+            z[k] = *reinterpret_cast<const vecw*>(zj + (int64_t)__builtin_amdgcn_readlane(e.cv, u + k) * ldz);
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, e.xl), u + k));
+#pragma unroll
+            for (int t = 0; t < W; ++t) acc[t] = fmaf(x, z[k][t], acc[t]);
+        }
+    }
+}
+
 // acc[t] = sum over the stored entries p in [a, b) of xv[p] * Z[ci[p]][j + t], t < W, for this lane's columns
-// j .. j + W - 1 (a, b wave-uniform).
-// 64 stored entries at a time: one coalesced load of (column, weight) per lane, then each entry is broadcast
-// with readlane and its row segment of Z gathered; the gathers of a batch are independent of one another.
+// j .. j + W - 1 (a, b wave-uniform).  `first` holds the entries [a, a + 64) already (requested by the caller while it
+// was busy with the row before: a row costs the round trips of its gathers only).
 template <int W>
-__device__ inline void row_times_strip(int64_t a, int64_t b, const int32_t* __restrict__ ci, const float* __restrict__ xv,
-                                       const float* __restrict__ Z, int64_t ldz, int64_t ncols, int64_t j, int lane,
-                                       float* acc)
+__device__ inline void row_times_strip(int64_t a, int64_t b, EntryBatch first, const int32_t* __restrict__ ci,
+                                       const float* __restrict__ xv, const float* __restrict__ Z, int64_t ldz, int64_t ncols,
+                                       int64_t j, int lane, float* acc)
 {
 #pragma unroll
     for (int t = 0; t < W; ++t) acc[t] = 0.f;
     const bool full = j + W - 1 < ncols;
     const float* zj = Z + j;
-    typedef float vecw __attribute__((ext_vector_type(W)));
+    EntryBatch e = first;
     for (int64_t p0 = a; p0 < b; p0 += 64) {
-        const int cnt = (int)(b - p0 < 64 ? b - p0 : 64);
-        int cv = 0;
-        float xl = 0.f;
-        if (lane < cnt) { cv = ci[p0 + lane]; xl = xv[p0 + lane]; }
-        // lanes past the end repeat the batch's first column with weight 0: the batch can then be walked in
-        // full groups of 8 (a repeated row is a valid, finite row of Z; it contributes nothing)
-        const int c_first = __builtin_amdgcn_readfirstlane(cv);
-        if (lane >= cnt) cv = c_first;
-        const int cnt8 = (cnt + 7) & ~7;
+        if (p0 > a) e = load_entries(p0, b, ci, xv, lane);
         if (full) {
-            for (int u = 0; u < cnt8; u += 8) {
-                vecw z[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    z[k] = *reinterpret_cast<const vecw*>(zj + (int64_t)__builtin_amdgcn_readlane(cv, u + k) * ldz);
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xl), u + k));
-#pragma unroll
-                    for (int t = 0; t < W; ++t) acc[t] = fmaf(x, z[k][t], acc[t]);
-                }
-            }
+            batch_times_strip<W, 8>(e, zj, ldz, acc);
         } else {
-            for (int u = 0; u < cnt; ++u) {
-                const float* zr = zj + (int64_t)__builtin_amdgcn_readlane(cv, u) * ldz;
-                const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, xl), u));
+            for (int u = 0; u < e.cnt; ++u) {
+                const float* zr = zj + (int64_t)__builtin_amdgcn_readlane(e.cv, u) * ldz;
+                const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, e.xl), u));
 #pragma unroll
                 for (int t = 0; t < W; ++t)
                     if (j + t < ncols) acc[t] = fmaf(x, zr[t], acc[t]);
@@ -61,34 +86,51 @@ __device__ inline void row_times_strip(int64_t a, int64_t b, const int32_t* __re
     }
 }
 
-// One wavefront per (row, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
+__device__ inline int64_t uniform_i64(int64_t x)
+{
+    return (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)x) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(x >> 32)) << 32);
+}
+
+// One wavefront per (RPW consecutive rows, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
 // Units are ordered strip-major and workgroup ids follow that order, so at any time the whole chip works on
 // one strip of columns: the strip of Z (rows of 256 W bytes) is what has to stay in the L2s / Infinity Cache,
-// not the full rows.
+// not the full rows.  The row pointers of a unit are fetched in one load and the entries of the next row are
+// requested before the gathers of the current one.
+constexpr int RPW = 4;
 template <int W, int COMBINE>
 __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
                                                    const float* __restrict__ xv, int64_t rows,
                                                    const float* __restrict__ Z, int64_t ldz, int64_t ncols,
-                                                   float* __restrict__ D, int64_t ldd, int64_t strips)
+                                                   float* __restrict__ D, int64_t ldd, int64_t strips, int64_t row_units)
 {
     const int lane = threadIdx.x & 63;
     const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t strip = unit / rows;
-    const int64_t i = unit - strip * rows;
+    const int64_t strip = unit / row_units;
+    const int64_t i0 = (unit - strip * row_units) * RPW;
     if (strip >= strips) return;
     const int64_t j = strip * (64 * W) + (int64_t)lane * W;
     // row bounds are wave-uniform: keep them scalar so that the loop control and the row addresses of Z are scalar too
-    const int64_t a = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[i]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i] >> 32)) << 32);
-    const int64_t b = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[i + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[i + 1] >> 32)) << 32);
-    float acc[W];
-    row_times_strip<W>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
-
+    const int nr = (int)(rows - i0 < RPW ? rows - i0 : RPW);
+    const int64_t mine = rp[i0 + (lane <= nr ? lane : nr)];
+    int64_t bound[RPW + 1];
 #pragma unroll
-    for (int t = 0; t < W; ++t) {
-        if (j + t < ncols) {
-            float* d = D + i * ldd + j + t;
-            if (COMBINE == 0) *d = acc[t];
-            else *d = fmaxf(*d, acc[t]);
+    for (int r = 0; r <= RPW; ++r) bound[r] = uniform_i64(__shfl(mine, r < nr ? r : nr));
+    EntryBatch next = load_entries(bound[0], bound[1], ci, xv, lane);
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) {
+        if (r < nr) {
+            const EntryBatch cur = next;
+            if (r + 1 < nr) next = load_entries(bound[r + 1], bound[r + 2], ci, xv, lane);
+            float acc[W];
+            row_times_strip<W>(bound[r], bound[r + 1], cur, ci, xv, Z, ldz, ncols, j, lane, acc);
+#pragma unroll
+            for (int t = 0; t < W; ++t) {
+                if (j + t < ncols) {
+                    float* d = D + (i0 + r) * ldd + j + t;
+                    if (COMBINE == 0) *d = acc[t];
+                    else *d = fmaxf(*d, acc[t]);
+                }
+            }
         }
     }
 }
@@ -165,14 +207,26 @@ __global__ __launch_bounds__(256) void k_spmm_tmax_wide(const int64_t* __restric
     const int64_t r0 = rt * WR, c0 = ct * WC;
     const int64_t j = c0 + (int64_t)lane * 4;
 
-    for (int k = 0; k < WR / 4; ++k) {
-        const int rr = wave * (WR / 4) + k;
-        const int64_t r = r0 + rr;
+    // this wavefront's WR / 4 rows: their bounds in one load, the entries of the next row requested before the gathers of
+    // the current one
+    constexpr int NR = WR / 4;
+    const int64_t rw = r0 + wave * NR;
+    const int nr = (int)(rows - rw < NR ? (rows - rw > 0 ? rows - rw : 0) : NR);
+    int64_t bound[NR + 1];
+    {
+        const int64_t mine = nr > 0 ? rp[rw + (lane <= nr ? lane : nr)] : 0;
+#pragma unroll
+        for (int r = 0; r <= NR; ++r) bound[r] = uniform_i64(__shfl(mine, r < nr ? r : nr));
+    }
+    EntryBatch next = load_entries(bound[0], bound[1], ci, xv, lane);
+#pragma unroll
+    for (int k = 0; k < NR; ++k) {
+        const int rr = wave * NR + k;
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        if (r < rows) {
-            const int64_t a = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[r]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r] >> 32)) << 32);
-            const int64_t b = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rp[r + 1]) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(rp[r + 1] >> 32)) << 32);
-            row_times_strip<4>(a, b, ci, xv, Z, ldz, ncols, j, lane, acc);
+        if (k < nr) {
+            const EntryBatch cur = next;
+            if (k + 1 < nr) next = load_entries(bound[k + 1], bound[k + 2], ci, xv, lane);
+            row_times_strip<4>(bound[k], bound[k + 1], cur, ci, xv, Z, ldz, ncols, j, lane, acc);
         }
 #pragma unroll
         for (int t = 0; t < 4; ++t) tile[rr][4 * lane + t] = acc[t];
@@ -215,9 +269,10 @@ hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, in
     if ((ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 256) W = 4;
     else if ((ldz % 2 == 0) && (((uintptr_t)Z & 7) == 0) && ncols >= 128) W = 2;
     const int64_t strips = (ncols + 64 * W - 1) / (64 * W);
-    const int64_t grid = (rows * strips + 3) / 4;
+    const int64_t row_units = (rows + RPW - 1) / RPW;
+    const int64_t grid = (row_units * strips + 3) / 4;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-#define LAUNCH_ROWS(WW, CC) k_spmm_rows<WW, CC><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips)
+#define LAUNCH_ROWS(WW, CC) k_spmm_rows<WW, CC><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips, row_units)
     if (W == 4) { if (combine == 0) LAUNCH_ROWS(4, 0); else LAUNCH_ROWS(4, 1); }
     else if (W == 2) { if (combine == 0) LAUNCH_ROWS(2, 0); else LAUNCH_ROWS(2, 1); }
     else { if (combine == 0) LAUNCH_ROWS(1, 0); else LAUNCH_ROWS(1, 1); }
