@@ -90,6 +90,7 @@ struct P1T {
     // norm - a pair of close or equal words, for which the norm expansion is not accurate.  Every word is written.
     uint64_t* close_bits;
     int64_t close_pitch;
+    int32_t park;              // bf16 k_phase1_pingpong: collect four histograms' results per lane in LDS and store 16 bytes
 };
 
 // Arithmetic of the contraction.
@@ -611,9 +612,12 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     auto copy_octet = [&](auto o_c, uint32_t off, unsigned char* lbase) {
         constexpr int oct = decltype(o_c)::value;
         const uint32_t o = off + ((F32 && oct == NOCT - 1) ? off_last : (uint32_t)(oct * 8) * PIECE);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(WIDE ? Eb + ((uint64_t)o << 4) : Eb + o),
-                                         (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
-                                         16, 0, 0);
+        // bf16: pieces 38 and 39 of a row (columns 304..319) are never multiplied; the copies leave their 32 bytes per
+        // row alone, and those bytes - 8 KiB over the four tile buffers - are where results are parked (see flush)
+        if (!BF16 || oct != NOCT - 1 || pieceO < 6)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(WIDE ? Eb + ((uint64_t)o << 4) : Eb + o),
+                                             (__attribute__((address_space(3))) void*)(lbase + (oct * (ROWS / 8) + wave) * 1024),
+                                             16, 0, 0);
     };
     auto copy_tile = [&](const Ids& ids, unsigned char* lbase) {
         const uint32_t off = row_offset(ids);
@@ -640,11 +644,44 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     // and the upper lanes those of column tile 1, so one store serves 64 words (with a single column tile both
     // halves end up with the same value and store it to the same place).
     uint64_t* const bits = p.close_bits ? p.close_bits + ((int64_t)vt * 8 + wave) : nullptr;      // this wavefront's slice
+    // bf16: a lane's results of four consecutive histograms are collected in 16 bytes of LDS of its own and leave as
+    // one aligned 16-byte store.  (One 4-byte store per word and histogram reaches the memory system as a write of its
+    // own - the L2s are swept by the token tiles before a sector's neighbours arrive - and at this kernel's pace those
+    // requests cost it a tenth of its time.)  The 16 bytes: wavefront w, lane l -> tile buffer w mod 4, token row l,
+    // piece 38 + w / 4 of that row, which no copy writes and no MFMA reads.  park_q: first histogram of the quad being
+    // collected, counted from a 16-byte boundary of Z's rows; park_mask: which of its four slots are filled.
+    const bool parking = BF16 && p.park;
+    const int zoff = (int)(((uintptr_t)p.Z >> 2) & 3);
+    float* const park_slot = reinterpret_cast<float*>(smem + (wave & 3) * TILE_BYTES + (4 * (ROWS / 8) + (lane >> 3)) * 1024 +
+                                                      (lane & 7) * 128 + (((6 + (wave >> 2)) ^ ((lane >> 1) & 7)) * 16));
+    int park_q = -4;
+    unsigned park_mask = 0;
+    auto unpark = [&]() {          // stores whatever is collected, slot by slot (only where a run starts or ends inside a quad)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (park_mask & (1u << t)) zrow[park_q - zoff + t] = park_slot[t];
+        park_mask = 0;
+    };
     auto flush = [&]() {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(run[0]), __float_as_uint(run[NCT - 1]), false, false);
         const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
         const float d2 = nEsel - 2.f * best;
-        zrow[cur] = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
+        const float z = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));
+        if (parking) {
+            const int a = cur + zoff, q = a & ~3;
+            if (q != park_q) {
+                if (park_mask) unpark();
+                park_q = q;
+            }
+            park_slot[a & 3] = z;
+            park_mask |= 1u << (a & 3);
+            if (park_mask == 15u) {
+                *reinterpret_cast<f32x4*>(zrow + (q - zoff)) = *reinterpret_cast<const f32x4*>(park_slot);
+                park_mask = 0;
+            }
+        } else {
+            zrow[cur] = z;
+        }
         if (bits) {
             const uint64_t close = __ballot(4.f * d2 < nEsel);
             if (lane == 0) bits[(int64_t)cur * p.close_pitch] = close;
@@ -819,6 +856,7 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
     pp_barrier();
     if (grp == 0) pp_barrier();             // both groups pass the same number of barriers; nobody reads LDS any more
     if (cur >= 0) flush();
+    if (park_mask) unpark();
     }   // runs of this workgroup
 }
 
@@ -872,6 +910,7 @@ P1T common_args(const Phase1Args& a, const TokenPlan& tp)
     d.ldz = a.ldz;
     d.close_bits = a.close_bits;
     d.close_pitch = 0;
+    d.park = a.ldz % 4 == 0 ? 1 : 0;      // 16-byte stores need rows of Z that keep the alignment of the first one
     return d;
 }
 
@@ -1001,6 +1040,7 @@ hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* t
     d.ldz = a.ldz;
     d.close_bits = nullptr;
     d.close_pitch = 0;
+    d.park = 0;
     if (mode == 1) {
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kBF16>::NOCT * 8;
