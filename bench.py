@@ -271,8 +271,13 @@ class Job:
         wq = b.alloc_workspace(self.ctx.rwmd_quadratic_workspace_bytes(self.v, self.m, self.n, self.db.nnz, qn, sub.nnz, self.emb_dtype))
         wl = b.alloc_workspace(self.ctx.workspace_bytes(self.v, self.m, self.n, self.db.nnz, qn, sub.nnz, self.emb_dtype))
         times = {}
-        for name, fn in (("linear", lambda: self.ctx.rwmd(sub, self.db, self.E, Dl, wl)),
-                         ("quadratic", lambda: self.ctx.rwmd_quadratic(sub, self.db, self.E, Dq, wq))):
+        for name, dedup, fn in (("linear", 0, lambda: self.ctx.rwmd(sub, self.db, self.E, Dl, wl)),
+                                ("quadratic", 0, lambda: self.ctx.rwmd_quadratic(sub, self.db, self.E, Dq, wq)),
+                                ("linear_auto", 2, lambda: self.ctx.rwmd(sub, self.db, self.E, Dl, wl))):
+            self.ctx.set_options(compute=saved["compute"], dedup=dedup)
+            if dedup:
+                wl = None
+                wl = b.alloc_workspace(self.ctx.workspace_bytes(self.v, self.m, self.n, self.db.nnz, qn, sub.nnz, self.emb_dtype))
             torch.cuda.synchronize()
             self.ctx.profile_begin()
             t = time.perf_counter()
@@ -280,12 +285,15 @@ class Job:
             torch.cuda.synchronize()
             times[name] = time.perf_counter() - t
             times[name + "_prof"] = self.ctx.profile_end()
+            times[name + "_form"] = FORM_NAMES[self.ctx.forms_ran()]
         self.ctx.set_options(**saved)
         pq = times["quadratic_prof"]
         progress(f"{self.cfg.name}: quadratic method on {qn} queries, {1e3 * times['quadratic']:.0f} ms against "
                  f"{1e3 * times['linear']:.0f} ms")
         return {"queries": qn, "quadratic_ms": 1e3 * times["quadratic"], "linear_complexity_ms": 1e3 * times["linear"],
                 "speedup_of_linear_complexity": times["quadratic"] / times["linear"],
+                "linear_complexity_library_choice_ms": 1e3 * times["linear_auto"], "library_choice_form": times["linear_auto_form"],
+                "speedup_of_library_choice": times["quadratic"] / times["linear_auto"],
                 "mean_histogram_size": self.db.nnz / self.n,
                 "quadratic_first_phase_TFLOPs": pq["phase1_flops"] / max(pq["phase1_ms"], 1e-9) / 1e9,
                 "quadratic_flops": pq["phase1_flops"], "linear_complexity_flops": times["linear_prof"]["phase1_flops"],
@@ -355,6 +363,14 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False):
             out["auto_form"] = job.report(max(1, steps), sec_a, prof_a)
             job.options()
             out["quadratic_method"] = job.quadratic_leg(16)
+        if "auto_form" not in out:
+            # short documents, many queries: what the library picks by itself (the same step, option dedup = 2)
+            job.options(dedup=2)
+            sec_a, prof_a = job.timed(1, 1, reduce or bool(job.batches))
+            rep = job.report(1, sec_a, prof_a)
+            out["auto_form"] = {"ms_per_step": rep["ms_per_step"], "form": rep["form"], "steps": 1,
+                                "step": "reduced on the device" if (reduce or job.batches) else "full matrix"}
+            job.options()
         return out
     finally:
         job.close()

@@ -131,8 +131,11 @@ lcrwmd_status lcrwmd_get_options(const lcrwmd_ctx* ctx, lcrwmd_options* opt);
  * preferred batch sizes.  lcrwmd_rwmd and lcrwmd_rwmd_topk also run with less, in smaller
  * batches, down to a floor below which they return LCRWMD_EWORKSPACE.
  * nnz_db / nnz_q are the stored entries of X1 / X2; k = 0 when no top-k is wanted.
- * With the dedup option set the figure includes the word-pair table at its upper bound
- * (distinct words <= stored entries); any size that suffices without the option still works.
+ * With dedup = 1 the figure includes the word-pair table at its upper bound (distinct words <=
+ * stored entries); with dedup = 2 it does so where the cost model picks the table form at those
+ * bounds and the table then fits three quarters of the device's memory, and is the per-entry
+ * form's figure otherwise.  Any size that suffices without the
+ * option still works: a range of queries whose table does not fit runs the per-entry form.
  */
 lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int64_t n, int64_t nnz_db,
                                      int64_t q, int64_t nnz_q, lcrwmd_dtype emb_dtype, int k,

@@ -300,6 +300,7 @@ lcrwmd_status run_spmm(lcrwmd_ctx* ctx, const int64_t* rp, const int32_t* ci, co
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
+
 // Vocabulary tile count the token plan sizes its chunks for (it aims at a few thousand (tile, chunk) pairs).  The
 // bf16 kernel balances its load in units of chunks, so it gets eight times as many, shorter chunks.
 int64_t plan_tiles(int64_t nvt, bool bf16) { return bf16 ? (nvt + 7) / 8 : nvt; }
@@ -672,6 +673,7 @@ lcrwmd_status lcrwmd_create(lcrwmd_ctx** out, int device)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
     c->num_cu = prop.multiProcessorCount;
+    c->device_bytes = prop.totalGlobalMem;
     // this device's address of the scratch array behind lcrwmd_topk_noalloc (looked up with the device current)
     if (hipSetDevice(device) != hipSuccess || topk_static_init(device) != hipSuccess) { delete c; return LCRWMD_EHIP; }
     c->opt.validate = 0;
@@ -772,18 +774,24 @@ lcrwmd_status lcrwmd_workspace_bytes(lcrwmd_ctx* ctx, int64_t v, int64_t m, int6
     const size_t f = token_plan_bytes(qr, nnz_q) + close_bits_bytes(qr, ve_max);
     const size_t r = rev_batch_bytes(vq, nb, nnz_db) + tile + close_bits_bytes(nb, vq);
     size_t region = f > r ? f : r;
+    // room for the word-pair table at its upper bound (distinct words <= stored entries); when the library picks the
+    // form, only where its cost model picks the table at those bounds and the table then fits the device (a large
+    // vocabulary against thousands of queries would otherwise ask for a table of terabytes that no range ever builds)
     if (ctx->opt.dedup) {
-        // room for the word-pair table at its upper bound (distinct words <= stored entries)
         const size_t t = (size_t)ve_max * (size_t)(round_up(vq, 32) + 32 * ((vq + 255) / 256)) * 4 + (size_t)(ve_max + 256) * 8 +
                          table_bucket_bytes(vq, qr, nnz_q) + (size_t)n * (size_t)ldz * 4 + 2 * tile + 8192;
-        if (t > region) region = t;
+        const bool wanted = ctx->opt.dedup == 1 ||
+                            (qr <= table_max_queries() && table_form_is_faster(bf16, (int32_t)m, ve_max, vq, n, nnz_db, qr, nnz_q) &&
+                             fixed + zfull + t <= ctx->device_bytes / 4 * 3);
+        if (wanted && t > region) region = t;
     }
     size_t total = fixed + zfull + region + 4096;
     // lcrwmd_rwmd_reduce: the running lists, a block's list and its partial lists, the column sums' scratch
     total += 6 * ((size_t)qr * (size_t)(k > 0 ? k : 1) * 4 + 256) + topk_bytes(nb, qr, k > 0 ? k : 1) + col_sums_bytes(qr) + 2048;
-    // the stand-alone first phase needs norms, the optional bf16 copy and one token plan
+    // the stand-alone first phase needs norms, the optional bf16 copy, one token plan (of either set) and, for the
+    // queries, the map of close pairs (without room for the map the kernel's results are scanned instead)
     size_t p1 = emb_prep_bytes(v, (int32_t)m, bf16, padded, widened) + token_plan_bytes(q > n ? q : n, nnz_q > nnz_db ? nnz_q : nnz_db) +
-                close_bits_bytes(q > n ? q : n, v) + 4096;
+                close_bits_bytes(q, v) + 4096;
     *out_bytes = total > p1 ? total : p1;
     return LCRWMD_OK;
 }

@@ -19,6 +19,7 @@ struct lcrwmd_prof_rec {
 struct lcrwmd_ctx {
     int device;
     int num_cu;
+    size_t device_bytes;              // the device's total memory
     lcrwmd_options opt;
     char err[512];
     bool profiling;

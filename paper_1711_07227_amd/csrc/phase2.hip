@@ -91,20 +91,37 @@ __device__ inline int64_t uniform_i64(int64_t x)
     return (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)x) | ((int64_t)__builtin_amdgcn_readfirstlane((int)(x >> 32)) << 32);
 }
 
+// Which item of a strip-major list of `total` work items this workgroup takes, or -1.  The part has eight XCDs, each
+// with an L2 of its own, and hands workgroup b to XCD b mod 8: item k of XCD x is item x * per + k of the list, so an
+// XCD works through one contiguous eighth of it - its own strips of columns - and its L2 holds segments of Z's rows
+// that no other XCD asks for.  (With the whole chip on one strip at a time every L2 fetched every segment: eight
+// copies of the same lines, an eighth of the cache.)  Any other assignment of workgroups to XCDs is still correct:
+// every item is taken exactly once.  per = ceil(total / 8), grid = 8 * per.
+constexpr int kXcds = 8;
+__device__ inline int64_t xcd_item(int64_t per, int64_t total)
+{
+    const int64_t x = blockIdx.x % kXcds, k = blockIdx.x / kXcds;
+    const int64_t it = x * per + k;
+    return it < total ? it : -1;
+}
+
 // One wavefront per (RPW consecutive rows, strip of 64*W columns); W = 4 uses 16-byte gathers, W = 2 8-byte ones.
-// Units are ordered strip-major and workgroup ids follow that order, so at any time the whole chip works on
-// one strip of columns: the strip of Z (rows of 256 W bytes) is what has to stay in the L2s / Infinity Cache,
-// not the full rows.  The row pointers of a unit are fetched in one load and the entries of the next row are
-// requested before the gathers of the current one.
+// Units are ordered strip-major and dealt to the XCDs in contiguous ranges (xcd_item), so an XCD works on one strip of
+// columns at a time: its strip of Z (rows of 256 W bytes) is what has to stay in its L2, not the full rows.  The row
+// pointers of a unit are fetched in one load and the entries of the next row are requested before the gathers of the
+// current one.
 constexpr int RPW = 4;
 template <int W, int COMBINE>
 __global__ __launch_bounds__(256) void k_spmm_rows(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
                                                    const float* __restrict__ xv, int64_t rows,
                                                    const float* __restrict__ Z, int64_t ldz, int64_t ncols,
-                                                   float* __restrict__ D, int64_t ldd, int64_t strips, int64_t row_units)
+                                                   float* __restrict__ D, int64_t ldd, int64_t strips, int64_t row_units,
+                                                   int64_t per, int64_t total)
 {
     const int lane = threadIdx.x & 63;
-    const int64_t unit = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t item = xcd_item(per, total);
+    if (item < 0) return;
+    const int64_t unit = item * 4 + (threadIdx.x >> 6);
     const int64_t strip = unit / row_units;
     const int64_t i0 = (unit - strip * row_units) * RPW;
     if (strip >= strips) return;
@@ -190,20 +207,23 @@ __global__ __launch_bounds__(256) void k_spmm_tmax(const int64_t* __restrict__ r
 // Transposed maximum, wide form: a workgroup computes a 32 (rows of X) x 256 (columns) tile of S, every wavefront
 // 8 rows with 16-byte gathers exactly as k_spmm_rows does, and turns the tile through LDS so that the
 // read-modify-write of D runs along D's rows (32 consecutive floats = one 128-byte line per column of the tile).
-// Needs 16-byte aligned rows of Z.  Row tiles vary fastest, so the workgroups that share a strip of columns of Z
-// run together.
+// Needs 16-byte aligned rows of Z.  Row tiles vary fastest and the list of tiles is dealt to the XCDs in contiguous
+// ranges (xcd_item), so the workgroups that share a strip of columns of Z share an L2.
 constexpr int WR = 32, WC = 256;
 
 __global__ __launch_bounds__(256) void k_spmm_tmax_wide(const int64_t* __restrict__ rp, const int32_t* __restrict__ ci,
                                                         const float* __restrict__ xv, int64_t rows,
                                                         const float* __restrict__ Z, int64_t ldz, int64_t ncols,
-                                                        float* __restrict__ D, int64_t ldd, int64_t row_tiles)
+                                                        float* __restrict__ D, int64_t ldd, int64_t row_tiles,
+                                                        int64_t per, int64_t total)
 {
     __shared__ float tile[WR][WC + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t ct = blockIdx.x / row_tiles;
-    const int64_t rt = blockIdx.x - ct * row_tiles;
+    const int64_t item = xcd_item(per, total);
+    if (item < 0) return;                       // the whole workgroup: no barrier is left waiting
+    const int64_t ct = item / row_tiles;
+    const int64_t rt = item - ct * row_tiles;
     const int64_t r0 = rt * WR, c0 = ct * WC;
     const int64_t j = c0 + (int64_t)lane * 4;
 
@@ -252,9 +272,9 @@ hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, in
     if (rows <= 0 || ncols <= 0) return hipSuccess;
     if (combine == 2 && (ldz % 4 == 0) && (((uintptr_t)Z & 15) == 0) && ncols >= 128) {
         const int64_t row_tiles = (rows + WR - 1) / WR, col_tiles = (ncols + WC - 1) / WC;
-        const int64_t grid = row_tiles * col_tiles;
+        const int64_t total = row_tiles * col_tiles, per = (total + kXcds - 1) / kXcds, grid = per * kXcds;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        k_spmm_tmax_wide<<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, row_tiles);
+        k_spmm_tmax_wide<<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, row_tiles, per, total);
         return hipGetLastError();
     }
     if (combine == 2) {
@@ -270,9 +290,10 @@ hipError_t launch_spmm(const int64_t* rp, const int32_t* ci, const float* xv, in
     else if ((ldz % 2 == 0) && (((uintptr_t)Z & 7) == 0) && ncols >= 128) W = 2;
     const int64_t strips = (ncols + 64 * W - 1) / (64 * W);
     const int64_t row_units = (rows + RPW - 1) / RPW;
-    const int64_t grid = (row_units * strips + 3) / 4;
+    const int64_t total = (row_units * strips + 3) / 4, per = (total + kXcds - 1) / kXcds, grid = per * kXcds;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-#define LAUNCH_ROWS(WW, CC) k_spmm_rows<WW, CC><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips, row_units)
+#define LAUNCH_ROWS(WW, CC) \
+    k_spmm_rows<WW, CC><<<(unsigned)grid, 256, 0, s>>>(rp, ci, xv, rows, Z, ldz, ncols, D, ldd, strips, row_units, per, total)
     if (W == 4) { if (combine == 0) LAUNCH_ROWS(4, 0); else LAUNCH_ROWS(4, 1); }
     else if (W == 2) { if (combine == 0) LAUNCH_ROWS(2, 0); else LAUNCH_ROWS(2, 1); }
     else { if (combine == 0) LAUNCH_ROWS(1, 0); else LAUNCH_ROWS(1, 1); }

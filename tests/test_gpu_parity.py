@@ -410,6 +410,42 @@ def test_split_bf16_compute_keeps_fp32_tolerance(ctx, tiny):
         ctx.set_options()
 
 
+@pytest.mark.parametrize("offset,pad", [(0, 3), (1, 2), (2, 1), (3, 0), (0, 0), (2, 2)])      # pitch 304 four times, then 301 and 305
+def test_phase1_bf16_with_z_at_any_alignment(ctx, offset, pad):
+    """The bf16 kernel stores four histograms' results at a time where the rows of Z allow aligned 16-byte stores (row
+    pitch a multiple of 4, quads counted from a 16-byte boundary wherever the first column lies) and value by value
+    otherwise: Z as a view that starts `offset` floats into a row of pitch q + offset + pad, hundreds of short
+    histograms, several vocabulary tiles."""
+    print(f"phase1 bf16 offset={offset} pad={pad}", flush=True)
+    v, m, q = 1100, 300, 301
+    Er = bf16_round(synth.embeddings(v, m, 61))
+    qs = synth.corpus(q, v, 1, 12, 1.1, 62)
+    ref = oracle.phase1(Er, qs)
+    Q = binding.Csr.from_numpy(qs, v)
+    big = torch.full((v, q + offset + pad), -9.0, dtype=torch.float32, device="cuda")
+    Z = big[:, offset:offset + q]
+    ws = binding.alloc_workspace(ctx.workspace_bytes(v, m, 0, 0, q, Q.nnz, binding.BF16))
+    ctx.phase1_mindist(torch.from_numpy(Er).cuda().to(torch.bfloat16), Q, Z, ws)
+    torch.cuda.synchronize()
+    bigh = big.cpu().numpy()
+    assert_close(bigh[:, offset:offset + q], ref, what="bf16 Z in an offset view")
+    assert np.all(bigh[:, :offset] == -9.0) and np.all(bigh[:, offset + q:] == -9.0)      # nothing outside the view is touched
+
+
+def test_rwmd_bf16_forward_batches_at_odd_columns(ctx):
+    """Forward batches of 7 queries write column ranges of Z that start at every alignment; blocks of 50 database rows."""
+    p = problem(v=3000, m=300, n=330, q=45, h_lo=1, h_hi=60, seed=71)
+    Er = bf16_round(p["E"])
+    ref = oracle.rwmd_table(Er, p["db"], p["queries"])
+    E, db, qs = upload({"E": Er, "db": p["db"], "queries": p["queries"]}, dtype=torch.bfloat16)
+    ctx.set_options(max_query_batch=7, max_db_batch=50)
+    try:
+        got = run_rwmd(ctx, E, db, qs, emb_dtype=binding.BF16)
+    finally:
+        ctx.set_options()
+    assert_close(got, ref, what="bf16 D, forward batches of 7")
+
+
 def test_rwmd_bf16_tiny_and_ragged(ctx, tiny):
     for p in (tiny, problem(v=3000, m=300, n=700, q=37, h_lo=1, h_hi=90, seed=21)):
         Er = bf16_round(p["E"])

@@ -134,3 +134,17 @@ def test_automatic_choice_of_form(ctx):
     got = run_rwmd(ctx, *upload(p, dtype=torch.bfloat16), emb_dtype=binding.BF16)
     assert ctx.forms_ran() == 1
     assert_close(got, oracle.rwmd_table(p["E"], p["db"], p["queries"]), what="auto form: per entry")
+
+
+def test_workspace_for_the_automatic_choice_follows_the_cost_model(ctx):
+    """dedup = 2 asks for table room only where the table form would be picked: never for a million-word vocabulary
+    against thousands of short queries (a table of terabytes), always for long documents against few queries."""
+    knn = (1_000_000, 300, 1_000_000, 110_000_000, 2048, 225_000, binding.BF16, 16)
+    medium = (100_000, 300, 100_000, 10_000_000, 1000, 100_000, binding.F32, 0)
+    sizes = {}
+    for dedup in (0, 1, 2):
+        ctx.set_options(dedup=dedup)
+        sizes[dedup] = (ctx.workspace_bytes(*knn), ctx.workspace_bytes(*medium))
+    ctx.set_options()
+    assert sizes[2][0] == sizes[0][0] < 200e9 < sizes[1][0]
+    assert sizes[2][1] == sizes[1][1] > sizes[0][1]
