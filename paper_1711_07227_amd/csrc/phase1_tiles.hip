@@ -1,7 +1,11 @@
-// First phase of LC-RWMD (Sec. IV, Fig. 6, many-to-many form): the tile kernel shared by the fp32 and the
-// bf16-in / fp32-accumulate paths, for embedding dimensions up to 300.
+// First phase of LC-RWMD (Sec. IV, Fig. 6, many-to-many form): the tile kernels shared by the fp32, the split-bf16 and
+// the bf16-in / fp32-accumulate paths, for embedding dimensions up to 300.
 //
 //   Z[w][j] = sqrt(max(|E_w|^2 - 2 * max_{a in histogram j} (T_a . E_w - |T_a|^2 / 2), 0))
+//
+// Two kernels: k_phase1_pingpong computes Z (contraction + minimum per histogram, nothing else leaves the
+// accumulators); k_distance_table is the plain pairwise-distance operation C = T o E of Sec. III, every element stored,
+// for the table form of the bound.  They share the layout described here.
 //
 // Token rows are the M dimension of the 32x32 MFMA and vocabulary words the N dimension, so a lane owns one
 // vocabulary word per column tile and 16 token rows: the minimum over a histogram's tokens is lane-local but
@@ -16,7 +20,7 @@
 //     (no registers) into a ring of NBUF buffers, ONE barrier per tile; the copy instructions of the tile
 //     NBUF - 1 ahead are spread over the K steps of the current one so that they never queue up behind each
 //     other.  fp32: 64-row tiles, 2 buffers (a tile is ~44k MFMA clocks, far more than the memory latency);
-//     bf16: 32-row tiles, 4 buffers (a tile is only ~1.2k MFMA clocks: copies have to be three tiles ahead).
+//     bf16 table kernel: 32-row tiles, 4 buffers (a tile is only ~1.2k MFMA clocks: copies have to be three tiles ahead).
 //
 // Rows are handled as 16-byte pieces, 8 pieces (one 128-byte cache line) to an "octet": bf16 rows are 5 octets
 // (the whole 640-byte packed row), fp32 rows 10 octets (1200 bytes = 75 pieces; the pieces past the end of the row
@@ -75,8 +79,8 @@ struct P1T {
     int64_t nvoc;
     int32_t nvt;
     int32_t nchunks;
-    int32_t ntok;              // table mode: number of token rows (tok_ids is readable up to the next multiple of 64 + 64)
-    int32_t chunk_tokens;      // table mode: token rows per chunk (a multiple of 64)
+    int32_t ntok;              // k_distance_table: number of token rows (tok_ids is readable up to the next multiple of 64 + 64)
+    int32_t chunk_tokens;      // k_distance_table: token rows per chunk (a multiple of 64)
     const int32_t* pofs;
     const int32_t* tok_ids;
     const float* tok_hn;
@@ -119,17 +123,16 @@ struct Layout {
 };
 constexpr int kMaxRows = 64;
 
-// TABLE = true turns the kernel into the plain pairwise-distance operation C = T o E of Sec. III: no minimum, every
-// element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0)) is stored, row t (token) x column u (vocabulary position) with
-// pitch ldz.  Tokens are then simply the rows tok_ids[0 .. ntok) cut into chunks of chunk_tokens.
-template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
-__global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
+// The plain pairwise-distance operation C = T o E of Sec. III: every element sqrt(max(|E_u|^2 + |T_t|^2 - 2 T_t . E_u, 0))
+// is stored, row t (token) x column u (vocabulary position) with pitch ldz.  Tokens are the rows tok_ids[0 .. ntok) cut
+// into chunks of chunk_tokens.  One workgroup of four wavefronts per (vocabulary tile of 128 NCT words, chunk).
+template <int MODE, int NCT, int WGS_PER_CU, bool WIDE>
+__global__ __launch_bounds__(256, WGS_PER_CU) void k_distance_table(P1T p)
 {
     using L = Layout<MODE>;
     constexpr bool BF16 = MODE == kBF16, X3 = MODE == kX3;
     constexpr int NS = L::NS, NITER = L::NITER;
     constexpr int ROWS = L::ROWS, NRT = L::NRT, NBUF = L::NBUF, PD = L::PD;
-    constexpr int NG = ROWS / 8;               // token groups per tile
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -159,26 +162,14 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         }
         if (chunk < 0 || chunk >= p.nchunks) return;
     }
-    int s0 = 0, t0, t1;
-    if (TABLE) {
-        t0 = chunk * p.chunk_tokens;
-        t1 = t0 + p.chunk_tokens < p.ntok ? t0 + p.chunk_tokens : p.ntok;
-    } else {
-        s0 = p.chunk_seg[chunk];
-        const int s1 = p.chunk_seg[chunk + 1];
-        if (s0 >= s1) return;
-        t0 = p.pofs[s0];
-        t1 = p.pofs[s1];
-    }
+    const int t0 = chunk * p.chunk_tokens;
+    const int t1 = t0 + p.chunk_tokens < p.ntok ? t0 + p.chunk_tokens : p.ntok;
     if (t0 >= t1) return;
-    (void)s0;
 
     const unsigned char* Eb = p.Eb;
 
     // ---- vocabulary operand -> registers ----
-    // Lanes past the end of the vocabulary repeat its last word: they compute and store the same value to the same
-    // place as the lane that owns it.  Z is written by position in the vocabulary list (registers are scarce: the
-    // row pointer is formed at flush time from the lane id).
+    // Lanes past the end of the vocabulary repeat its last word and store nothing.
     float nEw[NCT];
     f32x4 breg[NS][NCT];
 #pragma unroll
@@ -214,7 +205,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 
     // ---- copy jobs of this wavefront ----
     // job J -> octet J / NRT, row block (of 8 rows) wave + 4 (J % NRT); lane -> row lane / 8, slot lane % 8
-    const int lane8 = lane >> 3;                                   // row within an 8-row block; also this lane's token group
+    const int lane8 = lane >> 3;                                   // row within an 8-row block
     // Source offsets in units of U bytes: 16-byte pieces when the operand rows span 4 GiB or more (32 bits then reach
     // 64 GiB; the host checks it), bytes otherwise.
     constexpr uint32_t U = WIDE ? 16 : 1, PIECE = 16 / U;
@@ -250,29 +241,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
 
     f32x16 acc[NRT][NCT];
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    int cur = -1;
-    float run[NCT];
-#pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) run[ct] = 0.f;
-    auto flush = [&]() {
-        if (cur >= 0) {
-#pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                // both lane halves hold 4 of the 8 rows of every group: exchange and combine
-                const unsigned r = __float_as_uint(run[ct]);
-                const auto sw = __builtin_amdgcn_permlane32_swap(r, r, false, false);
-                const float best = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-                if (half == 0) {
-                    int64_t pos = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
-                    if (pos >= p.nvoc) pos = p.nvoc - 1;
-                    p.Z[pos * p.ldz + cur] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * best, 0.f));
-                }
-            }
-        }
-    };
 
-    // per-tile side data, fetched one tile ahead: group -> histogram (lane g < NG) and, fp32, -|T|^2/2 per row
-    auto load_gs = [&](int tb) { return TABLE ? 0 : (p.grp_seg + (tb >> 3))[lane8]; };   // lanes 8 g .. 8 g + 7 hold group g
+    // per-tile side data, fetched one tile ahead: fp32, -|T|^2/2 per row
     float hn[NRT], hn_next[NRT];
     auto load_hn = [&](int tb, float* h) {
 #pragma unroll
@@ -288,7 +258,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         }
     });
     if (t0 + PD * ROWS < t1) load_words(t0 + PD * ROWS);
-    int gsv = load_gs(t0);
     if (!BF16) load_hn(t0, hn);
     int buf = 0;                               // ring position of the tile being multiplied
 
@@ -392,7 +361,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
             }
             __builtin_amdgcn_sched_barrier(0);
         });
-        if constexpr (WGS_PER_CU > 1) __builtin_amdgcn_s_setprio(3);      // the epilogue's few instructions go first
+        if constexpr (WGS_PER_CU > 1) __builtin_amdgcn_s_setprio(3);      // the stores go first
         if (!BF16) {
             // one more rank-1 step adds -|T_a|^2/2 to every element of token row a
             const float one = half == 0 ? 1.f : 0.f;
@@ -403,49 +372,19 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
                     acc[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(half == 0 ? hn[rt] : 0.f, one, acc[rt][ct], 0, 0, 0);
         }
 
-        if constexpr (TABLE) {
-            // every element is a result: register r of row tile rt is token row 32 rt + 8 (r / 4) + 4 half + r % 4
+        // every element is a result: register r of row tile rt is token row 32 rt + 8 (r / 4) + 4 half + r % 4
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                const int64_t pos = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
-                if (pos < p.nvoc) {
-                    float* out = p.Z + pos;
+        for (int ct = 0; ct < NCT; ++ct) {
+            const int64_t pos = (int64_t)vt * (128 * NCT) + wave * (32 * NCT) + ct * 32 + l31;
+            if (pos < p.nvoc) {
+                float* out = p.Z + pos;
 #pragma unroll
-                    for (int rt = 0; rt < NRT; ++rt)
+                for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = tb + rt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                            if (row < t1) out[(int64_t)row * p.ldz] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * acc[rt][ct][r], 0.f));
-                        }
-                }
-            }
-        }
-        // Epilogue: registers 4g'..4g'+3 of row tile rt hold token rows 32 rt + 8 g' + 4 half + {0..3}: group 4 rt + g'.
-        int ng = TABLE ? 0 : (t1 - tb) >> 3;
-        if (ng > NG) ng = NG;
-        // the groups' histograms move to scalar registers; the register then takes the next tile's (one tile ahead)
-        int sgs[NG];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) sgs[g] = __builtin_amdgcn_readlane(gsv, 8 * g);
-        if (more) gsv = load_gs(tb + ROWS);
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            if (g < ng) {
-                const int sg = sgs[g];
-                const int rt = g >> 2, r0 = (g & 3) * 4;
-                float mg[NCT];
-#pragma unroll
-                for (int ct = 0; ct < NCT; ++ct)
-                    mg[ct] = fmaxf(fmaxf(acc[rt][ct][r0], acc[rt][ct][r0 + 1]), fmaxf(acc[rt][ct][r0 + 2], acc[rt][ct][r0 + 3]));
-                if (sg != cur) {
-                    flush();
-                    cur = sg;
-#pragma unroll
-                    for (int ct = 0; ct < NCT; ++ct) run[ct] = mg[ct];
-                } else {
-#pragma unroll
-                    for (int ct = 0; ct < NCT; ++ct) run[ct] = fmaxf(run[ct], mg[ct]);
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = tb + rt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                        if (row < t1) out[(int64_t)row * p.ldz] = __builtin_amdgcn_sqrtf(fmaxf(nEw[ct] - 2.f * acc[rt][ct][r], 0.f));
+                    }
             }
         }
         if (!BF16) {
@@ -454,7 +393,6 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void k_phase1_tiles(P1T p)
         }
         buf = buf == NBUF - 1 ? 0 : buf + 1;
     }
-    if (!TABLE) flush();
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -862,17 +800,17 @@ __global__ __launch_bounds__(512, 1) void k_phase1_pingpong(P1T p, const int32_t
 
 bool rows_within_4gib(int64_t rows, int64_t pitch_bytes) { return rows * pitch_bytes < ((int64_t)1 << 32); }
 
-template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
+template <int MODE, int NCT, int WGS_PER_CU, bool WIDE>
 hipError_t launch_tiles_w(P1T d, hipStream_t s);
 
-template <int MODE, int NCT, int WGS_PER_CU, bool TABLE>
+template <int MODE, int NCT, int WGS_PER_CU>
 hipError_t launch_tiles(P1T d, int64_t erows, hipStream_t s)
 {
-    return rows_within_4gib(erows, d.pitch_b) ? launch_tiles_w<MODE, NCT, WGS_PER_CU, TABLE, false>(d, s)
-                                              : launch_tiles_w<MODE, NCT, WGS_PER_CU, TABLE, true>(d, s);
+    return rows_within_4gib(erows, d.pitch_b) ? launch_tiles_w<MODE, NCT, WGS_PER_CU, false>(d, s)
+                                              : launch_tiles_w<MODE, NCT, WGS_PER_CU, true>(d, s);
 }
 
-template <int MODE, int NCT, int WGS_PER_CU, bool TABLE, bool WIDE>
+template <int MODE, int NCT, int WGS_PER_CU, bool WIDE>
 hipError_t launch_tiles_w(P1T d, hipStream_t s)
 {
     d.nvt = (int32_t)((d.nvoc + 128 * NCT - 1) / (128 * NCT));
@@ -881,12 +819,12 @@ hipError_t launch_tiles_w(P1T d, hipStream_t s)
     const size_t smem = (size_t)Layout<MODE>::NBUF * (size_t)Layout<MODE>::TILE_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE, WIDE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_distance_table<MODE, NCT, WGS_PER_CU, WIDE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    k_phase1_tiles<MODE, NCT, WGS_PER_CU, TABLE, WIDE><<<(unsigned)grid, 256, smem, s>>>(d);
+    k_distance_table<MODE, NCT, WGS_PER_CU, WIDE><<<(unsigned)grid, 256, smem, s>>>(d);
     return hipGetLastError();
 }
 
@@ -1045,18 +983,18 @@ hipError_t launch_distance_table(const Phase1Args& a, int mode, const int32_t* t
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kBF16>::NOCT * 8;
         d.nzero_from = 0;
-        return launch_tiles<kBF16, 2, 2, true>(d, a.erows, s);
+        return launch_tiles<kBF16, 2, 2>(d, a.erows, s);
     }
     if (mode == 2) {
         d.pitch_b = a.ld * 2;
         d.nreal = Layout<kX3>::NOCT * 8;
         d.nzero_from = 0;
-        return launch_tiles<kX3, 2, 1, true>(d, a.erows, s);
+        return launch_tiles<kX3, 2, 1>(d, a.erows, s);
     }
     d.pitch_b = a.ld * 4;
     d.nreal = a.m / 4;
     d.nzero_from = a.m;
-    return launch_tiles<kF32, 2, 1, true>(d, a.erows, s);
+    return launch_tiles<kF32, 2, 1>(d, a.erows, s);
 }
 
 }  // namespace lcrwmd
