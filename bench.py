@@ -310,7 +310,7 @@ class Job:
         self.torch.cuda.empty_cache()
 
 
-def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False):
+def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_sweep=False):
     """A short run of another workload family at full size: the line's `configs` entry for it."""
     job = Job(name, "f32", batches=steps + warmup)
     try:
@@ -356,6 +356,39 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False):
                 out["all_pairs_sweep"] = {"batches": nbatch, "seconds": sw, "pairs_per_s": job.n * job.n / sw,
                                           "sum_of_all_distances": total,
                                           "includes": "host-side slicing and upload of every batch of queries"}
+            if self_sweep:
+                # the same job in one call: lcrwmd_rwmd_self evaluates every pair once (the bound is symmetric) and
+                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch
+                torch = job.torch
+                rp = job.prob["db"][0]
+                starts = np.arange(0, job.n, job.q)
+                most = int(np.max(rp[np.minimum(starts + job.q, job.n)] - rp[starts]))
+                ws = job.binding.alloc_workspace(job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, job.q, most,
+                                                                         job.emb_dtype, 16))
+                R_idx = torch.empty((job.n, 16), dtype=torch.int32, device="cuda")
+                R_dist = torch.empty((job.n, 16), dtype=torch.float32, device="cuda")
+                sums = torch.empty((job.n,), dtype=torch.float64, device="cuda")
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                job.ctx.rwmd_self(job.db, job.E, job.q, 16, R_idx, R_dist, sums, ws)
+                torch.cuda.synchronize()
+                sw = time.perf_counter() - t0
+                progress(f"all-pairs in one call: {sw:.1f} s")
+                selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": job.q, "k": 16,
+                           "sum_of_all_distances": float(sums.sum()),
+                           "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
+                if with_cpu:
+                    # sampled documents: their lists against the oracle's full columns
+                    import oracle
+                    pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
+                    ref = oracle.rwmd_table(job.prob["E"], job.prob["db"], job.synth.csr_rows(*job.prob["db"], pick))
+                    _, rdist = oracle.topk(ref, 16)
+                    got = R_dist[torch.from_numpy(pick).cuda()].cpu().numpy()
+                    selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
+                    selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
+                                                                               - ref.sum(axis=0)) / ref.sum(axis=0)))
+                out["all_pairs_in_one_call"] = selfrec
+                del ws, R_idx, R_dist, sums
         elif not reduce and job.cfg.h_hi > 200:
             # long documents: the form the library picks by itself
             job.options(dedup=2)
@@ -396,7 +429,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", action="store_true",
                     help="only the timed workload: no variants, no other configurations, no WMD leg (keeps a profile to the timed kernels)")
-    ap.add_argument("--sweep", action="store_true", help="workload short: also run all 245 batches of the all-pairs job (about a minute)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="workload short: also run the whole all-pairs job, batch by batch through lcrwmd_rwmd_reduce (245 "
+                         "calls, over a minute) and in one call of lcrwmd_rwmd_self")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -521,8 +556,9 @@ def main():
     sweep_cfg = None
     if args.workload == "short" and args.sweep:
         job.close()
-        sweep_cfg = config_leg("short", args.steps, args.warmup, min(args.cpu_queries, 8), with_cpu, sweep=True)
+        sweep_cfg = config_leg("short", args.steps, args.warmup, min(args.cpu_queries, 8), with_cpu, sweep=True, self_sweep=True)
         out["all_pairs_sweep"] = sweep_cfg.get("all_pairs_sweep")
+        out["all_pairs_in_one_call"] = sweep_cfg.get("all_pairs_in_one_call")
     else:
         job.close()
 
@@ -532,7 +568,7 @@ def main():
         for name, csteps, cwarm, cq in (("long", 2, 1, 2), ("short", 5, 2, 8), ("knn", 2, 1, 1)):
             t = time.perf_counter()
             try:
-                configs[name] = config_leg(name, csteps, cwarm, cq, with_cpu)
+                configs[name] = config_leg(name, csteps, cwarm, cq, with_cpu, self_sweep=(name == "short"))
             except Exception as e:      # a leg that fails must not take the line with it
                 configs[name] = {"failed": f"{type(e).__name__}: {str(e)[:300]}"}
             configs[name]["leg_wall_s"] = round(time.perf_counter() - t, 1)

@@ -223,6 +223,30 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
                                void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * The all-pairs job within one set of histograms (Sec. IV, "Many-to-many LC-RWMD", with X2 = X1: the set is
+ * compared with itself, `batch` histograms at a time): for every histogram i of `docs`
+ *
+ *     R_idx[i*k .. i*k + k-1], R_dist[...]  its k nearest histograms of the set by the bound D of lcrwmd_rwmd,
+ *                                           ascending by (distance, index); itself included, at distance 0
+ *     dist_sum[i]                           the sum of D(i, j) over all j of the set, accumulated in fp64
+ *
+ * (k = 0: sums only; dist_sum = NULL: lists only).  The n x n matrix is never formed.  The bound is the
+ * maximum of the two one-sided bounds and therefore symmetric, D(i, j) = D(j, i): a batch is compared only
+ * with the histograms from its own first one on, and every tile of distances updates the lists and sums of
+ * its columns (the batch) and of its rows (the later histograms) - half the work of n / batch calls of
+ * lcrwmd_rwmd_reduce.  D(i, j) is evaluated once, with the histogram of the smaller batch as the query: a
+ * list can differ from lcrwmd_rwmd_reduce's in the order of distances that agree to fp32 rounding.
+ * batch: histograms per pass (0 = 4,096; at most 4,096 with dedup = 1).  Workspace:
+ * lcrwmd_workspace_bytes with q = batch and nnz_q = the most stored entries of `batch` consecutive rows;
+ * LCRWMD_EWORKSPACE if it does not suffice (nothing useful is in the outputs then).  docs as for lcrwmd_rwmd;
+ * R_idx, R_dist: n x k; dist_sum: n doubles.  Results do not depend on timing; they do depend on `batch`
+ * and on the database-block option in the last bits of sums and in the order of near-ties.
+ */
+lcrwmd_status lcrwmd_rwmd_self(lcrwmd_ctx* ctx, const lcrwmd_csr* docs, const lcrwmd_emb* E, int64_t batch, int k,
+                               int32_t* R_idx, float* R_dist, double* dist_sum, void* ws, size_t ws_bytes,
+                               void* hip_stream);
+
+/*
  * The bound reduced on the device, for jobs whose n x q matrix is too large to keep (Sec. IV, many-to-many
  * LC-RWMD in batches; Sec. III, top-k): lcrwmd_rwmd_topk's lists (when k > 0; R_idx / R_dist may be NULL when
  * k == 0) and / or, when col_sum is not NULL, the column sums

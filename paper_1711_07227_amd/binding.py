@@ -28,7 +28,7 @@ EXPORTS = (
     "lcrwmd_rwmd_topk", "lcrwmd_topk", "lcrwmd_profile_begin", "lcrwmd_profile_end",
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
     "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc", "lcrwmd_rwmd_reduce", "lcrwmd_forms_ran",
-    "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes", "lcrwmd_probe_mfma",
+    "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes", "lcrwmd_probe_mfma", "lcrwmd_rwmd_self",
 )
 
 
@@ -91,6 +91,7 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_rwmd_reduce.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
+        lib.lcrwmd_rwmd_self.argtypes = [vp, P(CsrStruct), P(EmbStruct), i64, i32, vp, vp, vp, vp, sz, vp]
         lib.lcrwmd_forms_ran.argtypes = [vp]
         lib.lcrwmd_probe_mfma.argtypes = [vp, i32, i32, i32, ctypes.c_double, vp, sz, P(ctypes.c_double), P(ctypes.c_double), vp]
         lib.lcrwmd_rwmd_quadratic.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
@@ -257,6 +258,19 @@ class Context:
         self._check(self._lib.lcrwmd_rwmd_reduce(self._h, ctypes.byref(qs), ctypes.byref(ds), ctypes.byref(es), k,
                                                  R_idx.data_ptr() if k > 0 else None, R_dist.data_ptr() if k > 0 else None,
                                                  col_sum.data_ptr() if col_sum is not None else None, p, nbytes, _stream()))
+
+    def rwmd_self(self, docs: Csr, E: torch.Tensor, batch: int, k: int, R_idx: torch.Tensor | None,
+                  R_dist: torch.Tensor | None, dist_sum: torch.Tensor | None, ws: torch.Tensor):
+        if k > 0:
+            assert R_idx.dtype == torch.int32 and R_dist.dtype == torch.float32 and R_idx.is_contiguous() and R_dist.is_contiguous()
+            assert R_idx.numel() >= docs.rows * k and R_dist.numel() >= docs.rows * k
+        assert dist_sum is None or (dist_sum.is_cuda and dist_sum.dtype == torch.float64 and dist_sum.is_contiguous()
+                                    and dist_sum.numel() >= docs.rows)
+        es, ds = _emb_struct(E), docs.struct()
+        p, nbytes = self._ws(ws)
+        self._check(self._lib.lcrwmd_rwmd_self(self._h, ctypes.byref(ds), ctypes.byref(es), batch, k,
+                                               R_idx.data_ptr() if k > 0 else None, R_dist.data_ptr() if k > 0 else None,
+                                               dist_sum.data_ptr() if dist_sum is not None else None, p, nbytes, _stream()))
 
     def rwmd_quadratic_workspace_bytes(self, v, m, n, nnz_db, q, nnz_q, emb_dtype=F32) -> int:
         out = ctypes.c_size_t()

@@ -411,9 +411,10 @@ bool table_form_is_faster(int mode, int32_t m, int64_t ve, int64_t vq, int64_t n
 //   swapped second phase   tile  = max(tile, (X2 * Z')^T)        (table form: both steps from the table)
 // so a block's tile is produced, completed and consumed while it is cache resident.
 // Returns LCRWMD_EWORKSPACE with *shrink = true when the range's Z does not fit and a smaller range could.
+// db_row0: first database row of the bound (the all-pairs job within one set skips the rows before its batch).
 lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq, int64_t jq0, int64_t jq1,
                         const lcrwmd_csr* DB, const int64_t* rdb, const lcrwmd_emb* E, float* D, int64_t ldd,
-                        TileSink* sink, void* ws, size_t ws_bytes, hipStream_t s, bool* shrink)
+                        TileSink* sink, void* ws, size_t ws_bytes, hipStream_t s, bool* shrink, int64_t db_row0 = 0)
 {
     const int64_t v = E->v, n = DB->rows, q = jq1 - jq0;
     const int64_t qoff = rq[jq0], nnz_q = rq[jq1] - rq[jq0];
@@ -525,12 +526,12 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
                 ProfScope ps(ctx, s, 3, 4.0 * (double)ve * (double)vq + 4.0 * (double)ve * (double)q + 8.0 * (double)nnz_q);
                 HIP_TRY(launch_table_fwd(W, ldw, ve, vc, boffs, bpos, q, Z, ldz, s));
             }
-            for (int64_t i0 = 0; i0 < n; i0 += nb) {
+            for (int64_t i0 = db_row0; i0 < n; i0 += nb) {
                 const int64_t i1 = i0 + nb < n ? i0 + nb : n;
                 const int64_t nnz_b = rdb[i1] - rdb[i0];
                 float* Db = sink ? tile : D + i0 * ldd;
                 const int64_t ldb = sink ? ldz : ldd;
-                ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == 0));
+                ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == db_row0));
                 {   // swapped: one table row per stored database entry, the block read and written once
                     ProfScope ps(ctx, s, 4, 4.0 * (double)nnz_b * (double)vq + 8.0 * (double)(i1 - i0) * (double)q + 4.0 * (double)nnz_b);
                     HIP_TRY(launch_table_rev(W, ldw, vc, DB->row_ptr + i0, dbcol_pos, i1 - i0, boffs, bpos, bval, q, D2, ldz, Db, ldb, s));
@@ -571,7 +572,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     // ---- per block of database rows: forward second phase, swapped first and second phase, D = max(D1, D2^T) ----
     int64_t nb = nb_max;
     for (;;) {
-        int64_t tok = max_tokens_per_batch(rdb, n, nb);
+        int64_t tok = max_tokens_per_batch(rdb + db_row0, n - db_row0, nb);
         if (tok + 7 * nb < kMaxTokens && rev_batch_bytes(vq, nb, tok) + (size_t)nb * tile_row + 256 <= region) break;
         if (nb == 1) {
             if (shrink) *shrink = q > 1;
@@ -580,7 +581,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         nb = (nb + 1) / 2;
     }
     const int64_t nvt_r = (vq + kTileVocab - 1) / kTileVocab;
-    for (int64_t i0 = 0; i0 < n; i0 += nb) {
+    for (int64_t i0 = db_row0; i0 < n; i0 += nb) {
         const int64_t i1 = i0 + nb < n ? i0 + nb : n;
         const int64_t nnz_b = rdb[i1] - rdb[i0];
         Bump bb(b.base + region_off, region);
@@ -593,7 +594,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
         uint64_t* bits = take_close_bits(bb, i1 - i0, vq);
         float* Db = sink ? tile : D + i0 * ldd;
         const int64_t ldb = sink ? ldz : ldd;
-        ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == 0));
+        ST_TRY(run_spmm(ctx, DB->row_ptr + i0, dbcol_pos, DB->val, i1 - i0, nnz_b, ve, Z, ldz, q, Db, ldb, 0, s, i0 == db_row0));
         ST_TRY(run_phase1(ctx, ep, m, list_q, vq, /*z_by_position=*/1, /*zero_map=*/map_q, DB->row_ptr + i0,
                           DB->col_idx, nnz_b, tp, Zr, ldzr, s, /*swapped=*/true, bits));
         // the queries' row_ptr holds offsets into the caller's arrays; shift the renumbered columns to match
@@ -941,6 +942,27 @@ struct ReduceSink : TileSink {
     }
 };
 
+// Sink of lcrwmd_rwmd_self.  A tile holds the distances of histograms [i0, i1) (rows) to the batch [j0, j1) (columns).
+// Columns: as in ReduceSink, except that a column's list starts from what earlier batches already found for that
+// histogram.  Rows beyond the batch: the same distances belong to those histograms' own lists and sums (the bound is
+// symmetric), which are updated in place - no later batch computes these pairs again.
+struct SelfSink : ReduceSink {
+    int64_t j0 = 0, j1 = 0;
+    int32_t* R_idx = nullptr;        // n x k, all histograms
+    float* R_dist = nullptr;
+    double* all_sums = nullptr;      // n, or null
+
+    lcrwmd_status consume(int64_t i0, int64_t i1, const float* tile, int64_t ldt, hipStream_t s) override
+    {
+        ST_TRY(ReduceSink::consume(i0, i1, tile, ldt, s));
+        const int64_t r0 = i0 > j1 ? i0 : j1;          // rows of the batch itself are columns too: nothing to mirror
+        if (r0 < i1)
+            HIP_TRY(launch_topk_rows(tile + (r0 - i0) * ldt, i1 - r0, q, ldt, k, j0, k > 0 ? R_dist + r0 * k : nullptr,
+                                     k > 0 ? R_idx + r0 * k : nullptr, all_sums ? all_sums + r0 : nullptr, s));
+        return LCRWMD_OK;
+    }
+};
+
 }  // namespace
 
 extern "C" {
@@ -1021,6 +1043,88 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
     if (!ctx) return LCRWMD_EINVAL;
     if (k < 1) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
     return lcrwmd_rwmd_reduce(ctx, queries, database, E, k, R_idx, R_dist, nullptr, ws, ws_bytes, hip_stream);
+}
+
+lcrwmd_status lcrwmd_rwmd_self(lcrwmd_ctx* ctx, const lcrwmd_csr* docs, const lcrwmd_emb* E, int64_t batch, int k,
+                               int32_t* R_idx, float* R_dist, double* dist_sum, void* ws, size_t ws_bytes, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ST_TRY(check_rwmd_args(ctx, docs, docs, E));
+    const int64_t n = docs->rows;
+    if (batch < 0) return fail(ctx, LCRWMD_EINVAL, "batch < 0");
+    if (k < 0) return fail(ctx, LCRWMD_EINVAL, "k < 0");
+    if (k == 0 && !dist_sum) return fail(ctx, LCRWMD_EINVAL, "nothing asked for: k == 0 and dist_sum is NULL");
+    if (n == 0) return LCRWMD_OK;
+    if (k > 0 && (!R_idx || !R_dist)) return fail(ctx, LCRWMD_EINVAL, "R_idx or R_dist is NULL");
+    if (k > n) return fail(ctx, LCRWMD_EINVAL, "k must be in [1, n]");
+    if (k > kMaxTopK) return fail(ctx, LCRWMD_EUNSUPPORTED, "k > %d is not supported", kMaxTopK);
+    if (n > 0x7fffffffLL) return fail(ctx, LCRWMD_EUNSUPPORTED, "n exceeds int32 row indices");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    HIP_TRY(hipSetDevice(ctx->device));
+    HostPtr rd, again;
+    ST_TRY(fetch_rows_and_validate(ctx, docs, docs, rd, again, ws, ws_bytes, s));
+    ctx->forms_ran = 0;
+    if (batch == 0) batch = 4096;
+    if (batch > n) batch = n;
+    if (ctx->opt.dedup == 1 && batch > table_max_queries()) batch = table_max_queries();
+    int64_t nb = n < kDbBatch ? n : kDbBatch;
+    if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
+
+    // every list empty, every sum zero
+    if (k > 0) {
+        HIP_TRY(launch_fill_i32(reinterpret_cast<int32_t*>(R_dist), n * k, 0x7f7fffff, s));     // FLT_MAX
+        HIP_TRY(launch_fill_i32(R_idx, n * k, 0x7fffffff, s));
+    }
+    if (dist_sum) HIP_TRY(launch_fill_i32(reinterpret_cast<int32_t*>(dist_sum), 2 * n, 0, s));
+
+    for (int64_t j0 = 0; j0 < n; j0 += batch) {
+        const int64_t j1 = j0 + batch < n ? j0 + batch : n, nq = j1 - j0;
+        Bump b(ws, ws_bytes);
+        SelfSink sink;
+        sink.ctx = ctx;
+        sink.k = k;
+        sink.q = nq;
+        sink.j0 = j0;
+        sink.j1 = j1;
+        sink.R_idx = R_idx;
+        sink.R_dist = R_dist;
+        sink.all_sums = dist_sum;
+        if (k > 0) {
+            for (int t = 0; t < 2; ++t) {
+                sink.run_d[t] = b.take_n<float>((size_t)nq * k);
+                sink.run_i[t] = b.take_n<int32_t>((size_t)nq * k);
+            }
+            sink.blk_d = b.take_n<float>((size_t)nq * k);
+            sink.blk_i = b.take_n<int32_t>((size_t)nq * k);
+            sink.tkb = topk_bytes(nb, nq, k) + 512;
+            sink.tk = b.take(sink.tkb);
+        }
+        if (dist_sum) {
+            sink.sums = dist_sum + j0;
+            sink.part = (double*)b.take(col_sums_bytes(nq));
+        }
+        const size_t off = (b.used + 255) & ~(size_t)255;
+        if (!b.ok || off >= ws_bytes) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the lists of a batch of %lld", (long long)nq);
+        if (k > 0) {
+            // the batch's lists so far: what the rows of earlier batches' tiles put there
+            HIP_TRY(hipMemcpyAsync(sink.run_d[0], R_dist + j0 * k, sizeof(float) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+            HIP_TRY(hipMemcpyAsync(sink.run_i[0], R_idx + j0 * k, sizeof(int32_t) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+        }
+        sink.any = true;                    // lists and sums continue, they do not start
+        bool shrink = false;
+        lcrwmd_status st = rwmd_core(ctx, docs, rd.p, j0, j1, docs, rd.p, E, nullptr, 0, &sink, (char*)ws + off, ws_bytes - off, s,
+                                     &shrink, /*db_row0=*/j0);
+        if (st == LCRWMD_EWORKSPACE)
+            return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for batches of %lld histograms: size it with "
+                        "lcrwmd_workspace_bytes for q = batch, or pass a smaller batch", (long long)batch);
+        if (st != LCRWMD_OK) return st;
+        if (k > 0) {
+            HIP_TRY(hipMemcpyAsync(R_dist + j0 * k, sink.run_d[sink.cur], sizeof(float) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+            HIP_TRY(hipMemcpyAsync(R_idx + j0 * k, sink.run_i[sink.cur], sizeof(int32_t) * (size_t)nq * k, hipMemcpyDeviceToDevice, s));
+        }
+    }
+    return LCRWMD_OK;
 }
 
 int lcrwmd_forms_ran(const lcrwmd_ctx* ctx) { return ctx ? ctx->forms_ran : 0; }

@@ -208,6 +208,10 @@ hipError_t launch_topk_merge2(const float* a_d, const int32_t* a_i, bool have_a,
 size_t col_sums_bytes(int64_t q);
 hipError_t launch_col_sums(const float* tile, int64_t rows, int64_t q, int64_t ldt, double* part, bool first, double* sums,
                            hipStream_t s);
+// rows of a tile against the lists of their histograms (k nearest so far, in place) and their running sums: tile row
+// r, column c is the distance of histogram row (R_dist + r * k) to histogram col_id0 + c
+hipError_t launch_topk_rows(const float* tile, int64_t rows, int64_t q, int64_t ldt, int k, int64_t col_id0, float* R_dist,
+                            int32_t* R_idx, double* row_sum, hipStream_t s);
 // the file-scope device array behind lcrwmd_topk_noalloc: its size, the per-device address look-up (device current)
 size_t topk_static_bytes();
 hipError_t topk_static_init(int device);

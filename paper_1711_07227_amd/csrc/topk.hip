@@ -207,6 +207,68 @@ __global__ void k_col_sums_add(const double* __restrict__ part, int64_t q, int f
     sums[j] = acc;
 }
 
+// Row-wise update for the all-pairs job within one set (lcrwmd_rwmd_self): row r of the tile holds the distances of
+// histogram row0 + r to the histograms col_id0 .. col_id0 + q - 1, and R_dist / R_idx hold that row's k nearest so far
+// (sorted by (distance, index), unfilled slots FLT_MAX / INT_MAX).  One wavefront per row: the list sits in lanes
+// 0 .. k - 1; the row is read 512 values at a time, values that do not beat the list's last entry are skipped, and a
+// value that does is inserted by all lanes at once (its place = the number of entries before it; the entries behind
+// move up one lane).  Candidates are inserted in column order, so the result does not depend on timing.  row_sum (or
+// null): the row's values are added up in fp64 - per lane, then across the lanes in a fixed order - and added to
+// row_sum[r].
+__global__ __launch_bounds__(256) void k_topk_rows(const float* __restrict__ tile, int64_t rows, int64_t q, int64_t ldt,
+                                                   int k, int32_t col_id0, float* __restrict__ R_dist,
+                                                   int32_t* __restrict__ R_idx, double* __restrict__ row_sum)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;                       // whole wavefronts leave
+    const float* row = tile + r * ldt;
+    float ld = FLT_MAX;
+    int32_t li = INT_MAX;
+    if (lane < k) { ld = R_dist[r * k + lane]; li = R_idx[r * k + lane]; }
+    float wd = k > 0 ? __shfl(ld, k - 1) : 0.f;
+    int32_t wi = k > 0 ? __shfl(li, k - 1) : 0;
+    double acc = 0.0;
+    constexpr int UN = 8;
+    for (int64_t c0 = 0; c0 < q; c0 += 64 * UN) {
+        float v[UN];
+#pragma unroll
+        for (int t = 0; t < UN; ++t) {
+            const int64_t c = c0 + 64 * t + lane;
+            v[t] = c < q ? row[c] : FLT_MAX;
+        }
+#pragma unroll
+        for (int t = 0; t < UN; ++t) {
+            const int64_t cb = c0 + 64 * t;
+            const bool ok = cb + lane < q;
+            if (ok) acc += (double)v[t];
+            if (k > 0) {
+                uint64_t cand = __ballot(ok && before(v[t], col_id0 + (int32_t)(cb + lane), wd, wi));
+                while (cand) {
+                    const int l = __builtin_ctzll(cand);
+                    cand &= cand - 1;
+                    const float cv = __shfl(v[t], l);
+                    const int32_t ci = col_id0 + (int32_t)(cb + l);
+                    const int pos = __builtin_popcountll(__ballot(lane < k && before(ld, li, cv, ci)));
+                    if (pos < k) {               // wave-uniform; an earlier insertion of this batch may have closed the gap
+                        const float ud = __shfl_up(ld, 1);
+                        const int32_t ui = __shfl_up(li, 1);
+                        if (lane == pos) { ld = cv; li = ci; }
+                        else if (lane > pos) { ld = ud; li = ui; }
+                        wd = __shfl(ld, k - 1);
+                        wi = __shfl(li, k - 1);
+                    }
+                }
+            }
+        }
+    }
+    if (lane < k) { R_dist[r * k + lane] = ld; R_idx[r * k + lane] = li; }
+    if (row_sum) {
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) row_sum[r] += acc;
+    }
+}
+
 // Scratch of the entry point that allocates nothing: the partial lists live in this array instead of a workspace.
 // Every device the library runs on holds its own copy at its own address; host code uses the address obtained by
 // topk_static_init, never the array's name.
@@ -238,6 +300,15 @@ hipError_t launch_topk_merge2(const float* a_d, const int32_t* a_i, bool have_a,
 {
     if (q <= 0) return hipSuccess;
     k_topk_merge2<<<(unsigned)((q + 63) / 64), 64, 0, s>>>(a_d, a_i, have_a ? 1 : 0, b_d, b_i, (int32_t)row0, q, k, out_d, out_i);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_rows(const float* tile, int64_t rows, int64_t q, int64_t ldt, int k, int64_t col_id0, float* R_dist,
+                            int32_t* R_idx, double* row_sum, hipStream_t s)
+{
+    if (rows <= 0 || q <= 0) return hipSuccess;
+    if (k < 0 || k > 64 || col_id0 + q > 0x7fffffffLL || (rows + 3) / 4 > 0x7fffffffLL) return hipErrorInvalidValue;
+    k_topk_rows<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(tile, rows, q, ldt, k, (int32_t)col_id0, R_dist, R_idx, row_sum);
     return hipGetLastError();
 }
 

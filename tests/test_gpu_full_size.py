@@ -89,6 +89,56 @@ def test_short_text_batches_full_size(ctx):
         del D
 
 
+def test_short_text_all_pairs_in_one_call_full_size(ctx):
+    """The whole all-pairs job, 1,000,000 documents against themselves, through lcrwmd_rwmd_self (245 batches of 4,096,
+    every pair evaluated once): lists and sums of documents from the first, a middle and the last batch against the
+    oracle's full columns, and the first batch's lists against lcrwmd_rwmd_reduce."""
+    cfg = synth.CONFIGS["short"]
+    print("short, all pairs in one call: generating", flush=True)
+    E = synth.embeddings(cfg.v, cfg.m, synth.seed_for(cfg.index, 0), bf16_valued=True)
+    db = synth.corpus(cfg.n, cfg.v, cfg.h_lo, cfg.h_hi, cfg.zipf_s, synth.seed_for(cfg.index, 1))
+    Ed = torch.from_numpy(E).cuda().to(torch.bfloat16)
+    dbd = binding.Csr.from_numpy(db, cfg.v)
+    n, qb, k = cfg.n, cfg.q, 16
+    starts = np.arange(0, n, qb)
+    most = int(np.max(db[0][np.minimum(starts + qb, n)] - db[0][starts]))
+    ws = binding.alloc_workspace(ctx.workspace_bytes(cfg.v, cfg.m, n, dbd.nnz, qb, most, binding.BF16, k))
+    R_idx = torch.full((n, k), -3, dtype=torch.int32, device="cuda")
+    R_dist = torch.full((n, k), -3.0, dtype=torch.float32, device="cuda")
+    S = torch.full((n,), -3.0, dtype=torch.float64, device="cuda")
+    print("short, all pairs in one call: device pass", flush=True)
+    ctx.rwmd_self(dbd, Ed, qb, k, R_idx, R_dist, S, ws)
+    torch.cuda.synchronize()
+    assert bool((R_dist[:, 0] == 0.0).all()) and bool((R_idx >= 0).all()) and bool((R_idx < n).all())
+    assert bool((R_dist[:, 1:] >= R_dist[:, :-1]).all())
+    print("short, all pairs in one call: oracle columns", flush=True)
+    pick = np.array([0, qb - 1, qb, n // 2 + 17, n - 1])
+    ref = oracle.rwmd_table(E, db, synth.csr_rows(*db, pick))
+    ridx, rdist = oracle.topk(ref, k + 1)
+    sel = torch.from_numpy(pick).cuda()
+    gi, gd = R_idx[sel].cpu().numpy(), R_dist[sel].cpu().numpy()
+    assert_close(gd, rdist[:, :k], what="all pairs: list distances")
+    assert_close(S[sel].cpu().numpy(), ref.sum(axis=0), rtol=1e-6, what="all pairs: sums")
+    for t in range(len(pick)):
+        gap_ok = np.diff(rdist[t]) > 8e-6 * np.maximum(rdist[t, 1:], 1e-30)
+        sure = [r for r in range(k) if (r == 0 or gap_ok[r - 1]) and gap_ok[r]]
+        assert len(sure) >= k - 4
+        for r in sure:
+            assert gi[t, r] == ridx[t, r], (pick[t], r)
+    # the first batch through the batch-by-batch entry point: the same lists
+    print("short, all pairs in one call: against lcrwmd_rwmd_reduce", flush=True)
+    rows = np.arange(qb)
+    qs = binding.Csr.from_numpy(synth.csr_rows(*db, rows), cfg.v)
+    Ri = torch.empty((qb, k), dtype=torch.int32, device="cuda")
+    Rd = torch.empty((qb, k), dtype=torch.float32, device="cuda")
+    Sq = torch.empty((qb,), dtype=torch.float64, device="cuda")
+    ctx.rwmd_reduce(qs, dbd, Ed, k, Ri, Rd, Sq, ws)
+    torch.cuda.synchronize()
+    assert_close(R_dist[:qb].cpu().numpy(), Rd.cpu().numpy(), rtol=2e-6, what="all pairs against reduce: distances")
+    assert_close(S[:qb].cpu().numpy(), Sq.cpu().numpy(), rtol=1e-9, what="all pairs against reduce: sums")
+    assert float((R_idx[:qb] == Ri).float().mean()) > 0.999
+
+
 def test_large_vocabulary_knn_full_size(ctx):
     cfg = synth.CONFIGS["knn"]
     print("knn, full size: generating", flush=True)
