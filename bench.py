@@ -358,37 +358,40 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_swe
                                           "includes": "host-side slicing and upload of every batch of queries"}
             if self_sweep:
                 # the same job in one call: lcrwmd_rwmd_self evaluates every pair once (the bound is symmetric) and
-                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch
+                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch.  Batches of
+                # 16,384 (what the entry point picks by itself in a workspace of this size); with --sweep also 4,096.
                 torch = job.torch
                 rp = job.prob["db"][0]
-                starts = np.arange(0, job.n, job.q)
-                most = int(np.max(rp[np.minimum(starts + job.q, job.n)] - rp[starts]))
-                ws = job.binding.alloc_workspace(job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, job.q, most,
-                                                                         job.emb_dtype, 16))
                 R_idx = torch.empty((job.n, 16), dtype=torch.int32, device="cuda")
                 R_dist = torch.empty((job.n, 16), dtype=torch.float32, device="cuda")
                 sums = torch.empty((job.n,), dtype=torch.float64, device="cuda")
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                job.ctx.rwmd_self(job.db, job.E, job.q, 16, R_idx, R_dist, sums, ws)
-                torch.cuda.synchronize()
-                sw = time.perf_counter() - t0
-                progress(f"all-pairs in one call: {sw:.1f} s")
-                selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": job.q, "k": 16,
-                           "sum_of_all_distances": float(sums.sum()),
-                           "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
-                if with_cpu:
-                    # sampled documents: their lists against the oracle's full columns
-                    import oracle
-                    pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
-                    ref = oracle.rwmd_table(job.prob["E"], job.prob["db"], job.synth.csr_rows(*job.prob["db"], pick))
-                    _, rdist = oracle.topk(ref, 16)
-                    got = R_dist[torch.from_numpy(pick).cuda()].cpu().numpy()
-                    selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
-                    selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
-                                                                               - ref.sum(axis=0)) / ref.sum(axis=0)))
-                out["all_pairs_in_one_call"] = selfrec
-                del ws, R_idx, R_dist, sums
+                for qb in ((16384, job.q) if sweep else (16384,)):
+                    starts = np.arange(0, job.n, qb)
+                    most = int(np.max(rp[np.minimum(starts + qb, job.n)] - rp[starts]))
+                    ws = job.binding.alloc_workspace(job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, qb, most,
+                                                                             job.emb_dtype, 16))
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    job.ctx.rwmd_self(job.db, job.E, qb, 16, R_idx, R_dist, sums, ws)
+                    torch.cuda.synchronize()
+                    sw = time.perf_counter() - t0
+                    del ws
+                    progress(f"all-pairs in one call, batches of {qb}: {sw:.1f} s")
+                    selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": qb, "k": 16,
+                               "sum_of_all_distances": float(sums.sum()),
+                               "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
+                    if with_cpu and qb == 16384:
+                        # sampled documents: their lists against the oracle's full columns
+                        import oracle
+                        pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
+                        ref = oracle.rwmd_table(job.prob["E"], job.prob["db"], job.synth.csr_rows(*job.prob["db"], pick))
+                        _, rdist = oracle.topk(ref, 16)
+                        got = R_dist[torch.from_numpy(pick).cuda()].cpu().numpy()
+                        selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
+                        selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
+                                                                                   - ref.sum(axis=0)) / ref.sum(axis=0)))
+                    out["all_pairs_in_one_call" if qb == 16384 else "all_pairs_in_one_call_batches_of_%d" % qb] = selfrec
+                del R_idx, R_dist, sums
         elif not reduce and job.cfg.h_hi > 200:
             # long documents: the form the library picks by itself
             job.options(dedup=2)
@@ -558,7 +561,9 @@ def main():
         job.close()
         sweep_cfg = config_leg("short", args.steps, args.warmup, min(args.cpu_queries, 8), with_cpu, sweep=True, self_sweep=True)
         out["all_pairs_sweep"] = sweep_cfg.get("all_pairs_sweep")
-        out["all_pairs_in_one_call"] = sweep_cfg.get("all_pairs_in_one_call")
+        for key in sweep_cfg:
+            if key.startswith("all_pairs_in_one_call"):
+                out[key] = sweep_cfg[key]
     else:
         job.close()
 

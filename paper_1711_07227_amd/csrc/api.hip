@@ -437,10 +437,12 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     int32_t* qcol_pos = b.take_n<int32_t>((size_t)nnz_q);
     if (!b.ok) return fail(ctx, LCRWMD_EWORKSPACE, "workspace too small for the vocabulary maps");
 
+    // the database's words: those of the rows the bound covers (all of them unless db_row0 says otherwise)
+    const int64_t e0 = rdb[db_row0], nnz_used = DB->nnz - e0;
     HIP_TRY(launch_fill_i32(flags, v, 0, s));
-    HIP_TRY(launch_mark_words(DB->col_idx, DB->nnz, flags, s));
+    HIP_TRY(launch_mark_words(DB->col_idx + e0, nnz_used, flags, s));
     HIP_TRY(launch_compact_words(flags, v, list_db, map_db, counters + 0, s));
-    HIP_TRY(launch_remap_cols(DB->col_idx, DB->nnz, map_db, dbcol_pos, s));
+    HIP_TRY(launch_remap_cols(DB->col_idx + e0, nnz_used, map_db, dbcol_pos + e0, s));
     HIP_TRY(launch_fill_i32(flags, v, 0, s));
     HIP_TRY(launch_mark_words(Q->col_idx + qoff, nnz_q, flags, s));
     HIP_TRY(launch_compact_words(flags, v, list_q, map_q, counters + 1, s));
@@ -468,7 +470,7 @@ lcrwmd_status rwmd_core(lcrwmd_ctx* ctx, const lcrwmd_csr* Q, const int64_t* rq,
     // ---- table form: one word-pair table for the range, both directions read it ----
     bool table = false;
     if (ctx->opt.dedup && ve > 0 && vq > 0 && q <= table_max_queries() &&
-        (ctx->opt.dedup == 1 || table_form_is_faster(ep.mode, m, ve, vq, n, DB->nnz, q, nnz_q))) {
+        (ctx->opt.dedup == 1 || table_form_is_faster(ep.mode, m, ve, vq, n - db_row0, nnz_used, q, nnz_q))) {
         Phase1Args a;
         a.E = ep.data;
         a.ld = ep.ld;
@@ -1065,9 +1067,25 @@ lcrwmd_status lcrwmd_rwmd_self(lcrwmd_ctx* ctx, const lcrwmd_csr* docs, const lc
     HostPtr rd, again;
     ST_TRY(fetch_rows_and_validate(ctx, docs, docs, rd, again, ws, ws_bytes, s));
     ctx->forms_ran = 0;
-    if (batch == 0) batch = 4096;
+    const int64_t batch_cap = ctx->opt.dedup == 1 ? table_max_queries() : n;
+    if (batch == 0) {
+        // the largest power of two up to 16,384 whose workspace figure fits: larger batches share more of their words,
+        // so the swapped first phase - rows of Z' = distinct words of a batch - does less work in total
+        for (batch = 16384; batch > 1; batch /= 2) {
+            const int64_t bb = batch < n ? batch : n;
+            int64_t most = 0;
+            for (int64_t a = 0; a < n; a += bb) {
+                const int64_t e = rd.p[a + bb < n ? a + bb : n] - rd.p[a];
+                if (e > most) most = e;
+            }
+            size_t need = 0;
+            if (bb <= batch_cap && lcrwmd_workspace_bytes(ctx, E->v, E->m, n, docs->nnz, bb, most, E->dtype, k, &need) == LCRWMD_OK &&
+                need <= ws_bytes)
+                break;
+        }
+    }
     if (batch > n) batch = n;
-    if (ctx->opt.dedup == 1 && batch > table_max_queries()) batch = table_max_queries();
+    if (batch > batch_cap) batch = batch_cap;
     int64_t nb = n < kDbBatch ? n : kDbBatch;
     if (ctx->opt.max_db_batch > 0 && nb > ctx->opt.max_db_batch) nb = ctx->opt.max_db_batch;
 
