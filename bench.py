@@ -358,18 +358,25 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_swe
                                           "includes": "host-side slicing and upload of every batch of queries"}
             if self_sweep:
                 # the same job in one call: lcrwmd_rwmd_self evaluates every pair once (the bound is symmetric) and
-                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch.  Batches of
-                # 16,384 (what the entry point picks by itself in a workspace of this size); with --sweep also 4,096.
+                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch.  In the
+                # largest batches (a power of two up to 65,536) whose workspace fits the free memory - what the entry point
+                # picks by itself in a workspace of that size; with --sweep also in batches of 4,096.
                 torch = job.torch
                 rp = job.prob["db"][0]
+                job.D = job.ws = None
+                torch.cuda.empty_cache()
+                def self_ws_bytes(qb):
+                    starts = np.arange(0, job.n, qb)
+                    most = int(np.max(rp[np.minimum(starts + qb, job.n)] - rp[starts]))
+                    return job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, qb, most, job.emb_dtype, 16)
+                big = 65536
+                while big > job.q and self_ws_bytes(big) > 0.85 * torch.cuda.mem_get_info()[0]:
+                    big //= 2
                 R_idx = torch.empty((job.n, 16), dtype=torch.int32, device="cuda")
                 R_dist = torch.empty((job.n, 16), dtype=torch.float32, device="cuda")
                 sums = torch.empty((job.n,), dtype=torch.float64, device="cuda")
-                for qb in ((16384, job.q) if sweep else (16384,)):
-                    starts = np.arange(0, job.n, qb)
-                    most = int(np.max(rp[np.minimum(starts + qb, job.n)] - rp[starts]))
-                    ws = job.binding.alloc_workspace(job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, qb, most,
-                                                                             job.emb_dtype, 16))
+                for qb in ((big, job.q) if sweep and big != job.q else (big,)):
+                    ws = job.binding.alloc_workspace(self_ws_bytes(qb))
                     torch.cuda.synchronize()
                     t0 = time.perf_counter()
                     job.ctx.rwmd_self(job.db, job.E, qb, 16, R_idx, R_dist, sums, ws)
@@ -380,7 +387,7 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_swe
                     selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": qb, "k": 16,
                                "sum_of_all_distances": float(sums.sum()),
                                "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
-                    if with_cpu and qb == 16384:
+                    if with_cpu and qb == big:
                         # sampled documents: their lists against the oracle's full columns
                         import oracle
                         pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
@@ -390,7 +397,7 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_swe
                         selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
                         selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
                                                                                    - ref.sum(axis=0)) / ref.sum(axis=0)))
-                    out["all_pairs_in_one_call" if qb == 16384 else "all_pairs_in_one_call_batches_of_%d" % qb] = selfrec
+                    out["all_pairs_in_one_call" if qb == big else "all_pairs_in_one_call_batches_of_%d" % qb] = selfrec
                 del R_idx, R_dist, sums
         elif not reduce and job.cfg.h_hi > 200:
             # long documents: the form the library picks by itself

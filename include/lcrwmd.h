@@ -236,9 +236,10 @@ lcrwmd_status lcrwmd_rwmd_topk(lcrwmd_ctx* ctx, const lcrwmd_csr* queries, const
  * its columns (the batch) and of its rows (the later histograms) - half the work of n / batch calls of
  * lcrwmd_rwmd_reduce.  D(i, j) is evaluated once, with the histogram of the smaller batch as the query: a
  * list can differ from lcrwmd_rwmd_reduce's in the order of distances that agree to fp32 rounding.
- * batch: histograms per pass (at most 4,096 with dedup = 1); 0 = the largest power of two up to 16,384 whose
+ * batch: histograms per pass (at most 4,096 with dedup = 1); 0 = the largest power of two up to 65,536 whose
  * workspace figure fits ws_bytes (larger batches share more of their words and cost less in total: the
- * 1,000,000-document job of the benchmark set takes 41 s in batches of 4,096 and 32 s in batches of 16,384).  Workspace:
+ * 1,000,000-document job of the benchmark set takes 39 s in batches of 4,096, 30 s in batches of 16,384 and
+ * 24.5 s in batches of 65,536, for which the workspace figure is 171 GB).  Workspace:
  * lcrwmd_workspace_bytes with q = batch and nnz_q = the most stored entries of `batch` consecutive rows;
  * LCRWMD_EWORKSPACE if it does not suffice (nothing useful is in the outputs then).  docs as for lcrwmd_rwmd;
  * R_idx, R_dist: n x k; dist_sum: n doubles.  Results do not depend on timing; they do depend on `batch`

@@ -1069,9 +1069,9 @@ lcrwmd_status lcrwmd_rwmd_self(lcrwmd_ctx* ctx, const lcrwmd_csr* docs, const lc
     ctx->forms_ran = 0;
     const int64_t batch_cap = ctx->opt.dedup == 1 ? table_max_queries() : n;
     if (batch == 0) {
-        // the largest power of two up to 16,384 whose workspace figure fits: larger batches share more of their words,
+        // the largest power of two up to 65,536 whose workspace figure fits: larger batches share more of their words,
         // so the swapped first phase - rows of Z' = distinct words of a batch - does less work in total
-        for (batch = 16384; batch > 1; batch /= 2) {
+        for (batch = 65536; batch > 1; batch /= 2) {
             const int64_t bb = batch < n ? batch : n;
             int64_t most = 0;
             for (int64_t a = 0; a < n; a += bb) {
