@@ -442,6 +442,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="workload short: also run the whole all-pairs job, batch by batch through lcrwmd_rwmd_reduce (245 "
                          "calls, over a minute) and in one call of lcrwmd_rwmd_self")
+    ap.add_argument("--all-pairs", action="store_true",
+                    help="workload short: also run the whole all-pairs job in one call of lcrwmd_rwmd_self (half a minute)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (outside the timed region): a kernel of known "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -564,9 +566,9 @@ def main():
     }
     out.update(extra)
     sweep_cfg = None
-    if args.workload == "short" and args.sweep:
+    if args.workload == "short" and (args.sweep or args.all_pairs):
         job.close()
-        sweep_cfg = config_leg("short", args.steps, args.warmup, min(args.cpu_queries, 8), with_cpu, sweep=True, self_sweep=True)
+        sweep_cfg = config_leg("short", args.steps, args.warmup, min(args.cpu_queries, 8), with_cpu, sweep=args.sweep, self_sweep=True)
         out["all_pairs_sweep"] = sweep_cfg.get("all_pairs_sweep")
         for key in sweep_cfg:
             if key.startswith("all_pairs_in_one_call"):
