@@ -121,3 +121,19 @@ def test_self_bf16_matches_the_batch_by_batch_job(ctx):
         assert_close(gd[rows], R_dist.cpu().numpy(), rtol=2e-6, what="self against reduce: distances")
         assert_close(gs[rows], S.cpu().numpy(), rtol=1e-6, what="self against reduce: sums")
         assert (gi[rows] == R_idx.cpu().numpy()).mean() > 0.99
+
+
+@pytest.mark.parametrize("n,batch,k", [(1, 0, 1), (5, 2, 5), (9, 1, 3), (64, 64, 64)])
+def test_self_on_very_small_sets(ctx, n, batch, k):
+    """One document (its only neighbour is itself), lists as long as the set, batches of one."""
+    v = 400
+    E = synth.embeddings(v, 300, 91)
+    docs = synth.corpus(n, v, 2, 12, 1.0, 92 + n)
+    gi, gd, gs = run_self(ctx, E, docs, v, batch, k)
+    ref = oracle.rwmd_table(E, docs, docs).reshape(n, n)
+    ridx, rdist = oracle.topk(ref, k)
+    assert_close(gd, rdist, what=f"n={n}: distances")
+    assert_close(gs, ref.sum(axis=1), rtol=1e-6, what=f"n={n}: sums")
+    for i in range(n):
+        assert sorted(gi[i]) == sorted(ridx[i]) or k < n, (n, i)
+        assert i in gi[i][gd[i] == 0.0]
