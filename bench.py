@@ -450,6 +450,9 @@ def main():
     ap.add_argument("--mfma-probe", action="store_true",
                     help="instead of a workload: bare MFMA loops (lcrwmd_probe_mfma) in fp32 and bf16, on zero and on random "
                          "operands, from registers and with the A operand from LDS; prints their rates and shader clocks")
+    ap.add_argument("--gather-probe", action="store_true",
+                    help="instead of a workload: the rate at which wavefronts gather row segments as the second phase does "
+                         "(lcrwmd_probe_gather), by number of distinct segments and load width")
     ap.add_argument("--cpu-queries", type=int, default=48, help="queries in the CPU oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -473,6 +476,19 @@ def main():
                                  "TFLOPs": tf, "of_peak": tf / peak, "shader_MHz": mhz})
                     progress(f"probe {name} {'random' if random_data else 'zero'} {'lds' if lds else 'reg'}: {tf:.1f} TFLOP/s at {mhz:.0f} MHz")
         print(json.dumps({"mfma_probe": rows, "peaks_TFLOPs": {"bf16": PEAK_BF16_MFMA_TFLOPS, "f32": PEAK_F32_MFMA_TFLOPS}}))
+        return
+    if args.gather_probe:
+        from paper_1711_07227_amd import binding
+        ctx = binding.Context(0)
+        rows = []
+        for segments in (128, 2048, 16384, 262144):
+            for width in (4, 2, 1):
+                tb = ctx.probe_gather(segments, width)
+                rows.append({"segments": segments, "distinct_MiB": segments * 64 * width * 4 / 2 ** 20, "bytes_per_lane": 4 * width,
+                             "TBps": tb})
+                progress(f"gather probe: {segments} segments, {4 * width} bytes per lane: {tb:.1f} TB/s")
+        print(json.dumps({"gather_probe": rows, "what": "wavefronts gather 64 x bytes_per_lane consecutive bytes of pseudo-random "
+                          "rows (pitch 16 KiB), eight loads in flight per wavefront, eight workgroups per CU"}))
         return
     main_is_default = args.workload == "medium" and args.compute == "f32" and args.dedup == 0 and not args.reduce
 

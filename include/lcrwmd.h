@@ -322,6 +322,18 @@ lcrwmd_status lcrwmd_profile_end(lcrwmd_ctx* ctx, lcrwmd_profile* out);
 lcrwmd_status lcrwmd_probe_mfma(lcrwmd_ctx* ctx, lcrwmd_dtype dtype, int random_data, int a_from_lds, double seconds,
                                 void* ws, size_t ws_bytes, double* tflops, double* shader_mhz, void* hip_stream);
 
+/*
+ * Diagnostic for benchmarks (not part of the method): the rate at which wavefronts gather row segments the way the
+ * second phase does (Sec. IV, Fig. 7: every stored entry reads a row of Z) - 64 * floats_per_lane consecutive floats
+ * of a pseudo-random row per load, eight loads in flight per wavefront, eight workgroups per CU - from a table of
+ * `segments` rows (a power of two, at most 2^24) with a pitch of 16 KiB.  floats_per_lane 4 is the second phase's own
+ * 16-byte load (1 KiB per wavefront and load), 2 and 1 the narrower ones.  The number of distinct segments decides
+ * which cache level serves them.  Output (HOST): terabytes per second loaded by the lanes.
+ * Workspace: segments * 16 KiB + 256 bytes (cleared by the call).  Synchronises the stream.
+ */
+lcrwmd_status lcrwmd_probe_gather(lcrwmd_ctx* ctx, int64_t segments, int floats_per_lane, void* ws, size_t ws_bytes,
+                                  double* tbytes_per_s, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Exact WMD behind the RWMD bound (Sec. II, Sec. III).  These calls take fp32 or bf16 E of any m and
  * pitch.  Cost matrices are fp32: |a|^2 + |b|^2 - 2 a.b on the matrix cores where the two words lie

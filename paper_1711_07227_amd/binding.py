@@ -29,6 +29,7 @@ EXPORTS = (
     "lcrwmd_wcd", "lcrwmd_wmd_pairs_workspace_bytes", "lcrwmd_wmd_pairs", "lcrwmd_wmd_topk_workspace_bytes",
     "lcrwmd_wmd_topk", "lcrwmd_topk_noalloc", "lcrwmd_rwmd_reduce", "lcrwmd_forms_ran",
     "lcrwmd_rwmd_quadratic", "lcrwmd_rwmd_quadratic_workspace_bytes", "lcrwmd_probe_mfma", "lcrwmd_rwmd_self",
+    "lcrwmd_probe_gather",
 )
 
 
@@ -92,6 +93,7 @@ def load_library() -> ctypes.CDLL:
         lib.lcrwmd_rwmd_topk.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, sz, vp]
         lib.lcrwmd_rwmd_reduce.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), i32, vp, vp, vp, vp, sz, vp]
         lib.lcrwmd_rwmd_self.argtypes = [vp, P(CsrStruct), P(EmbStruct), i64, i32, vp, vp, vp, vp, sz, vp]
+        lib.lcrwmd_probe_gather.argtypes = [vp, i64, i32, vp, sz, P(ctypes.c_double), vp]
         lib.lcrwmd_forms_ran.argtypes = [vp]
         lib.lcrwmd_probe_mfma.argtypes = [vp, i32, i32, i32, ctypes.c_double, vp, sz, P(ctypes.c_double), P(ctypes.c_double), vp]
         lib.lcrwmd_rwmd_quadratic.argtypes = [vp, P(CsrStruct), P(CsrStruct), P(EmbStruct), vp, i64, vp, sz, vp]
@@ -271,6 +273,13 @@ class Context:
         self._check(self._lib.lcrwmd_rwmd_self(self._h, ctypes.byref(ds), ctypes.byref(es), batch, k,
                                                R_idx.data_ptr() if k > 0 else None, R_dist.data_ptr() if k > 0 else None,
                                                dist_sum.data_ptr() if dist_sum is not None else None, p, nbytes, _stream()))
+
+    def probe_gather(self, segments: int, floats_per_lane: int = 4) -> float:
+        ws = alloc_workspace(segments * 16384 + 256)
+        p, nbytes = self._ws(ws)
+        out = ctypes.c_double()
+        self._check(self._lib.lcrwmd_probe_gather(self._h, segments, floats_per_lane, p, nbytes, ctypes.byref(out), _stream()))
+        return float(out.value)
 
     def rwmd_quadratic_workspace_bytes(self, v, m, n, nnz_db, q, nnz_q, emb_dtype=F32) -> int:
         out = ctypes.c_size_t()

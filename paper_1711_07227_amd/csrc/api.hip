@@ -1147,6 +1147,42 @@ lcrwmd_status lcrwmd_rwmd_self(lcrwmd_ctx* ctx, const lcrwmd_csr* docs, const lc
 
 int lcrwmd_forms_ran(const lcrwmd_ctx* ctx) { return ctx ? ctx->forms_ran : 0; }
 
+lcrwmd_status lcrwmd_probe_gather(lcrwmd_ctx* ctx, int64_t segments, int floats_per_lane, void* ws, size_t ws_bytes,
+                                  double* tbytes_per_s, void* hip_stream)
+{
+    if (!ctx) return LCRWMD_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (!tbytes_per_s) return fail(ctx, LCRWMD_EINVAL, "the output pointer is NULL");
+    if (segments < 1 || segments > ((int64_t)1 << 24) || (segments & (segments - 1)) != 0)
+        return fail(ctx, LCRWMD_EINVAL, "segments must be a power of two in [1, 2^24]");
+    if (floats_per_lane != 1 && floats_per_lane != 2 && floats_per_lane != 4)
+        return fail(ctx, LCRWMD_EINVAL, "floats_per_lane must be 1, 2 or 4");
+    ST_TRY(check_ws(ctx, ws, ws_bytes));
+    const size_t table = (size_t)segments * 4096 * 4;
+    if (ws_bytes < table + 256) return fail(ctx, LCRWMD_EWORKSPACE, "the probe needs %zu bytes", table + 256);
+    HIP_TRY(hipSetDevice(ctx->device));
+    float* T = (float*)ws;
+    float* out = (float*)((char*)ws + table);
+    HIP_TRY(launch_fill_i32((int32_t*)ws, (int64_t)(table / 4) + 1, 0, s));
+    const int blocks = ctx->num_cu * 8, iters = 400;
+    double bytes = 0.0;
+    HIP_TRY(launch_probe_gather(T, segments, floats_per_lane, blocks, iters / 4, out, &bytes, s));     // warm-up: caches and clock
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(ctx, LCRWMD_EHIP, "hipEventCreate failed"); }
+    float ms = 0.f;
+    hipError_t e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch_probe_gather(T, segments, floats_per_lane, blocks, iters, out, &bytes, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return fail(ctx, LCRWMD_EHIP, "probe failed: %s", hipGetErrorString(e));
+    *tbytes_per_s = bytes / (ms * 1e-3) / 1e12;
+    return LCRWMD_OK;
+}
+
 lcrwmd_status lcrwmd_probe_mfma(lcrwmd_ctx* ctx, lcrwmd_dtype dtype, int random_data, int a_from_lds, double seconds,
                                 void* ws, size_t ws_bytes, double* tflops, double* shader_mhz, void* hip_stream)
 {

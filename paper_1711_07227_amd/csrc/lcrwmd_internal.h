@@ -219,6 +219,8 @@ void* topk_static_ptr(int device);
 
 // probe.hip: bare MFMA loops (diagnostic)
 size_t probe_bytes(int num_cu);
+hipError_t launch_probe_gather(const float* T, int64_t rows, int width, int blocks, int iters, float* out, double* bytes,
+                               hipStream_t s);
 hipError_t launch_probe_mfma(bool bf16, bool random, bool a_from_lds, int iters, int num_cu, void* ws, double* flops,
                              long long** clk_dev, hipStream_t s);
 

@@ -5,6 +5,8 @@
 // its instruction stream looks like.  lcrwmd_probe_mfma measures that ceiling: a loop of nothing but MFMAs on
 // operands held in registers (or with the A operand re-read from LDS every two MFMAs, the rate of the first-phase
 // kernel), timed with events; the shader clock follows from the ratio of the cycle counter to the wall-clock counter.
+// lcrwmd_probe_gather does the same for the second phase: the rate at which wavefronts gather row segments from a
+// table, as a function of how many distinct segments there are (which cache level serves them).
 #include "lcrwmd_internal.h"
 
 namespace lcrwmd {
@@ -67,7 +69,48 @@ __global__ __launch_bounds__(256) void k_probe_mfma(const f32x4* __restrict__ in
     if (threadIdx.x == 0 && blockIdx.x == 0) { clk[0] = c1 - c0; clk[1] = w1 - w0; }
 }
 
+// Gathers as the second phase issues them: a wavefront reads the first 64 * W floats (W = 4: 1 KiB, one 16-byte load per
+// lane) of a pseudo-random row of a table with a pitch of 16 KiB, eight rows requested before the first is used.  What
+// varies is the number of distinct rows, i.e. whether the gathered segments fit an XCD's L2, the Infinity Cache, or
+// neither.  Row numbers come from a per-wavefront linear congruential sequence masked to the table's (power of two)
+// row count.
+template <int W>
+__global__ __launch_bounds__(256) void k_probe_gather(const float* __restrict__ T, uint32_t row_mask, int iters, float* __restrict__ out)
+{
+    typedef float vecw __attribute__((ext_vector_type(W)));
+    const int lane = threadIdx.x & 63;
+    uint32_t seed = __builtin_amdgcn_readfirstlane((blockIdx.x * 4 + (threadIdx.x >> 6)) * 2654435761u + 12345u);
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        vecw z[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            seed = seed * 1664525u + 1013904223u;
+            const uint32_t r = (seed >> 8) & row_mask;
+            z[k] = *reinterpret_cast<const vecw*>(T + (int64_t)r * 4096 + lane * W);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int t = 0; t < W; ++t) acc += reinterpret_cast<const float*>(&z[k])[t];
+    }
+    if (acc == 123.456f) out[0] = acc;          // keeps the loads alive; the table holds zeros
+}
+
 }  // namespace
+
+// One launch: `blocks` workgroups of four wavefronts, each wavefront `iters` groups of eight gathers of 64 * W floats
+// from a table of `rows` rows (a power of two) x 4096 floats at T.  *bytes: what the lanes loaded.
+hipError_t launch_probe_gather(const float* T, int64_t rows, int width, int blocks, int iters, float* out, double* bytes,
+                               hipStream_t s)
+{
+    const uint32_t mask = (uint32_t)(rows - 1);
+    if (width == 4) k_probe_gather<4><<<blocks, 256, 0, s>>>(T, mask, iters, out);
+    else if (width == 2) k_probe_gather<2><<<blocks, 256, 0, s>>>(T, mask, iters, out);
+    else k_probe_gather<1><<<blocks, 256, 0, s>>>(T, mask, iters, out);
+    *bytes = (double)blocks * 4 * (double)iters * 8 * 64 * width * 4;
+    return hipGetLastError();
+}
 
 size_t probe_bytes(int num_cu) { return 4096 * 16 + (size_t)num_cu * 2 * 256 * 4 + 256 + 64; }
 
