@@ -579,6 +579,12 @@ def main():
         "variants": variants or None,
         "wmd_topk": wmd,
         "numpy": np.__version__,
+        # the paper's own figures for this path (Sec. VI, read off its Figs. 12 and 13): other hardware, other data,
+        # one query at a time - context, not a target, and not what vs_baseline refers to
+        "paper_context": {"hardware": "NVIDIA Tesla P100 16 GB, CUDA 8 (paper, Sec. VI)", "workload": "one query against the whole resident set",
+                          "set_1_1M_docs_mean_107_words": {"one_gpu_ms": 120, "pairs_per_s": 8.3e6, "sixteen_gpus_ms": 8},
+                          "set_2_2.8M_docs_mean_27_words": {"one_gpu_ms": 160, "pairs_per_s": 1.75e7, "sixteen_gpus_ms": 10},
+                          "note": "approximate values as the paper states them; its datasets are not public"},
     }
     out.update(extra)
     sweep_cfg = None
