@@ -273,7 +273,9 @@ lcrwmd_status run_phase1(lcrwmd_ctx* ctx, const EmbPrep& ep, int32_t m, const in
     // a word that occurs in the histogram is at distance exactly 0 from it; the norm expansion
     // only gets there up to cancellation error.  (A vocabulary that lists words more than once - the stacked
     // histograms of the quadratic method - has no word -> row map: the pass below finds those entries itself.)
-    if (!voc_rows || zero_map) HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s));
+    if (!voc_rows || zero_map)
+        HIP_TRY(launch_zero_matches(rp_batch, col_idx, tp.nseg, zero_map, Z, ldz, s, mapped ? close_bits : nullptr,
+                                    close_bits_pitch(ep.mode, nvoc), close_bits_slice(ep.mode)));
     // ... and loses relative accuracy where two different words lie close together: those entries are redone
     if (mapped)
         HIP_TRY(launch_redo_close_bits(ep.xdata, ep.xbf16, ep.xld, ep.xm, voc_rows, nvoc, rp_batch, col_idx, tp.nseg, Z, ldz, close_bits,

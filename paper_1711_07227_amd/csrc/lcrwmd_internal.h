@@ -121,7 +121,8 @@ hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, 
                              const float* normE, hipStream_t s);
 // Z[row(word) * ldz + seg] = 0 for every stored (seg, word) of the batch; row() through map when given
 hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg,
-                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s);
+                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s, uint64_t* bits = nullptr,
+                               int64_t pitch = 0, int slice_words = 0);
 // Entries of Z (rows by position in voc_rows, or by word id when voc_rows is null) whose square is below a quarter of
 // the word's squared norm are recomputed from coordinate differences over the histogram's words.  E: fp32 rows, or
 // bf16 rows when `bf16`, pitch ld elements.  Runs after launch_zero_matches.

@@ -212,11 +212,13 @@ __global__ void k_chunk_bounds(const int32_t* __restrict__ pofs, int32_t nseg, i
     chunk_seg[c] = lo;
 }
 
-// One wavefront per histogram.
+// One wavefront per histogram.  bits (or null): the contraction kernel's map of close pairs (see k_redo_close_bits);
+// the entries set to exactly 0 here are taken out of it, so that the pass over the map is left with the pairs of
+// different words only - on ordinary embeddings nothing at all.
 __global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict__ rp,
                                                       const int32_t* __restrict__ col_idx, int64_t nseg,
                                                       const int32_t* __restrict__ map, float* __restrict__ Z,
-                                                      int64_t ldz)
+                                                      int64_t ldz, uint64_t* __restrict__ bits, int64_t pitch, int slice_words)
 {
     const int lane = threadIdx.x & 63;
     int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -224,7 +226,15 @@ __global__ __launch_bounds__(256) void k_zero_matches(const int64_t* __restrict_
     for (int64_t p = rp[seg] + lane; p < rp[seg + 1]; p += 64) {
         int32_t w = col_idx[p];
         int32_t row = map ? map[w] : w;
-        if (row >= 0) Z[(int64_t)row * ldz + seg] = 0.f;
+        if (row >= 0) {
+            Z[(int64_t)row * ldz + seg] = 0.f;
+            if (bits) {
+                const int b = row % slice_words;
+                // 32-position slices carry every bit twice (both lane halves of the wavefront that wrote them)
+                const unsigned long long gone = slice_words == 32 ? ((1ull << b) | (1ull << (b + 32))) : (1ull << b);
+                atomicAnd(reinterpret_cast<unsigned long long*>(bits + seg * pitch + row / slice_words), ~gone);
+            }
+        }
     }
 }
 
@@ -535,10 +545,12 @@ hipError_t launch_token_plan(const TokenPlan& tp, const int64_t* row_ptr_batch, 
 }
 
 hipError_t launch_zero_matches(const int64_t* row_ptr_batch, const int32_t* col_idx, int64_t nseg,
-                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s)
+                               const int32_t* map, float* Z, int64_t ldz, hipStream_t s, uint64_t* bits, int64_t pitch,
+                               int slice_words)
 {
     if (nseg <= 0) return hipSuccess;
-    k_zero_matches<<<(unsigned)((nseg + 3) / 4), 256, 0, s>>>(row_ptr_batch, col_idx, nseg, map, Z, ldz);
+    k_zero_matches<<<(unsigned)((nseg + 3) / 4), 256, 0, s>>>(row_ptr_batch, col_idx, nseg, map, Z, ldz, bits, pitch,
+                                                              slice_words > 0 ? slice_words : 64);
     return hipGetLastError();
 }
 
