@@ -357,48 +357,51 @@ def config_leg(name, steps, warmup, cpu_queries, with_cpu, sweep=False, self_swe
                                           "sum_of_all_distances": total,
                                           "includes": "host-side slicing and upload of every batch of queries"}
             if self_sweep:
-                # the same job in one call: lcrwmd_rwmd_self evaluates every pair once (the bound is symmetric) and
-                # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch.  In the
-                # largest batches (a power of two up to 65,536) whose workspace fits the free memory - what the entry point
-                # picks by itself in a workspace of that size; with --sweep also in batches of 4,096.
-                torch = job.torch
-                rp = job.prob["db"][0]
-                job.D = job.ws = None
-                torch.cuda.empty_cache()
-                def self_ws_bytes(qb):
-                    starts = np.arange(0, job.n, qb)
-                    most = int(np.max(rp[np.minimum(starts + qb, job.n)] - rp[starts]))
-                    return job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, qb, most, job.emb_dtype, 16)
-                big = 65536
-                while big > job.q and self_ws_bytes(big) > 0.85 * torch.cuda.mem_get_info()[0]:
-                    big //= 2
-                R_idx = torch.empty((job.n, 16), dtype=torch.int32, device="cuda")
-                R_dist = torch.empty((job.n, 16), dtype=torch.float32, device="cuda")
-                sums = torch.empty((job.n,), dtype=torch.float64, device="cuda")
-                for qb in ((big, job.q) if sweep and big != job.q else (big,)):
-                    ws = job.binding.alloc_workspace(self_ws_bytes(qb))
-                    torch.cuda.synchronize()
-                    t0 = time.perf_counter()
-                    job.ctx.rwmd_self(job.db, job.E, qb, 16, R_idx, R_dist, sums, ws)
-                    torch.cuda.synchronize()
-                    sw = time.perf_counter() - t0
-                    del ws
-                    progress(f"all-pairs in one call, batches of {qb}: {sw:.1f} s")
-                    selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": qb, "k": 16,
-                               "sum_of_all_distances": float(sums.sum()),
-                               "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
-                    if with_cpu and qb == big:
-                        # sampled documents: their lists against the oracle's full columns
-                        import oracle
-                        pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
-                        ref = oracle.rwmd_table(job.prob["E"], job.prob["db"], job.synth.csr_rows(*job.prob["db"], pick))
-                        _, rdist = oracle.topk(ref, 16)
-                        got = R_dist[torch.from_numpy(pick).cuda()].cpu().numpy()
-                        selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
-                        selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
-                                                                                   - ref.sum(axis=0)) / ref.sum(axis=0)))
-                    out["all_pairs_in_one_call" if qb == big else "all_pairs_in_one_call_batches_of_%d" % qb] = selfrec
-                del R_idx, R_dist, sums
+                try:
+                    # the same job in one call: lcrwmd_rwmd_self evaluates every pair once (the bound is symmetric) and
+                    # keeps every document's list and sum on the device; nothing is sliced or uploaded per batch.  In the
+                    # largest batches (a power of two up to 65,536) whose workspace fits the free memory - what the entry point
+                    # picks by itself in a workspace of that size; with --sweep also in batches of 4,096.
+                    torch = job.torch
+                    rp = job.prob["db"][0]
+                    job.D = job.ws = None
+                    torch.cuda.empty_cache()
+                    def self_ws_bytes(qb):
+                        starts = np.arange(0, job.n, qb)
+                        most = int(np.max(rp[np.minimum(starts + qb, job.n)] - rp[starts]))
+                        return job.ctx.workspace_bytes(job.v, job.cfg.m, job.n, job.db.nnz, qb, most, job.emb_dtype, 16)
+                    big = 65536
+                    while big > job.q and self_ws_bytes(big) > 0.85 * torch.cuda.mem_get_info()[0]:
+                        big //= 2
+                    R_idx = torch.empty((job.n, 16), dtype=torch.int32, device="cuda")
+                    R_dist = torch.empty((job.n, 16), dtype=torch.float32, device="cuda")
+                    sums = torch.empty((job.n,), dtype=torch.float64, device="cuda")
+                    for qb in ((big, job.q) if sweep and big != job.q else (big,)):
+                        ws = job.binding.alloc_workspace(self_ws_bytes(qb))
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        job.ctx.rwmd_self(job.db, job.E, qb, 16, R_idx, R_dist, sums, ws)
+                        torch.cuda.synchronize()
+                        sw = time.perf_counter() - t0
+                        del ws
+                        progress(f"all-pairs in one call, batches of {qb}: {sw:.1f} s")
+                        selfrec = {"seconds": sw, "pairs_per_s": job.n * job.n / sw, "batch": qb, "k": 16,
+                                   "sum_of_all_distances": float(sums.sum()),
+                                   "entry_point": "lcrwmd_rwmd_self: every pair evaluated once, lists and sums of all documents on the device"}
+                        if with_cpu and qb == big:
+                            # sampled documents: their lists against the oracle's full columns
+                            import oracle
+                            pick = np.array([0, job.q - 1, job.q, job.n // 2, job.n - 1])
+                            ref = oracle.rwmd_table(job.prob["E"], job.prob["db"], job.synth.csr_rows(*job.prob["db"], pick))
+                            _, rdist = oracle.topk(ref, 16)
+                            got = R_dist[torch.from_numpy(pick).cuda()].cpu().numpy()
+                            selfrec["max_rel_err_of_5_lists_vs_oracle"] = float(np.max(np.abs(got - rdist) / np.maximum(rdist, 1e-6)))
+                            selfrec["sum_max_rel_err_vs_oracle"] = float(np.max(np.abs(sums[torch.from_numpy(pick).cuda()].cpu().numpy()
+                                                                                       - ref.sum(axis=0)) / ref.sum(axis=0)))
+                        out["all_pairs_in_one_call" if qb == big else "all_pairs_in_one_call_batches_of_%d" % qb] = selfrec
+                    del R_idx, R_dist, sums
+                except Exception as e:      # this leg's failure must not take the per-batch figures with it
+                    out["all_pairs_in_one_call"] = {"failed": f"{type(e).__name__}: {str(e)[:300]}"}
         elif not reduce and job.cfg.h_hi > 200:
             # long documents: the form the library picks by itself
             job.options(dedup=2)
